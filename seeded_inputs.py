@@ -1,0 +1,199 @@
+"""Seeded synthetic inputs for the PHOTON decode hot path.
+
+This module is the only code shared by the CPU oracle and the HIP path.  It
+holds no arithmetic of the method: it only names shapes (the hierarchy of the
+paper's Notation paragraph: levels L, chunk lengths C_l, prefix lengths R_l,
+widths) and draws seeded random tensors of those shapes.  Everything is
+returned as float32 / int32 numpy arrays; for a bf16 configuration the values
+are rounded to bf16-representable numbers so that both sides start from
+bit-identical inputs.
+
+Recipe (stands in for trained weights and tokenised text, which throughput and
+parity do not depend on): tokens i.i.d. uniform over the vocabulary, embedding
+tables N(0,1), every projection matrix and bias N(0,0.02), norm gains
+1 + 0.1*N(0,1) (so a dropped gain is visible), start latents N(0,1)*0.02.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field, replace
+from typing import Dict, List, Tuple
+
+import numpy as np
+import torch
+
+
+@dataclass(frozen=True)
+class PhotonConfig:
+    """Shape of one PHOTON model.  Level l (1-based) uses C[l-1] and R[l-1]."""
+    L: int
+    C: Tuple[int, ...]
+    R: Tuple[int, ...]
+    D: int
+    H: int
+    d_h: int
+    n_layers: int
+    d_ff: int
+    vocab: int
+    dtype: str = "f32"            # "f32" | "bf16": storage type of weights and caches
+    rms_eps: float = 1e-5
+    rope_theta: float = 10000.0   # 0 disables the rotary encoding
+    chunker_bias: bool = True
+
+    def __post_init__(self):
+        assert len(self.C) == self.L and len(self.R) == self.L
+        assert self.H * self.d_h == self.D
+        assert self.dtype in ("f32", "bf16")
+
+    @property
+    def meta_context(self) -> int:
+        """Number of tokens one top-level step emits (product of all C_l)."""
+        return int(np.prod(self.C))
+
+    def W(self, level: int) -> int:
+        """Window length of the level-`level` local decoder: R_l + C_l - 1."""
+        return self.R[level - 1] + self.C[level - 1] - 1
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    cfg: PhotonConfig
+    Bt: int           # concurrent sequences
+    T: int            # context tokens per sequence at the start of decode
+    steps: int        # decode steps (one step = one meta-context per sequence)
+    note: str = ""
+
+    @property
+    def S0(self) -> int:
+        """Coarse KV length at the start of decode."""
+        return self.T // self.cfg.meta_context
+
+
+def _cfg(L, C, D, H, nl, vocab, dtype, R=None, d_ff=None):
+    return PhotonConfig(L=L, C=tuple(C), R=tuple(R or (1,) * L), D=D, H=H, d_h=D // H,
+                        n_layers=nl, d_ff=int(2.5 * D) if d_ff is None else d_ff,
+                        vocab=vocab, dtype=dtype)
+
+
+# The five configurations of the benchmark spec.  d_ff = 2.5*D follows the ratio of
+# the paper's parameter tables (4096/1664, 4608/1792, 5120/1920); vocab 32000
+# is the paper's tokenizer size; R=1 makes the local window exactly C.
+WORKLOADS: Dict[str, Workload] = {
+    "cfg1_tiny_f32": Workload("cfg1_tiny_f32", _cfg(2, (4, 4), 64, 2, 1, 512, "f32"), 1, 256, 1),
+    "cfg2_bf16_8k": Workload("cfg2_bf16_8k", _cfg(2, (4, 4), 1024, 16, 4, 32000, "bf16"), 16, 8192, 128),
+    "cfg3_bf16_128k": Workload("cfg3_bf16_128k", _cfg(2, (4, 4), 2048, 32, 8, 32000, "bf16"), 4, 131072, 256),
+    "cfg4_bf16_serving": Workload("cfg4_bf16_serving", _cfg(2, (4, 4), 1024, 16, 4, 32000, "bf16"), 256, 32768, 64),
+    "cfg5_bf16_3level": Workload("cfg5_bf16_3level", _cfg(3, (8, 8, 8), 2048, 32, 8, 32000, "bf16"), 8, 32768, 128),
+}
+
+
+def round_to_dtype(x: torch.Tensor, dtype: str) -> torch.Tensor:
+    """Round a float32 tensor to values representable in `dtype` (still float32)."""
+    if dtype == "bf16":
+        return x.to(torch.bfloat16).to(torch.float32)
+    return x
+
+
+class _Draw:
+    """Fixed-order seeded normal draws."""
+
+    def __init__(self, seed: int, dtype: str):
+        self.g = torch.Generator(device="cpu")
+        self.g.manual_seed(int(seed))
+        self.dtype = dtype
+
+    def normal(self, shape, std=1.0, mean=0.0) -> np.ndarray:
+        t = torch.randn(tuple(shape), generator=self.g, dtype=torch.float32) * std + mean
+        return round_to_dtype(t, self.dtype).numpy()
+
+    def uniform_int(self, shape, high) -> np.ndarray:
+        return torch.randint(0, int(high), tuple(shape), generator=self.g,
+                             dtype=torch.int64).to(torch.int32).numpy()
+
+
+def _module(d: _Draw, cfg: PhotonConfig) -> dict:
+    D, F = cfg.D, cfg.d_ff
+    layers = []
+    for _ in range(cfg.n_layers):
+        lay = {
+            "g1": d.normal((D,), 0.1, 1.0),
+            "wq": d.normal((D, D), 0.02), "wk": d.normal((D, D), 0.02),
+            "wv": d.normal((D, D), 0.02), "wo": d.normal((D, D), 0.02),
+        }
+        if F > 0:
+            lay.update({
+                "g2": d.normal((D,), 0.1, 1.0),
+                "wg": d.normal((F, D), 0.02), "wu": d.normal((F, D), 0.02),
+                "wd": d.normal((D, F), 0.02),
+            })
+        layers.append(lay)
+    return {"layers": layers, "g_final": d.normal((D,), 0.1, 1.0)}
+
+
+def make_weights(cfg: PhotonConfig, seed: int = 0, *, encoders: bool = True,
+                 emb_std: float = 1.0) -> dict:
+    """All parameters of one model.  Every linear map is stored [out, in]
+    (y = W x), so the contraction index is contiguous.
+
+    encoders=False leaves out the level < L encoders and the encoder-side
+    embedding (recursive generation keeps only the decoder stack, the top
+    chunker and the top encoder resident).
+    """
+    d = _Draw(seed, cfg.dtype)
+    D = cfg.D
+    w = {"E_dec": d.normal((cfg.vocab, D), emb_std), "W_lm": d.normal((cfg.vocab, D), 0.02)}
+    if encoders:
+        w["E_enc"] = d.normal((cfg.vocab, D), emb_std)
+    enc: List[dict] = []
+    for l in range(1, cfg.L + 1):
+        if not encoders and l < cfg.L:
+            enc.append({})
+            continue
+        e = {"chunker": {"w": d.normal((D, cfg.C[l - 1] * D), 0.02)}, "module": _module(d, cfg)}
+        if cfg.chunker_bias:
+            e["chunker"]["b"] = d.normal((D,), 0.02)
+        enc.append(e)
+    dec: List[dict] = []
+    for l in range(1, cfg.L + 1):
+        R = cfg.R[l - 1]
+        dec.append({
+            "converter": {"w": d.normal((R * D, D), 0.02), "b": d.normal((R * D,), 0.02)},
+            "x0": d.normal((D,), 0.02),
+            "module": _module(d, cfg),
+        })
+    w["enc"] = enc
+    w["dec"] = dec
+    return w
+
+
+def make_tokens(vocab: int, Bt: int, T: int, seed: int = 0) -> np.ndarray:
+    """Prompt tokens, i.i.d. uniform over the vocabulary: int32 [Bt, T]."""
+    return _Draw(seed + 7919, "f32").uniform_int((Bt, T), vocab)
+
+
+def make_normal(shape, seed: int, dtype: str = "f32", std: float = 1.0) -> np.ndarray:
+    """A seeded N(0, std) tensor rounded to `dtype`-representable float32."""
+    return _Draw(seed, dtype).normal(shape, std)
+
+
+def make_decode_state(cfg: PhotonConfig, Bt: int, S: int, S_max: int, seed: int = 0) -> dict:
+    """Benchmark-style decode state without a prefill: coarse K/V ~ N(0,1) for
+    the first S slots of every (layer, sequence, head) stream, top state and
+    carries ~ N(0,1).  Layouts: kv [n_layers, Bt, H, S_max, d_h]; x_top [Bt, D];
+    carry [L-1, Bt, D] (carry[l-1] is the last reconstructed level-l unit)."""
+    d = _Draw(seed + 104729, cfg.dtype)
+    k = np.zeros((cfg.n_layers, Bt, cfg.H, S_max, cfg.d_h), np.float32)
+    v = np.zeros_like(k)
+    k[:, :, :, :S] = d.normal((cfg.n_layers, Bt, cfg.H, S, cfg.d_h))
+    v[:, :, :, :S] = d.normal((cfg.n_layers, Bt, cfg.H, S, cfg.d_h))
+    return {
+        "k": k, "v": v,
+        "seq_len": np.full((Bt,), S, np.int32),
+        "x_top": _Draw(seed + 1, "f32").normal((Bt, cfg.D)),
+        "carry": _Draw(seed + 2, "f32").normal((max(cfg.L - 1, 0), Bt, cfg.D)),
+    }
+
+
+def shrink(cfg: PhotonConfig, **kw) -> PhotonConfig:
+    """A copy of `cfg` with some fields replaced (reduced-size parity cases)."""
+    return replace(cfg, **kw)
