@@ -1,0 +1,124 @@
+/*
+ * photon.h -- C ABI of the MI355X (gfx950) implementation of the PHOTON
+ * hierarchical decode hot path (arXiv 2512.20687).
+ *
+ * Notation follows the paper (Section 2.1, "Notation"): an L-level hierarchy,
+ * level l groups C_l level-(l-1) units into one level-l unit; the converter of
+ * level l expands one level-l vector into R_l conditioning vectors; the local
+ * decoder of level l works on a window of W_l = R_l + C_l - 1 positions; all
+ * levels share one width D = H * d_h.
+ *
+ * General rules for every entry point
+ *  - Every pointer is a DEVICE pointer unless its comment says "host".
+ *    Device pointers must be 16-byte aligned (the kernels use 128-bit accesses).
+ *  - The library never allocates, frees or synchronises.  A call validates its
+ *    arguments on the host, then only enqueues kernels on `stream` (a
+ *    hipStream_t passed as void*; NULL is the default stream) and returns.
+ *    Buffers must stay alive until the stream has run the work.
+ *  - Return value: PHOTON_OK or a negative photon_status.  On error nothing has
+ *    been enqueued (PHOTON_ERR_HIP excepted: a launch failed part-way) and
+ *    photon_last_error() describes the problem (thread-local, host string).
+ *  - dtype: PHOTON_F32 stores every tensor as IEEE fp32; PHOTON_BF16 stores
+ *    matrices, embedding tables and K/V caches as bfloat16 (round to nearest
+ *    even on store).  All arithmetic accumulates in fp32.
+ *  - Linear maps are stored W[out, in] row-major (y = W x): the contraction
+ *    index is contiguous.
+ */
+#ifndef PHOTON_H_
+#define PHOTON_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define PHOTON_API __attribute__((visibility("default")))
+#else
+#define PHOTON_API
+#endif
+
+typedef enum { PHOTON_F32 = 0, PHOTON_BF16 = 1 } photon_dtype;
+
+typedef enum {
+  PHOTON_OK = 0,
+  PHOTON_ERR_INVALID_ARG = -1, /* null/misaligned pointer, non-positive size, sizes that do not divide */
+  PHOTON_ERR_UNSUPPORTED = -2, /* a size or dtype no kernel was compiled for */
+  PHOTON_ERR_WORKSPACE = -3,   /* workspace missing or too small */
+  PHOTON_ERR_HIP = -4          /* the HIP runtime refused a launch */
+} photon_status;
+
+enum { PHOTON_MAX_LEVELS = 4, PHOTON_MAX_WINDOW = 16 };
+
+/* Library version: major*10000 + minor*100 + patch. */
+PHOTON_API int32_t photon_version(void);
+
+/* Host string describing the last error on the calling thread ("" if none). */
+PHOTON_API const char* photon_last_error(void);
+
+/* --------------------------------------------------------------------------
+ * Context chunker (paper Eq. 4): fold C consecutive finer states into one
+ * coarser state,
+ *     out[r, :] = W_c * concat(x[r*C + 0, :], ..., x[r*C + C-1, :]) + bias .
+ *   x     [rows*C, d_in]   dt   (read as [rows, C*d_in]: the concatenation is free)
+ *   w     [d_out, C*d_in]  dt   or NULL: parameter-free concatenation (then
+ *                               d_out must equal C*d_in; out is a copy of x)
+ *   bias  [d_out]          fp32 or NULL
+ *   out   [rows, d_out]    dt
+ * bf16: fp32 accumulation on the matrix cores, one rounding on store.
+ * Requires C*d_in to be a multiple of 32 and d_out a multiple of 16.
+ * rows == 0 is a no-op.
+ * -------------------------------------------------------------------------- */
+PHOTON_API int32_t photon_chunker_project(const void* x, const void* w, const float* bias, void* out,
+                               int64_t rows, int32_t C, int32_t d_in, int32_t d_out,
+                               photon_dtype dt, void* stream);
+
+/* --------------------------------------------------------------------------
+ * Coarsest-stream decode attention: the attention inside the STEP operator of
+ * the top-level context encoder (paper Eq. 12-13, Appendix A.1).  One query
+ * per (sequence, head) attends to the first seq_len[b] entries of that
+ * stream's K/V cache (the entry appended by this step included):
+ *     out[b,h,:] = softmax(scale * q[b,h,:] . K[b,h,0:seq_len[b],:]) V[b,h,0:seq_len[b],:]
+ *   q        [Bt, H, d_h]          dt
+ *   k_cache  [Bt, H, S_max, d_h]   dt   (each (b,h) stream contiguous)
+ *   v_cache  [Bt, H, S_max, d_h]   dt
+ *   seq_len  [Bt]                  int32, device; values in [0, S_max]; 0 gives zeros
+ *   out      [Bt, H, d_h]          dt
+ * d_h in {32, 64, 128}.  The S axis is split over n_splits workgroups per
+ * stream (0 = choose from Bt*H and S_max); partial softmax states are merged
+ * in a fixed order, so the result is run-to-run deterministic for a given
+ * n_splits.  n_splits > 1 needs a workspace of
+ * photon_coarse_decode_attn_workspace_bytes() bytes (contents need no
+ * initialisation; calls that share a workspace must be stream-ordered).
+ * -------------------------------------------------------------------------- */
+PHOTON_API size_t photon_coarse_decode_attn_workspace_bytes(int32_t Bt, int32_t H, int32_t d_h, int32_t n_splits);
+PHOTON_API int32_t photon_coarse_decode_attn_auto_splits(int32_t Bt, int32_t H, int64_t S_max);
+PHOTON_API int32_t photon_coarse_decode_attn(const void* q, const void* k_cache, const void* v_cache,
+                                  const int32_t* seq_len, void* out,
+                                  int32_t Bt, int32_t H, int32_t d_h, int64_t S_max, float scale,
+                                  int32_t n_splits, void* workspace, size_t workspace_bytes,
+                                  photon_dtype dt, void* stream);
+
+/* --------------------------------------------------------------------------
+ * Chunk-local causal attention of the local decoders (paper Eq. 6-7): every
+ * chunk is an independent window of W positions; query i (0 <= i < q_len) sits
+ * at window position q_pos + i and attends to keys 0 .. q_pos + i of its own
+ * chunk only.
+ *   q    [n_chunks, q_len, H, d_h]   dt   (token-major, as a QKV projection writes it)
+ *   k,v  [n_chunks, W,     H, d_h]   dt   (the chunk's local cache / K,V tile)
+ *   out  [n_chunks, q_len, H, d_h]   dt
+ * q_len == W, q_pos == 0: the whole W x W causal tile (teacher-forced / prefill).
+ * q_len == 1: one decode sub-step at window position q_pos.
+ * Requires q_pos + q_len <= W <= PHOTON_MAX_WINDOW, d_h in {32, 64, 128}.
+ * n_chunks == 0 is a no-op.
+ * -------------------------------------------------------------------------- */
+PHOTON_API int32_t photon_chunk_local_attn(const void* q, const void* k, const void* v, void* out,
+                                int64_t n_chunks, int32_t W, int32_t q_len, int32_t q_pos,
+                                int32_t H, int32_t d_h, float scale, photon_dtype dt, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PHOTON_H_ */

@@ -1,0 +1,21 @@
+"""PHOTON hierarchical decode hot path for MI355X (gfx950).
+
+Thin Python binding over the C ABI in include/photon.h: each function here has
+the name of the C entry point it calls and only marshals arguments (torch
+tensors supply device memory and the current stream).  Every step of the path
+runs in the HIP kernels of libphoton_hip.so; there is no fallback: if the
+library is missing or fails to load, importing a function works but calling it
+raises.
+"""
+from .binding import (  # noqa: F401
+    PhotonError,
+    lib_path,
+    load_library,
+    photon_chunk_local_attn,
+    photon_chunker_project,
+    photon_coarse_decode_attn,
+    photon_coarse_decode_attn_auto_splits,
+    photon_coarse_decode_attn_workspace_bytes,
+    photon_last_error,
+    photon_version,
+)

@@ -1,0 +1,20 @@
+// Internal launch interface of the attention kernels (used by the C ABI
+// entry points and by the decode-step composition).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace photon {
+
+enum KvType { KV_F32 = 0, KV_BF16 = 1 };
+
+// q/out are fp32 when q_f32 (always the case for KV_F32), else bf16.
+int32_t launch_coarse_attn(KvType kv, bool q_f32, int d_h, const void* q, const void* kc, const void* vc,
+                           const int32_t* seq_len, void* out, int Bt, int H, int64_t S_max, float scale,
+                           int n_splits, void* ws, hipStream_t st);
+int32_t coarse_auto_splits(int Bt, int H, int64_t S_max);
+
+int32_t launch_local_attn(bool f32, int d_h, const void* q, const void* k, const void* v, void* out,
+                          int64_t n_chunks, int W, int q_len, int q_pos, int H, float scale, hipStream_t st);
+
+}  // namespace photon

@@ -1,0 +1,435 @@
+// Attention kernels of the PHOTON decode path for gfx950.
+//
+//  * coarse_attn_kernel: single-query attention over the coarsest stream's KV
+//    cache (STEP operator, paper Eq. 12-13).  HBM-bound streaming: every K/V
+//    byte is used once, so the S axis is split over workgroups, each lane
+//    issues 128-bit loads that together cover whole 128-byte+ rows, scores are
+//    reduced inside lane groups with DPP moves, the online-softmax states of
+//    the lane groups and waves are merged through shuffles and LDS, and the
+//    splits through a small fp32 workspace in a fixed order.
+//  * local_attn_kernel: chunk-local causal attention of the local decoders
+//    (paper Eq. 6-7).  A window has at most 16 positions, so one lane group
+//    keeps a whole (chunk, head) K/V tile in registers; nothing is re-read.
+#include "photon_attn.h"
+
+#include "photon_device.h"
+#include "photon_host.h"
+
+namespace photon {
+
+// ------------------------------------------------------------------ coarse stream
+
+constexpr int COARSE_THREADS = 256;
+constexpr int COARSE_WAVES = COARSE_THREADS / 64;
+constexpr int COARSE_UNROLL = 4;   // 16-byte K loads (and as many V loads) in flight per lane and buffer
+
+template <typename TKV, int DH> struct RowMap {
+  static constexpr int VEC = 16 / sizeof(TKV);      // elements per 16-byte lane chunk
+  static constexpr int LPR = DH / VEC;              // lanes that cover one row
+  static constexpr int RPW = 64 / LPR;              // rows one wave covers per load
+  static_assert(LPR >= 1 && LPR <= 32 && (LPR & (LPR - 1)) == 0, "row must map to 1..32 lanes");
+};
+
+// Online-softmax state of one lane group: running max m (log2 domain), sum l, weighted values o.
+template <int VEC> struct SoftState {
+  float m, l, o[VEC];
+  __device__ __forceinline__ void init() {
+    m = NEG_BIG; l = 0.f;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) o[i] = 0.f;
+  }
+};
+
+template <typename TKV, typename TQ, int DH>
+__global__ __launch_bounds__(COARSE_THREADS) void coarse_attn_kernel(
+    const TQ* __restrict__ q, const TKV* __restrict__ kc, const TKV* __restrict__ vc,
+    const int32_t* __restrict__ seq_len, TQ* __restrict__ out, float* __restrict__ ws,
+    int H, int64_t S_max, float scale_log2e, int n_splits) {
+  using M = RowMap<TKV, DH>;
+  constexpr int VEC = M::VEC, LPR = M::LPR, RPW = M::RPW, U = COARSE_UNROLL;
+  constexpr int TILE = RPW * U;                       // keys one wave consumes per buffer
+
+  const int split = blockIdx.x;
+  const int bh = blockIdx.y;
+  const int b = bh / H;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int g = lane / LPR, c = lane % LPR;
+
+  int64_t n = seq_len[b];
+  n = n < 0 ? 0 : (n > S_max ? S_max : n);
+  int64_t per = (n + n_splits - 1) / n_splits;
+  per = (per + TILE - 1) / TILE * TILE;
+  const int64_t begin = (int64_t)split * per;
+  const int64_t end = begin + per < n ? begin + per : n;
+
+  float qf[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) qf[i] = to_f32<TQ>(q[(int64_t)bh * DH + c * VEC + i]) * scale_log2e;
+
+  const TKV* kb = kc + (int64_t)bh * S_max * DH + c * VEC;
+  const TKV* vb = vc + (int64_t)bh * S_max * DH + c * VEC;
+
+  SoftState<VEC> st;
+  st.init();
+
+  // Loads use a clamped key index (always in bounds); keys past `end` get weight 0.
+  auto load = [&](int64_t t0, uint4_t (&kr)[U], uint4_t (&vr)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int64_t key = t0 + u * RPW + g;
+      key = key < end ? key : end - 1;
+      kr[u] = load16(kb + key * DH);
+      vr[u] = load16(vb + key * DH);
+    }
+  };
+  auto consume = [&](int64_t t0, const uint4_t (&kr)[U], const uint4_t (&vr)[U]) {
+    float s[U];
+    float mx = st.m;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[VEC];
+      unpack16<TKV>(kr[u], kf);
+      float acc = 0.f;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc = fmaf(qf[i], kf[i], acc);
+      s[u] = group_sum<LPR>(acc);
+      const bool ok = t0 + u * RPW + g < end;
+      s[u] = ok ? s[u] : NEG_BIG;
+      mx = fmaxf(mx, s[u]);
+    }
+    const float alpha = fast_exp2(st.m - mx);
+    st.m = mx;
+    st.l *= alpha;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) st.o[i] *= alpha;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool ok = t0 + u * RPW + g < end;
+      const float p = ok ? fast_exp2(s[u] - mx) : 0.f;
+      st.l += p;
+      float vf[VEC];
+      unpack16<TKV>(vr[u], vf);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) st.o[i] = fmaf(p, vf[i], st.o[i]);
+    }
+  };
+
+  // Waves take TILE-key slabs round-robin; two register buffers keep the next slab in flight.
+  const int64_t stride = (int64_t)COARSE_WAVES * TILE;
+  int64_t t0 = begin + (int64_t)wave * TILE;
+  if (t0 < end) {
+    uint4_t ka[U], va[U], kb2[U], vb2[U];
+    load(t0, ka, va);
+    while (true) {
+      const int64_t t1 = t0 + stride;
+      const bool more1 = t1 < end;
+      if (more1) load(t1, kb2, vb2);
+      consume(t0, ka, va);
+      if (!more1) break;
+      const int64_t t2 = t1 + stride;
+      const bool more2 = t2 < end;
+      if (more2) load(t2, ka, va);
+      consume(t1, kb2, vb2);
+      if (!more2) break;
+      t0 = t2;
+    }
+  }
+
+  // Merge the RPW lane groups of the wave (lanes with equal c).
+#pragma unroll
+  for (int mask = LPR; mask < 64; mask <<= 1) {
+    const float m2 = __shfl_xor(st.m, mask);
+    const float mm = fmaxf(st.m, m2);
+    const float a1 = fast_exp2(st.m - mm), a2 = fast_exp2(m2 - mm);
+    st.l = st.l * a1 + __shfl_xor(st.l, mask) * a2;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) st.o[i] = st.o[i] * a1 + __shfl_xor(st.o[i], mask) * a2;
+    st.m = mm;
+  }
+
+  // Merge the waves through LDS.
+  __shared__ float sm[COARSE_WAVES], sl[COARSE_WAVES], so[COARSE_WAVES][DH];
+  if (g == 0) {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) so[wave][c * VEC + i] = st.o[i];
+    if (c == 0) { sm[wave] = st.m; sl[wave] = st.l; }
+  }
+  __syncthreads();
+  if (tid < DH) {
+    float mm = sm[0];
+#pragma unroll
+    for (int w = 1; w < COARSE_WAVES; ++w) mm = fmaxf(mm, sm[w]);
+    float l = 0.f, o = 0.f;
+#pragma unroll
+    for (int w = 0; w < COARSE_WAVES; ++w) {
+      const float a = fast_exp2(sm[w] - mm);
+      l = fmaf(sl[w], a, l);
+      o = fmaf(so[w][tid], a, o);
+    }
+    if (n_splits == 1) {
+      out[(int64_t)bh * DH + tid] = from_f32<TQ>(l > 0.f ? o / l : 0.f);
+    } else {
+      float* p = ws + ((int64_t)bh * n_splits + split) * (DH + 2);
+      if (tid == 0) { p[0] = mm; p[1] = l; }
+      p[2 + tid] = o;
+    }
+  }
+}
+
+// Merge the split partials of one (b, h) stream in split order.
+template <typename TQ, int DH>
+__global__ __launch_bounds__(DH) void coarse_merge_kernel(const float* __restrict__ ws, TQ* __restrict__ out, int n_splits) {
+  const int bh = blockIdx.x, d = threadIdx.x;
+  const float* p = ws + (int64_t)bh * n_splits * (DH + 2);
+  float mm = NEG_BIG;
+  for (int s = 0; s < n_splits; ++s) mm = fmaxf(mm, p[s * (DH + 2)]);
+  float l = 0.f, o = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const float a = fast_exp2(p[s * (DH + 2)] - mm);
+    l = fmaf(p[s * (DH + 2) + 1], a, l);
+    o = fmaf(p[s * (DH + 2) + 2 + d], a, o);
+  }
+  out[(int64_t)bh * DH + d] = from_f32<TQ>(l > 0.f ? o / l : 0.f);
+}
+
+template <typename TKV, typename TQ, int DH>
+static int32_t launch_coarse_t(const void* q, const void* kc, const void* vc, const int32_t* seq_len, void* out,
+                               int Bt, int H, int64_t S_max, float scale, int n_splits, void* ws, hipStream_t st) {
+  dim3 grid(n_splits, Bt * H);
+  hipLaunchKernelGGL((coarse_attn_kernel<TKV, TQ, DH>), grid, dim3(COARSE_THREADS), 0, st,
+                     (const TQ*)q, (const TKV*)kc, (const TKV*)vc, seq_len, (TQ*)out, (float*)ws, H, S_max,
+                     scale * LOG2E, n_splits);
+  int32_t rc = check_launch("coarse_attn_kernel");
+  if (rc != PHOTON_OK || n_splits == 1) return rc;
+  hipLaunchKernelGGL((coarse_merge_kernel<TQ, DH>), dim3(Bt * H), dim3(DH), 0, st, (const float*)ws, (TQ*)out, n_splits);
+  return check_launch("coarse_merge_kernel");
+}
+
+template <typename TKV, typename TQ>
+static int32_t launch_coarse_dh(int d_h, const void* q, const void* kc, const void* vc, const int32_t* seq_len, void* out,
+                                int Bt, int H, int64_t S_max, float scale, int n_splits, void* ws, hipStream_t st) {
+  switch (d_h) {
+    case 32: return launch_coarse_t<TKV, TQ, 32>(q, kc, vc, seq_len, out, Bt, H, S_max, scale, n_splits, ws, st);
+    case 64: return launch_coarse_t<TKV, TQ, 64>(q, kc, vc, seq_len, out, Bt, H, S_max, scale, n_splits, ws, st);
+    case 128: return launch_coarse_t<TKV, TQ, 128>(q, kc, vc, seq_len, out, Bt, H, S_max, scale, n_splits, ws, st);
+  }
+  return fail(PHOTON_ERR_UNSUPPORTED, "coarse attention: d_h=%d not in {32, 64, 128}", d_h);
+}
+
+int32_t launch_coarse_attn(KvType kv, bool q_f32, int d_h, const void* q, const void* kc, const void* vc,
+                           const int32_t* seq_len, void* out, int Bt, int H, int64_t S_max, float scale,
+                           int n_splits, void* ws, hipStream_t st) {
+  if (kv == KV_F32) return launch_coarse_dh<float, float>(d_h, q, kc, vc, seq_len, out, Bt, H, S_max, scale, n_splits, ws, st);
+  if (q_f32) return launch_coarse_dh<bf16_t, float>(d_h, q, kc, vc, seq_len, out, Bt, H, S_max, scale, n_splits, ws, st);
+  return launch_coarse_dh<bf16_t, bf16_t>(d_h, q, kc, vc, seq_len, out, Bt, H, S_max, scale, n_splits, ws, st);
+}
+
+int32_t coarse_auto_splits(int Bt, int H, int64_t S_max) {
+  // Aim at ~8 waves of loads in flight per SIMD-quad on all 256 CUs (>= 1024 workgroups)
+  // while every split still streams at least 256 keys.
+  int64_t streams = (int64_t)Bt * H;
+  int64_t want = (1024 + streams - 1) / streams;
+  int64_t cap = S_max / 256;
+  if (cap < 1) cap = 1;
+  if (want > cap) want = cap;
+  if (want > 64) want = 64;
+  if (want < 1) want = 1;
+  return (int32_t)want;
+}
+
+// ------------------------------------------------------------------ chunk-local
+
+constexpr int LOCAL_THREADS = 256;
+
+// One lane group owns one (chunk, head) unit: it holds the unit's NK key and
+// value rows in registers and walks over the query rows.  TILE: q_len == NK and
+// q_pos == 0, fully unrolled.
+template <typename T, int DH, int NK, bool TILE>
+__global__ __launch_bounds__(LOCAL_THREADS) void local_attn_kernel(
+    const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, T* __restrict__ out,
+    int64_t n_units, int H, int W, int q_len_rt, int q_pos_rt, float scale_log2e) {
+  using M = RowMap<T, DH>;
+  constexpr int VEC = M::VEC, LPR = M::LPR, UPW = M::RPW;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = (int64_t)blockIdx.x * (LOCAL_THREADS / 64) + (threadIdx.x >> 6);
+  int64_t unit = wave * UPW + lane / LPR;
+  const bool live = unit < n_units;
+  unit = live ? unit : n_units - 1;
+  const int64_t chunk = unit / H;
+  const int h = (int)(unit % H);
+  const int col = (lane % LPR) * VEC;
+  const int q_len = TILE ? NK : q_len_rt;
+  const int q_pos = TILE ? 0 : q_pos_rt;
+  const int64_t row = (int64_t)H * DH;
+
+  const T* kp = k + (chunk * W * H + h) * DH + col;
+  const T* vp = v + (chunk * W * H + h) * DH + col;
+  uint4_t kr[NK], vr[NK];
+#pragma unroll
+  for (int j = 0; j < NK; ++j) { kr[j] = load16(kp + j * row); vr[j] = load16(vp + j * row); }
+
+  const T* qp = q + (chunk * q_len * H + h) * DH + col;
+  T* op = out + (chunk * q_len * H + h) * DH + col;
+
+  auto one_query = [&](int i, int nvis) {
+    float qf[VEC];
+    unpack16<T>(load16(qp + i * row), qf);
+#pragma unroll
+    for (int t = 0; t < VEC; ++t) qf[t] *= scale_log2e;
+    float s[NK];
+    float mx = NEG_BIG;
+#pragma unroll
+    for (int j = 0; j < NK; ++j) {
+      if (j < nvis) {
+        float kf[VEC];
+        unpack16<T>(kr[j], kf);
+        float acc = 0.f;
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) acc = fmaf(qf[t], kf[t], acc);
+        s[j] = group_sum<LPR>(acc);
+        mx = fmaxf(mx, s[j]);
+      }
+    }
+    float l = 0.f, o[VEC];
+#pragma unroll
+    for (int t = 0; t < VEC; ++t) o[t] = 0.f;
+#pragma unroll
+    for (int j = 0; j < NK; ++j) {
+      if (j < nvis) {
+        const float p = fast_exp2(s[j] - mx);
+        l += p;
+        float vf[VEC];
+        unpack16<T>(vr[j], vf);
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) o[t] = fmaf(p, vf[t], o[t]);
+      }
+    }
+    const float inv = 1.f / l;
+#pragma unroll
+    for (int t = 0; t < VEC; ++t) o[t] *= inv;
+    if (live) Vec16<T>::store(op + i * row, o);
+  };
+
+  if (TILE) {
+#pragma unroll
+    for (int i = 0; i < NK; ++i) one_query(i, i + 1);
+  } else {
+    for (int i = 0; i < q_len; ++i) one_query(i, q_pos + i + 1);
+  }
+}
+
+template <typename T, int DH, int NK>
+static int32_t launch_local_nk(bool tile, const void* q, const void* k, const void* v, void* out, int64_t n_chunks,
+                               int W, int q_len, int q_pos, int H, float scale, hipStream_t st) {
+  using M = RowMap<T, DH>;
+  const int64_t n_units = n_chunks * H;
+  const int64_t units_per_block = (int64_t)M::RPW * (LOCAL_THREADS / 64);
+  const int64_t blocks = (n_units + units_per_block - 1) / units_per_block;
+  if (blocks > 0x7fffffffLL) return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: too many chunks for one launch");
+  if (tile)
+    hipLaunchKernelGGL((local_attn_kernel<T, DH, NK, true>), dim3((unsigned)blocks), dim3(LOCAL_THREADS), 0, st,
+                       (const T*)q, (const T*)k, (const T*)v, (T*)out, n_units, H, W, q_len, q_pos, scale * LOG2E);
+  else
+    hipLaunchKernelGGL((local_attn_kernel<T, DH, NK, false>), dim3((unsigned)blocks), dim3(LOCAL_THREADS), 0, st,
+                       (const T*)q, (const T*)k, (const T*)v, (T*)out, n_units, H, W, q_len, q_pos, scale * LOG2E);
+  return check_launch("local_attn_kernel");
+}
+
+template <typename T, int DH>
+static int32_t launch_local_dh(const void* q, const void* k, const void* v, void* out, int64_t n_chunks,
+                               int W, int q_len, int q_pos, int H, float scale, hipStream_t st) {
+  const int nk = q_pos + q_len;
+  const bool tile = (q_pos == 0);
+#define PHOTON_NK_CASE(N) \
+  case N: return launch_local_nk<T, DH, N>(tile, q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
+  switch (nk) {
+    PHOTON_NK_CASE(1) PHOTON_NK_CASE(2) PHOTON_NK_CASE(3) PHOTON_NK_CASE(4)
+    PHOTON_NK_CASE(5) PHOTON_NK_CASE(6) PHOTON_NK_CASE(7) PHOTON_NK_CASE(8)
+    PHOTON_NK_CASE(9) PHOTON_NK_CASE(10) PHOTON_NK_CASE(11) PHOTON_NK_CASE(12)
+    PHOTON_NK_CASE(13) PHOTON_NK_CASE(14) PHOTON_NK_CASE(15) PHOTON_NK_CASE(16)
+  }
+#undef PHOTON_NK_CASE
+  return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: window position %d out of range", nk);
+}
+
+int32_t launch_local_attn(bool f32, int d_h, const void* q, const void* k, const void* v, void* out,
+                          int64_t n_chunks, int W, int q_len, int q_pos, int H, float scale, hipStream_t st) {
+  if (f32) {
+    switch (d_h) {
+      case 32: return launch_local_dh<float, 32>(q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
+      case 64: return launch_local_dh<float, 64>(q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
+      case 128: return launch_local_dh<float, 128>(q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
+    }
+  } else {
+    switch (d_h) {
+      case 32: return launch_local_dh<bf16_t, 32>(q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
+      case 64: return launch_local_dh<bf16_t, 64>(q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
+      case 128: return launch_local_dh<bf16_t, 128>(q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
+    }
+  }
+  return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: d_h=%d not in {32, 64, 128}", d_h);
+}
+
+}  // namespace photon
+
+// ------------------------------------------------------------------ C ABI
+
+using namespace photon;
+
+extern "C" size_t photon_coarse_decode_attn_workspace_bytes(int32_t Bt, int32_t H, int32_t d_h, int32_t n_splits) {
+  if (Bt <= 0 || H <= 0 || d_h <= 0 || n_splits <= 1) return 0;
+  return (size_t)Bt * H * n_splits * (d_h + 2) * sizeof(float);
+}
+
+extern "C" int32_t photon_coarse_decode_attn_auto_splits(int32_t Bt, int32_t H, int64_t S_max) {
+  if (Bt <= 0 || H <= 0 || S_max <= 0) return 1;
+  return coarse_auto_splits(Bt, H, S_max);
+}
+
+extern "C" int32_t photon_coarse_decode_attn(const void* q, const void* k_cache, const void* v_cache,
+                                             const int32_t* seq_len, void* out, int32_t Bt, int32_t H, int32_t d_h,
+                                             int64_t S_max, float scale, int32_t n_splits, void* workspace,
+                                             size_t workspace_bytes, photon_dtype dt, void* stream) {
+  clear_error();
+  PHOTON_REQUIRE(valid_dtype(dt), PHOTON_ERR_UNSUPPORTED, "%s: unknown dtype %d", __func__, (int)dt);
+  PHOTON_REQUIRE(Bt > 0 && H > 0 && S_max > 0, PHOTON_ERR_INVALID_ARG, "%s: Bt=%d H=%d S_max=%lld must be positive",
+                 __func__, Bt, H, (long long)S_max);
+  PHOTON_REQUIRE((int64_t)Bt * H <= 65535, PHOTON_ERR_UNSUPPORTED, "%s: Bt*H=%lld exceeds 65535 streams per launch",
+                 __func__, (long long)Bt * H);
+  PHOTON_REQUIRE(d_h == 32 || d_h == 64 || d_h == 128, PHOTON_ERR_UNSUPPORTED, "%s: d_h=%d not in {32, 64, 128}", __func__, d_h);
+  PHOTON_REQUIRE(n_splits >= 0 && n_splits <= 1024, PHOTON_ERR_INVALID_ARG, "%s: n_splits=%d out of [0, 1024]", __func__, n_splits);
+  PHOTON_REQUIRE_PTR(q);
+  PHOTON_REQUIRE_PTR(k_cache);
+  PHOTON_REQUIRE_PTR(v_cache);
+  PHOTON_REQUIRE_PTR(out);
+  PHOTON_REQUIRE(seq_len != nullptr, PHOTON_ERR_INVALID_ARG, "%s: seq_len is null", __func__);
+  if (n_splits == 0) n_splits = coarse_auto_splits(Bt, H, S_max);
+  if (n_splits > 1) {
+    const size_t need = photon_coarse_decode_attn_workspace_bytes(Bt, H, d_h, n_splits);
+    PHOTON_REQUIRE(workspace != nullptr && aligned16(workspace) && workspace_bytes >= need, PHOTON_ERR_WORKSPACE,
+                   "%s: n_splits=%d needs a 16-byte aligned workspace of %zu bytes (got %zu)", __func__, n_splits, need,
+                   workspace_bytes);
+  }
+  return launch_coarse_attn(dt == PHOTON_F32 ? KV_F32 : KV_BF16, dt == PHOTON_F32, d_h, q, k_cache, v_cache, seq_len, out,
+                            Bt, H, S_max, scale, n_splits, workspace, (hipStream_t)stream);
+}
+
+extern "C" int32_t photon_chunk_local_attn(const void* q, const void* k, const void* v, void* out, int64_t n_chunks,
+                                           int32_t W, int32_t q_len, int32_t q_pos, int32_t H, int32_t d_h, float scale,
+                                           photon_dtype dt, void* stream) {
+  clear_error();
+  PHOTON_REQUIRE(valid_dtype(dt), PHOTON_ERR_UNSUPPORTED, "%s: unknown dtype %d", __func__, (int)dt);
+  PHOTON_REQUIRE(n_chunks >= 0 && H > 0, PHOTON_ERR_INVALID_ARG, "%s: n_chunks=%lld H=%d invalid", __func__,
+                 (long long)n_chunks, H);
+  PHOTON_REQUIRE(W >= 1 && W <= PHOTON_MAX_WINDOW, PHOTON_ERR_UNSUPPORTED, "%s: W=%d not in [1, %d]", __func__, W,
+                 (int)PHOTON_MAX_WINDOW);
+  PHOTON_REQUIRE(q_len >= 1 && q_pos >= 0 && q_pos + q_len <= W, PHOTON_ERR_INVALID_ARG,
+                 "%s: queries [%d, %d) do not fit the window W=%d", __func__, q_pos, q_pos + q_len, W);
+  PHOTON_REQUIRE(d_h == 32 || d_h == 64 || d_h == 128, PHOTON_ERR_UNSUPPORTED, "%s: d_h=%d not in {32, 64, 128}", __func__, d_h);
+  if (n_chunks == 0) return PHOTON_OK;
+  PHOTON_REQUIRE_PTR(q);
+  PHOTON_REQUIRE_PTR(k);
+  PHOTON_REQUIRE_PTR(v);
+  PHOTON_REQUIRE_PTR(out);
+  return launch_local_attn(dt == PHOTON_F32, d_h, q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, (hipStream_t)stream);
+}

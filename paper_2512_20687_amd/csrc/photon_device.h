@@ -1,0 +1,98 @@
+// Device-side helpers shared by the gfx950 kernels: 128-bit vector access,
+// bf16 <-> fp32 conversion, DPP lane-group reductions for 64-wide wavefronts.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace photon {
+
+typedef uint16_t bf16_t;          // raw bfloat16 bits
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// fp32 -> bf16, round to nearest even (NaN kept quiet).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// One 16-byte chunk of a row as VEC fp32 values (VEC = 4 for fp32 storage, 8 for bf16).
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int VEC = 4;
+  __device__ static __forceinline__ void load(const float* p, float (&v)[4]) {
+    float4_t r = *reinterpret_cast<const float4_t*>(p);
+    v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+  }
+  __device__ static __forceinline__ void zero(float (&v)[4]) { v[0] = v[1] = v[2] = v[3] = 0.f; }
+  __device__ static __forceinline__ void store(float* p, const float (&v)[4]) {
+    float4_t r; r.x = v[0]; r.y = v[1]; r.z = v[2]; r.w = v[3];
+    *reinterpret_cast<float4_t*>(p) = r;
+  }
+};
+template <> struct Vec16<bf16_t> {
+  static constexpr int VEC = 8;
+  __device__ static __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
+    uint4_t r = *reinterpret_cast<const uint4_t*>(p);
+    v[0] = bf16_lo(r.x); v[1] = bf16_hi(r.x); v[2] = bf16_lo(r.y); v[3] = bf16_hi(r.y);
+    v[4] = bf16_lo(r.z); v[5] = bf16_hi(r.z); v[6] = bf16_lo(r.w); v[7] = bf16_hi(r.w);
+  }
+  __device__ static __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
+    uint4_t r;
+    r.x = pack_bf16x2(v[0], v[1]); r.y = pack_bf16x2(v[2], v[3]);
+    r.z = pack_bf16x2(v[4], v[5]); r.w = pack_bf16x2(v[6], v[7]);
+    *reinterpret_cast<uint4_t*>(p) = r;
+  }
+};
+
+// Raw 16-byte load kept as bits (conversion deferred so many loads stay in flight).
+__device__ __forceinline__ uint4_t load16(const void* p) { return *reinterpret_cast<const uint4_t*>(p); }
+template <typename T> __device__ __forceinline__ void unpack16(const uint4_t& r, float* v);
+template <> __device__ __forceinline__ void unpack16<float>(const uint4_t& r, float* v) {
+  v[0] = __uint_as_float(r.x); v[1] = __uint_as_float(r.y); v[2] = __uint_as_float(r.z); v[3] = __uint_as_float(r.w);
+}
+template <> __device__ __forceinline__ void unpack16<bf16_t>(const uint4_t& r, float* v) {
+  v[0] = bf16_lo(r.x); v[1] = bf16_hi(r.x); v[2] = bf16_lo(r.y); v[3] = bf16_hi(r.y);
+  v[4] = bf16_lo(r.z); v[5] = bf16_hi(r.z); v[6] = bf16_lo(r.w); v[7] = bf16_hi(r.w);
+}
+
+template <typename T> __device__ __forceinline__ float to_f32(T x);
+template <> __device__ __forceinline__ float to_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t x) { return __uint_as_float(uint32_t(x) << 16); }
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return bf16_t(f32_to_bf16_bits(x)); }
+
+// ---- cross-lane moves on the data-parallel-primitive path (no LDS traffic) ----
+template <int CTRL> __device__ __forceinline__ float dpp(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+constexpr int DPP_XOR1 = 0xB1;          // quad_perm [1,0,3,2]
+constexpr int DPP_XOR2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141;  // lane i <-> 7-i inside each 8 lanes
+constexpr int DPP_MIRROR = 0x140;       // lane i <-> 15-i inside each 16 lanes
+
+// Sum over aligned groups of G consecutive lanes (G = 1, 2, 4, 8, 16, 32); every lane gets the total.
+template <int G> __device__ __forceinline__ float group_sum(float x) {
+  if (G >= 2) x += dpp<DPP_XOR1>(x);
+  if (G >= 4) x += dpp<DPP_XOR2>(x);
+  if (G >= 8) x += dpp<DPP_HALF_MIRROR>(x);
+  if (G >= 16) x += dpp<DPP_MIRROR>(x);
+  if (G >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float NEG_BIG = -1.0e30f;     // finite stand-in for -inf as running maximum
+
+}  // namespace photon

@@ -1,0 +1,33 @@
+// Host-side helpers of the C ABI: status/error reporting and argument checks.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "../../include/photon.h"
+
+namespace photon {
+
+char* error_buffer();                       // thread-local, 512 bytes
+int32_t fail(int32_t code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t dtype_size(photon_dtype dt) { return dt == PHOTON_BF16 ? 2 : 4; }
+inline bool valid_dtype(photon_dtype dt) { return dt == PHOTON_F32 || dt == PHOTON_BF16; }
+
+// Report a launch failure of the kernel just enqueued (does not synchronise).
+inline int32_t check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PHOTON_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return PHOTON_OK;
+}
+
+#define PHOTON_REQUIRE(cond, code, ...) \
+  do { if (!(cond)) return ::photon::fail((code), __VA_ARGS__); } while (0)
+#define PHOTON_REQUIRE_PTR(p) \
+  PHOTON_REQUIRE((p) != nullptr && ::photon::aligned16(p), PHOTON_ERR_INVALID_ARG, \
+                 "%s: %s must be a non-null, 16-byte aligned device pointer", __func__, #p)
+
+}  // namespace photon

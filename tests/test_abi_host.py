@@ -1,0 +1,58 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol
+the public header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "photon.h")).read()
+    return sorted(set(re.findall(r"PHOTON_API\s+[\w\s\*]+?\b(photon_\w+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2512_20687_amd as ph
+    if not os.path.exists(ph.lib_path()):
+        from paper_2512_20687_amd import build
+        build.build(verbose=False)
+    return ph.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert len(names) >= 7
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in photon.h but not exported"
+
+
+def test_version_and_error_string(lib):
+    assert lib.photon_version() >= 100
+    assert lib.photon_last_error() == b""
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    p = ctypes.c_void_p(4096)        # aligned fake address; never dereferenced because validation fails first
+    bad = ctypes.c_void_p(4100)
+    # unsupported head size
+    assert lib.photon_coarse_decode_attn(p, p, p, p, p, 1, 2, 48, 16, 0.1, 1, None, 0, 0, None) == -2
+    assert b"d_h=48" in lib.photon_last_error()
+    # null and misaligned pointers
+    assert lib.photon_coarse_decode_attn(None, p, p, p, p, 1, 2, 64, 16, 0.1, 1, None, 0, 0, None) == -1
+    assert lib.photon_coarse_decode_attn(bad, p, p, p, p, 1, 2, 64, 16, 0.1, 1, None, 0, 0, None) == -1
+    # missing workspace for a split launch
+    assert lib.photon_coarse_decode_attn(p, p, p, p, p, 1, 2, 64, 4096, 0.1, 4, None, 0, 0, None) == -3
+    assert lib.photon_coarse_decode_attn(p, p, p, p, p, 0, 2, 64, 16, 0.1, 1, None, 0, 0, None) == -1
+    assert lib.photon_coarse_decode_attn(p, p, p, p, p, 1, 2, 64, 16, 0.1, 1, None, 0, 7, None) == -2
+    # window and query range
+    assert lib.photon_chunk_local_attn(p, p, p, p, 4, 17, 1, 0, 2, 64, 0.1, 1, None) == -2
+    assert lib.photon_chunk_local_attn(p, p, p, p, 4, 4, 2, 3, 2, 64, 0.1, 1, None) == -1
+    assert lib.photon_chunk_local_attn(p, p, p, p, 4, 4, 4, 0, 2, 48, 0.1, 1, None) == -2
+    assert lib.photon_chunk_local_attn(None, p, p, p, 4, 4, 4, 0, 2, 64, 0.1, 1, None) == -1
+    # workspace size formula
+    assert lib.photon_coarse_decode_attn_workspace_bytes(4, 32, 64, 8) == 4 * 32 * 8 * 66 * 4
+    assert lib.photon_coarse_decode_attn_workspace_bytes(4, 32, 64, 1) == 0
