@@ -118,6 +118,91 @@ PHOTON_API int32_t photon_chunk_local_attn(const void* q, const void* k, const v
                                 int64_t n_chunks, int32_t W, int32_t q_len, int32_t q_pos,
                                 int32_t H, int32_t d_h, float scale, photon_dtype dt, void* stream);
 
+
+/* --------------------------------------------------------------------------
+ * One recursive-generation step g -> g+1 for Bt sequences (paper Section
+ * 2.3.3 steps (i)-(iii); Appendix A, Definition 2):
+ *   (i)  top-down: the level-L local decoder expands X^(L)_g into C_L new
+ *        level-(L-1) units; every lower level l decodes one chunk per new
+ *        level-l unit, all chunks of a level batched, each chunk conditioned on
+ *        the previous level-l unit (the carry for the first one); level 1 emits
+ *        the prod(C) tokens of the next meta-context (greedy argmax, lowest
+ *        index on ties, or the caller's forced tokens) and feeds back their
+ *        decoder-side embeddings;
+ *   (ii) the top chunker (Eq. 4) folds the C_L new level-(L-1) units into A-hat;
+ *   (iii) STEP (Eq. 13): every layer of the top encoder appends one K/V entry
+ *        and attends over the whole coarse cache; X^(L)_{g+1} is stored.
+ * Block structure: pre-RMSNorm LLaMA blocks (rotary positions local to each
+ * module, SwiGLU feed-forward unless d_ff == 0), one final RMSNorm per module.
+ *
+ * Host structs below hold DEVICE pointers.  Matrices/tables are `dt`; gains,
+ * biases and all state vectors are fp32.
+ * -------------------------------------------------------------------------- */
+typedef struct photon_config {
+  int32_t L;                     /* levels, 1..PHOTON_MAX_LEVELS */
+  int32_t C[PHOTON_MAX_LEVELS];  /* C[l-1] = C_l >= 1 */
+  int32_t R[PHOTON_MAX_LEVELS];  /* R[l-1] = R_l >= 1;  R_l + C_l - 1 <= PHOTON_MAX_WINDOW */
+  int32_t D, H, d_h;             /* D == H * d_h */
+  int32_t n_layers;              /* blocks per module */
+  int32_t d_ff;                  /* SwiGLU width, 0 = attention-only blocks */
+  int32_t vocab;
+  photon_dtype dt;               /* storage of matrices, tables and the coarse K/V cache */
+  float rms_eps;
+  float rope_theta;              /* 0 disables the rotary encoding */
+} photon_config;
+
+typedef struct photon_layer_weights {
+  const float* g1;   /* [D]      pre-attention norm gain */
+  const void* wqkv;  /* [3D, D]  rows: Wq, then Wk, then Wv */
+  const void* wo;    /* [D, D] */
+  const float* g2;   /* [D]      pre-MLP norm gain       (d_ff > 0) */
+  const void* wgu;   /* [2F, D]  rows: Wgate, then Wup   (d_ff > 0) */
+  const void* wd;    /* [D, F]                           (d_ff > 0) */
+} photon_layer_weights;
+
+typedef struct photon_module_weights {
+  const photon_layer_weights* layers; /* HOST array of n_layers entries */
+  const float* g_final;               /* [D] */
+} photon_module_weights;
+
+typedef struct photon_weights {
+  const void* E_dec;        /* [vocab, D] decoder-side token embedding */
+  const void* W_lm;         /* [vocab, D] vocabulary projection */
+  const void* chunker_w;    /* [D, C_L*D] top-level chunker */
+  const float* chunker_b;   /* [D] or NULL */
+  photon_module_weights top;                      /* top-level context encoder F^(L) */
+  const void* conv_w[PHOTON_MAX_LEVELS];          /* conv_w[l-1]: [R_l*D, D] converter of level l */
+  const float* conv_b[PHOTON_MAX_LEVELS];         /* conv_b[l-1]: [R_l*D] */
+  photon_module_weights dec[PHOTON_MAX_LEVELS];   /* dec[l-1]: local decoder G^(l) */
+} photon_weights;
+
+typedef struct photon_state {
+  void* k_cache;        /* [n_layers, Bt, H, S_max, d_h] dt : KV^(L) */
+  void* v_cache;
+  int32_t* seq_len;     /* [Bt] entries cached per sequence; the step adds 1.  Must be < S_max on entry. */
+  float* x_top;         /* [Bt, D]       X^(L)_g, replaced by X^(L)_{g+1} */
+  float* carry;         /* [L-1, Bt, D]  carry[l-1] = last reconstructed level-l unit, updated */
+  int64_t S_max;
+  void* workspace;      /* photon_decode_step_workspace_bytes(); contents need no initialisation */
+  size_t workspace_bytes;
+} photon_state;
+
+/* Optional outputs for inspection (each pointer may be NULL). */
+typedef struct photon_trace {
+  float* logits;                        /* [Bt, prod(C), vocab] */
+  float* new_units[PHOTON_MAX_LEVELS];  /* new_units[l]: [Bt, C_L*...*C_{l+1}, D] new level-l units, l = 0..L-1 */
+  float* a_hat;                         /* [Bt, D] chunker output */
+} photon_trace;
+
+PHOTON_API size_t photon_decode_step_workspace_bytes(const photon_config* cfg, int32_t Bt, int64_t S_max);
+
+/* forced_tokens: device int32 [Bt, prod(C)] or NULL; out_tokens: device int32
+ * [Bt, prod(C)].  cfg, w, st and trace are host structs, read during the call
+ * only.  All work is enqueued on `stream`; tokens stay on the device. */
+PHOTON_API int32_t photon_decode_step(const photon_config* cfg, const photon_weights* w, const photon_state* st,
+                                      int32_t Bt, const int32_t* forced_tokens, int32_t* out_tokens,
+                                      const photon_trace* trace, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

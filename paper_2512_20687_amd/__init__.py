@@ -9,6 +9,8 @@ raises.
 """
 from .binding import (  # noqa: F401
     PhotonError,
+    PhotonModel,
+    PhotonState,
     lib_path,
     load_library,
     photon_chunk_local_attn,
@@ -16,6 +18,8 @@ from .binding import (  # noqa: F401
     photon_coarse_decode_attn,
     photon_coarse_decode_attn_auto_splits,
     photon_coarse_decode_attn_workspace_bytes,
+    photon_decode_step,
+    photon_decode_step_workspace_bytes,
     photon_last_error,
     photon_version,
 )

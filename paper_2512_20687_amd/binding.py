@@ -127,3 +127,188 @@ def photon_chunk_local_attn(q, k, v, out, q_pos: int = 0, scale: Optional[float]
     _check(lib.photon_chunk_local_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), n_chunks, W, q_len, q_pos, H, d_h, scale,
                                        _dt(k), _stream()))
     return out
+
+
+# --------------------------------------------------------------------------
+# photon_decode_step: host structs of device pointers (mirrors include/photon.h)
+# --------------------------------------------------------------------------
+MAX_LEVELS = 4
+
+
+class _Config(C.Structure):
+    _fields_ = [("L", C.c_int32), ("C", C.c_int32 * MAX_LEVELS), ("R", C.c_int32 * MAX_LEVELS),
+                ("D", C.c_int32), ("H", C.c_int32), ("d_h", C.c_int32), ("n_layers", C.c_int32),
+                ("d_ff", C.c_int32), ("vocab", C.c_int32), ("dt", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class _Layer(C.Structure):
+    _fields_ = [("g1", C.c_void_p), ("wqkv", C.c_void_p), ("wo", C.c_void_p),
+                ("g2", C.c_void_p), ("wgu", C.c_void_p), ("wd", C.c_void_p)]
+
+
+class _Module(C.Structure):
+    _fields_ = [("layers", C.POINTER(_Layer)), ("g_final", C.c_void_p)]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("E_dec", C.c_void_p), ("W_lm", C.c_void_p), ("chunker_w", C.c_void_p), ("chunker_b", C.c_void_p),
+                ("top", _Module), ("conv_w", C.c_void_p * MAX_LEVELS), ("conv_b", C.c_void_p * MAX_LEVELS),
+                ("dec", _Module * MAX_LEVELS)]
+
+
+class _State(C.Structure):
+    _fields_ = [("k_cache", C.c_void_p), ("v_cache", C.c_void_p), ("seq_len", C.c_void_p), ("x_top", C.c_void_p),
+                ("carry", C.c_void_p), ("S_max", C.c_int64), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+class _Trace(C.Structure):
+    _fields_ = [("logits", C.c_void_p), ("new_units", C.c_void_p * MAX_LEVELS), ("a_hat", C.c_void_p)]
+
+
+def _register_step(lib):
+    if getattr(lib, "_photon_step_registered", False):
+        return
+    lib.photon_decode_step_workspace_bytes.restype = C.c_size_t
+    lib.photon_decode_step_workspace_bytes.argtypes = [C.POINTER(_Config), C.c_int32, C.c_int64]
+    lib.photon_decode_step.restype = C.c_int32
+    lib.photon_decode_step.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(_State), C.c_int32,
+                                       C.c_void_p, C.c_void_p, C.POINTER(_Trace), C.c_void_p]
+    lib._photon_step_registered = True
+
+
+def _c_config(cfg) -> _Config:
+    c = _Config()
+    c.L = cfg.L
+    for i in range(cfg.L):
+        c.C[i], c.R[i] = cfg.C[i], cfg.R[i]
+    c.D, c.H, c.d_h, c.n_layers, c.d_ff, c.vocab = cfg.D, cfg.H, cfg.d_h, cfg.n_layers, cfg.d_ff, cfg.vocab
+    c.dt = PHOTON_BF16 if cfg.dtype == "bf16" else PHOTON_F32
+    c.rms_eps, c.rope_theta = cfg.rms_eps, cfg.rope_theta
+    return c
+
+
+class PhotonModel:
+    """Device copies of the decode-time parameters plus the host structs that
+    point at them.  `weights` is the nested dict of seeded_inputs.make_weights
+    (numpy float32 arrays, or torch tensors already on the device)."""
+
+    def __init__(self, cfg, weights, device="cuda"):
+        self.cfg = cfg
+        self.device = torch.device(device)
+        self.mat_dtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        self._keep = []
+        self.c_cfg = _c_config(cfg)
+        w = _Weights()
+        w.E_dec = self._mat(weights["E_dec"])
+        w.W_lm = self._mat(weights["W_lm"])
+        top = weights["enc"][cfg.L - 1]
+        w.chunker_w = self._mat(top["chunker"]["w"])
+        w.chunker_b = self._vec(top["chunker"]["b"]) if "b" in top["chunker"] else None
+        self._fill_module(w.top, top["module"])
+        for l in range(cfg.L):
+            d = weights["dec"][l]
+            w.conv_w[l] = self._mat(d["converter"]["w"])
+            w.conv_b[l] = self._vec(d["converter"]["b"])
+            self._fill_module(w.dec[l], d["module"])
+        self.c_weights = w
+
+    def _dev(self, a, dtype):
+        t = a if isinstance(a, torch.Tensor) else torch.from_numpy(a)
+        t = t.to(device=self.device, dtype=dtype).contiguous()
+        self._keep.append(t)
+        return t
+
+    def _mat(self, a):
+        return self._dev(a, self.mat_dtype).data_ptr()
+
+    def _vec(self, a):
+        return self._dev(a, torch.float32).data_ptr()
+
+    def _cat(self, parts, dtype):
+        ts = [p if isinstance(p, torch.Tensor) else torch.from_numpy(p) for p in parts]
+        t = torch.cat([x.to(device=self.device, dtype=dtype) for x in ts], dim=0).contiguous()
+        self._keep.append(t)
+        return t.data_ptr()
+
+    def _fill_module(self, m: _Module, mod):
+        n = len(mod["layers"])
+        arr = (_Layer * n)()
+        for i, lay in enumerate(mod["layers"]):
+            arr[i].g1 = self._vec(lay["g1"])
+            arr[i].wqkv = self._cat([lay["wq"], lay["wk"], lay["wv"]], self.mat_dtype)
+            arr[i].wo = self._mat(lay["wo"])
+            if self.cfg.d_ff > 0:
+                arr[i].g2 = self._vec(lay["g2"])
+                arr[i].wgu = self._cat([lay["wg"], lay["wu"]], self.mat_dtype)
+                arr[i].wd = self._mat(lay["wd"])
+        self._keep.append(arr)
+        m.layers = C.cast(arr, C.POINTER(_Layer))
+        m.g_final = self._vec(mod["g_final"])
+
+
+class PhotonState:
+    """Decode state on the device: coarse K/V cache, per-sequence lengths, top
+    state, carries, and the step's workspace."""
+
+    def __init__(self, model: PhotonModel, Bt: int, S_max: int, k=None, v=None, seq_len=None, x_top=None, carry=None):
+        cfg, dev = model.cfg, model.device
+        lib = load_library()
+        _register_step(lib)
+        self.model, self.Bt, self.S_max = model, Bt, S_max
+        shape = (cfg.n_layers, Bt, cfg.H, S_max, cfg.d_h)
+
+        def put(a, dtype, shp):
+            if a is None:
+                return torch.zeros(shp, dtype=dtype, device=dev)
+            t = a if isinstance(a, torch.Tensor) else torch.from_numpy(np_contig(a))
+            t = t.to(device=dev, dtype=dtype).contiguous()
+            assert tuple(t.shape) == tuple(shp), (t.shape, shp)
+            return t
+
+        self.k = put(k, model.mat_dtype, shape)
+        self.v = put(v, model.mat_dtype, shape)
+        self.seq_len = put(seq_len, torch.int32, (Bt,))
+        self.x_top = put(x_top, torch.float32, (Bt, cfg.D))
+        self.carry = put(carry, torch.float32, (max(cfg.L - 1, 0), Bt, cfg.D))
+        nbytes = lib.photon_decode_step_workspace_bytes(C.byref(model.c_cfg), Bt, S_max)
+        if nbytes == 0:
+            raise PhotonError(-1, lib.photon_last_error().decode())
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        s = _State()
+        s.k_cache, s.v_cache, s.seq_len = self.k.data_ptr(), self.v.data_ptr(), self.seq_len.data_ptr()
+        s.x_top = self.x_top.data_ptr()
+        s.carry = self.carry.data_ptr() if cfg.L > 1 else None
+        s.S_max, s.workspace, s.workspace_bytes = S_max, self.workspace.data_ptr(), nbytes
+        self.c_state = s
+
+
+def np_contig(a):
+    import numpy as np
+    return np.ascontiguousarray(a)
+
+
+def photon_decode_step_workspace_bytes(cfg, Bt: int, S_max: int) -> int:
+    lib = load_library()
+    _register_step(lib)
+    return lib.photon_decode_step_workspace_bytes(C.byref(_c_config(cfg)), Bt, S_max)
+
+
+def photon_decode_step(model: PhotonModel, state: PhotonState, out_tokens: torch.Tensor,
+                       forced_tokens: Optional[torch.Tensor] = None, trace: Optional[dict] = None):
+    """One recursive-generation step.  out_tokens int32 [Bt, prod(C)] on the device.
+    trace: optional dict of preallocated fp32 device tensors: "logits" [Bt, prod(C), vocab],
+    "new_units" (list over l = 0..L-1), "a_hat" [Bt, D]."""
+    lib = load_library()
+    _register_step(lib)
+    tr = None
+    if trace is not None:
+        tr = _Trace()
+        tr.logits = _ptr(trace.get("logits"))
+        tr.a_hat = _ptr(trace.get("a_hat"))
+        for l, t in enumerate(trace.get("new_units", [])):
+            tr.new_units[l] = _ptr(t)
+    _check(lib.photon_decode_step(C.byref(model.c_cfg), C.byref(model.c_weights), C.byref(state.c_state), state.Bt,
+                                  _ptr(forced_tokens), _ptr(out_tokens), C.byref(tr) if tr is not None else None,
+                                  _stream()))
+    return out_tokens

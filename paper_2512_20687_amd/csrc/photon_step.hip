@@ -1,0 +1,506 @@
+// photon_decode_step: one recursive-generation step (paper Section 2.3.3,
+// Appendix A Definition 2) composed from the attention and linear kernels plus
+// the small element-wise kernels below.  Everything is enqueued on one stream;
+// sequence lengths and tokens stay in device memory, so the enqueue pattern does
+// not depend on data and the whole step can be captured in a HIP graph.
+#include "photon_attn.h"
+#include "photon_device.h"
+#include "photon_host.h"
+#include "photon_linear.h"
+
+namespace photon {
+
+// ------------------------------------------------------------------ small kernels
+
+// out[i*out_mul + out_off] (and out2[i]) = rmsnorm(in[i*in_mul + in_off]) * g ; rows of D floats.
+__global__ __launch_bounds__(256) void rmsnorm_rows_kernel(const float* __restrict__ in, int in_mul, int in_off,
+                                                           const float* __restrict__ g, float eps, float* out,
+                                                           int out_mul, int out_off, float* out2, int D) {
+  const int i = blockIdx.x, tid = threadIdx.x;
+  const float* x = in + ((int64_t)i * in_mul + in_off) * D;
+  float ss = 0.f;
+  for (int d = tid; d < D; d += 256) { const float v = x[d]; ss = fmaf(v, v, ss); }
+  ss = group_sum<32>(ss);
+  ss += __shfl_xor(ss, 32);
+  __shared__ float part[4];
+  if ((tid & 63) == 0) part[tid >> 6] = ss;
+  __syncthreads();
+  const float tot = (part[0] + part[1]) + (part[2] + part[3]);
+  const float r = 1.0f / sqrtf(tot / (float)D + eps);
+  float* o = out + ((int64_t)i * out_mul + out_off) * D;
+  for (int d = tid; d < D; d += 256) {
+    const float v = x[d] * r * g[d];
+    o[d] = v;
+    if (out2 != nullptr) out2[(int64_t)i * D + d] = v;
+  }
+}
+
+__device__ __forceinline__ void rope_angle(int pos, int i, int d_h, float theta, float& c, float& s) {
+  if (theta == 0.f) { c = 1.f; s = 0.f; return; }
+  const double inv_freq = exp2(-2.0 * (double)i / (double)d_h * log2((double)theta));
+  double sd, cd;
+  sincos((double)pos * inv_freq, &sd, &cd);
+  c = (float)cd; s = (float)sd;
+}
+
+// Local decoder: rotate q and k of every row at its window position, write q to
+// qrot [rows, D] and k, v into the chunk's local cache [n_chunks, W, H, d_h] (fp32).
+__global__ __launch_bounds__(256) void rope_append_local_kernel(const float* __restrict__ qkv, float* __restrict__ qrot,
+                                                                float* __restrict__ lk, float* __restrict__ lv,
+                                                                int rows, int q_len, int q_pos, int W, int H, int d_h,
+                                                                float theta) {
+  const int half = d_h >> 1, D = H * d_h;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)rows * H * half) return;
+  const int i = (int)(idx % half);
+  const int h = (int)((idx / half) % H);
+  const int row = (int)(idx / ((int64_t)half * H));
+  const int chunk = row / q_len, pos = q_pos + row % q_len;
+  float c, s;
+  rope_angle(pos, i, d_h, theta, c, s);
+  const float* src = qkv + (int64_t)row * 3 * D + h * d_h;
+  const float qa = src[i], qb = src[i + half];
+  const float ka = src[D + i], kb = src[D + i + half];
+  float* qd = qrot + (int64_t)row * D + h * d_h;
+  qd[i] = qa * c - qb * s;
+  qd[i + half] = qb * c + qa * s;
+  const int64_t slot = (((int64_t)chunk * W + pos) * H + h) * d_h;
+  lk[slot + i] = ka * c - kb * s;
+  lk[slot + i + half] = kb * c + ka * s;
+  lv[slot + i] = src[2 * D + i];
+  lv[slot + i + half] = src[2 * D + i + half];
+}
+
+// Top-level STEP: position of sequence b is seq_len[b]-1 (the count already includes the new entry);
+// k, v go to cache[b, h, pos, :] of this layer.
+template <typename TKV>
+__global__ __launch_bounds__(256) void rope_append_coarse_kernel(const float* __restrict__ qkv, float* __restrict__ qrot,
+                                                                 TKV* __restrict__ kc, TKV* __restrict__ vc,
+                                                                 const int32_t* __restrict__ seq_len, int Bt, int H,
+                                                                 int d_h, int64_t S_max, float theta) {
+  const int half = d_h >> 1, D = H * d_h;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)Bt * H * half) return;
+  const int i = (int)(idx % half);
+  const int h = (int)((idx / half) % H);
+  const int b = (int)(idx / ((int64_t)half * H));
+  const int pos = seq_len[b] - 1;
+  float c, s;
+  rope_angle(pos, i, d_h, theta, c, s);
+  const float* src = qkv + (int64_t)b * 3 * D + h * d_h;
+  const float qa = src[i], qb = src[i + half];
+  const float ka = src[D + i], kb = src[D + i + half];
+  float* qd = qrot + (int64_t)b * D + h * d_h;
+  qd[i] = qa * c - qb * s;
+  qd[i + half] = qb * c + qa * s;
+  if (pos < 0 || pos >= S_max) return;                        // full cache: nothing is written out of bounds
+  const int64_t slot = (((int64_t)b * H + h) * S_max + pos) * d_h;
+  kc[slot + i] = from_f32<TKV>(ka * c - kb * s);
+  kc[slot + i + half] = from_f32<TKV>(kb * c + ka * s);
+  vc[slot + i] = from_f32<TKV>(src[2 * D + i]);
+  vc[slot + i + half] = from_f32<TKV>(src[2 * D + i + half]);
+}
+
+// act[r, f] = silu(gu[r, f]) * gu[r, F + f]
+__global__ __launch_bounds__(256) void silu_mul_kernel(const float* __restrict__ gu, float* __restrict__ act, int64_t total, int F) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int64_t r = idx / F;
+  const int f = (int)(idx % F);
+  const float g = gu[r * 2 * F + f], u = gu[r * 2 * F + F + f];
+  act[idx] = g / (1.0f + __expf(-g)) * u;
+}
+
+// Token choice for one row of logits (greedy, lowest index on ties, or the forced token), then the
+// decoder-side embedding of that token as the next input row.
+template <typename TE>
+__global__ __launch_bounds__(256) void choose_token_kernel(const float* __restrict__ logits, int64_t ld_logits, int vocab,
+                                                           const int32_t* __restrict__ forced, int32_t* __restrict__ tokens,
+                                                           int tok_mul, int tok_off, const TE* __restrict__ E,
+                                                           float* __restrict__ x_next, int D) {
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const float* lg = logits + (int64_t)row * ld_logits;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int t = tid; t < vocab; t += 256) {
+    const float v = lg[t];
+    if (v > best || bi == 0x7fffffff) { best = v; bi = t; }
+  }
+#pragma unroll
+  for (int mask = 1; mask < 64; mask <<= 1) {
+    const float ov = __shfl_xor(best, mask);
+    const int oi = __shfl_xor(bi, mask);
+    if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+  }
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  __shared__ int chosen;
+  if ((tid & 63) == 0) { sv[tid >> 6] = best; si[tid >> 6] = bi; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
+    const int64_t flat = (int64_t)row * tok_mul + tok_off;
+    if (forced != nullptr) bi = forced[flat];
+    bi = bi < 0 ? 0 : (bi >= vocab ? vocab - 1 : bi);
+    tokens[flat] = bi;
+    chosen = bi;
+  }
+  __syncthreads();
+  if (x_next != nullptr) {
+    const TE* e = E + (int64_t)chosen * D;
+    for (int d = tid; d < D; d += 256) x_next[(int64_t)row * D + d] = to_f32<TE>(e[d]);
+  }
+}
+
+// Conditioning of the next lower level: sequence b's chunks hang off [carry[b], new[b,0], ..., new[b,n-2]];
+// new[b,n-1] becomes the carry.
+__global__ __launch_bounds__(256) void shift_condition_kernel(const float* __restrict__ fresh, float* __restrict__ carry,
+                                                              float* __restrict__ cond, int Bt, int n, int D) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)Bt * n * D) return;
+  const int d = (int)(idx % D);
+  const int i = (int)((idx / D) % n);
+  const int b = (int)(idx / ((int64_t)D * n));
+  cond[idx] = (i == 0) ? carry[(int64_t)b * D + d] : fresh[((int64_t)b * n + i - 1) * D + d];
+}
+__global__ __launch_bounds__(256) void update_carry_kernel(const float* __restrict__ fresh, float* __restrict__ carry, int Bt, int n, int D) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)Bt * D) return;
+  const int d = (int)(idx % D), b = (int)(idx / D);
+  carry[idx] = fresh[((int64_t)b * n + n - 1) * D + d];
+}
+
+// Start of a step: clear the split-K arrival counters and count the entry this step will append.
+__global__ __launch_bounds__(256) void step_begin_kernel(int* __restrict__ counters, int n_counters, int32_t* __restrict__ seq_len, int Bt) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx < n_counters) counters[idx] = 0;
+  if (idx < Bt) seq_len[idx] += 1;
+}
+
+__global__ __launch_bounds__(256) void copy_f32_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx < n) dst[idx] = src[idx];
+}
+
+static inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
+
+// ------------------------------------------------------------------ workspace plan
+
+struct Plan {
+  int L = 0;
+  int64_t chunks[PHOTON_MAX_LEVELS + 1] = {0};   // chunks[l], l = 1..L: chunks decoded per step at level l
+  int64_t rows_max = 0;
+  int n_splits = 1;
+  size_t lin_ws = 0, lin_ws_bytes = 0, coarse_ws = 0, coarse_ws_bytes = 0;
+  size_t h = 0, xn = 0, attn = 0, qkv = 0, qrot = 0, gu = 0, act = 0, cond = 0, logits = 0, a_hat = 0;
+  size_t fresh[PHOTON_MAX_LEVELS] = {0};         // fresh[l]: new level-l units, l = 0..L-1
+  size_t lk[PHOTON_MAX_LEVELS] = {0}, lv[PHOTON_MAX_LEVELS] = {0};   // local caches of level l (index l-1), all layers
+  size_t total = 0;
+};
+
+static size_t bump(size_t& cur, size_t bytes) {
+  const size_t at = cur;
+  cur += (bytes + 255) / 256 * 256;
+  return at;
+}
+
+static Plan make_plan(const photon_config& c, int Bt, int64_t S_max) {
+  Plan p;
+  p.L = c.L;
+  p.chunks[c.L] = Bt;
+  for (int l = c.L - 1; l >= 1; --l) p.chunks[l] = p.chunks[l + 1] * c.C[l];
+  for (int l = 1; l <= c.L; ++l) {
+    const int64_t r = p.chunks[l] * c.R[l - 1];
+    if (r > p.rows_max) p.rows_max = r;
+  }
+  const int64_t D = c.D, F = c.d_ff;
+  int64_t maxN = 3 * D;
+  if (2 * F > maxN) maxN = 2 * F;
+  if (c.vocab > maxN) maxN = c.vocab;
+  for (int l = 0; l < c.L; ++l)
+    if ((int64_t)c.R[l] * D > maxN) maxN = (int64_t)c.R[l] * D;
+  const int64_t mpad = ((p.rows_max < 64 ? p.rows_max : 64) + 15) / 16 * 16;
+  p.n_splits = coarse_auto_splits(Bt, c.H, S_max);
+  size_t cur = 0;
+  p.lin_ws_bytes = LINEAR_COUNTER_BYTES + (size_t)mpad * (size_t)(32768 + maxN) * sizeof(float);
+  p.lin_ws = bump(cur, p.lin_ws_bytes);
+  p.coarse_ws_bytes = photon_coarse_decode_attn_workspace_bytes(Bt, c.H, c.d_h, p.n_splits);
+  p.coarse_ws = bump(cur, p.coarse_ws_bytes);
+  const size_t f = sizeof(float);
+  p.h = bump(cur, p.rows_max * D * f);
+  p.xn = bump(cur, p.rows_max * D * f);
+  p.attn = bump(cur, p.rows_max * D * f);
+  p.qkv = bump(cur, p.rows_max * 3 * D * f);
+  p.qrot = bump(cur, p.rows_max * D * f);
+  p.gu = bump(cur, p.rows_max * 2 * F * f);
+  p.act = bump(cur, p.rows_max * F * f);
+  p.cond = bump(cur, p.rows_max * D * f);
+  p.logits = bump(cur, (size_t)p.chunks[1] * c.vocab * f);
+  p.a_hat = bump(cur, (size_t)Bt * D * f);
+  for (int l = 1; l <= c.L; ++l) {
+    p.fresh[l - 1] = bump(cur, (size_t)p.chunks[l] * c.C[l - 1] * D * f);
+    const int W = c.R[l - 1] + c.C[l - 1] - 1;
+    const size_t cache = (size_t)c.n_layers * p.chunks[l] * W * D * f;
+    p.lk[l - 1] = bump(cur, cache);
+    p.lv[l - 1] = bump(cur, cache);
+  }
+  p.total = cur;
+  return p;
+}
+
+static int32_t validate_config(const photon_config* c, int Bt, int64_t S_max) {
+  PHOTON_REQUIRE(c != nullptr, PHOTON_ERR_INVALID_ARG, "config is null");
+  PHOTON_REQUIRE(valid_dtype(c->dt), PHOTON_ERR_UNSUPPORTED, "unknown dtype %d", (int)c->dt);
+  PHOTON_REQUIRE(c->L >= 1 && c->L <= PHOTON_MAX_LEVELS, PHOTON_ERR_INVALID_ARG, "L=%d not in [1, %d]", c->L, (int)PHOTON_MAX_LEVELS);
+  PHOTON_REQUIRE(Bt > 0 && S_max > 0, PHOTON_ERR_INVALID_ARG, "Bt=%d and S_max=%lld must be positive", Bt, (long long)S_max);
+  PHOTON_REQUIRE(c->D > 0 && c->H > 0 && c->d_h > 0 && c->H * c->d_h == c->D, PHOTON_ERR_INVALID_ARG,
+                 "D=%d must equal H*d_h=%d*%d", c->D, c->H, c->d_h);
+  PHOTON_REQUIRE(c->d_h == 32 || c->d_h == 64 || c->d_h == 128, PHOTON_ERR_UNSUPPORTED, "d_h=%d not in {32, 64, 128}", c->d_h);
+  PHOTON_REQUIRE(c->n_layers >= 1 && c->vocab >= 1 && c->d_ff >= 0, PHOTON_ERR_INVALID_ARG, "n_layers=%d vocab=%d d_ff=%d invalid",
+                 c->n_layers, c->vocab, c->d_ff);
+  int64_t chunks = Bt;
+  for (int l = c->L; l >= 1; --l) {
+    const int C = c->C[l - 1], R = c->R[l - 1];
+    PHOTON_REQUIRE(C >= 1 && R >= 1 && R + C - 1 <= PHOTON_MAX_WINDOW, PHOTON_ERR_UNSUPPORTED,
+                   "level %d: C=%d R=%d need C, R >= 1 and R+C-1 <= %d", l, C, R, (int)PHOTON_MAX_WINDOW);
+    chunks *= C;
+    PHOTON_REQUIRE(chunks * R <= (1 << 20), PHOTON_ERR_UNSUPPORTED, "level %d: %lld rows per sub-step is too many", l, (long long)chunks * R);
+  }
+  if (c->dt == PHOTON_BF16) {
+    PHOTON_REQUIRE(c->D % 64 == 0 && c->d_ff % 64 == 0 && c->vocab % 16 == 0, PHOTON_ERR_UNSUPPORTED,
+                   "bf16 path needs D (%d) and d_ff (%d) multiples of 64 and vocab (%d) a multiple of 16", c->D, c->d_ff, c->vocab);
+  } else {
+    PHOTON_REQUIRE(c->D % 4 == 0 && c->d_ff % 4 == 0, PHOTON_ERR_UNSUPPORTED, "fp32 path needs D and d_ff multiples of 4");
+  }
+  PHOTON_REQUIRE((int64_t)Bt * c->H <= 65535, PHOTON_ERR_UNSUPPORTED, "Bt*H=%lld exceeds 65535", (long long)Bt * c->H);
+  return PHOTON_OK;
+}
+
+// ------------------------------------------------------------------ composition
+
+struct Ctx {
+  const photon_config* c;
+  const photon_weights* w;
+  const photon_state* s;
+  int Bt;
+  hipStream_t st;
+  Plan p;
+  char* base;
+  bool bf16;
+  float* f(size_t off) const { return reinterpret_cast<float*>(base + off); }
+};
+
+static int32_t linear(const Ctx& x, const float* in, int64_t ldx, const void* W, const float* bias, const float* res,
+                      float* out, int64_t ldo, int M, int N, int K) {
+  LinearArgs a;
+  a.x = in; a.ldx = ldx; a.W = W; a.w_bf16 = x.bf16; a.bias = bias; a.res = res; a.ldres = ldo; a.out = out; a.ldo = ldo;
+  a.M = M; a.N = N; a.K = K;
+  a.workspace = x.base + x.p.lin_ws; a.workspace_bytes = x.p.lin_ws_bytes;
+  return launch_linear(a, x.st);
+}
+
+static int32_t rmsnorm(const Ctx& x, const float* in, int in_mul, int in_off, const float* g, float* out, int out_mul,
+                       int out_off, float* out2, int rows) {
+  hipLaunchKernelGGL(rmsnorm_rows_kernel, dim3(rows), dim3(256), 0, x.st, in, in_mul, in_off, g, x.c->rms_eps, out, out_mul,
+                     out_off, out2, x.c->D);
+  return check_launch("rmsnorm_rows_kernel");
+}
+
+#define PHOTON_TRY(expr) do { const int32_t rc_ = (expr); if (rc_ != PHOTON_OK) return rc_; } while (0)
+
+static int32_t mlp(const Ctx& x, const photon_layer_weights& lw, int rows) {
+  const photon_config& c = *x.c;
+  if (c.d_ff == 0) return PHOTON_OK;
+  float *h = x.f(x.p.h), *xn = x.f(x.p.xn), *gu = x.f(x.p.gu), *act = x.f(x.p.act);
+  PHOTON_TRY(rmsnorm(x, h, 1, 0, lw.g2, xn, 1, 0, nullptr, rows));
+  PHOTON_TRY(linear(x, xn, c.D, lw.wgu, nullptr, nullptr, gu, 2 * c.d_ff, rows, 2 * c.d_ff, c.D));
+  const int64_t total = (int64_t)rows * c.d_ff;
+  hipLaunchKernelGGL(silu_mul_kernel, dim3(blocks_for(total)), dim3(256), 0, x.st, gu, act, total, c.d_ff);
+  PHOTON_TRY(check_launch("silu_mul_kernel"));
+  return linear(x, act, c.d_ff, lw.wd, nullptr, h, h, c.D, rows, c.D, c.d_ff);
+}
+
+// All blocks of the level-`level` local decoder on the rows in p.h (n_chunks * q_len rows,
+// window positions q_pos .. q_pos+q_len-1 of every chunk).
+static int32_t local_module_pass(const Ctx& x, int level, int64_t n_chunks, int q_len, int q_pos) {
+  const photon_config& c = *x.c;
+  const photon_module_weights& mod = x.w->dec[level - 1];
+  const int W = c.R[level - 1] + c.C[level - 1] - 1;
+  const int rows = (int)(n_chunks * q_len);
+  float *h = x.f(x.p.h), *xn = x.f(x.p.xn), *qkv = x.f(x.p.qkv), *qrot = x.f(x.p.qrot), *attn = x.f(x.p.attn);
+  const size_t layer_cache = (size_t)n_chunks * W * c.D;
+  const float scale = 1.0f / sqrtf((float)c.d_h);
+  for (int i = 0; i < c.n_layers; ++i) {
+    const photon_layer_weights& lw = mod.layers[i];
+    float* lk = x.f(x.p.lk[level - 1]) + (size_t)i * layer_cache;
+    float* lv = x.f(x.p.lv[level - 1]) + (size_t)i * layer_cache;
+    PHOTON_TRY(rmsnorm(x, h, 1, 0, lw.g1, xn, 1, 0, nullptr, rows));
+    PHOTON_TRY(linear(x, xn, c.D, lw.wqkv, nullptr, nullptr, qkv, 3 * c.D, rows, 3 * c.D, c.D));
+    const int64_t n_el = (int64_t)rows * c.H * (c.d_h / 2);
+    hipLaunchKernelGGL(rope_append_local_kernel, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot, lk, lv, rows, q_len,
+                       q_pos, W, c.H, c.d_h, c.rope_theta);
+    PHOTON_TRY(check_launch("rope_append_local_kernel"));
+    PHOTON_TRY(launch_local_attn(true, c.d_h, qrot, lk, lv, attn, n_chunks, W, q_len, q_pos, c.H, scale, x.st));
+    PHOTON_TRY(linear(x, attn, c.D, lw.wo, nullptr, h, h, c.D, rows, c.D, c.D));
+    PHOTON_TRY(mlp(x, lw, rows));
+  }
+  return PHOTON_OK;
+}
+
+// STEP of the top-level encoder on the Bt rows in p.h; leaves X^(L)_{g+1} in state.x_top.
+static int32_t top_step(const Ctx& x) {
+  const photon_config& c = *x.c;
+  const photon_module_weights& mod = x.w->top;
+  const int rows = x.Bt;
+  float *h = x.f(x.p.h), *xn = x.f(x.p.xn), *qkv = x.f(x.p.qkv), *qrot = x.f(x.p.qrot), *attn = x.f(x.p.attn);
+  const size_t esz = dtype_size(c.dt);
+  const size_t layer_cache = (size_t)x.Bt * c.H * x.s->S_max * c.d_h * esz;
+  const float scale = 1.0f / sqrtf((float)c.d_h);
+  for (int i = 0; i < c.n_layers; ++i) {
+    const photon_layer_weights& lw = mod.layers[i];
+    char* kc = reinterpret_cast<char*>(x.s->k_cache) + (size_t)i * layer_cache;
+    char* vc = reinterpret_cast<char*>(x.s->v_cache) + (size_t)i * layer_cache;
+    PHOTON_TRY(rmsnorm(x, h, 1, 0, lw.g1, xn, 1, 0, nullptr, rows));
+    PHOTON_TRY(linear(x, xn, c.D, lw.wqkv, nullptr, nullptr, qkv, 3 * c.D, rows, 3 * c.D, c.D));
+    const int64_t n_el = (int64_t)rows * c.H * (c.d_h / 2);
+    if (x.bf16)
+      hipLaunchKernelGGL(rope_append_coarse_kernel<bf16_t>, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot, (bf16_t*)kc,
+                         (bf16_t*)vc, x.s->seq_len, x.Bt, c.H, c.d_h, x.s->S_max, c.rope_theta);
+    else
+      hipLaunchKernelGGL(rope_append_coarse_kernel<float>, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot, (float*)kc,
+                         (float*)vc, x.s->seq_len, x.Bt, c.H, c.d_h, x.s->S_max, c.rope_theta);
+    PHOTON_TRY(check_launch("rope_append_coarse_kernel"));
+    PHOTON_TRY(launch_coarse_attn(x.bf16 ? KV_BF16 : KV_F32, true, c.d_h, qrot, kc, vc, x.s->seq_len, attn, x.Bt, c.H,
+                                  x.s->S_max, scale, x.p.n_splits, x.base + x.p.coarse_ws, x.st));
+    PHOTON_TRY(linear(x, attn, c.D, lw.wo, nullptr, h, h, c.D, rows, c.D, c.D));
+    PHOTON_TRY(mlp(x, lw, rows));
+  }
+  return rmsnorm(x, h, 1, 0, mod.g_final, x.s->x_top, 1, 0, nullptr, rows);
+}
+
+static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* out_tokens, const photon_trace* tr) {
+  const photon_config& c = *x.c;
+  const int D = c.D, L = c.L, Bt = x.Bt;
+  float* h = x.f(x.p.h);
+  float* cond = x.f(x.p.cond);
+
+  hipLaunchKernelGGL(step_begin_kernel, dim3(blocks_for(LINEAR_COUNTER_BYTES / 4 > Bt ? LINEAR_COUNTER_BYTES / 4 : Bt)),
+                     dim3(256), 0, x.st, reinterpret_cast<int*>(x.base + x.p.lin_ws), (int)(LINEAR_COUNTER_BYTES / 4),
+                     x.s->seq_len, Bt);
+  PHOTON_TRY(check_launch("step_begin_kernel"));
+
+  float* fresh[PHOTON_MAX_LEVELS];
+  for (int l = 0; l < L; ++l) fresh[l] = (tr && tr->new_units[l]) ? tr->new_units[l] : x.f(x.p.fresh[l]);
+
+  const float* cond_in = x.s->x_top;                       // level L: one chunk per sequence, conditioned on X^(L)_g
+  for (int l = L; l >= 1; --l) {
+    const int C = c.C[l - 1], R = c.R[l - 1];
+    const int64_t n = x.p.chunks[l];
+    const photon_module_weights& mod = x.w->dec[l - 1];
+    float* units = fresh[l - 1];                           // [n * C, D]: chunk-major, item j of chunk ch at row ch*C + j
+    // sub-step 0: the converter's R vectors at window positions 0..R-1 (row ch*R + r)
+    PHOTON_TRY(linear(x, cond_in, D, x.w->conv_w[l - 1], x.w->conv_b[l - 1], nullptr, h, (int64_t)R * D, (int)n, R * D, D));
+    for (int j = 0; j < C; ++j) {
+      const int q_len = (j == 0) ? R : 1;
+      const int q_pos = (j == 0) ? 0 : R + j - 1;
+      PHOTON_TRY(local_module_pass(x, l, n, q_len, q_pos));
+      // item j = final norm of the last row of each chunk; levels >= 2 feed it back as the next input
+      const bool feed_back = (l >= 2) && (j + 1 < C);
+      PHOTON_TRY(rmsnorm(x, h, q_len, q_len - 1, mod.g_final, units, C, j, feed_back ? x.f(x.p.xn) : nullptr, (int)n));
+      if (feed_back) {
+        hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(n * D)), dim3(256), 0, x.st, x.f(x.p.xn), h, n * D);
+        PHOTON_TRY(check_launch("copy_f32_kernel"));
+      }
+      if (l == 1) {
+        float* lg = (tr && tr->logits) ? tr->logits + (int64_t)j * c.vocab : x.f(x.p.logits);
+        const int64_t ld = (tr && tr->logits) ? (int64_t)C * c.vocab : c.vocab;
+        // logits of item j of every chunk: rows of `units` with pitch C*D
+        LinearArgs a;
+        a.x = units + (int64_t)j * D; a.ldx = (int64_t)C * D; a.W = x.w->W_lm; a.w_bf16 = x.bf16;
+        a.out = lg; a.ldo = ld; a.M = (int)n; a.N = c.vocab; a.K = D;
+        a.workspace = x.base + x.p.lin_ws; a.workspace_bytes = x.p.lin_ws_bytes;
+        PHOTON_TRY(launch_linear(a, x.st));
+        float* x_next = (j + 1 < C) ? h : nullptr;
+        if (x.bf16)
+          hipLaunchKernelGGL(choose_token_kernel<bf16_t>, dim3((unsigned)n), dim3(256), 0, x.st, lg, ld, c.vocab, forced,
+                             out_tokens, C, j, (const bf16_t*)x.w->E_dec, x_next, D);
+        else
+          hipLaunchKernelGGL(choose_token_kernel<float>, dim3((unsigned)n), dim3(256), 0, x.st, lg, ld, c.vocab, forced,
+                             out_tokens, C, j, (const float*)x.w->E_dec, x_next, D);
+        PHOTON_TRY(check_launch("choose_token_kernel"));
+      }
+    }
+    if (l >= 2) {
+      // chunks of level l-1: one per new level-(l-1) unit, hanging off the previous unit
+      const int64_t per_seq = n * C / Bt;
+      float* carry = x.s->carry + (int64_t)(l - 2) * Bt * D;
+      hipLaunchKernelGGL(shift_condition_kernel, dim3(blocks_for(n * C * D)), dim3(256), 0, x.st, units, carry, cond, Bt,
+                         (int)per_seq, D);
+      PHOTON_TRY(check_launch("shift_condition_kernel"));
+      hipLaunchKernelGGL(update_carry_kernel, dim3(blocks_for((int64_t)Bt * D)), dim3(256), 0, x.st, units, carry, Bt,
+                         (int)per_seq, D);
+      PHOTON_TRY(check_launch("update_carry_kernel"));
+      cond_in = cond;
+    }
+  }
+
+  // (ii) top chunker on the C_L new level-(L-1) units of every sequence, (iii) STEP
+  float* a_hat = (tr && tr->a_hat) ? tr->a_hat : x.f(x.p.a_hat);
+  const int CL = c.C[L - 1];
+  PHOTON_TRY(linear(x, fresh[L - 1], (int64_t)CL * D, x.w->chunker_w, x.w->chunker_b, nullptr, a_hat, D, Bt, D, CL * D));
+  hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for((int64_t)Bt * D)), dim3(256), 0, x.st, a_hat, h, (int64_t)Bt * D);
+  PHOTON_TRY(check_launch("copy_f32_kernel"));
+  return top_step(x);
+}
+
+}  // namespace photon
+
+using namespace photon;
+
+extern "C" size_t photon_decode_step_workspace_bytes(const photon_config* cfg, int32_t Bt, int64_t S_max) {
+  clear_error();
+  if (validate_config(cfg, Bt, S_max) != PHOTON_OK) return 0;
+  return make_plan(*cfg, Bt, S_max).total;
+}
+
+extern "C" int32_t photon_decode_step(const photon_config* cfg, const photon_weights* w, const photon_state* st, int32_t Bt,
+                                      const int32_t* forced_tokens, int32_t* out_tokens, const photon_trace* trace,
+                                      void* stream) {
+  clear_error();
+  PHOTON_REQUIRE(cfg && w && st, PHOTON_ERR_INVALID_ARG, "%s: cfg, w and st must not be null", __func__);
+  PHOTON_TRY(validate_config(cfg, Bt, st->S_max));
+  const photon_config& c = *cfg;
+  PHOTON_REQUIRE(out_tokens != nullptr, PHOTON_ERR_INVALID_ARG, "%s: out_tokens is null", __func__);
+  PHOTON_REQUIRE_PTR(st->k_cache);
+  PHOTON_REQUIRE_PTR(st->v_cache);
+  PHOTON_REQUIRE_PTR(st->x_top);
+  PHOTON_REQUIRE(st->seq_len != nullptr, PHOTON_ERR_INVALID_ARG, "%s: state.seq_len is null", __func__);
+  PHOTON_REQUIRE(c.L == 1 || (st->carry != nullptr && aligned16(st->carry)), PHOTON_ERR_INVALID_ARG,
+                 "%s: state.carry must be a 16-byte aligned device pointer when L > 1", __func__);
+  PHOTON_REQUIRE_PTR(w->E_dec);
+  PHOTON_REQUIRE_PTR(w->W_lm);
+  PHOTON_REQUIRE_PTR(w->chunker_w);
+  PHOTON_REQUIRE(w->top.layers && w->top.g_final, PHOTON_ERR_INVALID_ARG, "%s: top module weights missing", __func__);
+  for (int l = 0; l < c.L; ++l) {
+    PHOTON_REQUIRE(w->conv_w[l] && aligned16(w->conv_w[l]) && w->conv_b[l] && w->dec[l].layers && w->dec[l].g_final,
+                   PHOTON_ERR_INVALID_ARG, "%s: weights of decoder level %d missing or misaligned", __func__, l + 1);
+  }
+  for (int m = 0; m <= c.L; ++m) {
+    const photon_module_weights& mod = (m == 0) ? w->top : w->dec[m - 1];
+    for (int i = 0; i < c.n_layers; ++i) {
+      const photon_layer_weights& lw = mod.layers[i];
+      const bool ok = lw.g1 && lw.wqkv && aligned16(lw.wqkv) && lw.wo && aligned16(lw.wo) &&
+                      (c.d_ff == 0 || (lw.g2 && lw.wgu && aligned16(lw.wgu) && lw.wd && aligned16(lw.wd)));
+      PHOTON_REQUIRE(ok, PHOTON_ERR_INVALID_ARG, "%s: module %d layer %d has a null or misaligned weight", __func__, m, i);
+    }
+  }
+  Ctx x;
+  x.c = cfg; x.w = w; x.s = st; x.Bt = Bt; x.st = (hipStream_t)stream;
+  x.p = make_plan(c, Bt, st->S_max);
+  x.bf16 = (c.dt == PHOTON_BF16);
+  PHOTON_REQUIRE(st->workspace != nullptr && aligned16(st->workspace) && st->workspace_bytes >= x.p.total, PHOTON_ERR_WORKSPACE,
+                 "%s: workspace of %zu bytes needed (got %zu)", __func__, x.p.total, st->workspace_bytes);
+  x.base = reinterpret_cast<char*>(st->workspace);
+  return decode_step_impl(x, forced_tokens, out_tokens, trace);
+}

@@ -1,0 +1,160 @@
+"""GPU parity of photon_decode_step against the oracle's recursive-generation
+step: every intermediate the library can expose (new units of each level,
+logits, chunker output, top state, appended K/V, carries, tokens)."""
+import numpy as np
+import pytest
+import torch
+
+import seeded_inputs as si
+from oracle import photon_oracle as po
+from util import TOL, dev, nerr, require_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def run_step(cfg, w, st_np, Bt, S_max, forced=None):
+    """One GPU step from the numpy state `st_np`; returns (model, state, tokens, trace tensors)."""
+    import paper_2512_20687_amd as ph
+    model = ph.PhotonModel(cfg, w)
+    state = ph.PhotonState(model, Bt, S_max, k=np.asarray(st_np["k"], np.float32), v=np.asarray(st_np["v"], np.float32),
+                           seq_len=np.asarray(st_np["seq_len"], np.int32), x_top=np.asarray(st_np["x_top"], np.float32),
+                           carry=np.asarray(st_np["carry"], np.float32))
+    B = cfg.meta_context
+    n_units = [B]
+    for l in range(1, cfg.L):
+        n_units.append(n_units[-1] // cfg.C[l - 1])
+    trace = {
+        "logits": torch.full((Bt, B, cfg.vocab), float("nan"), device="cuda"),
+        "new_units": [torch.full((Bt, n_units[l], cfg.D), float("nan"), device="cuda") for l in range(cfg.L)],
+        "a_hat": torch.full((Bt, cfg.D), float("nan"), device="cuda"),
+    }
+    toks = torch.full((Bt, B), -1, dtype=torch.int32, device="cuda")
+    f = None if forced is None else dev(np.asarray(forced, np.int32))
+    ph.photon_decode_step(model, state, toks, forced_tokens=f, trace=trace)
+    torch.cuda.synchronize()
+    return model, state, toks, trace
+
+
+def check_against_oracle(cfg, w, st_np, Bt, S_max, forced, tol):
+    w64 = po.weights_to_f64(w)
+    ost = po.state_to_f64(st_np)
+    s0 = ost["seq_len"].copy()
+    otr = po.decode_step(cfg, w64, ost, forced_tokens=forced)
+    model, state, toks, tr = run_step(cfg, w, st_np, Bt, S_max, forced)
+    errs = {}
+    for l in range(cfg.L):
+        errs[f"new{l}"] = nerr(tr["new_units"][l], otr["new"][l])
+    errs["logits"] = nerr(tr["logits"], otr["logits"])
+    errs["a_hat"] = nerr(tr["a_hat"], otr["a_hat"])
+    errs["x_top"] = nerr(state.x_top, otr["x_top"])
+    if cfg.L > 1:
+        errs["carry"] = nerr(state.carry, ost["carry"])
+    for name, got, ref in (("k", state.k, ost["k"]), ("v", state.v, ost["v"])):
+        new_rows = np.stack([ref[:, b, :, s0[b]] for b in range(Bt)], 1)
+        got_rows = torch.stack([got[:, b, :, int(s0[b])] for b in range(Bt)], 1)
+        errs[name + "_new"] = nerr(got_rows, new_rows)
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, (bad, errs)
+    assert np.array_equal(state.seq_len.cpu().numpy(), s0 + 1)
+    gt = toks.cpu().numpy()
+    if forced is not None:
+        assert np.array_equal(gt, np.asarray(forced))
+    else:
+        # compare the greedy choice wherever the oracle's two best logits are clearly apart
+        lg = otr["logits"]
+        top2 = np.sort(lg, axis=-1)[..., -2:]
+        clear = (top2[..., 1] - top2[..., 0]) > 10 * tol * np.abs(lg).max()
+        assert np.array_equal(gt[clear], otr["tokens"][clear])
+        assert clear.mean() > 0.5
+    return errs, otr, state
+
+
+def test_cfg1_prefill_then_one_step_fp32():
+    """Configuration 1: real hierarchical prefill of a 256-token prompt (oracle),
+    then one decode step = 16 tokens, all in fp32, every intermediate <= 1e-5."""
+    require_gpu()
+    wl = si.WORKLOADS["cfg1_tiny_f32"]
+    cfg = wl.cfg
+    w = si.make_weights(cfg, 0)
+    toks = si.make_tokens(cfg.vocab, wl.Bt, wl.T, 0)
+    S_max = wl.S0 + 4
+    st = po.prefill(cfg, po.weights_to_f64(w), toks, S_max)
+    assert st["seq_len"][0] == 16
+    check_against_oracle(cfg, w, st, wl.Bt, S_max, None, TOL["f32"])
+
+
+@pytest.mark.parametrize("kw", [
+    dict(),                                   # L=2, C=(4,4), R=1
+    dict(R=(2, 2)),                           # the paper's converter length
+    dict(R=(3, 1), C=(2, 5)),
+    dict(d_ff=0),                             # attention-only blocks
+    dict(L=3, C=(2, 3, 2), R=(1, 2, 1)),
+    dict(L=1, C=(4,), R=(2,)),
+    dict(rope_theta=0.0),
+])
+def test_small_fp32_variants(kw):
+    require_gpu()
+    base = dict(L=2, C=(4, 4), R=(1, 1), D=64, H=2, d_h=32, n_layers=2, d_ff=160, vocab=96, dtype="f32")
+    base.update(kw)
+    cfg = si.PhotonConfig(**base)
+    w = si.make_weights(cfg, 21)
+    Bt, S_max = 3, 24
+    st = si.make_decode_state(cfg, Bt, 9, S_max, seed=5)
+    st["seq_len"] = np.array([9, 1, 5], np.int32)
+    check_against_oracle(cfg, w, st, Bt, S_max, None, TOL["f32"])
+
+
+@pytest.mark.parametrize("kw,Bt", [
+    (dict(), 3),
+    (dict(R=(2, 2)), 2),
+    (dict(L=3, C=(2, 2, 4), R=(1, 1, 1), n_layers=1), 5),      # 80 rows at the token level: two row passes
+    (dict(d_h=128, H=2, d_ff=0), 1),
+])
+def test_bf16_variants(kw, Bt):
+    """bf16 weights and coarse cache, fp32 accumulation; tokens forced so that a
+    near-tie in the argmax cannot derail the comparison."""
+    require_gpu()
+    base = dict(L=2, C=(4, 4), R=(1, 1), D=256, H=4, d_h=64, n_layers=2, d_ff=640, vocab=1024, dtype="bf16")
+    base.update(kw)
+    cfg = si.PhotonConfig(**base)
+    w = si.make_weights(cfg, 33)
+    S_max = 300
+    st = si.make_decode_state(cfg, Bt, 257, S_max, seed=6)
+    st["seq_len"] = np.array([257 - 3 * b for b in range(Bt)], np.int32)
+    forced = si.make_tokens(cfg.vocab, Bt, cfg.meta_context, 9)
+    errs, _, _ = check_against_oracle(cfg, w, st, Bt, S_max, forced, TOL["bf16"])
+    print(errs)
+
+
+def test_three_steps_follow_the_oracle_fp32():
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    cfg = si.PhotonConfig(L=2, C=(4, 4), R=(1, 1), D=64, H=2, d_h=32, n_layers=1, d_ff=160, vocab=512, dtype="f32")
+    w = si.make_weights(cfg, 2)
+    w64 = po.weights_to_f64(w)
+    Bt, S_max = 2, 12
+    toks = si.make_tokens(cfg.vocab, Bt, 64, 3)
+    ost = po.prefill(cfg, w64, toks, S_max)
+    model = ph.PhotonModel(cfg, w)
+    state = ph.PhotonState(model, Bt, S_max, k=ost["k"].astype(np.float32), v=ost["v"].astype(np.float32),
+                           seq_len=ost["seq_len"].astype(np.int32), x_top=ost["x_top"].astype(np.float32),
+                           carry=ost["carry"].astype(np.float32))
+    out = torch.empty((Bt, 16), dtype=torch.int32, device="cuda")
+    for step in range(3):
+        tr = po.decode_step(cfg, w64, ost)
+        ph.photon_decode_step(model, state, out, forced_tokens=dev(tr["tokens"].astype(np.int32)))
+        assert nerr(state.x_top, tr["x_top"]) <= 10 * TOL["f32"], step       # free-running: error may grow slowly
+        assert nerr(state.k, ost["k"]) <= 10 * TOL["f32"]
+    assert state.seq_len.cpu().tolist() == [7, 7]
+
+
+def test_step_is_deterministic():
+    require_gpu()
+    cfg = si.PhotonConfig(L=2, C=(4, 4), R=(1, 1), D=256, H=4, d_h=64, n_layers=2, d_ff=640, vocab=1024, dtype="bf16")
+    w = si.make_weights(cfg, 1)
+    st = si.make_decode_state(cfg, 2, 100, 128, seed=1)
+    a = run_step(cfg, w, st, 2, 128)
+    b = run_step(cfg, w, st, 2, 128)
+    assert torch.equal(a[3]["logits"], b[3]["logits"])
+    assert torch.equal(a[1].x_top, b[1].x_top)
+    assert torch.equal(a[2], b[2])
