@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the PHOTON decode hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-graph] [--no-cpu]
+
+A "step" is one photon_decode_step: one recursive-generation step (all chunk-
+local sub-steps of every level, LM head, top chunker, STEP over the coarse KV
+cache) for every sequence of the workload.  Default workload: the benchmark's
+headline configuration (128k-token context, batch 4).  Inputs are seeded and
+synthetic (weights N(0,0.02), K/V ~ N(0,1)); they are resident in HBM before
+the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="cfg3_bf16_128k")
+    ap.add_argument("--no-graph", action="store_true", help="enqueue every step instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (CPU baseline) leg")
+    return ap.parse_args()
+
+
+def weight_bytes_per_step(cfg, esz):
+    """Weight bytes one step streams: every module's matrices once per pass
+    (C_l passes for the level-l decoder, 1 for the top encoder), the LM head C_1
+    times, converters and the top chunker once."""
+    D, F = cfg.D, cfg.d_ff
+    per_layer = (4 * D * D + 3 * D * F) * esz
+    module = cfg.n_layers * per_layer
+    total = module                                       # top encoder STEP
+    for l in range(1, cfg.L + 1):
+        total += cfg.C[l - 1] * module + cfg.R[l - 1] * D * D * esz
+    total += cfg.C[0] * cfg.vocab * D * esz              # LM head per token sub-step
+    total += cfg.C[cfg.L - 1] * D * D * esz              # top chunker
+    return total
+
+
+def cpu_baseline(wl, min_seconds=12.0, max_steps=120):
+    """Time the oracle's decode step on the host cores on a bounded sample of the
+    workload: same widths, heads, context length and batch, but `sample_layers`
+    blocks per module instead of n_layers, repeated for about `min_seconds`; the
+    time is scaled by n_layers / sample_layers (embedding, LM-head and converter
+    work is thereby over-counted, which flatters the GPU slightly less than the
+    CPU deserves; the figure is a baseline, not a target)."""
+    import seeded_inputs as si
+    from oracle import photon_oracle as po
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    sample_layers = min(2, wl.cfg.n_layers)
+    cfg = si.shrink(wl.cfg, n_layers=sample_layers)
+    Bt, S = wl.Bt, wl.S0
+    w = po.weights_to_f64(si.make_weights(cfg, 0, encoders=False))
+    st = po.state_to_f64(si.make_decode_state(cfg, Bt, S, S + max_steps + 2, seed=0))
+    forced = si.make_tokens(cfg.vocab, Bt, cfg.meta_context, 1)
+    n = 0
+    t0 = time.perf_counter()
+    while n < max_steps and (n < 1 or time.perf_counter() - t0 < min_seconds):
+        po.decode_step(cfg, w, st, forced_tokens=forced)
+        n += 1
+    dt = time.perf_counter() - t0
+    scale = wl.cfg.n_layers / sample_layers
+    return {
+        "value": n * Bt * cfg.meta_context / (dt * scale), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"{n} oracle decode steps at {wl.name} shapes (D={cfg.D}, H={cfg.H}, Bt={Bt}, coarse S={S}, vocab={cfg.vocab}) "
+                  f"with {sample_layers} of {wl.cfg.n_layers} blocks per module: {dt:.1f} s measured, time scaled x{scale:g}",
+        "seconds_measured": dt,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py measures one GPU; --gpus {args.gpus} is not supported in this build (every box has one GPU).",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import seeded_inputs as si
+    import paper_2512_20687_amd as ph
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    ph.load_library()
+    wl = si.WORKLOADS[args.workload]
+    cfg = wl.cfg
+    dev = "cuda"
+    esz = 2 if cfg.dtype == "bf16" else 4
+    Bt, S0 = wl.Bt, wl.S0
+    total_steps = args.warmup + args.steps + 4
+    S_max = S0 + total_steps + 8
+
+    t_setup = time.perf_counter()
+    weights = si.make_weights(cfg, 0, encoders=False, device=dev)
+    model = ph.PhotonModel(cfg, weights)
+    del weights
+    st0 = si.make_decode_state(cfg, Bt, S0, S_max, seed=0, device=dev)
+    state = ph.PhotonState(model, Bt, S_max, **{k: st0[k] for k in ("k", "v", "seq_len", "x_top", "carry")})
+    del st0
+    out_tokens = torch.zeros((Bt, cfg.meta_context), dtype=torch.int32, device=dev)
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t_setup
+
+    def step():
+        ph.photon_decode_step(model, state, out_tokens)
+
+    graph = None
+    mode = "eager"
+    if not args.no_graph:
+        try:
+            step()                                        # one eager step first (lazy module load, etc.)
+            torch.cuda.synchronize()
+            state.seq_len.sub_(1)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            mode = "hip_graph_replay"
+            state.seq_len.fill_(S0)
+        except Exception as e:                            # capture unsupported: fall back to eager enqueue
+            print(f"[bench] graph capture failed ({e}); timing eager enqueue", file=sys.stderr)
+            graph = None
+            mode = "eager"
+            state.seq_len.fill_(S0)
+
+    run = (lambda: graph.replay()) if graph is not None else step
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        run()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    tokens_per_step = Bt * cfg.meta_context
+    tok_s = tokens_per_step / (wall / args.steps)
+    S_end = int(state.seq_len.max().item())
+
+    # ---- per-kernel durations: a few eager steps with every launch bracketed by HIP events on its stream ----
+    prof_steps = 4
+    ph.photon_profile_reset()
+    ph.photon_profile_enable(True)
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
+    ph.photon_profile_enable(False)
+    prof = ph.photon_profile_get()
+    ph.photon_profile_reset()
+    S_prof = S_end + (prof_steps + 1) / 2.0            # mean coarse length seen by the profiled steps
+    H, d_h, nl = cfg.H, cfg.d_h, cfg.n_layers
+    wbytes = weight_bytes_per_step(cfg, esz)
+    kv_launch_bytes = 2 * Bt * H * S_prof * d_h * esz
+    kernels = {}
+    for name, (n, ms) in prof.items():
+        kernels[name] = {"launches_per_step": n / prof_steps, "us_per_launch": ms * 1e3 / n, "ms_per_step": ms / prof_steps}
+    alg_bytes = {"skinny_gemm_bf16_kernel": wbytes, "coarse_attn_kernel": kv_launch_bytes * nl}     # per step
+    for name, b in alg_bytes.items():
+        if name in kernels:
+            k = kernels[name]
+            k["bytes_per_launch"] = b / k["launches_per_step"]
+            k["gbs"] = b / (k["ms_per_step"] * 1e-3) / 1e9
+            k["frac_of_hbm_peak"] = k["gbs"] / HBM_PEAK_GBS
+    dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    dk = kernels[dominant]
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": dk.get("gbs"), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": dk.get("frac_of_hbm_peak"), "traffic": None, "bytes_per_launch": dk.get("bytes_per_launch"),
+                "us_per_launch": dk["us_per_launch"], "launches_per_step": dk["launches_per_step"],
+                "share_of_kernel_time": dk["ms_per_step"] / sum(k["ms_per_step"] for k in kernels.values())}
+    ca = kernels.get("coarse_attn_kernel", {})
+    kv_gbs = ca.get("gbs", 0.0)
+
+    kv_step_bytes = kv_launch_bytes * nl
+    step_bytes = wbytes + kv_step_bytes
+    result = {
+        "metric": "decode tokens/s and KV-read HBM GB/s (% of peak) at 128k context, batch 4",
+        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "L": cfg.L, "C": list(cfg.C), "R": list(cfg.R), "d_model": cfg.D, "heads": cfg.H,
+                   "head_dim": cfg.d_h, "layers_per_module": cfg.n_layers, "d_ff": cfg.d_ff, "vocab": cfg.vocab,
+                   "batch": Bt, "context_tokens": wl.T, "coarse_kv_len_start": S0, "coarse_kv_len_end": S_end,
+                   "tokens_per_step": tokens_per_step, "mode": mode},
+        "kv_read_gbs": kv_gbs, "kv_read_frac_of_hbm_peak": kv_gbs / HBM_PEAK_GBS,
+        "kv_read_bytes_per_launch": kv_launch_bytes,
+        "step_hbm_bytes_model": step_bytes, "step_hbm_gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_roofline": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "roofline": roofline,
+        "kernels": kernels,
+        "setup_s": setup_s,
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -68,7 +68,8 @@ PHOTON_API const char* photon_last_error(void);
  *   bias  [d_out]          fp32 or NULL
  *   out   [rows, d_out]    dt
  * bf16: fp32 accumulation on the matrix cores, one rounding on store.
- * Requires C*d_in to be a multiple of 32 and d_out a multiple of 16.
+ * bf16 requires C*d_in to be a multiple of 64 and d_out a multiple of 16;
+ * fp32 requires C*d_in to be a multiple of 4.
  * rows == 0 is a no-op.
  * -------------------------------------------------------------------------- */
 PHOTON_API int32_t photon_chunker_project(const void* x, const void* w, const float* bias, void* out,
@@ -118,6 +119,26 @@ PHOTON_API int32_t photon_chunk_local_attn(const void* q, const void* k, const v
                                 int64_t n_chunks, int32_t W, int32_t q_len, int32_t q_pos,
                                 int32_t H, int32_t d_h, float scale, photon_dtype dt, void* stream);
 
+
+/* --------------------------------------------------------------------------
+ * Few-row linear map, the weight-streaming building block of the decode step
+ * (every projection of the LLaMA blocks, the converter, the LM head):
+ *     out[m, :] = W * x[m, :] (+ bias) (+ res[m, :])        m < M
+ *   x    [M, K]  fp32 activations
+ *   w    [N, K]  dt
+ *   bias [N]     fp32 or NULL
+ *   res  [M, N]  fp32 or NULL (may alias out)
+ *   out  [M, N]  fp32
+ * bf16 needs K % 64 == 0 and N % 16 == 0; fp32 needs K % 4 == 0.
+ * workspace: photon_linear_workspace_bytes(M, N) bytes (no initialisation
+ * needed), or NULL (then K is not split over workgroups, which is slower for
+ * small N).  Results do not depend on whether K is split beyond fp32 summation
+ * order, and are run-to-run deterministic.
+ * -------------------------------------------------------------------------- */
+PHOTON_API size_t photon_linear_workspace_bytes(int32_t M, int32_t N);
+PHOTON_API int32_t photon_linear(const float* x, const void* w, const float* bias, const float* res, float* out,
+                                 int32_t M, int32_t N, int32_t K, void* workspace, size_t workspace_bytes,
+                                 photon_dtype dt, void* stream);
 
 /* --------------------------------------------------------------------------
  * One recursive-generation step g -> g+1 for Bt sequences (paper Section
@@ -202,6 +223,21 @@ PHOTON_API size_t photon_decode_step_workspace_bytes(const photon_config* cfg, i
 PHOTON_API int32_t photon_decode_step(const photon_config* cfg, const photon_weights* w, const photon_state* st,
                                       int32_t Bt, const int32_t* forced_tokens, int32_t* out_tokens,
                                       const photon_trace* trace, void* stream);
+
+/* --------------------------------------------------------------------------
+ * Per-kernel timing for benchmarks.  While enabled, every kernel launch of the
+ * library is bracketed by a pair of HIP events on the launch stream (this
+ * allocates events and must not be used under stream capture).  Kernels are
+ * grouped in classes 0 .. photon_profile_num_classes()-1, named by
+ * photon_profile_class_name().  photon_profile_get() waits for the recorded
+ * events of a class and returns the launch count and the summed elapsed
+ * milliseconds; photon_profile_reset() drops all records.
+ * -------------------------------------------------------------------------- */
+PHOTON_API int32_t photon_profile_enable(int32_t on);
+PHOTON_API int32_t photon_profile_reset(void);
+PHOTON_API int32_t photon_profile_num_classes(void);
+PHOTON_API const char* photon_profile_class_name(int32_t cls);
+PHOTON_API int32_t photon_profile_get(int32_t cls, int64_t* launches, double* total_ms);
 
 #ifdef __cplusplus
 }

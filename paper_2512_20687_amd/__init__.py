@@ -21,5 +21,10 @@ from .binding import (  # noqa: F401
     photon_decode_step,
     photon_decode_step_workspace_bytes,
     photon_last_error,
+    photon_linear,
+    photon_linear_workspace_bytes,
+    photon_profile_enable,
+    photon_profile_get,
+    photon_profile_reset,
     photon_version,
 )

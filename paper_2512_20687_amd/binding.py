@@ -42,6 +42,8 @@ def load_library() -> C.CDLL:
         "photon_coarse_decode_attn_auto_splits": (i32, [i32, i32, i64]),
         "photon_coarse_decode_attn": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i64, f32, i32, vp, sz, i32, vp]),
         "photon_chunk_local_attn": (i32, [vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, f32, i32, vp]),
+        "photon_linear_workspace_bytes": (sz, [i32, i32]),
+        "photon_linear": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, vp, sz, i32, vp]),
     }
     for name, (res, args) in sigs.items():
         if not hasattr(lib, name):
@@ -126,6 +128,43 @@ def photon_chunk_local_attn(q, k, v, out, q_pos: int = 0, scale: Optional[float]
         scale = 1.0 / math.sqrt(d_h)
     _check(lib.photon_chunk_local_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), n_chunks, W, q_len, q_pos, H, d_h, scale,
                                        _dt(k), _stream()))
+    return out
+
+
+def photon_profile_enable(on: bool) -> None:
+    _check(load_library().photon_profile_enable(1 if on else 0))
+
+
+def photon_profile_reset() -> None:
+    _check(load_library().photon_profile_reset())
+
+
+def photon_profile_get() -> dict:
+    """{class name: (launches, total_ms)} for every kernel class with at least one recorded launch."""
+    lib = load_library()
+    lib.photon_profile_class_name.restype = C.c_char_p
+    out = {}
+    for cls in range(lib.photon_profile_num_classes()):
+        n, ms = C.c_int64(0), C.c_double(0.0)
+        _check(lib.photon_profile_get(cls, C.byref(n), C.byref(ms)))
+        if n.value:
+            out[lib.photon_profile_class_name(cls).decode()] = (n.value, ms.value)
+    return out
+
+
+def photon_linear_workspace_bytes(M: int, N: int) -> int:
+    return load_library().photon_linear_workspace_bytes(M, N)
+
+
+def photon_linear(x, w, out, bias=None, res=None, workspace: Optional[torch.Tensor] = None):
+    """out[M, N] = x[M, K] @ w[N, K]^T (+ bias) (+ res); x, bias, res, out fp32; w fp32 or bf16.
+    workspace: zero-initialised uint8 tensor of photon_linear_workspace_bytes(M, N) bytes, or None."""
+    lib = load_library()
+    M, K = x.shape
+    N = w.shape[0]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.photon_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(res), _ptr(out), M, N, K, _ptr(workspace), ws_bytes,
+                             _dt(w), _stream()))
     return out
 
 

@@ -196,12 +196,12 @@ template <typename TKV, typename TQ, int DH>
 static int32_t launch_coarse_t(const void* q, const void* kc, const void* vc, const int32_t* seq_len, void* out,
                                int Bt, int H, int64_t S_max, float scale, int n_splits, void* ws, hipStream_t st) {
   dim3 grid(n_splits, Bt * H);
-  hipLaunchKernelGGL((coarse_attn_kernel<TKV, TQ, DH>), grid, dim3(COARSE_THREADS), 0, st,
+  PHOTON_LAUNCH(KC_COARSE_ATTN, st, (coarse_attn_kernel<TKV, TQ, DH>), grid, dim3(COARSE_THREADS), 0, st,
                      (const TQ*)q, (const TKV*)kc, (const TKV*)vc, seq_len, (TQ*)out, (float*)ws, H, S_max,
                      scale * LOG2E, n_splits);
   int32_t rc = check_launch("coarse_attn_kernel");
   if (rc != PHOTON_OK || n_splits == 1) return rc;
-  hipLaunchKernelGGL((coarse_merge_kernel<TQ, DH>), dim3(Bt * H), dim3(DH), 0, st, (const float*)ws, (TQ*)out, n_splits);
+  PHOTON_LAUNCH(KC_COARSE_MERGE, st, (coarse_merge_kernel<TQ, DH>), dim3(Bt * H), dim3(DH), 0, st, (const float*)ws, (TQ*)out, n_splits);
   return check_launch("coarse_merge_kernel");
 }
 
@@ -327,10 +327,10 @@ static int32_t launch_local_nk(bool tile, const void* q, const void* k, const vo
   const int64_t blocks = (n_units + units_per_block - 1) / units_per_block;
   if (blocks > 0x7fffffffLL) return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: too many chunks for one launch");
   if (tile)
-    hipLaunchKernelGGL((local_attn_kernel<T, DH, NK, true>), dim3((unsigned)blocks), dim3(LOCAL_THREADS), 0, st,
+    PHOTON_LAUNCH(KC_LOCAL_ATTN, st, (local_attn_kernel<T, DH, NK, true>), dim3((unsigned)blocks), dim3(LOCAL_THREADS), 0, st,
                        (const T*)q, (const T*)k, (const T*)v, (T*)out, n_units, H, W, q_len, q_pos, scale * LOG2E);
   else
-    hipLaunchKernelGGL((local_attn_kernel<T, DH, NK, false>), dim3((unsigned)blocks), dim3(LOCAL_THREADS), 0, st,
+    PHOTON_LAUNCH(KC_LOCAL_ATTN, st, (local_attn_kernel<T, DH, NK, false>), dim3((unsigned)blocks), dim3(LOCAL_THREADS), 0, st,
                        (const T*)q, (const T*)k, (const T*)v, (T*)out, n_units, H, W, q_len, q_pos, scale * LOG2E);
   return check_launch("local_attn_kernel");
 }

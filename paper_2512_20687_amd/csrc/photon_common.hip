@@ -1,6 +1,9 @@
 // Error reporting and version of the C ABI.
 #include <string.h>
 
+#include <mutex>
+#include <vector>
+
 #include "photon_host.h"
 
 namespace photon {
@@ -20,7 +23,69 @@ int32_t fail(int32_t code, const char* fmt, ...) {
   return code;
 }
 
+// ---- per-kernel-class timing -------------------------------------------------------------------
+bool g_profile_on = false;
+namespace {
+struct ProfRec { int cls; hipEvent_t start, stop; };
+std::mutex g_prof_mu;
+std::vector<ProfRec> g_prof;
+const char* const kClassNames[KC_COUNT] = {
+    "coarse_attn_kernel", "coarse_merge_kernel", "local_attn_kernel", "skinny_gemm_bf16_kernel", "gemm_f32_kernel",
+    "reduce_splits_kernel", "chunker_gemm_bf16_kernel", "norm_rows_kernel", "rope_append_kernel", "silu_mul_kernel",
+    "choose_token_kernel", "misc"};
+}  // namespace
+
+void profile_mark(int cls, hipStream_t st, bool begin) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (begin) {
+    ProfRec r{cls, nullptr, nullptr};
+    if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
+    (void)hipEventRecord(r.start, st);
+    g_prof.push_back(r);
+  } else if (!g_prof.empty()) {
+    (void)hipEventRecord(g_prof.back().stop, st);
+  }
+}
+
 }  // namespace photon
+
+extern "C" int32_t photon_profile_enable(int32_t on) {
+  photon::g_profile_on = (on != 0);
+  return PHOTON_OK;
+}
+
+extern "C" int32_t photon_profile_reset(void) {
+  std::lock_guard<std::mutex> lk(photon::g_prof_mu);
+  for (auto& r : photon::g_prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+  photon::g_prof.clear();
+  return PHOTON_OK;
+}
+
+extern "C" int32_t photon_profile_num_classes(void) { return photon::KC_COUNT; }
+
+extern "C" const char* photon_profile_class_name(int32_t cls) {
+  return (cls >= 0 && cls < photon::KC_COUNT) ? photon::kClassNames[cls] : "";
+}
+
+extern "C" int32_t photon_profile_get(int32_t cls, int64_t* launches, double* total_ms) {
+  using namespace photon;
+  clear_error();
+  PHOTON_REQUIRE(cls >= 0 && cls < KC_COUNT && launches && total_ms, PHOTON_ERR_INVALID_ARG, "%s: bad class or null output", __func__);
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  int64_t n = 0;
+  double ms = 0.0;
+  for (auto& r : g_prof) {
+    if (r.cls != cls) continue;
+    if (hipEventSynchronize(r.stop) != hipSuccess) return fail(PHOTON_ERR_HIP, "%s: event synchronise failed", __func__);
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, r.start, r.stop) != hipSuccess) return fail(PHOTON_ERR_HIP, "%s: elapsed time failed", __func__);
+    ms += t;
+    ++n;
+  }
+  *launches = n;
+  *total_ms = ms;
+  return PHOTON_OK;
+}
 
 extern "C" int32_t photon_version(void) { return 100; }
 

@@ -24,6 +24,21 @@ inline int32_t check_launch(const char* what) {
   return PHOTON_OK;
 }
 
+// ---- optional per-kernel-class timing with HIP events (photon_profile_* entry points) ----
+enum KernelClass {
+  KC_COARSE_ATTN = 0, KC_COARSE_MERGE, KC_LOCAL_ATTN, KC_SKINNY_GEMM, KC_GEMM_F32, KC_REDUCE_SPLITS, KC_CHUNKER_GEMM,
+  KC_NORM, KC_ROPE_APPEND, KC_SILU_MUL, KC_CHOOSE_TOKEN, KC_MISC, KC_COUNT
+};
+extern bool g_profile_on;
+void profile_mark(int cls, hipStream_t st, bool begin);
+struct ProfScope {
+  int cls; hipStream_t st; bool on;
+  ProfScope(int c, hipStream_t s) : cls(c), st(s), on(g_profile_on) { if (on) profile_mark(cls, st, true); }
+  ~ProfScope() { if (on) profile_mark(cls, st, false); }
+};
+#define PHOTON_LAUNCH(cls, stream, ...) \
+  do { ::photon::ProfScope prof_scope_((cls), (stream)); hipLaunchKernelGGL(__VA_ARGS__); } while (0)
+
 #define PHOTON_REQUIRE(cond, code, ...) \
   do { if (!(cond)) return ::photon::fail((code), __VA_ARGS__); } while (0)
 #define PHOTON_REQUIRE_PTR(p) \

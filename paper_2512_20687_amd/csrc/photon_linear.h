@@ -8,7 +8,15 @@ namespace photon {
 
 constexpr int LINEAR_MAX_KSPLIT = 16;
 constexpr int LINEAR_TARGET_WORKGROUPS = 512;
-constexpr int LINEAR_COUNTER_BYTES = 4096;      // one int per 64-column output block, N <= 65536
+
+// A product whose K-splits have not been added yet:
+//   value[m][n] = sum_{s < ks} data[s*split_stride + m*ld + n]
+struct Pending {
+  const float* data = nullptr;
+  int ks = 0;
+  int64_t split_stride = 0;
+  int64_t ld = 0;
+};
 
 // out[M,N] = x[M,K] * W[N,K]^T (+ bias[N]) (+ res[M,N]); out may alias res.
 struct LinearArgs {
@@ -23,11 +31,11 @@ struct LinearArgs {
   float* out = nullptr;
   int64_t ldo = 0;
   int M = 0, N = 0, K = 0;
-  void* workspace = nullptr;   // split-K scratch: LINEAR_COUNTER_BYTES of zeroed counters, then partial tiles
+  void* workspace = nullptr;   // split-K scratch for the partial tiles (no initialisation needed)
   size_t workspace_bytes = 0;
 };
 
 size_t linear_workspace_bytes(int max_rows, int max_N);
-int32_t launch_linear(const LinearArgs& a, hipStream_t st);
+int32_t launch_linear(const LinearArgs& a, Pending* pend, hipStream_t st);
 
 }  // namespace photon

@@ -13,9 +13,11 @@
 //   * fp32 activations are split into a bf16 head and a bf16 remainder and
 //     both are multiplied (two MFMAs per weight fragment), so the result is as
 //     accurate as an fp32-activation x bf16-weight product,
-//   * K is split over workgroups to fill the chip; the partial tiles go to a
-//     workspace and the last workgroup to arrive at an output block adds them
-//     in split order (deterministic) and applies bias/residual.
+//   * K is split over workgroups to fill the chip; each split writes its partial
+//     tile to a workspace and whichever kernel consumes the result (a norm, the
+//     rotary/append kernel, the SwiGLU gate, or the plain reduce kernel below)
+//     adds the splits in split order.  No atomics, no in-kernel fences: the
+//     kernel boundary is the synchronisation, and the result is deterministic.
 #include "photon_linear.h"
 
 #include "photon_device.h"
@@ -65,13 +67,12 @@ template <typename TX, int MT>
 __global__ __launch_bounds__(SK_THREADS) void skinny_gemm_bf16_kernel(
     const TX* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ W, const float* __restrict__ bias,
     const float* res, int64_t ldres, float* out, int64_t ldo,
-    int M, int N, int K, int n_ksplit, int blocks_per_split, float* __restrict__ partial, int* __restrict__ counters) {
+    int M, int N, int K, int direct, int blocks_per_split, float* __restrict__ partial, int64_t split_stride) {
   constexpr bool SPLIT = XLoad<TX>::SPLIT;
   constexpr int CB = SK_CHUNK_BLOCKS;
   // operand fragments of the activations: [m-tile][block][half][lane] x 16 bytes
   __shared__ uint4_t xh[MT][CB][2][64];
   __shared__ uint4_t xl[SPLIT ? MT : 1][SPLIT ? CB : 1][SPLIT ? 2 : 1][SPLIT ? 64 : 1];
-  __shared__ int ticket_s;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nblock = blockIdx.x, ks = blockIdx.y;
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_gemm_bf16_kernel(
     *reinterpret_cast<float4_t*>(out + (int64_t)m * ldo + n_out) = v;
   };
 
-  if (n_ksplit == 1) {
+  if (direct) {
     if (wave_live) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
@@ -175,41 +176,29 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_gemm_bf16_kernel(
     return;
   }
 
-  // split-K: park the partial tile, the last workgroup of this output block adds all of them in order
-  const int Mpad = MT * 16;
+  // split-K: park the partial tile [ks][m][n]; the consumer adds the splits
   if (wave_live) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int m = mt * 16 + lrow;
-      *reinterpret_cast<float4_t*>(partial + ((int64_t)ks * Mpad + m) * N + n_out) = acc[mt];
+      if (m < M) *reinterpret_cast<float4_t*>(partial + (int64_t)ks * split_stride + (int64_t)m * N + n_out) = acc[mt];
     }
   }
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) ticket_s = atomicAdd(&counters[nblock], 1);
-  __syncthreads();
-  if (ticket_s != n_ksplit - 1) return;
-  __threadfence();
-  if (wave_live) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int m = mt * 16 + lrow;
-      if (m < M) {
-        float4_t s = float4_t{0.f, 0.f, 0.f, 0.f};
-        for (int k2 = 0; k2 < n_ksplit; ++k2) {
-          const float* p = partial + ((int64_t)k2 * Mpad + m) * N + n_out;
-          float4_t t;
-          t.x = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          t.y = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          t.z = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          t.w = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          s += t;
-        }
-        finish(m, s);
-      }
-    }
-  }
-  if (tid == 0) counters[nblock] = 0;                           // ready for the next launch on the stream
+}
+
+// out[m, n] = sum_s part[s][m][n] (+ bias[n]) (+ res[m, n])
+__global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ part, int ks, int64_t split_stride,
+                                                            const float* __restrict__ bias, const float* res, int64_t ldres,
+                                                            float* out, int64_t ldo, int M, int N) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)M * N) return;
+  const int n = (int)(idx % N);
+  const int64_t m = idx / N;
+  float v = 0.f;
+  for (int s2 = 0; s2 < ks; ++s2) v += part[(int64_t)s2 * split_stride + m * N + n];
+  if (bias != nullptr) v += bias[n];
+  if (res != nullptr) v += res[m * ldres + n];
+  out[m * ldo + n] = v;
 }
 
 // fp32 weights (the small all-fp32 configuration): one wave per output column,
@@ -253,9 +242,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
 }
 
 size_t linear_workspace_bytes(int max_rows, int max_N) {
-  // partial tiles of up to LINEAR_MAX_KSPLIT splits + one counter per 64-column block
-  const size_t mpad = (size_t)((max_rows < 64 ? max_rows : 64) + 15) / 16 * 16;
-  return (size_t)LINEAR_MAX_KSPLIT * mpad * max_N * sizeof(float) + LINEAR_COUNTER_BYTES;
+  const size_t mpad = (size_t)(max_rows + 15) / 16 * 16;
+  if (max_rows > 64) return mpad * (size_t)max_N * sizeof(float);            // many rows: K is not split
+  return mpad * (size_t)(LINEAR_TARGET_WORKGROUPS * SK_NB + max_N + SK_NB) * sizeof(float);
 }
 
 static int choose_ksplit(int n_blocks, int total_kblocks) {
@@ -268,25 +257,20 @@ static int choose_ksplit(int n_blocks, int total_kblocks) {
 }
 
 template <typename TX>
-static int32_t launch_skinny(const LinearArgs& a, int m_rows, const void* x, const float* res, float* out, hipStream_t st) {
+static int32_t launch_skinny(const LinearArgs& a, int m0, int m_rows, int ks, int bps, bool direct, float* partial,
+                             int64_t split_stride, hipStream_t st) {
   const int n_blocks = (a.N + SK_NB - 1) / SK_NB;
-  const int total_kblocks = a.K / SK_KBLOCK;
-  int ks = choose_ksplit(n_blocks, total_kblocks);
-  int bps = (total_kblocks + ks - 1) / ks;
-  bps = (bps + SK_CHUNK_BLOCKS - 1) / SK_CHUNK_BLOCKS * SK_CHUNK_BLOCKS;
-  ks = (total_kblocks + bps - 1) / bps;
-  float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(a.workspace) + LINEAR_COUNTER_BYTES);
-  int* counters = reinterpret_cast<int*>(a.workspace);
-  if (ks > 1) {
-    const size_t need = LINEAR_COUNTER_BYTES + (size_t)ks * ((m_rows + 15) / 16 * 16) * a.N * sizeof(float);
-    if (a.workspace == nullptr || a.workspace_bytes < need || n_blocks * (int)sizeof(int) > LINEAR_COUNTER_BYTES)
-      ks = 1, bps = total_kblocks;               // no room to split: stream K in one workgroup per block
-  }
+  const size_t xsz = sizeof(TX);
+  const TX* x = reinterpret_cast<const TX*>(reinterpret_cast<const char*>(a.x) + (size_t)m0 * a.ldx * xsz);
+  const float* res = (direct && a.res) ? a.res + (int64_t)m0 * a.ldres : nullptr;
+  const float* bias = direct ? a.bias : nullptr;
+  float* out = direct ? a.out + (int64_t)m0 * a.ldo : nullptr;
+  float* part = direct ? nullptr : partial + (int64_t)m0 * a.N;
   dim3 grid(n_blocks, ks);
   const int mt = (m_rows + 15) / 16;
-#define PHOTON_SK_LAUNCH(MTV)                                                                                       \
-  hipLaunchKernelGGL((skinny_gemm_bf16_kernel<TX, MTV>), grid, dim3(SK_THREADS), 0, st, (const TX*)x, a.ldx,       \
-                     (const bf16_t*)a.W, a.bias, res, a.ldres, out, a.ldo, m_rows, a.N, a.K, ks, bps, partial, counters)
+#define PHOTON_SK_LAUNCH(MTV)                                                                                    \
+  PHOTON_LAUNCH(KC_SKINNY_GEMM, st, (skinny_gemm_bf16_kernel<TX, MTV>), grid, dim3(SK_THREADS), 0, st, x, a.ldx, (const bf16_t*)a.W, \
+                     bias, res, a.ldres, out, a.ldo, m_rows, a.N, a.K, direct ? 1 : 0, bps, part, split_stride)
   switch (mt) {
     case 1: PHOTON_SK_LAUNCH(1); break;
     case 2: PHOTON_SK_LAUNCH(2); break;
@@ -298,28 +282,82 @@ static int32_t launch_skinny(const LinearArgs& a, int m_rows, const void* x, con
   return check_launch("skinny_gemm_bf16_kernel");
 }
 
-int32_t launch_linear(const LinearArgs& a, hipStream_t st) {
-  if (a.M <= 0) return PHOTON_OK;
+// Enqueue the product.  With pend == nullptr the complete result (bias, residual) lands in a.out.
+// With pend != nullptr the caller's next kernel consumes *pend: value = sum_s data[s*split_stride + m*ld + n],
+// bias and residual are NOT applied and a.out is not written.
+int32_t launch_linear(const LinearArgs& a, Pending* pend, hipStream_t st) {
+  if (a.M <= 0) { if (pend) *pend = Pending{}; return PHOTON_OK; }
   if (a.w_bf16) {
     if (a.K % SK_KBLOCK != 0 || a.N % 16 != 0)
       return fail(PHOTON_ERR_UNSUPPORTED, "linear (bf16): K=%d must be a multiple of 64 and N=%d of 16", a.K, a.N);
-    const size_t xsz = a.x_bf16 ? 2 : 4;
+    const int n_blocks = (a.N + SK_NB - 1) / SK_NB;
+    const int total_kblocks = a.K / SK_KBLOCK;
+    int ks = a.M > 64 ? 1 : choose_ksplit(n_blocks, total_kblocks);
+    int bps = (total_kblocks + ks - 1) / ks;
+    bps = (bps + SK_CHUNK_BLOCKS - 1) / SK_CHUNK_BLOCKS * SK_CHUNK_BLOCKS;
+    ks = (total_kblocks + bps - 1) / bps;
+    const int64_t mpad = (int64_t)(a.M + 15) / 16 * 16;
+    const int64_t split_stride = mpad * a.N;
+    const size_t need = (size_t)ks * split_stride * sizeof(float);
+    const bool have_ws = a.workspace != nullptr && a.workspace_bytes >= need;
+    if (!have_ws) {
+      if (pend) return fail(PHOTON_ERR_WORKSPACE, "linear: %zu bytes of workspace needed (got %zu)", need, a.workspace_bytes);
+      ks = 1; bps = total_kblocks;
+    }
+    const bool direct = (pend == nullptr) && ks == 1;
+    float* partial = reinterpret_cast<float*>(a.workspace);
     for (int m0 = 0; m0 < a.M; m0 += 64) {
       const int rows = a.M - m0 < 64 ? a.M - m0 : 64;
-      const void* x = reinterpret_cast<const char*>(a.x) + (size_t)m0 * a.ldx * xsz;
-      const float* res = a.res ? a.res + (int64_t)m0 * a.ldres : nullptr;
-      float* out = a.out + (int64_t)m0 * a.ldo;
-      const int32_t rc = a.x_bf16 ? launch_skinny<bf16_t>(a, rows, x, res, out, st) : launch_skinny<float>(a, rows, x, res, out, st);
+      const int32_t rc = a.x_bf16 ? launch_skinny<bf16_t>(a, m0, rows, ks, bps, direct, partial, split_stride, st)
+                                  : launch_skinny<float>(a, m0, rows, ks, bps, direct, partial, split_stride, st);
       if (rc != PHOTON_OK) return rc;
     }
-    return PHOTON_OK;
+    if (pend) { pend->data = partial; pend->ks = ks; pend->split_stride = split_stride; pend->ld = a.N; return PHOTON_OK; }
+    if (direct) return PHOTON_OK;
+    const int64_t total = (int64_t)a.M * a.N;
+    PHOTON_LAUNCH(KC_REDUCE_SPLITS, st, reduce_splits_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, ks, split_stride,
+                       a.bias, a.res, a.ldres, a.out, a.ldo, a.M, a.N);
+    return check_launch("reduce_splits_kernel");
   }
   if (a.x_bf16) return fail(PHOTON_ERR_UNSUPPORTED, "linear: bf16 activations need bf16 weights");
   if (a.K % 4 != 0) return fail(PHOTON_ERR_UNSUPPORTED, "linear (fp32): K=%d must be a multiple of 4", a.K);
   dim3 grid((a.N + 3) / 4, (a.M + F32_ROWS - 1) / F32_ROWS);
-  hipLaunchKernelGGL((gemm_f32_kernel<0>), grid, dim3(256), 0, st, (const float*)a.x, a.ldx, (const float*)a.W, a.bias,
+  if (pend) {
+    const size_t need = (size_t)a.M * a.N * sizeof(float);
+    if (a.workspace == nullptr || a.workspace_bytes < need)
+      return fail(PHOTON_ERR_WORKSPACE, "linear: %zu bytes of workspace needed (got %zu)", need, a.workspace_bytes);
+    float* partial = reinterpret_cast<float*>(a.workspace);
+    PHOTON_LAUNCH(KC_GEMM_F32, st, (gemm_f32_kernel<0>), grid, dim3(256), 0, st, (const float*)a.x, a.ldx, (const float*)a.W,
+                       (const float*)nullptr, (const float*)nullptr, (int64_t)0, partial, (int64_t)a.N, a.M, a.N, a.K);
+    pend->data = partial; pend->ks = 1; pend->split_stride = (int64_t)a.M * a.N; pend->ld = a.N;
+    return check_launch("gemm_f32_kernel");
+  }
+  PHOTON_LAUNCH(KC_GEMM_F32, st, (gemm_f32_kernel<0>), grid, dim3(256), 0, st, (const float*)a.x, a.ldx, (const float*)a.W, a.bias,
                      a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K);
   return check_launch("gemm_f32_kernel");
 }
 
 }  // namespace photon
+
+using namespace photon;
+
+extern "C" size_t photon_linear_workspace_bytes(int32_t M, int32_t N) {
+  if (M <= 0 || N <= 0) return 0;
+  return linear_workspace_bytes(M, N);
+}
+
+extern "C" int32_t photon_linear(const float* x, const void* w, const float* bias, const float* res, float* out, int32_t M,
+                                 int32_t N, int32_t K, void* workspace, size_t workspace_bytes, photon_dtype dt, void* stream) {
+  clear_error();
+  PHOTON_REQUIRE(valid_dtype(dt), PHOTON_ERR_UNSUPPORTED, "%s: unknown dtype %d", __func__, (int)dt);
+  PHOTON_REQUIRE(M >= 0 && N > 0 && K > 0, PHOTON_ERR_INVALID_ARG, "%s: M=%d N=%d K=%d invalid", __func__, M, N, K);
+  if (M == 0) return PHOTON_OK;
+  PHOTON_REQUIRE_PTR(x);
+  PHOTON_REQUIRE_PTR(w);
+  PHOTON_REQUIRE_PTR(out);
+  PHOTON_REQUIRE(workspace == nullptr || aligned16(workspace), PHOTON_ERR_WORKSPACE, "%s: workspace is misaligned", __func__);
+  LinearArgs a;
+  a.x = x; a.ldx = K; a.W = w; a.w_bf16 = (dt == PHOTON_BF16); a.bias = bias; a.res = res; a.ldres = N; a.out = out; a.ldo = N;
+  a.M = M; a.N = N; a.K = K; a.workspace = workspace; a.workspace_bytes = workspace_bytes;
+  return launch_linear(a, nullptr, (hipStream_t)stream);
+}

@@ -95,20 +95,34 @@ def round_to_dtype(x: torch.Tensor, dtype: str) -> torch.Tensor:
 
 
 class _Draw:
-    """Fixed-order seeded normal draws."""
+    """Fixed-order seeded draws.  device="cpu" returns numpy arrays (the form the
+    oracle and the parity tests use); another device returns torch tensors made
+    there by that device's own seeded generator (full-size benchmark inputs,
+    which are too large to route through host memory comfortably)."""
 
-    def __init__(self, seed: int, dtype: str):
-        self.g = torch.Generator(device="cpu")
+    def __init__(self, seed: int, dtype: str, device: str = "cpu"):
+        self.device = torch.device(device)
+        self.g = torch.Generator(device=self.device)
         self.g.manual_seed(int(seed))
         self.dtype = dtype
 
-    def normal(self, shape, std=1.0, mean=0.0) -> np.ndarray:
-        t = torch.randn(tuple(shape), generator=self.g, dtype=torch.float32) * std + mean
-        return round_to_dtype(t, self.dtype).numpy()
+    def _out(self, t: torch.Tensor):
+        return t.numpy() if self.device.type == "cpu" else t
 
-    def uniform_int(self, shape, high) -> np.ndarray:
-        return torch.randint(0, int(high), tuple(shape), generator=self.g,
-                             dtype=torch.int64).to(torch.int32).numpy()
+    def normal(self, shape, std=1.0, mean=0.0):
+        t = torch.randn(tuple(shape), generator=self.g, dtype=torch.float32, device=self.device)
+        if std != 1.0:
+            t.mul_(std)
+        if mean != 0.0:
+            t.add_(mean)
+        if self.device.type != "cpu" and self.dtype == "bf16":
+            return t.to(torch.bfloat16)           # kept in storage dtype on the device
+        return self._out(round_to_dtype(t, self.dtype))
+
+    def uniform_int(self, shape, high):
+        t = torch.randint(0, int(high), tuple(shape), generator=self.g, dtype=torch.int64,
+                          device=self.device).to(torch.int32)
+        return self._out(t)
 
 
 def _module(d: _Draw, cfg: PhotonConfig) -> dict:
@@ -131,7 +145,7 @@ def _module(d: _Draw, cfg: PhotonConfig) -> dict:
 
 
 def make_weights(cfg: PhotonConfig, seed: int = 0, *, encoders: bool = True,
-                 emb_std: float = 1.0) -> dict:
+                 emb_std: float = 1.0, device: str = "cpu") -> dict:
     """All parameters of one model.  Every linear map is stored [out, in]
     (y = W x), so the contraction index is contiguous.
 
@@ -139,7 +153,7 @@ def make_weights(cfg: PhotonConfig, seed: int = 0, *, encoders: bool = True,
     embedding (recursive generation keeps only the decoder stack, the top
     chunker and the top encoder resident).
     """
-    d = _Draw(seed, cfg.dtype)
+    d = _Draw(seed, cfg.dtype, device)
     D = cfg.D
     w = {"E_dec": d.normal((cfg.vocab, D), emb_std), "W_lm": d.normal((cfg.vocab, D), 0.02)}
     if encoders:
@@ -176,21 +190,28 @@ def make_normal(shape, seed: int, dtype: str = "f32", std: float = 1.0) -> np.nd
     return _Draw(seed, dtype).normal(shape, std)
 
 
-def make_decode_state(cfg: PhotonConfig, Bt: int, S: int, S_max: int, seed: int = 0) -> dict:
+def make_decode_state(cfg: PhotonConfig, Bt: int, S: int, S_max: int, seed: int = 0, device: str = "cpu") -> dict:
     """Benchmark-style decode state without a prefill: coarse K/V ~ N(0,1) for
     the first S slots of every (layer, sequence, head) stream, top state and
     carries ~ N(0,1).  Layouts: kv [n_layers, Bt, H, S_max, d_h]; x_top [Bt, D];
     carry [L-1, Bt, D] (carry[l-1] is the last reconstructed level-l unit)."""
-    d = _Draw(seed + 104729, cfg.dtype)
-    k = np.zeros((cfg.n_layers, Bt, cfg.H, S_max, cfg.d_h), np.float32)
-    v = np.zeros_like(k)
-    k[:, :, :, :S] = d.normal((cfg.n_layers, Bt, cfg.H, S, cfg.d_h))
-    v[:, :, :, :S] = d.normal((cfg.n_layers, Bt, cfg.H, S, cfg.d_h))
+    d = _Draw(seed + 104729, cfg.dtype, device)
+    shape = (cfg.n_layers, Bt, cfg.H, S_max, cfg.d_h)
+    if device == "cpu":
+        k = np.zeros(shape, np.float32)
+        v = np.zeros_like(k)
+        k[:, :, :, :S] = d.normal((cfg.n_layers, Bt, cfg.H, S, cfg.d_h))
+        v[:, :, :, :S] = d.normal((cfg.n_layers, Bt, cfg.H, S, cfg.d_h))
+        seq = np.full((Bt,), S, np.int32)
+    else:
+        k, v = d.normal(shape), d.normal(shape)
+        k[:, :, :, S:] = 0
+        v[:, :, :, S:] = 0
+        seq = torch.full((Bt,), S, dtype=torch.int32, device=device)
     return {
-        "k": k, "v": v,
-        "seq_len": np.full((Bt,), S, np.int32),
-        "x_top": _Draw(seed + 1, "f32").normal((Bt, cfg.D)),
-        "carry": _Draw(seed + 2, "f32").normal((max(cfg.L - 1, 0), Bt, cfg.D)),
+        "k": k, "v": v, "seq_len": seq,
+        "x_top": _Draw(seed + 1, "f32", device).normal((Bt, cfg.D)),
+        "carry": _Draw(seed + 2, "f32", device).normal((max(cfg.L - 1, 0), Bt, cfg.D)),
     }
 
 
