@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--workload", default="cfg3_bf16_128k")
     ap.add_argument("--no-graph", action="store_true", help="enqueue every step instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (CPU baseline) leg")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (known traffic) so that counter runs can be calibrated")
     return ap.parse_args()
 
 
@@ -121,6 +123,13 @@ def main():
 
     def step():
         ph.photon_decode_step(model, state, out_tokens)
+
+    if args.calib_copy:                                   # 1 GiB read + 1 GiB written by a plain copy kernel
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
 
     graph = None
     mode = "eager"

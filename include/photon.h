@@ -225,6 +225,14 @@ PHOTON_API int32_t photon_decode_step(const photon_config* cfg, const photon_wei
                                       const photon_trace* trace, void* stream);
 
 /* --------------------------------------------------------------------------
+ * Bandwidth probe for benchmarks: a trivial kernel that reads `bytes` bytes of
+ * `buf` once with 128-bit non-temporal loads (2048 workgroups, grid-stride) and discards
+ * them.  Timing it gives the streaming-read ceiling of the machine, which the
+ * attention kernels' GB/s can be set against.  sink: 4 writable device bytes.
+ * -------------------------------------------------------------------------- */
+PHOTON_API int32_t photon_hbm_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
+
+/* --------------------------------------------------------------------------
  * Per-kernel timing for benchmarks.  While enabled, every kernel launch of the
  * library is bracketed by a pair of HIP events on the launch stream (this
  * allocates events and must not be used under stream capture).  Kernels are

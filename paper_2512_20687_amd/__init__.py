@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     photon_coarse_decode_attn_workspace_bytes,
     photon_decode_step,
     photon_decode_step_workspace_bytes,
+    photon_hbm_read_probe,
     photon_last_error,
     photon_linear,
     photon_linear_workspace_bytes,

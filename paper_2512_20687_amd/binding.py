@@ -131,6 +131,13 @@ def photon_chunk_local_attn(q, k, v, out, q_pos: int = 0, scale: Optional[float]
     return out
 
 
+def photon_hbm_read_probe(buf: torch.Tensor, sink: torch.Tensor) -> None:
+    lib = load_library()
+    lib.photon_hbm_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.photon_hbm_read_probe.restype = C.c_int32
+    _check(lib.photon_hbm_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()))
+
+
 def photon_profile_enable(on: bool) -> None:
     _check(load_library().photon_profile_enable(1 if on else 0))
 

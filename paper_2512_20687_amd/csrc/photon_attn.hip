@@ -19,9 +19,8 @@ namespace photon {
 
 // ------------------------------------------------------------------ coarse stream
 
-constexpr int COARSE_THREADS = 256;
-constexpr int COARSE_WAVES = COARSE_THREADS / 64;
-constexpr int COARSE_UNROLL = 4;   // 16-byte K loads (and as many V loads) in flight per lane and buffer
+constexpr int COARSE_WAVES_PER_WG = 8;   // measured: 8 waves x 4 loads in flight per buffer streams best
+constexpr int COARSE_UNROLL = 4;
 
 template <typename TKV, int DH> struct RowMap {
   static constexpr int VEC = 16 / sizeof(TKV);      // elements per 16-byte lane chunk
@@ -40,13 +39,14 @@ template <int VEC> struct SoftState {
   }
 };
 
-template <typename TKV, typename TQ, int DH>
-__global__ __launch_bounds__(COARSE_THREADS) void coarse_attn_kernel(
+// COARSE_WAVES waves per workgroup; U 16-byte K loads (and as many V loads) in flight per lane and register buffer.
+template <typename TKV, typename TQ, int DH, int COARSE_WAVES, int U>
+__global__ __launch_bounds__(COARSE_WAVES * 64) void coarse_attn_kernel(
     const TQ* __restrict__ q, const TKV* __restrict__ kc, const TKV* __restrict__ vc,
     const int32_t* __restrict__ seq_len, TQ* __restrict__ out, float* __restrict__ ws,
     int H, int64_t S_max, float scale_log2e, int n_splits) {
   using M = RowMap<TKV, DH>;
-  constexpr int VEC = M::VEC, LPR = M::LPR, RPW = M::RPW, U = COARSE_UNROLL;
+  constexpr int VEC = M::VEC, LPR = M::LPR, RPW = M::RPW;
   constexpr int TILE = RPW * U;                       // keys one wave consumes per buffer
 
   const int split = blockIdx.x;
@@ -62,9 +62,11 @@ __global__ __launch_bounds__(COARSE_THREADS) void coarse_attn_kernel(
   const int64_t begin = (int64_t)split * per;
   const int64_t end = begin + per < n ? begin + per : n;
 
-  float qf[VEC];
+  // the query is fetched first but only converted after the first K/V slab is in flight
+  TQ qraw[VEC];
 #pragma unroll
-  for (int i = 0; i < VEC; ++i) qf[i] = to_f32<TQ>(q[(int64_t)bh * DH + c * VEC + i]) * scale_log2e;
+  for (int i = 0; i < VEC; ++i) qraw[i] = q[(int64_t)bh * DH + c * VEC + i];
+  float qf[VEC];
 
   const TKV* kb = kc + (int64_t)bh * S_max * DH + c * VEC;
   const TKV* vb = vc + (int64_t)bh * S_max * DH + c * VEC;
@@ -78,8 +80,8 @@ __global__ __launch_bounds__(COARSE_THREADS) void coarse_attn_kernel(
     for (int u = 0; u < U; ++u) {
       int64_t key = t0 + u * RPW + g;
       key = key < end ? key : end - 1;
-      kr[u] = load16(kb + key * DH);
-      vr[u] = load16(vb + key * DH);
+      kr[u] = load16_stream(kb + key * DH);
+      vr[u] = load16_stream(vb + key * DH);
     }
   };
   auto consume = [&](int64_t t0, const uint4_t (&kr)[U], const uint4_t (&vr)[U]) {
@@ -120,6 +122,8 @@ __global__ __launch_bounds__(COARSE_THREADS) void coarse_attn_kernel(
   if (t0 < end) {
     uint4_t ka[U], va[U], kb2[U], vb2[U];
     load(t0, ka, va);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) qf[i] = to_f32<TQ>(qraw[i]) * scale_log2e;
     while (true) {
       const int64_t t1 = t0 + stride;
       const bool more1 = t1 < end;
@@ -192,17 +196,24 @@ __global__ __launch_bounds__(DH) void coarse_merge_kernel(const float* __restric
   out[(int64_t)bh * DH + d] = from_f32<TQ>(l > 0.f ? o / l : 0.f);
 }
 
-template <typename TKV, typename TQ, int DH>
-static int32_t launch_coarse_t(const void* q, const void* kc, const void* vc, const int32_t* seq_len, void* out,
+template <typename TKV, typename TQ, int DH, int WAVES, int U>
+static int32_t launch_coarse_v(const void* q, const void* kc, const void* vc, const int32_t* seq_len, void* out,
                                int Bt, int H, int64_t S_max, float scale, int n_splits, void* ws, hipStream_t st) {
   dim3 grid(n_splits, Bt * H);
-  PHOTON_LAUNCH(KC_COARSE_ATTN, st, (coarse_attn_kernel<TKV, TQ, DH>), grid, dim3(COARSE_THREADS), 0, st,
+  PHOTON_LAUNCH(KC_COARSE_ATTN, st, (coarse_attn_kernel<TKV, TQ, DH, WAVES, U>), grid, dim3(WAVES * 64), 0, st,
                      (const TQ*)q, (const TKV*)kc, (const TKV*)vc, seq_len, (TQ*)out, (float*)ws, H, S_max,
                      scale * LOG2E, n_splits);
   int32_t rc = check_launch("coarse_attn_kernel");
   if (rc != PHOTON_OK || n_splits == 1) return rc;
   PHOTON_LAUNCH(KC_COARSE_MERGE, st, (coarse_merge_kernel<TQ, DH>), dim3(Bt * H), dim3(DH), 0, st, (const float*)ws, (TQ*)out, n_splits);
   return check_launch("coarse_merge_kernel");
+}
+
+template <typename TKV, typename TQ, int DH>
+static int32_t launch_coarse_t(const void* q, const void* kc, const void* vc, const int32_t* seq_len, void* out,
+                               int Bt, int H, int64_t S_max, float scale, int n_splits, void* ws, hipStream_t st) {
+  return launch_coarse_v<TKV, TQ, DH, COARSE_WAVES_PER_WG, COARSE_UNROLL>(q, kc, vc, seq_len, out, Bt, H, S_max, scale,
+                                                                          n_splits, ws, st);
 }
 
 template <typename TKV, typename TQ>
@@ -225,11 +236,12 @@ int32_t launch_coarse_attn(KvType kv, bool q_f32, int d_h, const void* q, const 
 }
 
 int32_t coarse_auto_splits(int Bt, int H, int64_t S_max) {
-  // Aim at ~8 waves of loads in flight per SIMD-quad on all 256 CUs (>= 1024 workgroups)
-  // while every split still streams at least 256 keys.
-  int64_t streams = (int64_t)Bt * H;
-  int64_t want = (1024 + streams - 1) / streams;
-  int64_t cap = S_max / 256;
+  // One workgroup (8 waves) per CU keeps enough loads in flight; more workgroups only add merge work.
+  // Very long streams get ~1024 workgroups so that no single one streams for too long.
+  const int64_t streams = (int64_t)Bt * H;
+  int64_t want = (256 + streams - 1) / streams;
+  if (S_max / want > 16384) want = (1024 + streams - 1) / streams;
+  int64_t cap = S_max / 512;                    // every split streams at least 512 keys
   if (cap < 1) cap = 1;
   if (want > cap) want = cap;
   if (want > 64) want = 64;
@@ -266,14 +278,14 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_attn_kernel(
   const T* vp = v + (chunk * W * H + h) * DH + col;
   uint4_t kr[NK], vr[NK];
 #pragma unroll
-  for (int j = 0; j < NK; ++j) { kr[j] = load16(kp + j * row); vr[j] = load16(vp + j * row); }
+  for (int j = 0; j < NK; ++j) { kr[j] = load16_stream(kp + j * row); vr[j] = load16_stream(vp + j * row); }
 
   const T* qp = q + (chunk * q_len * H + h) * DH + col;
   T* op = out + (chunk * q_len * H + h) * DH + col;
 
   auto one_query = [&](int i, int nvis) {
     float qf[VEC];
-    unpack16<T>(load16(qp + i * row), qf);
+    unpack16<T>(load16_stream(qp + i * row), qf);
 #pragma unroll
     for (int t = 0; t < VEC; ++t) qf[t] *= scale_log2e;
     float s[NK];

@@ -55,6 +55,10 @@ template <> struct Vec16<bf16_t> {
 
 // Raw 16-byte load kept as bits (conversion deferred so many loads stay in flight).
 __device__ __forceinline__ uint4_t load16(const void* p) { return *reinterpret_cast<const uint4_t*>(p); }
+// Same, marked non-temporal: data that is used exactly once should not displace anything in the caches.
+__device__ __forceinline__ uint4_t load16_stream(const void* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const uint4_t*>(p));
+}
 template <typename T> __device__ __forceinline__ void unpack16(const uint4_t& r, float* v);
 template <> __device__ __forceinline__ void unpack16<float>(const uint4_t& r, float* v) {
   v[0] = __uint_as_float(r.x); v[1] = __uint_as_float(r.y); v[2] = __uint_as_float(r.z); v[3] = __uint_as_float(r.w);

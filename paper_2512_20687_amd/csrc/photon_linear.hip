@@ -97,8 +97,8 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_gemm_bf16_kernel(
       int blk = blk0 + b;
       blk = blk < blk_end ? blk : blk_end - 1;                 // clamped: stays in bounds, result unused
       const bf16_t* p = wrow + (int64_t)blk * SK_KBLOCK;
-      wf[b][0] = load16(p);
-      wf[b][1] = load16(p + 8);
+      wf[b][0] = load16_stream(p);
+      wf[b][1] = load16_stream(p + 8);
     }
   };
 
