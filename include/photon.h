@@ -121,23 +121,22 @@ PHOTON_API int32_t photon_chunk_local_attn(const void* q, const void* k, const v
 
 
 /* --------------------------------------------------------------------------
- * Few-row linear map, the weight-streaming building block of the decode step
- * (every projection of the LLaMA blocks, the converter, the LM head):
- *     out[m, :] = W * x[m, :] (+ bias) (+ res[m, :])        m < M
- *   x    [M, K]  fp32 activations
- *   w    [N, K]  dt
- *   bias [N]     fp32 or NULL
- *   res  [M, N]  fp32 or NULL (may alias out)
- *   out  [M, N]  fp32
+ * Few-row linear map with fused pre-norm and epilogue: the weight-streaming
+ * building block of the decode step (every projection of the LLaMA blocks,
+ * the converters, the LM head, the chunker at decode shapes).
+ *     y[m, :] = rmsnorm(x[m, :]; gain, rms_eps) * W^T      (gain == NULL: y = x * W^T)
+ *     epilogue 0 (plain)   : out = y + bias
+ *     epilogue 1 (residual): out = res + y + bias          (out may alias res)
+ *     epilogue 2 (SwiGLU)  : out = silu(y[:, 0:N]) * y[:, N:2N]   (w has 2N rows: gate, then up)
+ *   x    [M, K]          fp32
+ *   w    [N or 2N, K]    dt
+ *   gain [K], bias [N]   fp32 or NULL;   res [M, N] fp32 (epilogue 1)
+ *   out  [M, N]          fp32
  * bf16 needs K % 64 == 0 and N % 16 == 0; fp32 needs K % 4 == 0.
- * workspace: photon_linear_workspace_bytes(M, N) bytes (no initialisation
- * needed), or NULL (then K is not split over workgroups, which is slower for
- * small N).  Results do not depend on whether K is split beyond fp32 summation
- * order, and are run-to-run deterministic.
+ * One kernel, no workspace; run-to-run deterministic.
  * -------------------------------------------------------------------------- */
-PHOTON_API size_t photon_linear_workspace_bytes(int32_t M, int32_t N);
-PHOTON_API int32_t photon_linear(const float* x, const void* w, const float* bias, const float* res, float* out,
-                                 int32_t M, int32_t N, int32_t K, void* workspace, size_t workspace_bytes,
+PHOTON_API int32_t photon_linear(const float* x, const void* w, const float* gain, float rms_eps, const float* bias,
+                                 const float* res, float* out, int32_t M, int32_t N, int32_t K, int32_t epilogue,
                                  photon_dtype dt, void* stream);
 
 /* --------------------------------------------------------------------------

@@ -23,7 +23,6 @@ from .binding import (  # noqa: F401
     photon_hbm_read_probe,
     photon_last_error,
     photon_linear,
-    photon_linear_workspace_bytes,
     photon_profile_enable,
     photon_profile_get,
     photon_profile_reset,

@@ -42,8 +42,7 @@ def load_library() -> C.CDLL:
         "photon_coarse_decode_attn_auto_splits": (i32, [i32, i32, i64]),
         "photon_coarse_decode_attn": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i64, f32, i32, vp, sz, i32, vp]),
         "photon_chunk_local_attn": (i32, [vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, f32, i32, vp]),
-        "photon_linear_workspace_bytes": (sz, [i32, i32]),
-        "photon_linear": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, vp, sz, i32, vp]),
+        "photon_linear": (i32, [vp, vp, vp, f32, vp, vp, vp, i32, i32, i32, i32, i32, vp]),
     }
     for name, (res, args) in sigs.items():
         if not hasattr(lib, name):
@@ -159,18 +158,13 @@ def photon_profile_get() -> dict:
     return out
 
 
-def photon_linear_workspace_bytes(M: int, N: int) -> int:
-    return load_library().photon_linear_workspace_bytes(M, N)
-
-
-def photon_linear(x, w, out, bias=None, res=None, workspace: Optional[torch.Tensor] = None):
-    """out[M, N] = x[M, K] @ w[N, K]^T (+ bias) (+ res); x, bias, res, out fp32; w fp32 or bf16.
-    workspace: zero-initialised uint8 tensor of photon_linear_workspace_bytes(M, N) bytes, or None."""
+def photon_linear(x, w, out, gain=None, rms_eps: float = 1e-5, bias=None, res=None, epilogue: int = 0):
+    """out[M, N] = epilogue(rmsnorm(x; gain) @ w^T); x, gain, bias, res, out fp32; w fp32 or bf16.
+    epilogue 0: + bias; 1: res + . + bias; 2: silu(gate) * up with w = [gate rows; up rows]."""
     lib = load_library()
     M, K = x.shape
-    N = w.shape[0]
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib.photon_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(res), _ptr(out), M, N, K, _ptr(workspace), ws_bytes,
+    N = out.shape[1]
+    _check(lib.photon_linear(_ptr(x), _ptr(w), _ptr(gain), rms_eps, _ptr(bias), _ptr(res), _ptr(out), M, N, K, epilogue,
                              _dt(w), _stream()))
     return out
 

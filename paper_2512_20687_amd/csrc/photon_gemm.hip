@@ -173,8 +173,8 @@ extern "C" int32_t photon_chunker_project(const void* x, const void* w, const fl
   if (dt == PHOTON_F32) {
     PHOTON_REQUIRE(K % 4 == 0, PHOTON_ERR_UNSUPPORTED, "%s: fp32 path needs C*d_in (%d) to be a multiple of 4", __func__, K);
     LinearArgs a;
-    a.x = x; a.ldx = K; a.W = w; a.bias = bias; a.out = (float*)out; a.ldo = d_out; a.M = (int)rows; a.N = d_out; a.K = K;
-    return launch_linear(a, nullptr, st);
+    a.x = (const float*)x; a.ldx = K; a.W = w; a.bias = bias; a.out = (float*)out; a.ldo = d_out; a.M = (int)rows; a.N = d_out; a.K = K;
+    return launch_linear(a, st);
   }
   PHOTON_REQUIRE(K % 64 == 0 && d_out % 16 == 0, PHOTON_ERR_UNSUPPORTED,
                  "%s: bf16 path needs C*d_in (%d) to be a multiple of 64 and d_out (%d) of 16", __func__, K, d_out);

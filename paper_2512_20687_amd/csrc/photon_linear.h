@@ -6,36 +6,28 @@
 
 namespace photon {
 
-constexpr int LINEAR_MAX_KSPLIT = 16;
-constexpr int LINEAR_TARGET_WORKGROUPS = 512;
+enum LinearEpilogue { EPI_PLAIN = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
 
-// A product whose K-splits have not been added yet:
-//   value[m][n] = sum_{s < ks} data[s*split_stride + m*ld + n]
-struct Pending {
-  const float* data = nullptr;
-  int ks = 0;
-  int64_t split_stride = 0;
-  int64_t ld = 0;
-};
-
-// out[M,N] = x[M,K] * W[N,K]^T (+ bias[N]) (+ res[M,N]); out may alias res.
+// y = rmsnorm(x; gain, eps) * W^T (gain == nullptr: y = x * W^T), then
+//   EPI_PLAIN : out = y + bias
+//   EPI_RESID : out = res + y + bias            (out may alias res)
+//   EPI_SWIGLU: out = silu(y[:, :N]) * y[:, N:] (W has 2N rows: gate rows, then up rows)
 struct LinearArgs {
-  const void* x = nullptr;     // fp32 (or bf16 when x_bf16) [M, K], row pitch ldx elements
+  const float* x = nullptr;    // fp32 [M, K], row pitch ldx elements
   int64_t ldx = 0;
-  bool x_bf16 = false;
-  const void* W = nullptr;     // [N, K] row-major, bf16 when w_bf16 else fp32
+  const void* W = nullptr;     // [N, K] (2N for EPI_SWIGLU) row-major, bf16 when w_bf16 else fp32
   bool w_bf16 = false;
-  const float* bias = nullptr;
-  const float* res = nullptr;
+  const float* gain = nullptr; // [K] or nullptr
+  float eps = 0.f;
+  const float* bias = nullptr; // [N] or nullptr
+  const float* res = nullptr;  // [M, N], row pitch ldres
   int64_t ldres = 0;
-  float* out = nullptr;
+  float* out = nullptr;        // [M, N], row pitch ldo
   int64_t ldo = 0;
   int M = 0, N = 0, K = 0;
-  void* workspace = nullptr;   // split-K scratch for the partial tiles (no initialisation needed)
-  size_t workspace_bytes = 0;
+  int epilogue = EPI_PLAIN;
 };
 
-size_t linear_workspace_bytes(int max_rows, int max_N);
-int32_t launch_linear(const LinearArgs& a, Pending* pend, hipStream_t st);
+int32_t launch_linear(const LinearArgs& a, hipStream_t st);
 
 }  // namespace photon

@@ -12,46 +12,16 @@ namespace photon {
 
 // ------------------------------------------------------------------ small kernels
 
-// Sum of the K-splits of a pending product at flat element index e (see Pending in photon_linear.h).
-// All loads are issued up front (splits past ks re-read the last one with weight 0), so the latency of
-// the partial tiles, which another XCD has just written, is paid once and not once per split.
-__device__ __forceinline__ float pending_sum(const float* __restrict__ part, int ks, int64_t stride, int64_t e) {
-  float t[LINEAR_MAX_KSPLIT];
-#pragma unroll
-  for (int s2 = 0; s2 < LINEAR_MAX_KSPLIT; ++s2) t[s2] = part[(int64_t)(s2 < ks ? s2 : ks - 1) * stride + e];
-  float v = 0.f;
-#pragma unroll
-  for (int s2 = 0; s2 < LINEAR_MAX_KSPLIT; ++s2) v += (s2 < ks) ? t[s2] : 0.f;
-  return v;
-}
-__device__ __forceinline__ float4_t pending_sum4(const float* __restrict__ part, int ks, int64_t stride, int64_t e) {
-  float4_t t[LINEAR_MAX_KSPLIT];
-#pragma unroll
-  for (int s2 = 0; s2 < LINEAR_MAX_KSPLIT; ++s2)
-    t[s2] = *reinterpret_cast<const float4_t*>(part + (int64_t)(s2 < ks ? s2 : ks - 1) * stride + e);
-  float4_t v = float4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int s2 = 0; s2 < LINEAR_MAX_KSPLIT; ++s2)
-    if (s2 < ks) v += t[s2];
-  return v;
-}
-
-// Row i of the input is  x = res[src] + sum_s part[s][src] + bias[src % bias_rows]   with src = i*in_mul + in_off
-// (each term optional; rows are D floats, D a multiple of 4).  Writes x to h_out[i] (the updated residual
-// stream, optional) and rmsnorm(x) * g to out[i*out_mul + out_off].
-__global__ __launch_bounds__(256) void norm_rows_kernel(const float* res, const float* __restrict__ part, int ks, int64_t stride,
-                                                        const float* __restrict__ bias, int bias_rows, float* h_out,
-                                                        int in_mul, int in_off, const float* __restrict__ g, float eps,
-                                                        float* __restrict__ out, int out_mul, int out_off, int D) {
+// out[i*out_mul + out_off] = rmsnorm(in[i*in_mul + in_off]) * g ; rows of D floats, D a multiple of 4.
+__global__ __launch_bounds__(256) void norm_rows_kernel(const float* __restrict__ in, int in_mul, int in_off,
+                                                        const float* __restrict__ g, float eps, float* __restrict__ out,
+                                                        int out_mul, int out_off, int D) {
   extern __shared__ float4_t xrow[];
   const int i = blockIdx.x, tid = threadIdx.x;
-  const int64_t src = (int64_t)i * in_mul + in_off;
+  const float* x = in + ((int64_t)i * in_mul + in_off) * D;
   float ss = 0.f;
   for (int d = tid * 4; d < D; d += 1024) {
-    float4_t v = float4_t{0.f, 0.f, 0.f, 0.f};
-    if (res != nullptr) v = *reinterpret_cast<const float4_t*>(res + src * D + d);
-    if (part != nullptr) v += pending_sum4(part, ks, stride, src * D + d);
-    if (bias != nullptr) v += *reinterpret_cast<const float4_t*>(bias + (src % bias_rows) * D + d);
+    const float4_t v = *reinterpret_cast<const float4_t*>(x + d);
     xrow[d >> 2] = v;
     ss = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss))));
   }
@@ -64,10 +34,8 @@ __global__ __launch_bounds__(256) void norm_rows_kernel(const float* res, const 
   const float r = 1.0f / sqrtf(tot / (float)D + eps);
   float* o = out + ((int64_t)i * out_mul + out_off) * D;
   for (int d = tid * 4; d < D; d += 1024) {
-    const float4_t v = xrow[d >> 2];
-    if (h_out != nullptr) *reinterpret_cast<float4_t*>(h_out + (int64_t)i * D + d) = v;
     const float4_t gv = *reinterpret_cast<const float4_t*>(g + d);
-    *reinterpret_cast<float4_t*>(o + d) = v * r * gv;
+    *reinterpret_cast<float4_t*>(o + d) = xrow[d >> 2] * r * gv;
   }
 }
 
@@ -81,8 +49,7 @@ __device__ __forceinline__ void rope_angle(int pos, int i, int d_h, float theta,
 
 // Local decoder: rotate q and k of every row at its window position, write q to
 // qrot [rows, D] and k, v into the chunk's local cache [n_chunks, W, H, d_h] (fp32).
-__global__ __launch_bounds__(256) void rope_append_local_kernel(const float* __restrict__ qkv, int ks, int64_t stride,
-                                                                float* __restrict__ qrot,
+__global__ __launch_bounds__(256) void rope_append_local_kernel(const float* __restrict__ qkv, float* __restrict__ qrot,
                                                                 float* __restrict__ lk, float* __restrict__ lv,
                                                                 int rows, int q_len, int q_pos, int W, int H, int d_h,
                                                                 float theta) {
@@ -95,24 +62,23 @@ __global__ __launch_bounds__(256) void rope_append_local_kernel(const float* __r
   const int chunk = row / q_len, pos = q_pos + row % q_len;
   float c, s;
   rope_angle(pos, i, d_h, theta, c, s);
-  const int64_t e = (int64_t)row * 3 * D + h * d_h;
-  const float qa = pending_sum(qkv, ks, stride, e + i), qb = pending_sum(qkv, ks, stride, e + i + half);
-  const float ka = pending_sum(qkv, ks, stride, e + D + i), kb = pending_sum(qkv, ks, stride, e + D + i + half);
+  const float* src = qkv + (int64_t)row * 3 * D + h * d_h;
+  const float qa = src[i], qb = src[i + half];
+  const float ka = src[D + i], kb = src[D + i + half];
   float* qd = qrot + (int64_t)row * D + h * d_h;
   qd[i] = qa * c - qb * s;
   qd[i + half] = qb * c + qa * s;
   const int64_t slot = (((int64_t)chunk * W + pos) * H + h) * d_h;
   lk[slot + i] = ka * c - kb * s;
   lk[slot + i + half] = kb * c + ka * s;
-  lv[slot + i] = pending_sum(qkv, ks, stride, e + 2 * D + i);
-  lv[slot + i + half] = pending_sum(qkv, ks, stride, e + 2 * D + i + half);
+  lv[slot + i] = src[2 * D + i];
+  lv[slot + i + half] = src[2 * D + i + half];
 }
 
 // Top-level STEP: position of sequence b is seq_len[b]-1 (the count already includes the new entry);
 // k, v go to cache[b, h, pos, :] of this layer.
 template <typename TKV>
-__global__ __launch_bounds__(256) void rope_append_coarse_kernel(const float* __restrict__ qkv, int ks, int64_t stride,
-                                                                 float* __restrict__ qrot,
+__global__ __launch_bounds__(256) void rope_append_coarse_kernel(const float* __restrict__ qkv, float* __restrict__ qrot,
                                                                  TKV* __restrict__ kc, TKV* __restrict__ vc,
                                                                  const int32_t* __restrict__ seq_len, int Bt, int H,
                                                                  int d_h, int64_t S_max, float theta) {
@@ -125,9 +91,9 @@ __global__ __launch_bounds__(256) void rope_append_coarse_kernel(const float* __
   const int pos = seq_len[b] - 1;
   float c, s;
   rope_angle(pos, i, d_h, theta, c, s);
-  const int64_t e = (int64_t)b * 3 * D + h * d_h;
-  const float qa = pending_sum(qkv, ks, stride, e + i), qb = pending_sum(qkv, ks, stride, e + i + half);
-  const float ka = pending_sum(qkv, ks, stride, e + D + i), kb = pending_sum(qkv, ks, stride, e + D + i + half);
+  const float* src = qkv + (int64_t)b * 3 * D + h * d_h;
+  const float qa = src[i], qb = src[i + half];
+  const float ka = src[D + i], kb = src[D + i + half];
   float* qd = qrot + (int64_t)b * D + h * d_h;
   qd[i] = qa * c - qb * s;
   qd[i + half] = qb * c + qa * s;
@@ -135,19 +101,8 @@ __global__ __launch_bounds__(256) void rope_append_coarse_kernel(const float* __
   const int64_t slot = (((int64_t)b * H + h) * S_max + pos) * d_h;
   kc[slot + i] = from_f32<TKV>(ka * c - kb * s);
   kc[slot + i + half] = from_f32<TKV>(kb * c + ka * s);
-  vc[slot + i] = from_f32<TKV>(pending_sum(qkv, ks, stride, e + 2 * D + i));
-  vc[slot + i + half] = from_f32<TKV>(pending_sum(qkv, ks, stride, e + 2 * D + i + half));
-}
-
-// act[r, f] = silu(gu[r, f]) * gu[r, F + f]
-__global__ __launch_bounds__(256) void silu_mul_kernel(const float* __restrict__ gu, int ks, int64_t stride,
-                                                       float* __restrict__ act, int64_t total, int F) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= total) return;
-  const int64_t r = idx / F;
-  const int f = (int)(idx % F);
-  const float g = pending_sum(gu, ks, stride, r * 2 * F + f), u = pending_sum(gu, ks, stride, r * 2 * F + F + f);
-  act[idx] = g / (1.0f + __expf(-g)) * u;
+  vc[slot + i] = from_f32<TKV>(src[2 * D + i]);
+  vc[slot + i + half] = from_f32<TKV>(src[2 * D + i + half]);
 }
 
 // Token choice for one row of logits (greedy, lowest index on ties, or the forced token), then the
@@ -225,8 +180,8 @@ struct Plan {
   int64_t chunks[PHOTON_MAX_LEVELS + 1] = {0};   // chunks[l], l = 1..L: chunks decoded per step at level l
   int64_t rows_max = 0;
   int n_splits = 1;
-  size_t lin_ws = 0, lin_ws_bytes = 0, coarse_ws = 0, coarse_ws_bytes = 0;
-  size_t h = 0, xn = 0, attn = 0, qrot = 0, act = 0, cond = 0, logits = 0, a_hat = 0;
+  size_t coarse_ws = 0, coarse_ws_bytes = 0;
+  size_t h = 0, attn = 0, qkv = 0, qrot = 0, act = 0, cond = 0, logits = 0, a_hat = 0;
   size_t fresh[PHOTON_MAX_LEVELS] = {0};         // fresh[l]: new level-l units, l = 0..L-1
   size_t lk[PHOTON_MAX_LEVELS] = {0}, lv[PHOTON_MAX_LEVELS] = {0};   // local caches of level l (index l-1), all layers
   size_t total = 0;
@@ -248,21 +203,14 @@ static Plan make_plan(const photon_config& c, int Bt, int64_t S_max) {
     if (r > p.rows_max) p.rows_max = r;
   }
   const int64_t D = c.D, F = c.d_ff;
-  int64_t maxN = 3 * D;
-  if (2 * F > maxN) maxN = 2 * F;
-  if (c.vocab > maxN) maxN = c.vocab;
-  for (int l = 0; l < c.L; ++l)
-    if ((int64_t)c.R[l] * D > maxN) maxN = (int64_t)c.R[l] * D;
   p.n_splits = coarse_auto_splits(Bt, c.H, S_max);
   size_t cur = 0;
-  p.lin_ws_bytes = linear_workspace_bytes((int)p.rows_max, (int)maxN);
-  p.lin_ws = bump(cur, p.lin_ws_bytes);
   p.coarse_ws_bytes = photon_coarse_decode_attn_workspace_bytes(Bt, c.H, c.d_h, p.n_splits);
   p.coarse_ws = bump(cur, p.coarse_ws_bytes);
   const size_t f = sizeof(float);
   p.h = bump(cur, p.rows_max * D * f);
-  p.xn = bump(cur, p.rows_max * D * f);
   p.attn = bump(cur, p.rows_max * D * f);
+  p.qkv = bump(cur, p.rows_max * 3 * D * f);
   p.qrot = bump(cur, p.rows_max * D * f);
   p.act = bump(cur, p.rows_max * F * f);
   p.cond = bump(cur, p.rows_max * D * f);
@@ -321,75 +269,62 @@ struct Ctx {
   float* f(size_t off) const { return reinterpret_cast<float*>(base + off); }
 };
 
-// Rows entering a module: x = res[i*mul + off] + pending + bias (each optional).
-struct RowsIn {
-  const float* res = nullptr;
-  int mul = 1, off = 0;
-  Pending pend;
-  const float* bias = nullptr;
-  int bias_rows = 1;
-};
-
 #define PHOTON_TRY(expr) do { const int32_t rc_ = (expr); if (rc_ != PHOTON_OK) return rc_; } while (0)
 
-// Product left pending in the shared split-K workspace; the very next kernel must consume it.
-static int32_t linear_pending(const Ctx& x, const float* in, int64_t ldx, const void* W, int M, int N, int K, Pending* pend) {
+// Rows entering a module pass: row i of the pass lives at in[i * ld] (D floats).
+struct RowsIn {
+  const float* ptr = nullptr;
+  int64_t ld = 0;
+};
+
+static int32_t linear(const Ctx& x, const float* in, int64_t ldx, const void* W, const float* gain, const float* bias,
+                      const float* res, int64_t ldres, float* out, int64_t ldo, int M, int N, int K, int epilogue) {
   LinearArgs a;
-  a.x = in; a.ldx = ldx; a.W = W; a.w_bf16 = x.bf16; a.M = M; a.N = N; a.K = K;
-  a.workspace = x.base + x.p.lin_ws; a.workspace_bytes = x.p.lin_ws_bytes;
-  return launch_linear(a, pend, x.st);
+  a.x = in; a.ldx = ldx; a.W = W; a.w_bf16 = x.bf16; a.gain = gain; a.eps = x.c->rms_eps; a.bias = bias; a.res = res;
+  a.ldres = ldres; a.out = out; a.ldo = ldo; a.M = M; a.N = N; a.K = K; a.epilogue = epilogue;
+  return launch_linear(a, x.st);
 }
 
-static int32_t norm(const Ctx& x, const RowsIn& in, float* h_out, const float* g, float* out, int out_mul, int out_off, int rows) {
-  PHOTON_LAUNCH(KC_NORM, x.st, norm_rows_kernel, dim3(rows), dim3(256), x.c->D * sizeof(float), x.st, in.res, in.pend.data, in.pend.ks,
-                     in.pend.split_stride, in.bias, in.bias_rows, h_out, in.mul, in.off, g, x.c->rms_eps, out, out_mul, out_off,
-                     x.c->D);
+static int32_t norm(const Ctx& x, const float* in, int in_mul, int in_off, const float* g, float* out, int out_mul, int out_off,
+                    int rows) {
+  PHOTON_LAUNCH(KC_NORM, x.st, norm_rows_kernel, dim3(rows), dim3(256), x.c->D * sizeof(float), x.st, in, in_mul, in_off, g,
+                x.c->rms_eps, out, out_mul, out_off, x.c->D);
   return check_launch("norm_rows_kernel");
 }
 
-// SwiGLU sub-layer: consumes the pending attention output (h += pend), leaves the down-projection pending.
-static int32_t mlp(const Ctx& x, const photon_layer_weights& lw, int rows, Pending* pend) {
+// Tail of a block once the attention output sits in p.attn: O projection + residual into p.h, then the
+// SwiGLU sub-layer.  `in` is the block's input (the residual stream before the block).
+static int32_t block_tail(const Ctx& x, const photon_layer_weights& lw, RowsIn in, int rows) {
   const photon_config& c = *x.c;
+  float *h = x.f(x.p.h), *attn = x.f(x.p.attn), *act = x.f(x.p.act);
+  PHOTON_TRY(linear(x, attn, c.D, lw.wo, nullptr, nullptr, in.ptr, in.ld, h, c.D, rows, c.D, c.D, EPI_RESID));
   if (c.d_ff == 0) return PHOTON_OK;
-  float *h = x.f(x.p.h), *xn = x.f(x.p.xn), *act = x.f(x.p.act);
-  RowsIn in;
-  in.res = h; in.pend = *pend;
-  PHOTON_TRY(norm(x, in, h, lw.g2, xn, 1, 0, rows));
-  Pending gu;
-  PHOTON_TRY(linear_pending(x, xn, c.D, lw.wgu, rows, 2 * c.d_ff, c.D, &gu));
-  const int64_t total = (int64_t)rows * c.d_ff;
-  PHOTON_LAUNCH(KC_SILU_MUL, x.st, silu_mul_kernel, dim3(blocks_for(total)), dim3(256), 0, x.st, gu.data, gu.ks, gu.split_stride, act, total,
-                     c.d_ff);
-  PHOTON_TRY(check_launch("silu_mul_kernel"));
-  return linear_pending(x, act, c.d_ff, lw.wd, rows, c.D, c.d_ff, pend);
+  PHOTON_TRY(linear(x, h, c.D, lw.wgu, lw.g2, nullptr, nullptr, 0, act, c.d_ff, rows, c.d_ff, c.D, EPI_SWIGLU));
+  return linear(x, act, c.d_ff, lw.wd, nullptr, nullptr, h, c.D, h, c.D, rows, c.D, c.d_ff, EPI_RESID);
 }
 
 // All blocks of the level-`level` local decoder on n_chunks * q_len rows (window positions
-// q_pos .. q_pos+q_len-1 of every chunk).  On return the residual stream is p.h + *pend.
-static int32_t local_module_pass(const Ctx& x, int level, int64_t n_chunks, int q_len, int q_pos, RowsIn in, Pending* pend) {
+// q_pos .. q_pos+q_len-1 of every chunk).  Leaves the residual stream in p.h.
+static int32_t local_module_pass(const Ctx& x, int level, int64_t n_chunks, int q_len, int q_pos, RowsIn in) {
   const photon_config& c = *x.c;
   const photon_module_weights& mod = x.w->dec[level - 1];
   const int W = c.R[level - 1] + c.C[level - 1] - 1;
   const int rows = (int)(n_chunks * q_len);
-  float *h = x.f(x.p.h), *xn = x.f(x.p.xn), *qrot = x.f(x.p.qrot), *attn = x.f(x.p.attn);
+  float *h = x.f(x.p.h), *qkv = x.f(x.p.qkv), *qrot = x.f(x.p.qrot), *attn = x.f(x.p.attn);
   const size_t layer_cache = (size_t)n_chunks * W * c.D;
   const float scale = 1.0f / sqrtf((float)c.d_h);
   for (int i = 0; i < c.n_layers; ++i) {
     const photon_layer_weights& lw = mod.layers[i];
     float* lk = x.f(x.p.lk[level - 1]) + (size_t)i * layer_cache;
     float* lv = x.f(x.p.lv[level - 1]) + (size_t)i * layer_cache;
-    PHOTON_TRY(norm(x, in, h, lw.g1, xn, 1, 0, rows));
-    Pending qkv;
-    PHOTON_TRY(linear_pending(x, xn, c.D, lw.wqkv, rows, 3 * c.D, c.D, &qkv));
+    PHOTON_TRY(linear(x, in.ptr, in.ld, lw.wqkv, lw.g1, nullptr, nullptr, 0, qkv, 3 * c.D, rows, 3 * c.D, c.D, EPI_PLAIN));
     const int64_t n_el = (int64_t)rows * c.H * (c.d_h / 2);
-    PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_local_kernel, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv.data, qkv.ks, qkv.split_stride,
-                       qrot, lk, lv, rows, q_len, q_pos, W, c.H, c.d_h, c.rope_theta);
+    PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_local_kernel, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot, lk, lv,
+                  rows, q_len, q_pos, W, c.H, c.d_h, c.rope_theta);
     PHOTON_TRY(check_launch("rope_append_local_kernel"));
     PHOTON_TRY(launch_local_attn(true, c.d_h, qrot, lk, lv, attn, n_chunks, W, q_len, q_pos, c.H, scale, x.st));
-    PHOTON_TRY(linear_pending(x, attn, c.D, lw.wo, rows, c.D, c.D, pend));
-    PHOTON_TRY(mlp(x, lw, rows, pend));
-    in = RowsIn{};
-    in.res = h; in.pend = *pend;
+    PHOTON_TRY(block_tail(x, lw, in, rows));
+    in.ptr = h; in.ld = c.D;
   }
   return PHOTON_OK;
 }
@@ -399,36 +334,29 @@ static int32_t top_step(const Ctx& x, RowsIn in) {
   const photon_config& c = *x.c;
   const photon_module_weights& mod = x.w->top;
   const int rows = x.Bt;
-  float *h = x.f(x.p.h), *xn = x.f(x.p.xn), *qrot = x.f(x.p.qrot), *attn = x.f(x.p.attn);
+  float *h = x.f(x.p.h), *qkv = x.f(x.p.qkv), *qrot = x.f(x.p.qrot), *attn = x.f(x.p.attn);
   const size_t esz = dtype_size(c.dt);
   const size_t layer_cache = (size_t)x.Bt * c.H * x.s->S_max * c.d_h * esz;
   const float scale = 1.0f / sqrtf((float)c.d_h);
-  Pending pend;
   for (int i = 0; i < c.n_layers; ++i) {
     const photon_layer_weights& lw = mod.layers[i];
     char* kc = reinterpret_cast<char*>(x.s->k_cache) + (size_t)i * layer_cache;
     char* vc = reinterpret_cast<char*>(x.s->v_cache) + (size_t)i * layer_cache;
-    PHOTON_TRY(norm(x, in, h, lw.g1, xn, 1, 0, rows));
-    Pending qkv;
-    PHOTON_TRY(linear_pending(x, xn, c.D, lw.wqkv, rows, 3 * c.D, c.D, &qkv));
+    PHOTON_TRY(linear(x, in.ptr, in.ld, lw.wqkv, lw.g1, nullptr, nullptr, 0, qkv, 3 * c.D, rows, 3 * c.D, c.D, EPI_PLAIN));
     const int64_t n_el = (int64_t)rows * c.H * (c.d_h / 2);
     if (x.bf16)
-      PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_coarse_kernel<bf16_t>, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv.data, qkv.ks,
-                         qkv.split_stride, qrot, (bf16_t*)kc, (bf16_t*)vc, x.s->seq_len, x.Bt, c.H, c.d_h, x.s->S_max,
-                         c.rope_theta);
+      PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_coarse_kernel<bf16_t>, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot,
+                    (bf16_t*)kc, (bf16_t*)vc, x.s->seq_len, x.Bt, c.H, c.d_h, x.s->S_max, c.rope_theta);
     else
-      PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_coarse_kernel<float>, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv.data, qkv.ks,
-                         qkv.split_stride, qrot, (float*)kc, (float*)vc, x.s->seq_len, x.Bt, c.H, c.d_h, x.s->S_max,
-                         c.rope_theta);
+      PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_coarse_kernel<float>, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot,
+                    (float*)kc, (float*)vc, x.s->seq_len, x.Bt, c.H, c.d_h, x.s->S_max, c.rope_theta);
     PHOTON_TRY(check_launch("rope_append_coarse_kernel"));
     PHOTON_TRY(launch_coarse_attn(x.bf16 ? KV_BF16 : KV_F32, true, c.d_h, qrot, kc, vc, x.s->seq_len, attn, x.Bt, c.H,
                                   x.s->S_max, scale, x.p.n_splits, x.base + x.p.coarse_ws, x.st));
-    PHOTON_TRY(linear_pending(x, attn, c.D, lw.wo, rows, c.D, c.D, &pend));
-    PHOTON_TRY(mlp(x, lw, rows, &pend));
-    in = RowsIn{};
-    in.res = h; in.pend = pend;
+    PHOTON_TRY(block_tail(x, lw, in, rows));
+    in.ptr = h; in.ld = c.D;
   }
-  return norm(x, in, nullptr, mod.g_final, x.s->x_top, 1, 0, rows);
+  return norm(x, h, 1, 0, mod.g_final, x.s->x_top, 1, 0, rows);
 }
 
 static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* out_tokens, const photon_trace* tr) {
@@ -449,41 +377,34 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
     const int64_t n = x.p.chunks[l];
     const photon_module_weights& mod = x.w->dec[l - 1];
     float* units = fresh[l - 1];                           // [n * C, D]: chunk-major, item j of chunk ch at row ch*C + j
-    // sub-step 0: the converter's R vectors at window positions 0..R-1 (row ch*R + r of a flat [n*R, D] view)
+    // sub-step 0: the converter's R vectors at window positions 0..R-1 (row ch*R + r of a flat [n*R, D] view of p.h)
+    PHOTON_TRY(linear(x, cond_in, D, x.w->conv_w[l - 1], nullptr, x.w->conv_b[l - 1], nullptr, 0, h, (int64_t)R * D, (int)n, R * D,
+                      D, EPI_PLAIN));
     RowsIn in;
-    PHOTON_TRY(linear_pending(x, cond_in, D, x.w->conv_w[l - 1], (int)n, R * D, D, &in.pend));
-    in.bias = x.w->conv_b[l - 1];
-    in.bias_rows = R;
+    in.ptr = h; in.ld = D;
     for (int j = 0; j < C; ++j) {
       const int q_len = (j == 0) ? R : 1;
       const int q_pos = (j == 0) ? 0 : R + j - 1;
-      Pending last;
-      PHOTON_TRY(local_module_pass(x, l, n, q_len, q_pos, in, &last));
+      PHOTON_TRY(local_module_pass(x, l, n, q_len, q_pos, in));
       // item j = final norm of the last row of each chunk
-      RowsIn fin;
-      fin.res = h; fin.mul = q_len; fin.off = q_len - 1; fin.pend = last;
-      PHOTON_TRY(norm(x, fin, nullptr, mod.g_final, units, C, j, (int)n));
-      in = RowsIn{};
+      PHOTON_TRY(norm(x, h, q_len, q_len - 1, mod.g_final, units, C, j, (int)n));
       if (l >= 2) {                                        // Eq. 6: the module's own output is the next input
-        in.res = units; in.mul = C; in.off = j;
+        in.ptr = units + (int64_t)j * D; in.ld = (int64_t)C * D;
       } else {
         float* lg = (tr && tr->logits) ? tr->logits + (int64_t)j * c.vocab : x.f(x.p.logits);
         const int64_t ld = (tr && tr->logits) ? (int64_t)C * c.vocab : c.vocab;
         // logits of item j of every chunk: rows of `units` with pitch C*D
-        LinearArgs a;
-        a.x = units + (int64_t)j * D; a.ldx = (int64_t)C * D; a.W = x.w->W_lm; a.w_bf16 = x.bf16;
-        a.out = lg; a.ldo = ld; a.M = (int)n; a.N = c.vocab; a.K = D;
-        a.workspace = x.base + x.p.lin_ws; a.workspace_bytes = x.p.lin_ws_bytes;
-        PHOTON_TRY(launch_linear(a, nullptr, x.st));
+        PHOTON_TRY(linear(x, units + (int64_t)j * D, (int64_t)C * D, x.w->W_lm, nullptr, nullptr, nullptr, 0, lg, ld, (int)n,
+                          c.vocab, D, EPI_PLAIN));
         float* x_next = (j + 1 < C) ? h : nullptr;         // decoder-side embedding of the chosen token
         if (x.bf16)
-          PHOTON_LAUNCH(KC_CHOOSE_TOKEN, x.st, choose_token_kernel<bf16_t>, dim3((unsigned)n), dim3(256), 0, x.st, lg, ld, c.vocab, forced,
-                             out_tokens, C, j, (const bf16_t*)x.w->E_dec, x_next, D);
+          PHOTON_LAUNCH(KC_CHOOSE_TOKEN, x.st, choose_token_kernel<bf16_t>, dim3((unsigned)n), dim3(256), 0, x.st, lg, ld, c.vocab,
+                        forced, out_tokens, C, j, (const bf16_t*)x.w->E_dec, x_next, D);
         else
-          PHOTON_LAUNCH(KC_CHOOSE_TOKEN, x.st, choose_token_kernel<float>, dim3((unsigned)n), dim3(256), 0, x.st, lg, ld, c.vocab, forced,
-                             out_tokens, C, j, (const float*)x.w->E_dec, x_next, D);
+          PHOTON_LAUNCH(KC_CHOOSE_TOKEN, x.st, choose_token_kernel<float>, dim3((unsigned)n), dim3(256), 0, x.st, lg, ld, c.vocab,
+                        forced, out_tokens, C, j, (const float*)x.w->E_dec, x_next, D);
         PHOTON_TRY(check_launch("choose_token_kernel"));
-        in.res = h;
+        in.ptr = h; in.ld = D;
       }
     }
     if (l >= 2) {
@@ -491,10 +412,10 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
       const int64_t per_seq = n * C / Bt;
       float* carry = x.s->carry + (int64_t)(l - 2) * Bt * D;
       PHOTON_LAUNCH(KC_MISC, x.st, shift_condition_kernel, dim3(blocks_for(n * C * D)), dim3(256), 0, x.st, units, carry, cond, Bt,
-                         (int)per_seq, D);
+                    (int)per_seq, D);
       PHOTON_TRY(check_launch("shift_condition_kernel"));
       PHOTON_LAUNCH(KC_MISC, x.st, update_carry_kernel, dim3(blocks_for((int64_t)Bt * D)), dim3(256), 0, x.st, units, carry, Bt,
-                         (int)per_seq, D);
+                    (int)per_seq, D);
       PHOTON_TRY(check_launch("update_carry_kernel"));
       cond_in = cond;
     }
@@ -502,19 +423,11 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
 
   // (ii) top chunker on the C_L new level-(L-1) units of every sequence, (iii) STEP
   const int CL = c.C[L - 1];
+  float* a_hat = (tr && tr->a_hat) ? tr->a_hat : x.f(x.p.a_hat);
+  PHOTON_TRY(linear(x, fresh[L - 1], (int64_t)CL * D, x.w->chunker_w, nullptr, x.w->chunker_b, nullptr, 0, a_hat, D, Bt, D, CL * D,
+                    EPI_PLAIN));
   RowsIn top_in;
-  if (tr && tr->a_hat) {
-    LinearArgs a;
-    a.x = fresh[L - 1]; a.ldx = (int64_t)CL * D; a.W = x.w->chunker_w; a.w_bf16 = x.bf16; a.bias = x.w->chunker_b;
-    a.out = tr->a_hat; a.ldo = D; a.M = Bt; a.N = D; a.K = CL * D;
-    a.workspace = x.base + x.p.lin_ws; a.workspace_bytes = x.p.lin_ws_bytes;
-    PHOTON_TRY(launch_linear(a, nullptr, x.st));
-    top_in.res = tr->a_hat;
-  } else {
-    PHOTON_TRY(linear_pending(x, fresh[L - 1], (int64_t)CL * D, x.w->chunker_w, Bt, D, CL * D, &top_in.pend));
-    top_in.bias = x.w->chunker_b;
-    top_in.bias_rows = 1;
-  }
+  top_in.ptr = a_hat; top_in.ld = D;
   return top_step(x, top_in);
 }
 

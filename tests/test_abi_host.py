@@ -53,6 +53,11 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.photon_chunk_local_attn(p, p, p, p, 4, 4, 2, 3, 2, 64, 0.1, 1, None) == -1
     assert lib.photon_chunk_local_attn(p, p, p, p, 4, 4, 4, 0, 2, 48, 0.1, 1, None) == -2
     assert lib.photon_chunk_local_attn(None, p, p, p, 4, 4, 4, 0, 2, 64, 0.1, 1, None) == -1
+    # few-row linear map: bad epilogue, bad sizes
+    assert lib.photon_linear(p, p, None, 1e-5, None, None, p, 4, 64, 64, 7, 1, None) == -1
+    assert lib.photon_linear(p, p, None, 1e-5, None, None, p, 4, 64, 100, 0, 1, None) == -2
+    assert lib.photon_linear(p, p, None, 1e-5, None, None, p, 4, 64, 64, 1, 1, None) == -1      # residual without res
+    assert lib.photon_linear(p, p, None, 1e-5, None, None, p, 0, 64, 64, 0, 1, None) == 0       # no rows: no-op
     # workspace size formula
     assert lib.photon_coarse_decode_attn_workspace_bytes(4, 32, 64, 8) == 4 * 32 * 8 * 66 * 4
     assert lib.photon_coarse_decode_attn_workspace_bytes(4, 32, 64, 1) == 0

@@ -1,0 +1,80 @@
+"""GPU parity of photon_linear (few-row linear map with fused pre-norm and
+epilogues) against the oracle's building blocks."""
+import numpy as np
+import pytest
+import torch
+
+import seeded_inputs as si
+from oracle import photon_oracle as po
+from util import TOL, dev, nerr, require_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_linear(x, w, gain, eps, bias, res, epilogue, N):
+    z = po.rmsnorm(x, gain, eps) if gain is not None else po.f64(x)
+    y = po.linear(z, w)
+    if epilogue == 2:
+        g, u = y[:, :N], y[:, N:]
+        y = g / (1.0 + np.exp(-g)) * u
+    if bias is not None:
+        y = y + bias
+    if epilogue == 1:
+        y = y + res
+    return y
+
+
+def case(dtype, M, N, K, epilogue, norm, bias, seed=0):
+    import paper_2512_20687_amd as ph
+    rows_w = 2 * N if epilogue == 2 else N
+    x = si.make_normal((M, K), seed, "f32")
+    w = si.make_normal((rows_w, K), seed + 1, dtype, std=0.05)
+    gain = si.make_normal((K,), seed + 2, "f32", std=0.3) + 1.0 if norm else None
+    b = si.make_normal((N,), seed + 3, "f32", std=0.1) if bias else None
+    res = si.make_normal((M, N), seed + 4, "f32") if epilogue == 1 else None
+    ref = oracle_linear(x, w, gain, 1e-5, b, res, epilogue, N)
+    out = torch.full((M, N), float("nan"), device="cuda")
+    opt = lambda a: None if a is None else dev(np.asarray(a, np.float32))
+    ph.photon_linear(dev(x), dev(w, dtype), out, gain=opt(gain), rms_eps=1e-5, bias=opt(b), res=opt(res), epilogue=epilogue)
+    torch.cuda.synchronize()
+    return out, ref
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,N,K", [(1, 64, 64), (4, 192, 256), (16, 96, 640), (17, 48, 128), (70, 160, 192)])
+@pytest.mark.parametrize("epilogue,norm,bias", [(0, False, False), (0, True, True), (1, False, True), (1, True, False), (2, True, False), (2, False, False)])
+def test_linear_parity(dtype, M, N, K, epilogue, norm, bias):
+    require_gpu()
+    out, ref = case(dtype, M, N, K, epilogue, norm, bias)
+    # fp32 activations against bf16 weights keep fp32-level accuracy (the weights are exact bf16 values)
+    assert nerr(out, ref) <= TOL["f32"] * (1 if dtype == "f32" else 2)
+
+
+@pytest.mark.parametrize("M,N,K,epilogue,norm", [
+    (16, 6144, 2048, 0, True),       # configuration 3: QKV with pre-norm, token level
+    (4, 2048, 2048, 1, False),       # O projection + residual
+    (16, 5120, 2048, 2, True),       # gate/up with SwiGLU
+    (16, 2048, 5120, 1, False),      # down projection + residual (ragged chunk count)
+    (16, 32000, 2048, 0, False),     # LM head
+    (4, 2048, 8192, 0, False),       # top chunker at decode shape
+    (64, 3072, 1024, 0, True),       # configuration 2, token level: four row tiles
+])
+def test_linear_real_shapes(M, N, K, epilogue, norm):
+    require_gpu()
+    out, ref = case("bf16", M, N, K, epilogue, norm, bias=(epilogue == 0), seed=3)
+    assert nerr(out, ref) <= 2 * TOL["f32"]
+
+
+def test_linear_in_place_residual_and_determinism():
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    M, N, K = 8, 256, 512
+    x = dev(si.make_normal((M, K), 1, "f32"))
+    w = dev(si.make_normal((N, K), 2, "bf16", std=0.05), "bf16")
+    h0 = si.make_normal((M, N), 3, "f32")
+    a, b = dev(h0), dev(h0)
+    ph.photon_linear(x, w, a, res=a, epilogue=1)
+    ph.photon_linear(x, w, b, res=b, epilogue=1)
+    assert torch.equal(a, b)
+    ref = h0 + po.linear(x.cpu().numpy(), w.float().cpu().numpy())
+    assert nerr(a, ref) <= 2 * TOL["f32"]
