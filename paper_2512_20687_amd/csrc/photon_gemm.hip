@@ -3,11 +3,11 @@
 //
 // One workgroup of 4 waves owns a 256x256 output tile; each wave owns a 128x128
 // quadrant as 4x4 MFMA 32x32x16 tiles (256 fp32 accumulators per lane).  K is
-// walked in 64-wide slabs, double-buffered in LDS (2 x 64 KB); the next slab's
-// global loads are issued before the current slab's MFMAs and parked in
-// registers.  LDS rows are 128 bytes with the 16-byte column index XOR-ed by
-// (row>>1)&7, which keeps the 128-bit operand reads of 16 consecutive rows on
-// distinct banks.  Workgroup ids are remapped so that the tiles resident on one
+// walked in 64-wide slabs, double-buffered in LDS (2 x 64 KB); the next slab is
+// moved global -> LDS directly (no staging registers) while the current slab's
+// MFMAs run, and operand fragments are double-buffered in registers.  LDS rows
+// are 128 bytes with the 16-byte column index XOR-ed by (row>>1)&7, which keeps
+// the 128-bit operand reads of 16 consecutive rows on distinct banks.  Workgroup ids are remapped so that the tiles resident on one
 // XCD at a time share x row-blocks and W column-blocks in that XCD's L2.
 #include "photon_device.h"
 #include "photon_host.h"
@@ -24,6 +24,9 @@ constexpr int G_TILE_BYTES = G_BM * G_BK * 2;          // 32 KB per operand slab
 
 __device__ __forceinline__ int swz(int row, int col16) { return row * 128 + ((col16 ^ ((row >> 1) & 7)) << 4); }
 
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
 __global__ __launch_bounds__(G_THREADS) void chunker_gemm_bf16_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const float* __restrict__ bias, bf16_t* __restrict__ Cout,
     int M, int N, int K, int tiles_m, int tiles_n) {
@@ -38,31 +41,29 @@ __global__ __launch_bounds__(G_THREADS) void chunker_gemm_bf16_kernel(
   const int tm = logical / tiles_n, tn = logical % tiles_n;
   const int m0 = tm * G_BM, n0 = tn * G_BN;
 
-  // global -> register staging: each thread moves 8 x 16 B of A and of B per slab
-  // thread t covers row (t>>3) + 32*i, 16-byte column (t&7)
-  const int lrow = tid >> 3, lcol = tid & 7;
+  // global -> LDS without passing through registers: one instruction moves 64 lanes x 16 B = 8 slab rows;
+  // lane l lands at LDS row l/8, 16-byte column l%8, so it fetches the logical column that the XOR
+  // swizzle maps there.  Round i of wave w covers slab rows i*32 + w*8 .. +8.
+  const int srow = lane >> 3, scol = lane & 7;
   const bf16_t* aptr[8];
   const bf16_t* bptr[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    int ra = m0 + lrow + 32 * i; ra = ra < M ? ra : M - 1;       // clamped rows are never stored
-    int rb = n0 + lrow + 32 * i; rb = rb < N ? rb : N - 1;
-    aptr[i] = A + (int64_t)ra * K + lcol * 8;
-    bptr[i] = B + (int64_t)rb * K + lcol * 8;
+    const int r = i * 32 + wave * 8 + srow;
+    const int c = scol ^ ((r >> 1) & 7);
+    int ra = m0 + r; ra = ra < M ? ra : M - 1;                   // clamped rows are never stored
+    int rb = n0 + r; rb = rb < N ? rb : N - 1;
+    aptr[i] = A + (int64_t)ra * K + c * 8;
+    bptr[i] = B + (int64_t)rb * K + c * 8;
   }
-  uint4_t ra[8], rb[8];
-  auto gload = [&](int kt) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) { ra[i] = load16(aptr[i] + (int64_t)kt * G_BK); rb[i] = load16(bptr[i] + (int64_t)kt * G_BK); }
-  };
-  auto lstore = [&](int buf) {
+  auto stage = [&](int kt, int buf) {
     char* sa = lds + buf * 2 * G_TILE_BYTES;
     char* sb = sa + G_TILE_BYTES;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int r = lrow + 32 * i;
-      *reinterpret_cast<uint4_t*>(sa + swz(r, lcol)) = ra[i];
-      *reinterpret_cast<uint4_t*>(sb + swz(r, lcol)) = rb[i];
+      const int off = (i * 32 + wave * 8) * 128;
+      __builtin_amdgcn_global_load_lds((gptr_t)(aptr[i] + (int64_t)kt * G_BK), (lptr_t)(sa + off), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(bptr[i] + (int64_t)kt * G_BK), (lptr_t)(sb + off), 16, 0, 0);
     }
   };
 
@@ -77,31 +78,53 @@ __global__ __launch_bounds__(G_THREADS) void chunker_gemm_bf16_kernel(
   const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;       // wave quadrant inside the tile
   const int frow = lane & 31, fk = lane >> 5;                    // operand fragment: row, 8-wide k group
 
+  // Pipeline over 64-wide K slabs with ONE barrier per slab, placed before the slab's last quarter:
+  //   MFMA(ks=0..2 of slab kt)  [reads of ks+1 issued ahead]
+  //   wait for slab kt+1 (its global->LDS loads were issued a whole slab ago), barrier
+  //     -> every wave has finished reading slab kt, so its buffer can take slab kt+2 right away
+  //   issue slab kt+2, read the first fragments of slab kt+1, MFMA(ks=3 of slab kt)
+  // so neither the load wait nor the first fragment reads of a slab leave the matrix cores idle.
   const int KT = K / G_BK;
-  gload(0);
-  lstore(0);
-  __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) gload(kt + 1);
+  constexpr int KS = G_BK / 16;
+  bf16x8_t af[2][4], bfr[2][4];
+  auto frags = [&](int buf, int ks, bf16x8_t (&a)[4], bf16x8_t (&b)[4]) {
     const char* sa = lds + buf * 2 * G_TILE_BYTES;
     const char* sb = sa + G_TILE_BYTES;
 #pragma unroll
-    for (int ks = 0; ks < G_BK / 16; ++ks) {
-      bf16x8_t af[4], bfr[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        af[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4_t*>(sa + swz(wm + i * 32 + frow, ks * 2 + fk)));
-        bfr[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4_t*>(sb + swz(wn + i * 32 + frow, ks * 2 + fk)));
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    for (int i = 0; i < 4; ++i) {
+      a[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4_t*>(sa + swz(wm + i * 32 + frow, ks * 2 + fk)));
+      b[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4_t*>(sb + swz(wn + i * 32 + frow, ks * 2 + fk)));
     }
-    if (kt + 1 < KT) lstore(buf ^ 1);
+  };
+  auto mfma16 = [&](const bf16x8_t (&a)[4], const bf16x8_t (&b)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  };
+
+  stage(0, 0);
+  if (KT > 1) stage(1, 1);
+  __builtin_amdgcn_s_waitcnt(0);                                 // both slabs have landed (vmcnt(0))
+  __syncthreads();
+  frags(0, 0, af[0], bfr[0]);
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+#pragma unroll
+    for (int ks = 0; ks < KS - 1; ++ks) {
+      frags(buf, ks + 1, af[(ks + 1) & 1], bfr[(ks + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma16(af[ks & 1], bfr[ks & 1]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // last quarter: slab kt is completely in registers / consumed from LDS
+    __builtin_amdgcn_s_waitcnt(0);                               // slab kt+1 landed, own LDS reads done
     __syncthreads();
+    if (kt + 2 < KT) stage(kt + 2, buf);
+    if (kt + 1 < KT) frags(buf ^ 1, 0, af[KS & 1], bfr[KS & 1]);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma16(af[(KS - 1) & 1], bfr[(KS - 1) & 1]);
+    __builtin_amdgcn_sched_barrier(0);
   }
 
   // acc[i][j][v] of lane l: row m = wm + i*32 + 8*(v/4) + 4*(l/32) + v%4, column n = wn + j*32 + l%32
