@@ -330,6 +330,124 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_attn_kernel(
   }
 }
 
+// Decode sub-step of a local decoder, fused: for the q_len new rows of every chunk (window positions
+// q_pos .. q_pos+q_len-1) take q, k, v from the QKV projection output, apply the rotary encoding at
+// the window position, append k and v to the chunk's local cache, and attend causally over the window
+// so far.  One lane group per (chunk, head); the window (<= 16 rows) lives in registers.  fp32.
+template <int DH, int NK>
+__global__ __launch_bounds__(LOCAL_THREADS) void local_step_attn_kernel(
+    const float* __restrict__ qkv, float* __restrict__ lk, float* __restrict__ lv, float* __restrict__ out,
+    int64_t n_units, int H, int W, int q_len, int q_pos, float scale_log2e, float theta) {
+  constexpr int VEC = 4, LPR = DH / 4, UPW = 64 / LPR, HALF = DH / 2;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = (int64_t)blockIdx.x * (LOCAL_THREADS / 64) + (threadIdx.x >> 6);
+  int64_t unit = wave * UPW + lane / LPR;
+  const bool live = unit < n_units;
+  unit = live ? unit : n_units - 1;
+  const int64_t chunk = unit / H;
+  const int h = (int)(unit % H);
+  const int col = (lane % LPR) * VEC;
+  const int D = H * DH;
+  const bool upper = col >= HALF;                            // this lane holds elements i + d_h/2 of the rotary pairs
+
+  float inv_freq[VEC];
+#pragma unroll
+  for (int t = 0; t < VEC; ++t)
+    inv_freq[t] = theta == 0.f ? 0.f : (float)exp2(-2.0 * (double)((col + t) % HALF) / (double)DH * log2((double)theta));
+
+  float4_t kr[NK], vr[NK];
+  float* kcache = lk + (chunk * W * H + h) * DH + col;
+  float* vcache = lv + (chunk * W * H + h) * DH + col;
+#pragma unroll
+  for (int j = 0; j < NK; ++j) {
+    if (j < q_pos) {
+      kr[j] = *reinterpret_cast<const float4_t*>(kcache + (int64_t)j * D);
+      vr[j] = *reinterpret_cast<const float4_t*>(vcache + (int64_t)j * D);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NK; ++j) {
+    if (j >= q_pos) {
+      const int64_t row = chunk * q_len + (j - q_pos);
+      const float* src = qkv + row * 3 * D + h * DH + col;
+      float4_t q4 = *reinterpret_cast<const float4_t*>(src);
+      float4_t k4 = *reinterpret_cast<const float4_t*>(src + D);
+      const float4_t v4 = *reinterpret_cast<const float4_t*>(src + 2 * D);
+      // rotary: out[i] = x[i] c - x[i+h] s ; out[i+h] = x[i+h] c + x[i] s ; the partner sits LPR/2 lanes away
+      float qa[VEC] = {q4.x, q4.y, q4.z, q4.w}, ka[VEC] = {k4.x, k4.y, k4.z, k4.w};
+#pragma unroll
+      for (int t = 0; t < VEC; ++t) {
+        const float qb = __shfl_xor(qa[t], LPR / 2), kb = __shfl_xor(ka[t], LPR / 2);
+        double sd, cd;
+        sincos((double)j * (double)inv_freq[t], &sd, &cd);
+        const float c = (float)cd, sn = upper ? (float)sd : -(float)sd;
+        qa[t] = qa[t] * c + qb * sn;
+        ka[t] = ka[t] * c + kb * sn;
+      }
+      kr[j] = float4_t{ka[0], ka[1], ka[2], ka[3]};
+      vr[j] = v4;
+      if (live) {
+        *reinterpret_cast<float4_t*>(kcache + (int64_t)j * D) = kr[j];
+        *reinterpret_cast<float4_t*>(vcache + (int64_t)j * D) = v4;
+      }
+      // attention of this row over window rows 0..j
+      float s[NK], mx = NEG_BIG;
+#pragma unroll
+      for (int jj = 0; jj <= j; ++jj) {
+        float acc = qa[0] * kr[jj].x;
+        acc = fmaf(qa[1], kr[jj].y, acc);
+        acc = fmaf(qa[2], kr[jj].z, acc);
+        acc = fmaf(qa[3], kr[jj].w, acc);
+        s[jj] = group_sum<LPR>(acc) * scale_log2e;
+        mx = fmaxf(mx, s[jj]);
+      }
+      float l = 0.f;
+      float4_t o = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int jj = 0; jj <= j; ++jj) {
+        const float pw = fast_exp2(s[jj] - mx);
+        l += pw;
+        o += pw * vr[jj];
+      }
+      o *= (1.f / l);
+      if (live) *reinterpret_cast<float4_t*>(out + row * D + h * DH + col) = o;
+    }
+  }
+}
+
+template <int DH>
+static int32_t launch_local_step_dh(const float* qkv, float* lk, float* lv, float* out, int64_t n_chunks, int W, int q_len,
+                                    int q_pos, int H, float scale, float theta, hipStream_t st) {
+  const int64_t n_units = n_chunks * H;
+  const int64_t units_per_block = (int64_t)(64 / (DH / 4)) * (LOCAL_THREADS / 64);
+  const int64_t blocks = (n_units + units_per_block - 1) / units_per_block;
+  if (blocks > 0x7fffffffLL) return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: too many chunks for one launch");
+#define PHOTON_LS_CASE(N)                                                                                                   \
+  case N:                                                                                                                   \
+    PHOTON_LAUNCH(KC_LOCAL_ATTN, st, (local_step_attn_kernel<DH, N>), dim3((unsigned)blocks), dim3(LOCAL_THREADS), 0, st, qkv, lk, \
+                  lv, out, n_units, H, W, q_len, q_pos, scale * LOG2E, theta);                                             \
+    break;
+  switch (q_pos + q_len) {
+    PHOTON_LS_CASE(1) PHOTON_LS_CASE(2) PHOTON_LS_CASE(3) PHOTON_LS_CASE(4)
+    PHOTON_LS_CASE(5) PHOTON_LS_CASE(6) PHOTON_LS_CASE(7) PHOTON_LS_CASE(8)
+    PHOTON_LS_CASE(9) PHOTON_LS_CASE(10) PHOTON_LS_CASE(11) PHOTON_LS_CASE(12)
+    PHOTON_LS_CASE(13) PHOTON_LS_CASE(14) PHOTON_LS_CASE(15) PHOTON_LS_CASE(16)
+    default: return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: window position %d out of range", q_pos + q_len);
+  }
+#undef PHOTON_LS_CASE
+  return check_launch("local_step_attn_kernel");
+}
+
+int32_t launch_local_step_attn(int d_h, const float* qkv, float* lk, float* lv, float* out, int64_t n_chunks, int W, int q_len,
+                               int q_pos, int H, float scale, float theta, hipStream_t st) {
+  switch (d_h) {
+    case 32: return launch_local_step_dh<32>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, scale, theta, st);
+    case 64: return launch_local_step_dh<64>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, scale, theta, st);
+    case 128: return launch_local_step_dh<128>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, scale, theta, st);
+  }
+  return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: d_h=%d not in {32, 64, 128}", d_h);
+}
+
 template <typename T, int DH, int NK>
 static int32_t launch_local_nk(bool tile, const void* q, const void* k, const void* v, void* out, int64_t n_chunks,
                                int W, int q_len, int q_pos, int H, float scale, hipStream_t st) {

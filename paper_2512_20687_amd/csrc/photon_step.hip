@@ -47,34 +47,6 @@ __device__ __forceinline__ void rope_angle(int pos, int i, int d_h, float theta,
   c = (float)cd; s = (float)sd;
 }
 
-// Local decoder: rotate q and k of every row at its window position, write q to
-// qrot [rows, D] and k, v into the chunk's local cache [n_chunks, W, H, d_h] (fp32).
-__global__ __launch_bounds__(256) void rope_append_local_kernel(const float* __restrict__ qkv, float* __restrict__ qrot,
-                                                                float* __restrict__ lk, float* __restrict__ lv,
-                                                                int rows, int q_len, int q_pos, int W, int H, int d_h,
-                                                                float theta) {
-  const int half = d_h >> 1, D = H * d_h;
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (int64_t)rows * H * half) return;
-  const int i = (int)(idx % half);
-  const int h = (int)((idx / half) % H);
-  const int row = (int)(idx / ((int64_t)half * H));
-  const int chunk = row / q_len, pos = q_pos + row % q_len;
-  float c, s;
-  rope_angle(pos, i, d_h, theta, c, s);
-  const float* src = qkv + (int64_t)row * 3 * D + h * d_h;
-  const float qa = src[i], qb = src[i + half];
-  const float ka = src[D + i], kb = src[D + i + half];
-  float* qd = qrot + (int64_t)row * D + h * d_h;
-  qd[i] = qa * c - qb * s;
-  qd[i + half] = qb * c + qa * s;
-  const int64_t slot = (((int64_t)chunk * W + pos) * H + h) * d_h;
-  lk[slot + i] = ka * c - kb * s;
-  lk[slot + i + half] = kb * c + ka * s;
-  lv[slot + i] = src[2 * D + i];
-  lv[slot + i + half] = src[2 * D + i + half];
-}
-
 // Top-level STEP: position of sequence b is seq_len[b]-1 (the count already includes the new entry);
 // k, v go to cache[b, h, pos, :] of this layer.
 template <typename TKV>
@@ -107,8 +79,9 @@ __global__ __launch_bounds__(256) void rope_append_coarse_kernel(const float* __
 
 // Token choice for one row of logits (greedy, lowest index on ties, or the forced token), then the
 // decoder-side embedding of that token as the next input row.
+constexpr int CHOOSE_THREADS = 1024;
 template <typename TE>
-__global__ __launch_bounds__(256) void choose_token_kernel(const float* __restrict__ logits, int64_t ld_logits, int vocab,
+__global__ __launch_bounds__(CHOOSE_THREADS) void choose_token_kernel(const float* __restrict__ logits, int64_t ld_logits, int vocab,
                                                            const int32_t* __restrict__ forced, int32_t* __restrict__ tokens,
                                                            int tok_mul, int tok_off, const TE* __restrict__ E,
                                                            float* __restrict__ x_next, int D) {
@@ -116,9 +89,16 @@ __global__ __launch_bounds__(256) void choose_token_kernel(const float* __restri
   const float* lg = logits + (int64_t)row * ld_logits;
   float best = -INFINITY;
   int bi = 0x7fffffff;
-  for (int t = tid; t < vocab; t += 256) {
-    const float v = lg[t];
-    if (v > best || bi == 0x7fffffff) { best = v; bi = t; }
+  for (int t0 = tid; t0 < vocab; t0 += 4 * CHOOSE_THREADS) {       // indices visited in increasing order: first maximum wins
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int t = t0 + u * CHOOSE_THREADS;
+      v[u] = t < vocab ? lg[t] : -INFINITY;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (v[u] > best || (bi == 0x7fffffff && t0 + u * CHOOSE_THREADS < vocab)) { best = v[u]; bi = t0 + u * CHOOSE_THREADS; }
   }
 #pragma unroll
   for (int mask = 1; mask < 64; mask <<= 1) {
@@ -126,13 +106,13 @@ __global__ __launch_bounds__(256) void choose_token_kernel(const float* __restri
     const int oi = __shfl_xor(bi, mask);
     if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
   }
-  __shared__ float sv[4];
-  __shared__ int si[4];
+  __shared__ float sv[CHOOSE_THREADS / 64];
+  __shared__ int si[CHOOSE_THREADS / 64];
   __shared__ int chosen;
   if ((tid & 63) == 0) { sv[tid >> 6] = best; si[tid >> 6] = bi; }
   __syncthreads();
   if (tid == 0) {
-    for (int w = 1; w < 4; ++w)
+    for (int w = 1; w < CHOOSE_THREADS / 64; ++w)
       if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
     const int64_t flat = (int64_t)row * tok_mul + tok_off;
     if (forced != nullptr) bi = forced[flat];
@@ -143,7 +123,7 @@ __global__ __launch_bounds__(256) void choose_token_kernel(const float* __restri
   __syncthreads();
   if (x_next != nullptr) {
     const TE* e = E + (int64_t)chosen * D;
-    for (int d = tid; d < D; d += 256) x_next[(int64_t)row * D + d] = to_f32<TE>(e[d]);
+    for (int d = tid; d < D; d += CHOOSE_THREADS) x_next[(int64_t)row * D + d] = to_f32<TE>(e[d]);
   }
 }
 
@@ -310,7 +290,7 @@ static int32_t local_module_pass(const Ctx& x, int level, int64_t n_chunks, int 
   const photon_module_weights& mod = x.w->dec[level - 1];
   const int W = c.R[level - 1] + c.C[level - 1] - 1;
   const int rows = (int)(n_chunks * q_len);
-  float *h = x.f(x.p.h), *qkv = x.f(x.p.qkv), *qrot = x.f(x.p.qrot), *attn = x.f(x.p.attn);
+  float *h = x.f(x.p.h), *qkv = x.f(x.p.qkv), *attn = x.f(x.p.attn);
   const size_t layer_cache = (size_t)n_chunks * W * c.D;
   const float scale = 1.0f / sqrtf((float)c.d_h);
   for (int i = 0; i < c.n_layers; ++i) {
@@ -318,11 +298,7 @@ static int32_t local_module_pass(const Ctx& x, int level, int64_t n_chunks, int 
     float* lk = x.f(x.p.lk[level - 1]) + (size_t)i * layer_cache;
     float* lv = x.f(x.p.lv[level - 1]) + (size_t)i * layer_cache;
     PHOTON_TRY(linear(x, in.ptr, in.ld, lw.wqkv, lw.g1, nullptr, nullptr, 0, qkv, 3 * c.D, rows, 3 * c.D, c.D, EPI_PLAIN));
-    const int64_t n_el = (int64_t)rows * c.H * (c.d_h / 2);
-    PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_local_kernel, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot, lk, lv,
-                  rows, q_len, q_pos, W, c.H, c.d_h, c.rope_theta);
-    PHOTON_TRY(check_launch("rope_append_local_kernel"));
-    PHOTON_TRY(launch_local_attn(true, c.d_h, qrot, lk, lv, attn, n_chunks, W, q_len, q_pos, c.H, scale, x.st));
+    PHOTON_TRY(launch_local_step_attn(c.d_h, qkv, lk, lv, attn, n_chunks, W, q_len, q_pos, c.H, scale, c.rope_theta, x.st));
     PHOTON_TRY(block_tail(x, lw, in, rows));
     in.ptr = h; in.ld = c.D;
   }
@@ -398,10 +374,10 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
                           c.vocab, D, EPI_PLAIN));
         float* x_next = (j + 1 < C) ? h : nullptr;         // decoder-side embedding of the chosen token
         if (x.bf16)
-          PHOTON_LAUNCH(KC_CHOOSE_TOKEN, x.st, choose_token_kernel<bf16_t>, dim3((unsigned)n), dim3(256), 0, x.st, lg, ld, c.vocab,
+          PHOTON_LAUNCH(KC_CHOOSE_TOKEN, x.st, choose_token_kernel<bf16_t>, dim3((unsigned)n), dim3(CHOOSE_THREADS), 0, x.st, lg, ld, c.vocab,
                         forced, out_tokens, C, j, (const bf16_t*)x.w->E_dec, x_next, D);
         else
-          PHOTON_LAUNCH(KC_CHOOSE_TOKEN, x.st, choose_token_kernel<float>, dim3((unsigned)n), dim3(256), 0, x.st, lg, ld, c.vocab,
+          PHOTON_LAUNCH(KC_CHOOSE_TOKEN, x.st, choose_token_kernel<float>, dim3((unsigned)n), dim3(CHOOSE_THREADS), 0, x.st, lg, ld, c.vocab,
                         forced, out_tokens, C, j, (const float*)x.w->E_dec, x_next, D);
         PHOTON_TRY(check_launch("choose_token_kernel"));
         in.ptr = h; in.ld = D;
