@@ -108,7 +108,7 @@ def main():
     esz = 2 if cfg.dtype == "bf16" else 4
     Bt, S0 = wl.Bt, wl.S0
     total_steps = args.warmup + args.steps + 4
-    S_max = S0 + total_steps + 8
+    S_max = (S0 + total_steps + 8 + 127) // 128 * 128      # cache capacity: a multiple of 128 entries (16 KB pitch at d_h=64 bf16)
 
     t_setup = time.perf_counter()
     weights = si.make_weights(cfg, 0, encoders=False, device=dev)
@@ -199,6 +199,27 @@ def main():
     ca = kernels.get("coarse_attn_kernel", {})
     kv_gbs = ca.get("gbs", 0.0)
 
+    # ---- the coarse-attention kernel alone at the same shape (rotating over the layers' caches) ----
+    q = torch.randn((Bt, H, d_h), device=dev, dtype=torch.float32).to(model.mat_dtype)
+    o = torch.empty_like(q)
+    ns = ph.photon_coarse_decode_attn_auto_splits(Bt, H, S_max)
+    ws = torch.empty(max(ph.photon_coarse_decode_attn_workspace_bytes(Bt, H, d_h, ns), 16), dtype=torch.uint8, device=dev)
+    for i in range(2 * nl):
+        ph.photon_coarse_decode_attn(q, state.k[i % nl], state.v[i % nl], state.seq_len, o, n_splits=ns, workspace=ws)
+    torch.cuda.synchronize()
+    ph.photon_profile_enable(True)
+    iso_iters = 5 * nl
+    for i in range(iso_iters):
+        ph.photon_coarse_decode_attn(q, state.k[i % nl], state.v[i % nl], state.seq_len, o, n_splits=ns, workspace=ws)
+    torch.cuda.synchronize()
+    ph.photon_profile_enable(False)
+    iso = ph.photon_profile_get().get("coarse_attn_kernel", (1, 1.0))
+    ph.photon_profile_reset()
+    S_now = int(state.seq_len.max().item())
+    iso_bytes = 2 * Bt * H * S_now * d_h * esz
+    iso_us = iso[1] * 1e3 / iso[0]
+    kv_iso_gbs = iso_bytes / (iso_us * 1e-6) / 1e9
+
     kv_step_bytes = kv_launch_bytes * nl
     step_bytes = wbytes + kv_step_bytes
     result = {
@@ -211,6 +232,8 @@ def main():
                    "batch": Bt, "context_tokens": wl.T, "coarse_kv_len_start": S0, "coarse_kv_len_end": S_end,
                    "tokens_per_step": tokens_per_step, "mode": mode},
         "kv_read_gbs": kv_gbs, "kv_read_frac_of_hbm_peak": kv_gbs / HBM_PEAK_GBS,
+        "kv_read_isolated": {"gbs": kv_iso_gbs, "frac_of_hbm_peak": kv_iso_gbs / HBM_PEAK_GBS, "us_per_launch": iso_us,
+                             "bytes_per_launch": iso_bytes, "n_splits": ns, "launches": iso[0]},
         "kv_read_bytes_per_launch": kv_launch_bytes,
         "step_hbm_bytes_model": step_bytes, "step_hbm_gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_roofline": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -218,7 +218,11 @@ PHOTON_API size_t photon_decode_step_workspace_bytes(const photon_config* cfg, i
 
 /* forced_tokens: device int32 [Bt, prod(C)] or NULL; out_tokens: device int32
  * [Bt, prod(C)].  cfg, w, st and trace are host structs, read during the call
- * only.  All work is enqueued on `stream`; tokens stay on the device. */
+ * only.  All work is enqueued on `stream`; tokens stay on the device.  For
+ * L >= 2 the top-level update (ii)-(iii) runs on an internal second stream
+ * beside the lower levels and is joined back into `stream` before the call
+ * returns its work (created on first use: the first call of a process must not
+ * be made under stream capture; later calls may be captured). */
 PHOTON_API int32_t photon_decode_step(const photon_config* cfg, const photon_weights* w, const photon_state* st,
                                       int32_t Bt, const int32_t* forced_tokens, int32_t* out_tokens,
                                       const photon_trace* trace, void* stream);
@@ -238,7 +242,8 @@ PHOTON_API int32_t photon_hbm_read_probe(const void* buf, size_t bytes, void* si
  * grouped in classes 0 .. photon_profile_num_classes()-1, named by
  * photon_profile_class_name().  photon_profile_get() waits for the recorded
  * events of a class and returns the launch count and the summed elapsed
- * milliseconds; photon_profile_reset() drops all records.
+ * milliseconds; photon_profile_reset() drops all records.  While enabled,
+ * photon_decode_step keeps all its work on the caller's stream (no side stream).
  * -------------------------------------------------------------------------- */
 PHOTON_API int32_t photon_profile_enable(int32_t on);
 PHOTON_API int32_t photon_profile_reset(void);

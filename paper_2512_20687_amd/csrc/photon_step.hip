@@ -162,6 +162,7 @@ struct Plan {
   int n_splits = 1;
   size_t coarse_ws = 0, coarse_ws_bytes = 0;
   size_t h = 0, attn = 0, qkv = 0, qrot = 0, act = 0, cond = 0, logits = 0, a_hat = 0;
+  size_t h2 = 0, attn2 = 0, qkv2 = 0, qrot2 = 0, act2 = 0;   // second set (Bt rows) for the STEP branch that runs beside the lower levels
   size_t fresh[PHOTON_MAX_LEVELS] = {0};         // fresh[l]: new level-l units, l = 0..L-1
   size_t lk[PHOTON_MAX_LEVELS] = {0}, lv[PHOTON_MAX_LEVELS] = {0};   // local caches of level l (index l-1), all layers
   size_t total = 0;
@@ -196,6 +197,11 @@ static Plan make_plan(const photon_config& c, int Bt, int64_t S_max) {
   p.cond = bump(cur, p.rows_max * D * f);
   p.logits = bump(cur, (size_t)p.chunks[1] * c.vocab * f);
   p.a_hat = bump(cur, (size_t)Bt * D * f);
+  p.h2 = bump(cur, (size_t)Bt * D * f);
+  p.attn2 = bump(cur, (size_t)Bt * D * f);
+  p.qkv2 = bump(cur, (size_t)Bt * 3 * D * f);
+  p.qrot2 = bump(cur, (size_t)Bt * D * f);
+  p.act2 = bump(cur, (size_t)Bt * F * f);
   for (int l = 1; l <= c.L; ++l) {
     p.fresh[l - 1] = bump(cur, (size_t)p.chunks[l] * c.C[l - 1] * D * f);
     const int W = c.R[l - 1] + c.C[l - 1] - 1;
@@ -246,6 +252,8 @@ struct Ctx {
   Plan p;
   char* base;
   bool bf16;
+  size_t o_h, o_attn, o_qkv, o_qrot, o_act;   // activation buffers of the branch this context drives
+  bool overlap;                               // run the top-level update beside the lower levels
   float* f(size_t off) const { return reinterpret_cast<float*>(base + off); }
 };
 
@@ -276,7 +284,7 @@ static int32_t norm(const Ctx& x, const float* in, int in_mul, int in_off, const
 // SwiGLU sub-layer.  `in` is the block's input (the residual stream before the block).
 static int32_t block_tail(const Ctx& x, const photon_layer_weights& lw, RowsIn in, int rows) {
   const photon_config& c = *x.c;
-  float *h = x.f(x.p.h), *attn = x.f(x.p.attn), *act = x.f(x.p.act);
+  float *h = x.f(x.o_h), *attn = x.f(x.o_attn), *act = x.f(x.o_act);
   PHOTON_TRY(linear(x, attn, c.D, lw.wo, nullptr, nullptr, in.ptr, in.ld, h, c.D, rows, c.D, c.D, EPI_RESID));
   if (c.d_ff == 0) return PHOTON_OK;
   PHOTON_TRY(linear(x, h, c.D, lw.wgu, lw.g2, nullptr, nullptr, 0, act, c.d_ff, rows, c.d_ff, c.D, EPI_SWIGLU));
@@ -290,7 +298,7 @@ static int32_t local_module_pass(const Ctx& x, int level, int64_t n_chunks, int 
   const photon_module_weights& mod = x.w->dec[level - 1];
   const int W = c.R[level - 1] + c.C[level - 1] - 1;
   const int rows = (int)(n_chunks * q_len);
-  float *h = x.f(x.p.h), *qkv = x.f(x.p.qkv), *attn = x.f(x.p.attn);
+  float *h = x.f(x.o_h), *qkv = x.f(x.o_qkv), *attn = x.f(x.o_attn);
   const size_t layer_cache = (size_t)n_chunks * W * c.D;
   const float scale = 1.0f / sqrtf((float)c.d_h);
   for (int i = 0; i < c.n_layers; ++i) {
@@ -310,7 +318,7 @@ static int32_t top_step(const Ctx& x, RowsIn in) {
   const photon_config& c = *x.c;
   const photon_module_weights& mod = x.w->top;
   const int rows = x.Bt;
-  float *h = x.f(x.p.h), *qkv = x.f(x.p.qkv), *qrot = x.f(x.p.qrot), *attn = x.f(x.p.attn);
+  float *h = x.f(x.o_h), *qkv = x.f(x.o_qkv), *qrot = x.f(x.o_qrot), *attn = x.f(x.o_attn);
   const size_t esz = dtype_size(c.dt);
   const size_t layer_cache = (size_t)x.Bt * c.H * x.s->S_max * c.d_h * esz;
   const float scale = 1.0f / sqrtf((float)c.d_h);
@@ -335,10 +343,38 @@ static int32_t top_step(const Ctx& x, RowsIn in) {
   return norm(x, h, 1, 0, mod.g_final, x.s->x_top, 1, 0, rows);
 }
 
+// (ii) top chunker (Eq. 4) on the C_L new level-(L-1) units of every sequence, (iii) STEP (Eq. 13).
+static int32_t chunk_and_step(const Ctx& x, const float* bottleneck, const photon_trace* tr) {
+  const photon_config& c = *x.c;
+  const int D = c.D, CL = c.C[c.L - 1];
+  float* a_hat = (tr && tr->a_hat) ? tr->a_hat : x.f(x.p.a_hat);
+  PHOTON_TRY(linear(x, bottleneck, (int64_t)CL * D, x.w->chunker_w, nullptr, x.w->chunker_b, nullptr, 0, a_hat, D, x.Bt, D, CL * D,
+                    EPI_PLAIN));
+  RowsIn top_in;
+  top_in.ptr = a_hat; top_in.ld = D;
+  return top_step(x, top_in);
+}
+
+// The top-level update depends only on the level-L decoder's output, not on the lower levels that turn
+// it into tokens, so for L >= 2 it runs on a second stream beside them (fork after level L, join at
+// the end of the step).  The stream and its two events are created on first use and live for the process.
+static hipStream_t g_side = nullptr;
+static hipEvent_t g_fork = nullptr, g_join = nullptr;
+static int32_t ensure_side_stream() {
+  if (g_side != nullptr) return PHOTON_OK;
+  if (hipStreamCreateWithFlags(&g_side, hipStreamNonBlocking) != hipSuccess ||
+      hipEventCreateWithFlags(&g_fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&g_join, hipEventDisableTiming) != hipSuccess) {
+    g_side = nullptr;
+    return fail(PHOTON_ERR_HIP, "decode step: cannot create the side stream");
+  }
+  return PHOTON_OK;
+}
+
 static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* out_tokens, const photon_trace* tr) {
   const photon_config& c = *x.c;
   const int D = c.D, L = c.L, Bt = x.Bt;
-  float* h = x.f(x.p.h);
+  float* h = x.f(x.o_h);
   float* cond = x.f(x.p.cond);
 
   PHOTON_LAUNCH(KC_MISC, x.st, step_begin_kernel, dim3(blocks_for(Bt)), dim3(256), 0, x.st, x.s->seq_len, Bt);
@@ -348,6 +384,7 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
   for (int l = 0; l < L; ++l) fresh[l] = (tr && tr->new_units[l]) ? tr->new_units[l] : x.f(x.p.fresh[l]);
 
   const float* cond_in = x.s->x_top;                       // level L: one chunk per sequence, conditioned on X^(L)_g
+  bool forked = false;
   for (int l = L; l >= 1; --l) {
     const int C = c.C[l - 1], R = c.R[l - 1];
     const int64_t n = x.p.chunks[l];
@@ -383,6 +420,16 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
         in.ptr = h; in.ld = D;
       }
     }
+    if (l == L && L >= 2 && x.overlap) {
+      PHOTON_TRY(ensure_side_stream());
+      if (hipEventRecord(g_fork, x.st) != hipSuccess || hipStreamWaitEvent(g_side, g_fork, 0) != hipSuccess)
+        return fail(PHOTON_ERR_HIP, "decode step: cannot fork the STEP branch");
+      Ctx side = x;
+      side.st = g_side;
+      side.o_h = x.p.h2; side.o_attn = x.p.attn2; side.o_qkv = x.p.qkv2; side.o_qrot = x.p.qrot2; side.o_act = x.p.act2;
+      PHOTON_TRY(chunk_and_step(side, units, tr));
+      forked = true;
+    }
     if (l >= 2) {
       // chunks of level l-1: one per new level-(l-1) unit, hanging off the previous unit
       const int64_t per_seq = n * C / Bt;
@@ -397,14 +444,12 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
     }
   }
 
-  // (ii) top chunker on the C_L new level-(L-1) units of every sequence, (iii) STEP
-  const int CL = c.C[L - 1];
-  float* a_hat = (tr && tr->a_hat) ? tr->a_hat : x.f(x.p.a_hat);
-  PHOTON_TRY(linear(x, fresh[L - 1], (int64_t)CL * D, x.w->chunker_w, nullptr, x.w->chunker_b, nullptr, 0, a_hat, D, Bt, D, CL * D,
-                    EPI_PLAIN));
-  RowsIn top_in;
-  top_in.ptr = a_hat; top_in.ld = D;
-  return top_step(x, top_in);
+  if (!forked) PHOTON_TRY(chunk_and_step(x, fresh[L - 1], tr));
+  else {
+    if (hipEventRecord(g_join, g_side) != hipSuccess || hipStreamWaitEvent(x.st, g_join, 0) != hipSuccess)
+      return fail(PHOTON_ERR_HIP, "decode step: cannot join the STEP branch");
+  }
+  return PHOTON_OK;
 }
 
 }  // namespace photon
@@ -452,6 +497,8 @@ extern "C" int32_t photon_decode_step(const photon_config* cfg, const photon_wei
   x.c = cfg; x.w = w; x.s = st; x.Bt = Bt; x.st = (hipStream_t)stream;
   x.p = make_plan(c, Bt, st->S_max);
   x.bf16 = (c.dt == PHOTON_BF16);
+  x.overlap = !g_profile_on;   // per-kernel timing wants one stream: concurrency would inflate the bracketed times
+  x.o_h = x.p.h; x.o_attn = x.p.attn; x.o_qkv = x.p.qkv; x.o_qrot = x.p.qrot; x.o_act = x.p.act;
   PHOTON_REQUIRE(st->workspace != nullptr && aligned16(st->workspace) && st->workspace_bytes >= x.p.total, PHOTON_ERR_WORKSPACE,
                  "%s: workspace of %zu bytes needed (got %zu)", __func__, x.p.total, st->workspace_bytes);
   x.base = reinterpret_cast<char*>(st->workspace);
