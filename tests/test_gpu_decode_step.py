@@ -158,3 +158,48 @@ def test_step_is_deterministic():
     assert torch.equal(a[3]["logits"], b[3]["logits"])
     assert torch.equal(a[1].x_top, b[1].x_top)
     assert torch.equal(a[2], b[2])
+
+
+def test_graph_replay_matches_eager_steps():
+    """The bench replays a captured step (with its side-stream fork/join).  Replays,
+    interleaved with eager work and synchronisations, must reproduce eager steps bit for bit."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    cfg = si.PhotonConfig(L=2, C=(4, 4), R=(1, 1), D=256, H=4, d_h=64, n_layers=2, d_ff=640, vocab=1024, dtype="bf16")
+    w = si.make_weights(cfg, 4)
+    Bt, S, S_max = 3, 90, 128
+    st = si.make_decode_state(cfg, Bt, S, S_max, seed=2)
+    model = ph.PhotonModel(cfg, w)
+
+    def fresh_state():
+        return ph.PhotonState(model, Bt, S_max, k=st["k"], v=st["v"], seq_len=st["seq_len"], x_top=st["x_top"], carry=st["carry"])
+
+    n_steps = 4
+    eager = fresh_state()
+    toks_e = []
+    out = torch.empty((Bt, 16), dtype=torch.int32, device="cuda")
+    for _ in range(n_steps):
+        ph.photon_decode_step(model, eager, out)
+        toks_e.append(out.clone())
+    torch.cuda.synchronize()
+
+    rep = fresh_state()
+    ph.photon_decode_step(model, rep, out)            # first call outside capture (creates the side stream)
+    torch.cuda.synchronize()
+    rep2 = fresh_state()
+    for name in ("k", "v", "seq_len", "x_top", "carry"):
+        getattr(rep, name).copy_(getattr(rep2, name))
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        ph.photon_decode_step(model, rep, out)
+    for name in ("k", "v", "seq_len", "x_top", "carry"):      # capture does not execute; reset anyway
+        getattr(rep, name).copy_(getattr(rep2, name))
+    for i in range(n_steps):
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, toks_e[i]), f"replay {i}: tokens differ from the eager step"
+        _ = (rep.x_top * 2).sum().item()              # unrelated eager work between replays
+    assert torch.equal(rep.x_top, eager.x_top)
+    assert torch.equal(rep.k, eager.k) and torch.equal(rep.v, eager.v)
+    assert torch.equal(rep.carry, eager.carry)
+    assert rep.seq_len.cpu().tolist() == eager.seq_len.cpu().tolist()
