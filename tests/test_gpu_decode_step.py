@@ -203,3 +203,18 @@ def test_graph_replay_matches_eager_steps():
     assert torch.equal(rep.k, eager.k) and torch.equal(rep.v, eager.v)
     assert torch.equal(rep.carry, eager.carry)
     assert rep.seq_len.cpu().tolist() == eager.seq_len.cpu().tolist()
+
+
+def test_full_width_step_one_block_per_module():
+    """Configuration 3 at its real widths (D=2048, 32 heads, d_ff=5120, vocab 32000, batch 4, coarse
+    length 8192: the launch shapes the bench times), with one block per module so that the float64
+    oracle finishes in seconds; every intermediate is compared."""
+    require_gpu()
+    wl = si.WORKLOADS["cfg3_bf16_128k"]
+    cfg = si.shrink(wl.cfg, n_layers=1)
+    w = si.make_weights(cfg, 8, encoders=False)
+    S, S_max = wl.S0, wl.S0 + 128
+    st = si.make_decode_state(cfg, wl.Bt, S, S_max, seed=9)
+    forced = si.make_tokens(cfg.vocab, wl.Bt, cfg.meta_context, 10)
+    errs, _, _ = check_against_oracle(cfg, w, st, wl.Bt, S_max, forced, TOL["bf16"])
+    assert errs["logits"] <= 1e-3, errs      # fp32 activations x bf16 weights: far inside the bf16 bar
