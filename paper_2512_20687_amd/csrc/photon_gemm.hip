@@ -15,7 +15,6 @@
 
 namespace photon {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
 constexpr int G_BM = 256, G_BN = 256, G_BK = 64;

@@ -30,4 +30,8 @@ struct LinearArgs {
 
 int32_t launch_linear(const LinearArgs& a, hipStream_t st);
 
+// bf16 weights, activations small enough to stay in LDS: issues the launch and returns true, else returns false
+// (the caller then takes the streaming kernel).  Arguments must have passed launch_linear's checks.
+bool launch_linear_resident(const LinearArgs& a, hipStream_t st);
+
 }  // namespace photon

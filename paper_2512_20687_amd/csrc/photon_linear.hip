@@ -9,22 +9,29 @@
 // weight-streaming kernels: every weight byte is read once and the (<= 16 per
 // workgroup) activation rows ride along.  bf16 weights go through the matrix
 // cores only because M multiply-adds per weight would otherwise occupy the
-// vector ALUs; the kernel is HBM-bound by construction:
+// vector ALUs.  This file holds the streaming kernel, which takes any shape;
+// shapes whose split activations fit in LDS go to the resident-activation
+// kernel (photon_linear_resident.hip) first.
 //   * a workgroup owns a few 16-column output tiles and the whole contraction;
 //     its 8 waves take interleaved k chunks and meet once, in LDS, at the end.
 //     Nothing crosses workgroups, so the output is complete when the kernel
 //     ends (bias, residual, SwiGLU gate applied in place) and the summation
 //     order is fixed: results are run-to-run deterministic;
-//   * each lane issues 2 x 128-bit non-temporal loads per 64-wide k block so
-//     that every weight row is fetched in whole 128-byte lines; the k order
-//     inside a block is permuted identically for both MFMA operands (a
-//     contraction does not care), which is what makes those loads line up with
-//     the 16x16x32 operand layout;
+//   * each lane issues 2 x 128-bit loads per 64-wide k block so that every
+//     weight row is fetched in whole 128-byte lines; the k order inside a block
+//     is permuted identically for both MFMA operands (a contraction does not
+//     care), which is what makes those loads line up with the 16x16x32 operand
+//     layout;
 //   * activations stay fp32 in memory; each wave loads its k slab coalesced,
 //     scales by the norm gain, splits it into a bf16 head and a bf16 remainder
 //     (two MFMAs per weight fragment, so the product is as accurate as
 //     fp32-activation x bf16-weight) and reshapes it to the operand layout
-//     through a wave-private LDS area;
+//     through a wave-private LDS area; rows beyond M are neither loaded nor
+//     staged (a compute unit's load path is the scarce resource here: a load
+//     that hits in cache costs it as much as one that misses);
+//   * every load of a chunk, the gain slice included, is issued before the
+//     next chunk's prefetch, so each wait names an exact number of younger
+//     loads and never drains the prefetch;
 //   * the RMS statistic of each row is accumulated from the same loads (every
 //     wave sees a disjoint k range), reduced with the tiles, and applied to the
 //     finished dot products, so a pre-norm costs no extra pass or launch.
@@ -35,15 +42,10 @@
 
 namespace photon {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
 constexpr int FL_WAVES = 8;
 constexpr int FL_THREADS = FL_WAVES * 64;
 constexpr int FL_KBLOCK = 64;                 // k elements per block: 128 bytes of a weight row
-
-__device__ __forceinline__ bf16x8_t as_bf16x8(const uint4_t& v) { return __builtin_bit_cast(bf16x8_t, v); }
-
-__device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
 
 // NT output tiles (16 columns each) per workgroup; a chunk is CB = 2 k blocks (128 k).
 // One workgroup row (blockIdx.y) = 16 activation rows.
@@ -57,33 +59,39 @@ constexpr int FL_CB = 2;
 constexpr int FL_FRAG_PITCH = 16 * 16 + 16;                 // bytes per (block, half, q) group of 16 fragments, padded
 constexpr int FL_STAGE_BYTES = FL_CB * 2 * 4 * FL_FRAG_PITCH;   // one of hi / lo
 
-template <int NT, int EPI, bool STREAM>
-__global__ __launch_bounds__(FL_THREADS) void fused_linear_bf16_kernel(
+// XP: slab pieces per lane that hold live rows (rows m0 .. m0 + 2*XP - 1); dead rows are neither loaded nor staged,
+// their MFMA columns then carry whatever the staging area held and are never stored.
+template <int NT, int EPI, bool STREAM, int XP, bool NORM>
+__global__ __launch_bounds__(FL_THREADS, (NT == 1 && EPI != EPI_SWIGLU && XP == 2) ? 4 : 2) void fused_linear_bf16_kernel(
     const float* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ W, const float* __restrict__ gain, float eps,
     const float* __restrict__ bias, const float* res, int64_t ldres, float* out, int64_t ldo, int M, int N, int K) {
   constexpr int CB = FL_CB;
+  constexpr bool XPF = true;
   constexpr int TL = (EPI == EPI_SWIGLU) ? 2 * NT : NT;            // MFMA tiles per wave
   constexpr int RED_BYTES = TL * 64 * 16;
   constexpr int AREA = (2 * FL_STAGE_BYTES > RED_BYTES) ? 2 * FL_STAGE_BYTES : RED_BYTES;
   __shared__ __align__(16) char area[FL_WAVES][AREA];              // per wave: staging (hi | lo), later its partial tiles
   __shared__ float ssum[FL_WAVES][16];
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform: chunk arithmetic stays on the scalar unit
   const int lrow = lane & 15, lq = lane >> 4;
   const int m0 = blockIdx.y * 16;
   const int n_base = blockIdx.x * (NT * 16);
   char* stage_hi = area[wave];
   char* stage_lo = area[wave] + FL_STAGE_BYTES;
 
-  const bf16_t* wrow[TL];
+  // Addresses are a wave-uniform base plus a 32-bit lane offset that does not change over the loop.
+  const char* wtile[TL];                                           // first weight row of each tile
   bool tile_live[TL];
 #pragma unroll
   for (int t = 0; t < TL; ++t) {
     const int n_rel = n_base + (t % NT) * 16;
     tile_live[t] = n_rel < N;                                      // N is a multiple of 16
     const int n_w = (t < NT ? 0 : N) + n_rel;                      // swiglu: up rows follow the N gate rows
-    wrow[t] = W + (int64_t)(tile_live[t] ? n_w + lrow : 0) * K + lq * 8;
+    wtile[t] = reinterpret_cast<const char*>(W + (int64_t)(tile_live[t] ? n_w : 0) * K);
   }
+  const uint32_t w_lane = (uint32_t)(lrow * K + lq * 8) * 2u;      // row lrow of the tile, 16-byte group lq of a block half
 
   const int total_blocks = K / FL_KBLOCK;
   const int chunks = (total_blocks + CB - 1) / CB;
@@ -91,12 +99,12 @@ __global__ __launch_bounds__(FL_THREADS) void fused_linear_bf16_kernel(
   float4_t acc[TL];
 #pragma unroll
   for (int t = 0; t < TL; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
-  float ss[8];                                                     // this lane's slab pieces belong to rows i*2 + lane/32
+  float ss[XP];                                                    // this lane's slab pieces belong to rows i*2 + lane/32
 #pragma unroll
-  for (int i = 0; i < 8; ++i) ss[i] = 0.f;
+  for (int i = 0; i < XP; ++i) ss[i] = 0.f;
 
   uint4_t wa[TL][CB][2], wb[TL][CB][2];
-  float4_t xa[8], xb[8];
+  float4_t xa[XP + 1], xb[XP + 1];                                 // last element: the chunk's slice of the norm gain
   auto load_w = [&](int chunk, uint4_t (&wf)[TL][CB][2]) {
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
@@ -104,9 +112,9 @@ __global__ __launch_bounds__(FL_THREADS) void fused_linear_bf16_kernel(
       blk = blk < total_blocks ? blk : total_blocks - 1;           // clamped: in bounds, result unused
 #pragma unroll
       for (int t = 0; t < TL; ++t) {
-        const bf16_t* p = wrow[t] + (int64_t)blk * FL_KBLOCK;
+        const char* p = wtile[t] + (int64_t)blk * (FL_KBLOCK * 2) + w_lane;
         wf[t][b][0] = STREAM ? load16_stream(p) : load16(p);               // bytes 0..63 of the row's 128-byte line
-        wf[t][b][1] = STREAM ? load16_stream(p + 32) : load16(p + 32);     // bytes 64..127
+        wf[t][b][1] = STREAM ? load16_stream(p + 64) : load16(p + 64);     // bytes 64..127
       }
     }
   };
@@ -114,31 +122,37 @@ __global__ __launch_bounds__(FL_THREADS) void fused_linear_bf16_kernel(
   const int c4 = lane & 31;
   // Loads are unconditional (row and k clamped into bounds, dead pieces zeroed at use) so that the
   // hardware load counter can be waited on precisely while the next chunk is in flight.
-  auto load_x = [&](int chunk, float4_t (&xr)[8]) {
-    int k = chunk * (CB * FL_KBLOCK) + c4 * 4;
-    k = k < K ? k : K - 4;
+  uint32_t x_lane[XP];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      int m = m0 + i * 2 + (lane >> 5);
-      m = m < M ? m : M - 1;
-      xr[i] = *reinterpret_cast<const float4_t*>(x + (int64_t)m * ldx + k);
-    }
+  for (int i = 0; i < XP; ++i) {
+    int m = m0 + i * 2 + (lane >> 5);
+    m = m < M ? m : M - 1;
+    x_lane[i] = (uint32_t)((int64_t)(m - m0) * ldx + (c4 & 15) * 4) * 4u;
+  }
+  const char* x_tile = reinterpret_cast<const char*>(x + (int64_t)m0 * ldx);
+  auto load_x = [&](int chunk, float4_t (&xr)[XP + 1]) {
+    int blk = chunk * CB + (c4 >> 4);                              // the k block this lane's pieces fall in
+    blk = blk < total_blocks ? blk : total_blocks - 1;
+    const uint32_t kb = (uint32_t)blk * (FL_KBLOCK * 4);
+#pragma unroll
+    for (int i = 0; i < XP; ++i) xr[i] = *reinterpret_cast<const float4_t*>(x_tile + (x_lane[i] + kb));
+    // fetched with the slab, not at its use: a load issued after the next chunk's prefetch could only be
+    // waited for by draining that prefetch as well
+    if (NORM) xr[XP] = *reinterpret_cast<const float4_t*>(reinterpret_cast<const char*>(gain) + (kb + (c4 & 15) * 16));
   };
-  auto compute = [&](int chunk, const uint4_t (&wf)[TL][CB][2], const float4_t (&xr)[8]) {
-    // stage: fragment (block b, half, q) slot `row` holds k = b*64 + half*32 + q*8 .. +8 of that row
+  auto stage = [&](int chunk, const float4_t (&xr)[XP + 1]) {
+    // fragment fragment (block b, half, q) slot `row` holds k = b*64 + half*32 + q*8 .. +8 of that row
     const int k_in = c4 * 4;
     const int b_ = k_in >> 6, half = (k_in >> 5) & 1, q = (k_in >> 3) & 3;
     const int group = (b_ * 2 + half) * 4 + q;
     const int kabs = chunk * (CB * FL_KBLOCK) + k_in;
     const bool k_live = kabs < K;
-    float4_t gv = float4_t{1.f, 1.f, 1.f, 1.f};
-    if (gain != nullptr) gv = *reinterpret_cast<const float4_t*>(gain + (k_live ? kabs : 0));
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < XP; ++i) {
       const int row = i * 2 + (lane >> 5);
       float4_t v = (k_live && m0 + row < M) ? xr[i] : float4_t{0.f, 0.f, 0.f, 0.f};
       ss[i] = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss[i]))));
-      v *= gv;
+      if (NORM) v *= xr[XP];
       uint32_t h01, l01, h23, l23;
       split_bf16x2(v.x, v.y, h01, l01);
       split_bf16x2(v.z, v.w, h23, l23);
@@ -147,6 +161,8 @@ __global__ __launch_bounds__(FL_THREADS) void fused_linear_bf16_kernel(
       *reinterpret_cast<uint2*>(stage_lo + off) = uint2{l01, l23};
     }
     __builtin_amdgcn_wave_barrier();
+  };
+  auto mma = [&](int chunk, const uint4_t (&wf)[TL][CB][2]) {
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
       if (chunk * CB + b < total_blocks) {
@@ -172,18 +188,29 @@ __global__ __launch_bounds__(FL_THREADS) void fused_linear_bf16_kernel(
   if (chunk < chunks) {
     load_w(chunk, wa);
     load_x(chunk, xa);
-    while (true) {
-      const int c1 = chunk + FL_WAVES;
-      if (c1 < chunks) { load_w(c1, wb); load_x(c1, xb); compute(chunk, wa, xa); } else { compute(chunk, wa, xa); break; }
-      const int c2 = c1 + FL_WAVES;
-      if (c2 < chunks) { load_w(c2, wa); load_x(c2, xa); compute(c1, wb, xb); } else { compute(c1, wb, xb); break; }
-      chunk = c2;
+    if (XPF) {
+      while (true) {
+        const int c1 = chunk + FL_WAVES;
+        if (c1 < chunks) { load_w(c1, wb); load_x(c1, xb); stage(chunk, xa); mma(chunk, wa); } else { stage(chunk, xa); mma(chunk, wa); break; }
+        const int c2 = c1 + FL_WAVES;
+        if (c2 < chunks) { load_w(c2, wa); load_x(c2, xa); stage(c1, xb); mma(c1, wb); } else { stage(c1, xb); mma(c1, wb); break; }
+        chunk = c2;
+      }
+    } else {
+      // one activation buffer: the next slab is requested as soon as this one sits in the staging area
+      while (true) {
+        const int c1 = chunk + FL_WAVES;
+        if (c1 < chunks) { load_w(c1, wb); stage(chunk, xa); load_x(c1, xa); mma(chunk, wa); } else { stage(chunk, xa); mma(chunk, wa); break; }
+        const int c2 = c1 + FL_WAVES;
+        if (c2 < chunks) { load_w(c2, wa); stage(c1, xa); load_x(c2, xa); mma(c1, wb); } else { stage(c1, xa); mma(c1, wb); break; }
+        chunk = c2;
+      }
     }
   }
 
   // row statistics: piece i of a lane belongs to row i*2 + lane/32; add the 32 lanes of each half-wave
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
+  for (int i = 0; i < XP; ++i) {
     float v = group_sum<32>(ss[i]);
     if ((lane & 31) == 0) ssum[wave][i * 2 + (lane >> 5)] = v;
   }
@@ -198,6 +225,10 @@ __global__ __launch_bounds__(FL_THREADS) void fused_linear_bf16_kernel(
   const int t = wave;
   const int m = m0 + lrow;
   if (!tile_live[t] || m >= M) return;
+  const int n_out = n_base + t * 16 + lq * 4;
+  float4_t extra = float4_t{0.f, 0.f, 0.f, 0.f};                   // bias and residual, fetched while the partials are added
+  if (bias != nullptr) extra = *reinterpret_cast<const float4_t*>(bias + n_out);
+  if (EPI == EPI_RESID) extra += *reinterpret_cast<const float4_t*>(res + (int64_t)m * ldres + n_out);
   float4_t y = float4_t{0.f, 0.f, 0.f, 0.f}, yu = float4_t{0.f, 0.f, 0.f, 0.f};
   float tot = 0.f;
 #pragma unroll
@@ -207,17 +238,15 @@ __global__ __launch_bounds__(FL_THREADS) void fused_linear_bf16_kernel(
     if (EPI == EPI_SWIGLU) yu += rw[(NT + t) * 64 + lane];
     tot += ssum[w][lrow];
   }
-  if (gain != nullptr) {
+  if (NORM) {
     const float r = 1.0f / sqrtf(tot / (float)K + eps);
     y *= r;
     yu *= r;
   }
-  const int n_out = n_base + t * 16 + lq * 4;
   if (EPI == EPI_SWIGLU) {
     y.x = silu(y.x) * yu.x; y.y = silu(y.y) * yu.y; y.z = silu(y.z) * yu.z; y.w = silu(y.w) * yu.w;
   }
-  if (bias != nullptr) y += *reinterpret_cast<const float4_t*>(bias + n_out);
-  if (EPI == EPI_RESID) y += *reinterpret_cast<const float4_t*>(res + (int64_t)m * ldres + n_out);
+  y += extra;
   *reinterpret_cast<float4_t*>(out + (int64_t)m * ldo + n_out) = y;
 }
 
@@ -278,20 +307,34 @@ __global__ __launch_bounds__(256) void fused_linear_f32_kernel(
   }
 }
 
-template <int NT, int EPI>
+template <int NT, int EPI, int XP>
 static void launch_bf16_v(const LinearArgs& a, hipStream_t st) {
   dim3 grid((a.N + NT * 16 - 1) / (NT * 16), (a.M + 15) / 16);
   // plain (cacheable) weight loads: each 128-byte line is fetched by two instructions (64 bytes each),
   // and measured faster than non-temporal ones here
-  PHOTON_LAUNCH(KC_SKINNY_GEMM, st, (fused_linear_bf16_kernel<NT, EPI, false>), grid, dim3(FL_THREADS), 0, st, a.x, a.ldx,
-                (const bf16_t*)a.W, a.gain, a.eps, a.bias, a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K);
+  if (a.gain != nullptr)
+    PHOTON_LAUNCH(KC_SKINNY_GEMM, st, (fused_linear_bf16_kernel<NT, EPI, false, XP, true>), grid, dim3(FL_THREADS), 0, st, a.x,
+                  a.ldx, (const bf16_t*)a.W, a.gain, a.eps, a.bias, a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K);
+  else
+    PHOTON_LAUNCH(KC_SKINNY_GEMM, st, (fused_linear_bf16_kernel<NT, EPI, false, XP, false>), grid, dim3(FL_THREADS), 0, st, a.x,
+                  a.ldx, (const bf16_t*)a.W, a.gain, a.eps, a.bias, a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K);
+}
+
+template <int EPI, int XP>
+static void launch_bf16_x(const LinearArgs& a, hipStream_t st) {
+  // more columns per workgroup (fewer re-reads of the activations) once there are enough workgroups to fill the chip
+  if constexpr (EPI != EPI_SWIGLU) {                          // SwiGLU already carries two tiles (gate, up) per workgroup
+    if (a.N >= 6144) return launch_bf16_v<2, EPI, XP>(a, st);
+  }
+  return launch_bf16_v<1, EPI, XP>(a, st);
 }
 
 template <int EPI>
 static void launch_bf16_e(const LinearArgs& a, hipStream_t st) {
-  // more columns per workgroup (fewer re-reads of the activations) once there are enough workgroups to fill the chip
-  if (EPI != EPI_SWIGLU && a.N >= 6144) return launch_bf16_v<2, EPI>(a, st);
-  return launch_bf16_v<1, EPI>(a, st);
+  // few live rows (decode steps of the upper levels): the dead rows' loads are skipped
+  if (a.M <= 4) return launch_bf16_x<EPI, 2>(a, st);
+  if (a.M <= 8) return launch_bf16_x<EPI, 4>(a, st);
+  return launch_bf16_x<EPI, 8>(a, st);
 }
 
 int32_t launch_linear(const LinearArgs& a, hipStream_t st) {
@@ -301,6 +344,7 @@ int32_t launch_linear(const LinearArgs& a, hipStream_t st) {
   if (a.w_bf16) {
     if (a.K % FL_KBLOCK != 0 || a.N % 16 != 0 || a.ldx % 4 != 0 || a.ldo % 4 != 0 || (a.res && a.ldres % 4 != 0))
       return fail(PHOTON_ERR_UNSUPPORTED, "linear (bf16): K=%d must be a multiple of 64, N=%d of 16, row pitches of 4", a.K, a.N);
+    if (launch_linear_resident(a, st)) return check_launch("resident_linear_bf16_kernel");
     switch (a.epilogue) {
       case EPI_PLAIN: launch_bf16_e<EPI_PLAIN>(a, st); break;
       case EPI_RESID: launch_bf16_e<EPI_RESID>(a, st); break;

@@ -1,0 +1,351 @@
+// Few-row linear maps, variant with the activations resident in LDS.
+//
+// What bounds a few-row linear map on this chip is not HBM alone but the bytes
+// each compute unit has to take in: its share of the weights plus ALL of the
+// activations it multiplies them with (every workgroup needs every k).  With
+// one output tile per workgroup the fp32 activations (64 B per k at 16 rows)
+// outweigh a tile's weights (32 B per k), and they are re-read, re-scaled and
+// re-split for every tile.  This kernel therefore
+//   * spreads the output columns evenly over (up to) one workgroup per compute
+//     unit, in units of 8 columns, several MFMA tiles per workgroup;
+//   * reads, normalises and splits the activations ONCE per workgroup into
+//     MFMA operand order (bf16 head + bf16 remainder) and keeps them in LDS,
+//     each of the 8 waves holding the k chunks it contracts over;
+//   * then only streams weights: per k chunk the operand fragments come out of
+//     LDS once and meet every tile's weight fragments.
+// It applies whenever the split activations fit in LDS; larger cases take the
+// streaming kernel.  Summation order is fixed (waves in order), as there.
+#include "photon_linear.h"
+
+#include "photon_device.h"
+#include "photon_host.h"
+
+namespace photon {
+
+namespace {
+
+constexpr int RL_WAVES = 8;
+constexpr int RL_THREADS = RL_WAVES * 64;
+constexpr int RL_KBLOCK = 64;                  // k per block: 128 bytes of a weight row
+constexpr int RL_CB = 2;                       // blocks per chunk
+constexpr int RL_CHUNK_K = RL_CB * RL_KBLOCK;
+constexpr int RL_LDS_LIMIT = 156 * 1024;
+
+// bytes of one fragment group (one 8-k group of ROWS rows, 16 bytes each) incl. padding that spreads groups over banks
+__host__ __device__ constexpr int rl_group_pitch(int rows) { return rows * 16 + 16; }
+// one chunk of one wave: 16 groups of heads, then 16 groups of remainders
+__host__ __device__ constexpr int rl_chunk_bytes(int rows) { return 2 * 16 * rl_group_pitch(rows); }
+
+// EPI as in LinearEpilogue; XP: live slab pieces per lane (rows = 2*XP of the 16-row tile are live);
+// NORM: RMS pre-norm with gain; TMAX: MFMA tiles per workgroup (register-resident accumulators).
+//
+// Columns are dealt in units of 8: workgroup g owns units [u0, u0 + cnt).  Plain / residual: a tile is two
+// consecutive units (16 columns), a trailing single unit repeats its rows in the upper half.  SwiGLU: a tile is
+// one unit, gate rows in the lower and the matching up rows in the upper half, so the gated product of a
+// column is formed from two accumulator rows of the same tile.
+template <int EPI, int XP, bool NORM, int TMAX>
+__global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
+    const float* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ W, const float* __restrict__ gain, float eps,
+    const float* __restrict__ bias, const float* res, int64_t ldres, float* out, int64_t ldo, int M, int N, int K,
+    int unit_base, int unit_rem, int wave_bytes) {
+  constexpr int CB = RL_CB;
+  constexpr int ROWS = 2 * XP;
+  constexpr int GP = rl_group_pitch(ROWS);
+  constexpr int CHUNK_BYTES = rl_chunk_bytes(ROWS);
+  constexpr int UPT = (EPI == EPI_SWIGLU) ? 1 : 2;                 // units per tile
+  extern __shared__ __align__(16) char smem[];                     // [8 waves][wave_bytes], then row statistics [8][16]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lrow = lane & 15, lq = lane >> 4;
+  const int m0 = blockIdx.y * 16;
+  char* my_area = smem + wave * wave_bytes;
+  float* ssum = reinterpret_cast<float*>(smem + RL_WAVES * wave_bytes);
+
+  const int g = blockIdx.x;
+  const int u_cnt = unit_base + (g < unit_rem ? 1 : 0);
+  const int u0 = g * unit_base + (g < unit_rem ? g : unit_rem);
+  const int tiles = (u_cnt + UPT - 1) / UPT;                       // 1 .. TMAX
+  const int n0 = u0 * 8, n_end = (u0 + u_cnt) * 8;
+
+  // weight row of this lane in every tile, as a byte offset from W (host checks that all of W is below 4 GiB)
+  uint32_t w_lane[TMAX];
+#pragma unroll
+  for (int t = 0; t < TMAX; ++t) {
+    const int tt = t < tiles ? t : tiles - 1;                      // surplus tiles repeat the last one (loaded, never stored)
+    int n;
+    if (EPI == EPI_SWIGLU) {
+      const int c = n0 + tt * 8 + (lrow & 7);
+      n = lrow < 8 ? c : N + c;
+    } else {
+      n = n0 + tt * 16 + lrow;
+      n = n < n_end ? n : n - 8;                                   // trailing half tile: upper half repeats the lower
+    }
+    w_lane[t] = ((uint32_t)n * (uint32_t)K + (uint32_t)lq * 8u) * 2u;
+  }
+  const char* w_base = reinterpret_cast<const char*>(W);
+
+  const int total_blocks = K / RL_KBLOCK;
+  const int chunks = (total_blocks + CB - 1) / CB;
+  const int n_my = wave < chunks ? (chunks - wave + RL_WAVES - 1) / RL_WAVES : 0;   // this wave contracts chunks wave, wave+8, ..
+
+  float4_t acc[TMAX];
+#pragma unroll
+  for (int t = 0; t < TMAX; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
+  float ss[XP];
+#pragma unroll
+  for (int i = 0; i < XP; ++i) ss[i] = 0.f;
+
+  // ---- loads: unconditional, clamped into bounds, so that the load counter can be waited on exactly ----
+  auto load_w = [&](int j, uint4_t (&wf)[TMAX][CB][2]) {
+    const int chunk = wave + j * RL_WAVES;
+#pragma unroll
+    for (int b = 0; b < CB; ++b) {
+      int blk = chunk * CB + b;
+      blk = blk < total_blocks ? blk : total_blocks - 1;
+      const char* wb = w_base + (int64_t)blk * (RL_KBLOCK * 2);
+#pragma unroll
+      for (int t = 0; t < TMAX; ++t) {
+        wf[t][b][0] = load16(wb + w_lane[t]);                      // bytes 0..63 of the row's 128-byte line
+        wf[t][b][1] = load16(wb + w_lane[t] + 64);                 // bytes 64..127
+      }
+    }
+  };
+  // slab piece i of a lane: row i*2 + lane/32, k offset (lane%32)*4 inside the chunk
+  const int c4 = lane & 31;
+  uint32_t x_lane[XP];
+#pragma unroll
+  for (int i = 0; i < XP; ++i) {
+    int m = m0 + i * 2 + (lane >> 5);
+    m = m < M ? m : M - 1;
+    x_lane[i] = (uint32_t)((int64_t)(m - m0) * ldx + (c4 & 15) * 4) * 4u;
+  }
+  const char* x_tile = reinterpret_cast<const char*>(x + (int64_t)m0 * ldx);
+  auto load_x = [&](int j, float4_t (&xr)[XP + 1]) {
+    const int chunk = wave + j * RL_WAVES;
+    int blk = chunk * CB + (c4 >> 4);
+    blk = blk < total_blocks ? blk : total_blocks - 1;
+    const uint32_t kb = (uint32_t)blk * (RL_KBLOCK * 4);
+#pragma unroll
+    for (int i = 0; i < XP; ++i) xr[i] = *reinterpret_cast<const float4_t*>(x_tile + (x_lane[i] + kb));
+    if (NORM) xr[XP] = *reinterpret_cast<const float4_t*>(reinterpret_cast<const char*>(gain) + (kb + (c4 & 15) * 16));
+  };
+  // scale, split and store chunk j in operand order: group (block, half, q) holds k = b*64 + half*32 + q*8 .. +8 of every row
+  auto stage = [&](int j, const float4_t (&xr)[XP + 1]) {
+    const int chunk = wave + j * RL_WAVES;
+    char* hi = my_area + j * CHUNK_BYTES;
+    char* lo = hi + 16 * GP;
+    const bool k_live = chunk * RL_CHUNK_K + c4 * 4 < K;
+    const int group = c4 >> 1;
+#pragma unroll
+    for (int i = 0; i < XP; ++i) {
+      const int row = i * 2 + (lane >> 5);
+      float4_t v = (k_live && m0 + row < M) ? xr[i] : float4_t{0.f, 0.f, 0.f, 0.f};
+      ss[i] = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss[i]))));
+      if (NORM) v *= xr[XP];
+      uint32_t h01, l01, h23, l23;
+      split_bf16x2(v.x, v.y, h01, l01);
+      split_bf16x2(v.z, v.w, h23, l23);
+      const int off = group * GP + row * 16 + (c4 & 1) * 8;
+      *reinterpret_cast<uint2*>(hi + off) = uint2{h01, h23};
+      *reinterpret_cast<uint2*>(lo + off) = uint2{l01, l23};
+    }
+  };
+  const int frag_row = (lrow & (ROWS - 1)) * 16;                   // dead rows read a live row's fragment: never stored
+  auto mma = [&](int j, const uint4_t (&wf)[TMAX][CB][2]) {
+    const int chunk = wave + j * RL_WAVES;
+    const char* hi = my_area + j * CHUNK_BYTES;
+    const char* lo = hi + 16 * GP;
+#pragma unroll
+    for (int b = 0; b < CB; ++b) {
+      if (chunk * CB + b < total_blocks) {
+#pragma unroll
+        for (int half2 = 0; half2 < 2; ++half2) {
+          const int off = ((b * 2 + half2) * 4 + lq) * GP + frag_row;
+          const bf16x8_t bh = as_bf16x8(*reinterpret_cast<const uint4_t*>(hi + off));
+          const bf16x8_t bl = as_bf16x8(*reinterpret_cast<const uint4_t*>(lo + off));
+#pragma unroll
+          for (int t = 0; t < TMAX; ++t) {
+            const bf16x8_t a = as_bf16x8(wf[t][b][half2]);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[t], 0, 0, 0);
+          }
+        }
+      }
+    }
+  };
+
+  uint4_t wa[TMAX][CB][2], wb[TMAX][CB][2];
+  float4_t xa[XP + 1], xb[XP + 1];
+  if (n_my > 0) {
+    // Activations are requested before the weights: loads return in order, and the (cached) activations must
+    // not queue behind weight lines coming from HBM.  Both arms keep the number of loads in flight static.
+    if (n_my == 1) {
+      load_x(0, xa);
+      load_w(0, wa);
+      stage(0, xa);
+    } else {
+      load_x(0, xa);
+      load_x(1, xb);
+      load_w(0, wa);
+      load_w(1, wb);
+      stage(0, xa);
+      stage(1, xb);
+      // further chunks (long contractions only): one slab in flight while the previous one is staged
+      int j = 2;
+      if (j < n_my) {
+        load_x(j, xa);
+        while (true) {
+          if (j + 1 < n_my) { load_x(j + 1, xb); stage(j, xa); } else { stage(j, xa); break; }
+          if (j + 2 < n_my) { load_x(j + 2, xa); stage(j + 1, xb); } else { stage(j + 1, xb); break; }
+          j += 2;
+        }
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+    // weights: chunk j+1 in flight while chunk j is multiplied (chunks 0 and 1 were requested above)
+    if (n_my == 1) {
+      mma(0, wa);
+    } else {
+      // wa holds chunk j, wb chunk j + 1; each arm issues a fixed number of loads between a request and its use
+      int j = 0;
+      while (true) {
+        mma(j, wa);
+        if (j + 2 < n_my) {
+          load_w(j + 2, wa);
+          mma(j + 1, wb);
+          if (j + 3 < n_my) { load_w(j + 3, wb); } else { mma(j + 2, wa); break; }
+        } else {
+          mma(j + 1, wb);
+          break;
+        }
+        j += 2;
+      }
+    }
+  }
+
+  // row statistics: piece i of a lane belongs to row i*2 + lane/32; add the 32 lanes of each half-wave
+#pragma unroll
+  for (int i = 0; i < XP; ++i) {
+    float v = group_sum<32>(ss[i]);
+    if ((lane & 31) == 0) ssum[wave * 16 + i * 2 + (lane >> 5)] = v;
+  }
+  __syncthreads();                                                 // every wave is done with its operands: the area is reused
+  float4_t* red = reinterpret_cast<float4_t*>(my_area);
+#pragma unroll
+  for (int t = 0; t < TMAX; ++t) red[t * 64 + lane] = acc[t];
+  __syncthreads();
+
+  // wave t finishes tile t: partial tiles added in wave order, 1/rms, epilogue.
+  // acc of lane l holds y[row m0 + l%16][tile row (l/16)*4 + 0..3] (tile row = weight row = output column)
+  if (wave >= TMAX || wave >= tiles) return;
+  const int t = wave;
+  const int m = m0 + lrow;
+  if (m >= M) return;
+  int n_out;
+  if (EPI == EPI_SWIGLU) {
+    if (lq >= 2) return;                                           // upper half of the tile: the up rows, read below
+    n_out = n0 + t * 8 + lq * 4;
+  } else {
+    n_out = n0 + t * 16 + lq * 4;
+    if (n_out >= n_end) return;                                    // repeated rows of a trailing half tile
+  }
+  float4_t extra = float4_t{0.f, 0.f, 0.f, 0.f};                   // bias and residual, fetched while the partials are added
+  if (bias != nullptr) extra = *reinterpret_cast<const float4_t*>(bias + n_out);
+  if (EPI == EPI_RESID) extra += *reinterpret_cast<const float4_t*>(res + (int64_t)m * ldres + n_out);
+  float4_t y = float4_t{0.f, 0.f, 0.f, 0.f}, yu = float4_t{0.f, 0.f, 0.f, 0.f};
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < RL_WAVES; ++w) {
+    const float4_t* rw = reinterpret_cast<const float4_t*>(smem + w * wave_bytes);
+    y += rw[t * 64 + lane];
+    if (EPI == EPI_SWIGLU) yu += rw[t * 64 + lane + 32];
+    tot += ssum[w * 16 + lrow];
+  }
+  if (NORM) {
+    const float r = 1.0f / sqrtf(tot / (float)K + eps);
+    y *= r;
+    yu *= r;
+  }
+  if (EPI == EPI_SWIGLU) {
+    y.x = silu(y.x) * yu.x; y.y = silu(y.y) * yu.y; y.z = silu(y.z) * yu.z; y.w = silu(y.w) * yu.w;
+  }
+  y += extra;
+  *reinterpret_cast<float4_t*>(out + (int64_t)m * ldo + n_out) = y;
+}
+
+template <int EPI, int XP, bool NORM, int TMAX>
+bool launch_resident_t(const LinearArgs& a, hipStream_t st, int G, int unit_base, int unit_rem, int wave_bytes, size_t lds) {
+  auto kern = resident_linear_bf16_kernel<EPI, XP, NORM, TMAX>;
+  static bool attr_done = false;                                   // more than 64 KiB of dynamic LDS has to be allowed once
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, RL_LDS_LIMIT) != hipSuccess) {
+      (void)hipGetLastError();
+      return false;
+    }
+    attr_done = true;
+  }
+  dim3 grid(G, (a.M + 15) / 16);
+  PHOTON_LAUNCH(KC_SKINNY_GEMM, st, kern, grid, dim3(RL_THREADS), lds, st, a.x, a.ldx, (const bf16_t*)a.W, a.gain, a.eps, a.bias,
+                a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K, unit_base, unit_rem, wave_bytes);
+  return true;
+}
+
+template <int EPI, int XP, bool NORM>
+bool launch_resident_x(const LinearArgs& a, hipStream_t st, int tmax, int G, int ub, int ur, int wave_bytes, size_t lds) {
+  switch (tmax) {
+    case 1: return launch_resident_t<EPI, XP, NORM, 1>(a, st, G, ub, ur, wave_bytes, lds);
+    case 2: return launch_resident_t<EPI, XP, NORM, 2>(a, st, G, ub, ur, wave_bytes, lds);
+    case 3: return launch_resident_t<EPI, XP, NORM, 3>(a, st, G, ub, ur, wave_bytes, lds);
+    default: return launch_resident_t<EPI, XP, NORM, 4>(a, st, G, ub, ur, wave_bytes, lds);
+  }
+}
+
+template <int EPI, bool NORM>
+bool launch_resident_e(const LinearArgs& a, hipStream_t st, int xp, int tmax, int G, int ub, int ur, int wave_bytes, size_t lds) {
+  switch (xp) {
+    case 2: return launch_resident_x<EPI, 2, NORM>(a, st, tmax, G, ub, ur, wave_bytes, lds);
+    case 4: return launch_resident_x<EPI, 4, NORM>(a, st, tmax, G, ub, ur, wave_bytes, lds);
+    default: return launch_resident_x<EPI, 8, NORM>(a, st, tmax, G, ub, ur, wave_bytes, lds);
+  }
+}
+
+}  // namespace
+
+// Returns true when the launch was issued here; false leaves the case to the streaming kernel.
+bool launch_linear_resident(const LinearArgs& a, hipStream_t st) {
+  if (!a.w_bf16 || a.K % RL_KBLOCK != 0 || a.N % 8 != 0) return false;
+  if (a.ldx % 4 != 0 || a.ldo % 4 != 0 || (a.res && a.ldres % 4 != 0)) return false;
+  const bool norm = a.gain != nullptr;
+  // instantiated combinations: the ones the decode path uses
+  const bool combo = (a.epilogue == EPI_PLAIN) || (a.epilogue == EPI_RESID && !norm) || (a.epilogue == EPI_SWIGLU && norm);
+  if (!combo) return false;
+  const int64_t w_rows = (a.epilogue == EPI_SWIGLU) ? 2 * (int64_t)a.N : a.N;
+  if (w_rows * a.K * 2 >= ((int64_t)1 << 32)) return false;       // 32-bit weight offsets
+  const int rows_live = a.M < 16 ? a.M : 16;
+  const int xp = rows_live <= 4 ? 2 : rows_live <= 8 ? 4 : 8;
+  const int upt = (a.epilogue == EPI_SWIGLU) ? 1 : 2;
+  const int units = a.N / 8;
+  // one workgroup per compute unit when there are enough units, more rounds only when a workgroup would exceed 4 tiles
+  constexpr int CUS = 256;
+  const int per_round = CUS * 4 * upt;
+  const int rounds = (units + per_round - 1) / per_round;
+  int G = units < CUS * rounds ? units : CUS * rounds;
+  const int ub = units / G, ur = units % G;
+  const int tmax = (ub + (ur ? 1 : 0) + upt - 1) / upt;
+  const int chunks = (a.K / RL_KBLOCK + RL_CB - 1) / RL_CB;
+  const int n_my_max = (chunks + RL_WAVES - 1) / RL_WAVES;
+  int wave_bytes = n_my_max * rl_chunk_bytes(2 * xp);
+  if (wave_bytes < tmax * 1024) wave_bytes = tmax * 1024;          // the partial tiles reuse the area
+  const size_t lds = (size_t)RL_WAVES * wave_bytes + RL_WAVES * 16 * sizeof(float);
+  if (lds > (size_t)RL_LDS_LIMIT) return false;
+  switch (a.epilogue) {
+    case EPI_PLAIN:
+      return norm ? launch_resident_e<EPI_PLAIN, true>(a, st, xp, tmax, G, ub, ur, wave_bytes, lds)
+                  : launch_resident_e<EPI_PLAIN, false>(a, st, xp, tmax, G, ub, ur, wave_bytes, lds);
+    case EPI_RESID: return launch_resident_e<EPI_RESID, false>(a, st, xp, tmax, G, ub, ur, wave_bytes, lds);
+    default: return launch_resident_e<EPI_SWIGLU, true>(a, st, xp, tmax, G, ub, ur, wave_bytes, lds);
+  }
+}
+
+}  // namespace photon

@@ -58,6 +58,10 @@ def test_linear_parity(dtype, M, N, K, epilogue, norm, bias):
     (16, 32000, 2048, 0, False),     # LM head
     (4, 2048, 8192, 0, False),       # top chunker at decode shape
     (64, 3072, 1024, 0, True),       # configuration 2, token level: four row tiles
+    (4, 2048, 5120, 1, False),       # down projection at the upper levels: five chunks per wave stay in LDS
+    (8, 1024, 2304, 0, True),        # 18 chunks: waves with three and with two chunks
+    (40, 272, 1024, 2, True),        # 34 column units, three row tiles, ragged last one
+    (5, 1040, 448, 0, False),        # odd number of k blocks, trailing half tile in every workgroup
 ])
 def test_linear_real_shapes(M, N, K, epilogue, norm):
     require_gpu()
