@@ -97,6 +97,17 @@ template <int G> __device__ __forceinline__ float group_sum(float x) {
   return x;
 }
 
+// rotate a 128-bit register by 8 lanes inside every row of 16 lanes
+__device__ __forceinline__ uint4_t rotate8(const uint4_t& v) {
+  constexpr int ROW_ROR8 = 0x128;
+  uint4_t r;
+  r.x = __builtin_amdgcn_update_dpp(0, v.x, ROW_ROR8, 0xf, 0xf, false);
+  r.y = __builtin_amdgcn_update_dpp(0, v.y, ROW_ROR8, 0xf, 0xf, false);
+  r.z = __builtin_amdgcn_update_dpp(0, v.z, ROW_ROR8, 0xf, 0xf, false);
+  r.w = __builtin_amdgcn_update_dpp(0, v.w, ROW_ROR8, 0xf, 0xf, false);
+  return r;
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
 

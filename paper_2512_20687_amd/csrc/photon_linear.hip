@@ -61,7 +61,11 @@ constexpr int FL_STAGE_BYTES = FL_CB * 2 * 4 * FL_FRAG_PITCH;   // one of hi / l
 
 // XP: slab pieces per lane that hold live rows (rows m0 .. m0 + 2*XP - 1); dead rows are neither loaded nor staged,
 // their MFMA columns then carry whatever the staging area held and are never stored.
-template <int NT, int EPI, bool STREAM, int XP, bool NORM>
+// FOLD (one tile, not SwiGLU): the workgroup owns 8 columns; tile row r and r + 8 are weight row r, lanes of rows 0..7
+// load the first 64 bytes of a block's line and lanes of rows 8..15 the second 64, so one load per block fetches
+// whole lines; the second MFMA of a block takes the registers rotated by 8 lanes.  Accumulator rows 8..15 are
+// meaningless.  Used when 16-column tiles would leave compute units without a workgroup.
+template <int NT, int EPI, bool FOLD, int XP, bool NORM>
 __global__ __launch_bounds__(FL_THREADS, (NT == 1 && EPI != EPI_SWIGLU && XP == 2) ? 4 : 2) void fused_linear_bf16_kernel(
     const float* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ W, const float* __restrict__ gain, float eps,
     const float* __restrict__ bias, const float* res, int64_t ldres, float* out, int64_t ldo, int M, int N, int K) {
@@ -77,7 +81,9 @@ __global__ __launch_bounds__(FL_THREADS, (NT == 1 && EPI != EPI_SWIGLU && XP == 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform: chunk arithmetic stays on the scalar unit
   const int lrow = lane & 15, lq = lane >> 4;
   const int m0 = blockIdx.y * 16;
-  const int n_base = blockIdx.x * (NT * 16);
+  static_assert(!FOLD || (NT == 1 && EPI != EPI_SWIGLU), "folded tiles: one per workgroup, no gate/up pairing");
+  constexpr int WL = FOLD ? 1 : 2;                                 // weight loads per k block and tile
+  const int n_base = blockIdx.x * (FOLD ? 8 : NT * 16);
   char* stage_hi = area[wave];
   char* stage_lo = area[wave] + FL_STAGE_BYTES;
 
@@ -91,7 +97,8 @@ __global__ __launch_bounds__(FL_THREADS, (NT == 1 && EPI != EPI_SWIGLU && XP == 
     const int n_w = (t < NT ? 0 : N) + n_rel;                      // swiglu: up rows follow the N gate rows
     wtile[t] = reinterpret_cast<const char*>(W + (int64_t)(tile_live[t] ? n_w : 0) * K);
   }
-  const uint32_t w_lane = (uint32_t)(lrow * K + lq * 8) * 2u;      // row lrow of the tile, 16-byte group lq of a block half
+  // row lrow of the tile, 16-byte group lq of a block half (folded: row lrow % 8, group lq of the half lrow / 8)
+  const uint32_t w_lane = FOLD ? (uint32_t)((lrow & 7) * K + (lq + 4 * (lrow >> 3)) * 8) * 2u : (uint32_t)(lrow * K + lq * 8) * 2u;
 
   const int total_blocks = K / FL_KBLOCK;
   const int chunks = (total_blocks + CB - 1) / CB;
@@ -103,9 +110,9 @@ __global__ __launch_bounds__(FL_THREADS, (NT == 1 && EPI != EPI_SWIGLU && XP == 
 #pragma unroll
   for (int i = 0; i < XP; ++i) ss[i] = 0.f;
 
-  uint4_t wa[TL][CB][2], wb[TL][CB][2];
+  uint4_t wa[TL][CB][WL], wb[TL][CB][WL];
   float4_t xa[XP + 1], xb[XP + 1];                                 // last element: the chunk's slice of the norm gain
-  auto load_w = [&](int chunk, uint4_t (&wf)[TL][CB][2]) {
+  auto load_w = [&](int chunk, uint4_t (&wf)[TL][CB][WL]) {
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
       int blk = chunk * CB + b;
@@ -113,8 +120,8 @@ __global__ __launch_bounds__(FL_THREADS, (NT == 1 && EPI != EPI_SWIGLU && XP == 
 #pragma unroll
       for (int t = 0; t < TL; ++t) {
         const char* p = wtile[t] + (int64_t)blk * (FL_KBLOCK * 2) + w_lane;
-        wf[t][b][0] = STREAM ? load16_stream(p) : load16(p);               // bytes 0..63 of the row's 128-byte line
-        wf[t][b][1] = STREAM ? load16_stream(p + 64) : load16(p + 64);     // bytes 64..127
+        wf[t][b][0] = load16(p);                                   // bytes 0..63 of the row's 128-byte line (folded: all of it)
+        if (!FOLD) wf[t][b][1] = load16(p + 64);                   // bytes 64..127
       }
     }
   };
@@ -162,7 +169,7 @@ __global__ __launch_bounds__(FL_THREADS, (NT == 1 && EPI != EPI_SWIGLU && XP == 
     }
     __builtin_amdgcn_wave_barrier();
   };
-  auto mma = [&](int chunk, const uint4_t (&wf)[TL][CB][2]) {
+  auto mma = [&](int chunk, const uint4_t (&wf)[TL][CB][WL]) {
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
       if (chunk * CB + b < total_blocks) {
@@ -173,7 +180,7 @@ __global__ __launch_bounds__(FL_THREADS, (NT == 1 && EPI != EPI_SWIGLU && XP == 
           const bf16x8_t bl = as_bf16x8(*reinterpret_cast<const uint4_t*>(stage_lo + off));
 #pragma unroll
           for (int t = 0; t < TL; ++t) {
-            const bf16x8_t a = as_bf16x8(wf[t][b][half2]);
+            const bf16x8_t a = as_bf16x8(FOLD ? (half2 ? rotate8(wf[t][b][0]) : wf[t][b][0]) : wf[t][b][WL - 1 < half2 ? WL - 1 : half2]);
             acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[t], 0, 0, 0);
             acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[t], 0, 0, 0);
           }
@@ -225,6 +232,7 @@ __global__ __launch_bounds__(FL_THREADS, (NT == 1 && EPI != EPI_SWIGLU && XP == 
   const int t = wave;
   const int m = m0 + lrow;
   if (!tile_live[t] || m >= M) return;
+  if (FOLD && lq >= 2) return;                                     // folded tile: accumulator rows 8..15 are meaningless
   const int n_out = n_base + t * 16 + lq * 4;
   float4_t extra = float4_t{0.f, 0.f, 0.f, 0.f};                   // bias and residual, fetched while the partials are added
   if (bias != nullptr) extra = *reinterpret_cast<const float4_t*>(bias + n_out);
@@ -307,26 +315,28 @@ __global__ __launch_bounds__(256) void fused_linear_f32_kernel(
   }
 }
 
-template <int NT, int EPI, int XP>
+template <int NT, int EPI, bool FOLD, int XP>
 static void launch_bf16_v(const LinearArgs& a, hipStream_t st) {
-  dim3 grid((a.N + NT * 16 - 1) / (NT * 16), (a.M + 15) / 16);
-  // plain (cacheable) weight loads: each 128-byte line is fetched by two instructions (64 bytes each),
-  // and measured faster than non-temporal ones here
+  constexpr int COLS = FOLD ? 8 : NT * 16;
+  dim3 grid((a.N + COLS - 1) / COLS, (a.M + 15) / 16);
+  // plain (cacheable) weight loads: measured faster than non-temporal ones here
   if (a.gain != nullptr)
-    PHOTON_LAUNCH(KC_SKINNY_GEMM, st, (fused_linear_bf16_kernel<NT, EPI, false, XP, true>), grid, dim3(FL_THREADS), 0, st, a.x,
+    PHOTON_LAUNCH(KC_SKINNY_GEMM, st, (fused_linear_bf16_kernel<NT, EPI, FOLD, XP, true>), grid, dim3(FL_THREADS), 0, st, a.x,
                   a.ldx, (const bf16_t*)a.W, a.gain, a.eps, a.bias, a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K);
   else
-    PHOTON_LAUNCH(KC_SKINNY_GEMM, st, (fused_linear_bf16_kernel<NT, EPI, false, XP, false>), grid, dim3(FL_THREADS), 0, st, a.x,
+    PHOTON_LAUNCH(KC_SKINNY_GEMM, st, (fused_linear_bf16_kernel<NT, EPI, FOLD, XP, false>), grid, dim3(FL_THREADS), 0, st, a.x,
                   a.ldx, (const bf16_t*)a.W, a.gain, a.eps, a.bias, a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K);
 }
 
 template <int EPI, int XP>
 static void launch_bf16_x(const LinearArgs& a, hipStream_t st) {
-  // more columns per workgroup (fewer re-reads of the activations) once there are enough workgroups to fill the chip
   if constexpr (EPI != EPI_SWIGLU) {                          // SwiGLU already carries two tiles (gate, up) per workgroup
-    if (a.N >= 6144) return launch_bf16_v<2, EPI, XP>(a, st);
+    // more columns per workgroup (fewer re-reads of the activations) once there are enough workgroups to fill the chip
+    if (a.N >= 6144) return launch_bf16_v<2, EPI, false, XP>(a, st);
+    // too few 16-column tiles for the compute units: 8-column folded tiles
+    if (a.N < 256 * 16) return launch_bf16_v<1, EPI, true, XP>(a, st);
   }
-  return launch_bf16_v<1, EPI, XP>(a, st);
+  return launch_bf16_v<1, EPI, false, XP>(a, st);
 }
 
 template <int EPI>

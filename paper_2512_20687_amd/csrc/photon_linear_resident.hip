@@ -7,7 +7,13 @@
 // outweigh a tile's weights (32 B per k), and they are re-read, re-scaled and
 // re-split for every tile.  This kernel therefore
 //   * spreads the output columns evenly over (up to) one workgroup per compute
-//     unit, in units of 8 columns, several MFMA tiles per workgroup;
+//     unit, in units of 8 columns, several units per workgroup.  A unit is one
+//     MFMA tile: for SwiGLU its 8 gate rows and the 8 matching up rows; else
+//     its 8 weight rows with the two halves of every 128-byte line folded
+//     into the tile's two row halves (one load instruction then fetches whole
+//     lines and no lane carries a duplicate: a compute unit's load path is the
+//     scarce resource, and a load that hits in cache costs it as much as one
+//     that misses);
 //   * reads, normalises and splits the activations ONCE per workgroup into
 //     MFMA operand order (bf16 head + bf16 remainder) and keeps them in LDS,
 //     each of the 8 waves holding the k chunks it contracts over;
@@ -37,12 +43,15 @@ __host__ __device__ constexpr int rl_group_pitch(int rows) { return rows * 16 + 
 __host__ __device__ constexpr int rl_chunk_bytes(int rows) { return 2 * 16 * rl_group_pitch(rows); }
 
 // EPI as in LinearEpilogue; XP: live slab pieces per lane (rows = 2*XP of the 16-row tile are live);
-// NORM: RMS pre-norm with gain; TMAX: MFMA tiles per workgroup (register-resident accumulators).
+// NORM: RMS pre-norm with gain; TMAX: units (MFMA tiles, register-resident accumulators) per workgroup.
 //
-// Columns are dealt in units of 8: workgroup g owns units [u0, u0 + cnt).  Plain / residual: a tile is two
-// consecutive units (16 columns), a trailing single unit repeats its rows in the upper half.  SwiGLU: a tile is
-// one unit, gate rows in the lower and the matching up rows in the upper half, so the gated product of a
-// column is formed from two accumulator rows of the same tile.
+// Columns are dealt in units of 8: workgroup g owns units [u0, u0 + cnt), one MFMA tile each.
+//   SwiGLU : tile rows 0..7 are the unit's gate rows, rows 8..15 the matching up rows; two loads per k block.
+//   else   : tile row r (and r + 8) is the unit's weight row r; lanes of rows 0..7 load the first 64 bytes of
+//            a block's line, lanes of rows 8..15 the second 64 (one load per k block).  The first MFMA of a
+//            block uses the registers as loaded, the second after a rotation by 8 lanes inside each row of
+//            16, which brings the second half under rows 0..7.  Accumulator rows 8..15 are meaningless there.
+// Either way the results of a unit's 8 columns sit in the accumulator rows 0..7 (lanes 0..31).
 template <int EPI, int XP, bool NORM, int TMAX>
 __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
     const float* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ W, const float* __restrict__ gain, float eps,
@@ -52,7 +61,8 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   constexpr int ROWS = 2 * XP;
   constexpr int GP = rl_group_pitch(ROWS);
   constexpr int CHUNK_BYTES = rl_chunk_bytes(ROWS);
-  constexpr int UPT = (EPI == EPI_SWIGLU) ? 1 : 2;                 // units per tile
+  constexpr bool FOLD = (EPI != EPI_SWIGLU);
+  constexpr int WL = FOLD ? 1 : 2;                                 // weight loads per k block and tile
   extern __shared__ __align__(16) char smem[];                     // [8 waves][wave_bytes], then row statistics [8][16]
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -65,23 +75,21 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   const int g = blockIdx.x;
   const int u_cnt = unit_base + (g < unit_rem ? 1 : 0);
   const int u0 = g * unit_base + (g < unit_rem ? g : unit_rem);
-  const int tiles = (u_cnt + UPT - 1) / UPT;                       // 1 .. TMAX
-  const int n0 = u0 * 8, n_end = (u0 + u_cnt) * 8;
+  const int tiles = u_cnt;                                         // 1 .. TMAX
+  const int n0 = u0 * 8;
 
   // weight row of this lane in every tile, as a byte offset from W (host checks that all of W is below 4 GiB)
   uint32_t w_lane[TMAX];
 #pragma unroll
   for (int t = 0; t < TMAX; ++t) {
     const int tt = t < tiles ? t : tiles - 1;                      // surplus tiles repeat the last one (loaded, never stored)
-    int n;
-    if (EPI == EPI_SWIGLU) {
-      const int c = n0 + tt * 8 + (lrow & 7);
-      n = lrow < 8 ? c : N + c;
+    const int c = n0 + tt * 8 + (lrow & 7);
+    if (FOLD) {
+      w_lane[t] = ((uint32_t)c * (uint32_t)K + (uint32_t)(lq + 4 * (lrow >> 3)) * 8u) * 2u;
     } else {
-      n = n0 + tt * 16 + lrow;
-      n = n < n_end ? n : n - 8;                                   // trailing half tile: upper half repeats the lower
+      const int n = lrow < 8 ? c : N + c;
+      w_lane[t] = ((uint32_t)n * (uint32_t)K + (uint32_t)lq * 8u) * 2u;
     }
-    w_lane[t] = ((uint32_t)n * (uint32_t)K + (uint32_t)lq * 8u) * 2u;
   }
   const char* w_base = reinterpret_cast<const char*>(W);
 
@@ -97,7 +105,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   for (int i = 0; i < XP; ++i) ss[i] = 0.f;
 
   // ---- loads: unconditional, clamped into bounds, so that the load counter can be waited on exactly ----
-  auto load_w = [&](int j, uint4_t (&wf)[TMAX][CB][2]) {
+  auto load_w = [&](int j, uint4_t (&wf)[TMAX][CB][WL]) {
     const int chunk = wave + j * RL_WAVES;
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
@@ -106,8 +114,8 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
       const char* wb = w_base + (int64_t)blk * (RL_KBLOCK * 2);
 #pragma unroll
       for (int t = 0; t < TMAX; ++t) {
-        wf[t][b][0] = load16(wb + w_lane[t]);                      // bytes 0..63 of the row's 128-byte line
-        wf[t][b][1] = load16(wb + w_lane[t] + 64);                 // bytes 64..127
+        wf[t][b][0] = load16(wb + w_lane[t]);                      // folded: the whole line; else its bytes 0..63
+        if (!FOLD) wf[t][b][1] = load16(wb + w_lane[t] + 64);      // bytes 64..127
       }
     }
   };
@@ -152,7 +160,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
     }
   };
   const int frag_row = (lrow & (ROWS - 1)) * 16;                   // dead rows read a live row's fragment: never stored
-  auto mma = [&](int j, const uint4_t (&wf)[TMAX][CB][2]) {
+  auto mma = [&](int j, const uint4_t (&wf)[TMAX][CB][WL]) {
     const int chunk = wave + j * RL_WAVES;
     const char* hi = my_area + j * CHUNK_BYTES;
     const char* lo = hi + 16 * GP;
@@ -166,7 +174,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
           const bf16x8_t bl = as_bf16x8(*reinterpret_cast<const uint4_t*>(lo + off));
 #pragma unroll
           for (int t = 0; t < TMAX; ++t) {
-            const bf16x8_t a = as_bf16x8(wf[t][b][half2]);
+            const bf16x8_t a = as_bf16x8(FOLD ? (half2 ? rotate8(wf[t][b][0]) : wf[t][b][0]) : wf[t][b][WL - 1 < half2 ? WL - 1 : half2]);
             acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[t], 0, 0, 0);
             acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[t], 0, 0, 0);
           }
@@ -175,40 +183,44 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
     }
   };
 
-  uint4_t wa[TMAX][CB][2], wb[TMAX][CB][2];
+  uint4_t wa[TMAX][CB][WL], wb[TMAX][CB][WL];
   float4_t xa[XP + 1], xb[XP + 1];
   if (n_my > 0) {
     // Activations are requested before the weights: loads return in order, and the (cached) activations must
     // not queue behind weight lines coming from HBM.  Both arms keep the number of loads in flight static.
+    // The common depths (one or two chunks per wave) are written out straight.
     if (n_my == 1) {
       load_x(0, xa);
       load_w(0, wa);
       stage(0, xa);
+      mma(0, wa);
+    } else if (n_my == 2) {
+      load_x(0, xa);
+      load_x(1, xb);
+      load_w(0, wa);
+      stage(0, xa);
+      stage(1, xb);
+      load_w(1, wb);                                               // after staging: the slabs' registers are free again, and
+                                                                   // the load path has been busy with the requests above anyway
+      mma(0, wa);
+      mma(1, wb);
     } else {
       load_x(0, xa);
       load_x(1, xb);
       load_w(0, wa);
-      load_w(1, wb);
       stage(0, xa);
       stage(1, xb);
-      // further chunks (long contractions only): one slab in flight while the previous one is staged
+      // further slabs: one in flight while the previous one is staged
       int j = 2;
-      if (j < n_my) {
-        load_x(j, xa);
-        while (true) {
-          if (j + 1 < n_my) { load_x(j + 1, xb); stage(j, xa); } else { stage(j, xa); break; }
-          if (j + 2 < n_my) { load_x(j + 2, xa); stage(j + 1, xb); } else { stage(j + 1, xb); break; }
-          j += 2;
-        }
+      load_x(j, xa);
+      while (true) {
+        if (j + 1 < n_my) { load_x(j + 1, xb); stage(j, xa); } else { stage(j, xa); break; }
+        if (j + 2 < n_my) { load_x(j + 2, xa); stage(j + 1, xb); } else { stage(j + 1, xb); break; }
+        j += 2;
       }
-    }
-    __builtin_amdgcn_wave_barrier();
-    // weights: chunk j+1 in flight while chunk j is multiplied (chunks 0 and 1 were requested above)
-    if (n_my == 1) {
-      mma(0, wa);
-    } else {
-      // wa holds chunk j, wb chunk j + 1; each arm issues a fixed number of loads between a request and its use
-      int j = 0;
+      load_w(1, wb);
+      // weights: wa holds chunk j, wb chunk j + 1; each arm issues a fixed number of loads between a request and its use
+      j = 0;
       while (true) {
         mma(j, wa);
         if (j + 2 < n_my) {
@@ -242,14 +254,8 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   const int t = wave;
   const int m = m0 + lrow;
   if (m >= M) return;
-  int n_out;
-  if (EPI == EPI_SWIGLU) {
-    if (lq >= 2) return;                                           // upper half of the tile: the up rows, read below
-    n_out = n0 + t * 8 + lq * 4;
-  } else {
-    n_out = n0 + t * 16 + lq * 4;
-    if (n_out >= n_end) return;                                    // repeated rows of a trailing half tile
-  }
+  if (lq >= 2) return;                                             // accumulator rows 8..15: up rows (read below) or meaningless
+  const int n_out = n0 + t * 8 + lq * 4;
   float4_t extra = float4_t{0.f, 0.f, 0.f, 0.f};                   // bias and residual, fetched while the partials are added
   if (bias != nullptr) extra = *reinterpret_cast<const float4_t*>(bias + n_out);
   if (EPI == EPI_RESID) extra += *reinterpret_cast<const float4_t*>(res + (int64_t)m * ldres + n_out);
@@ -297,7 +303,10 @@ bool launch_resident_x(const LinearArgs& a, hipStream_t st, int tmax, int G, int
     case 1: return launch_resident_t<EPI, XP, NORM, 1>(a, st, G, ub, ur, wave_bytes, lds);
     case 2: return launch_resident_t<EPI, XP, NORM, 2>(a, st, G, ub, ur, wave_bytes, lds);
     case 3: return launch_resident_t<EPI, XP, NORM, 3>(a, st, G, ub, ur, wave_bytes, lds);
-    default: return launch_resident_t<EPI, XP, NORM, 4>(a, st, G, ub, ur, wave_bytes, lds);
+    case 4: return launch_resident_t<EPI, XP, NORM, 4>(a, st, G, ub, ur, wave_bytes, lds);
+    default:
+      if constexpr (EPI != EPI_SWIGLU) return launch_resident_t<EPI, XP, NORM, 8>(a, st, G, ub, ur, wave_bytes, lds);
+      return false;
   }
 }
 
@@ -324,15 +333,16 @@ bool launch_linear_resident(const LinearArgs& a, hipStream_t st) {
   if (w_rows * a.K * 2 >= ((int64_t)1 << 32)) return false;       // 32-bit weight offsets
   const int rows_live = a.M < 16 ? a.M : 16;
   const int xp = rows_live <= 4 ? 2 : rows_live <= 8 ? 4 : 8;
-  const int upt = (a.epilogue == EPI_SWIGLU) ? 1 : 2;
   const int units = a.N / 8;
-  // one workgroup per compute unit when there are enough units, more rounds only when a workgroup would exceed 4 tiles
+  // one workgroup per compute unit when there are enough units; more rounds only when a workgroup would exceed the
+  // units its registers hold (8 folded tiles, or 4 gate/up tiles)
   constexpr int CUS = 256;
-  const int per_round = CUS * 4 * upt;
-  const int rounds = (units + per_round - 1) / per_round;
-  int G = units < CUS * rounds ? units : CUS * rounds;
+  const int cap = (a.epilogue == EPI_SWIGLU) ? 4 : 8;
+  const int rounds = (units + CUS * cap - 1) / (CUS * cap);
+  const int G = units < CUS * rounds ? units : CUS * rounds;
   const int ub = units / G, ur = units % G;
-  const int tmax = (ub + (ur ? 1 : 0) + upt - 1) / upt;
+  int tmax = ub + (ur ? 1 : 0);
+  if (tmax > 4) tmax = 8;                                          // instantiated: 1, 2, 3, 4, 8 (surplus tiles repeat the last)
   const int chunks = (a.K / RL_KBLOCK + RL_CB - 1) / RL_CB;
   const int n_my_max = (chunks + RL_WAVES - 1) / RL_WAVES;
   int wave_bytes = n_my_max * rl_chunk_bytes(2 * xp);
