@@ -120,7 +120,9 @@ __global__ __launch_bounds__(FL_THREADS, (NT == 1 && EPI != EPI_SWIGLU && XP == 
 #pragma unroll
       for (int t = 0; t < TL; ++t) {
         const char* p = wtile[t] + (int64_t)blk * (FL_KBLOCK * 2) + w_lane;
-        wf[t][b][0] = load16(p);                                   // bytes 0..63 of the row's 128-byte line (folded: all of it)
+        // bytes 0..63 of the row's 128-byte line; folded: all of it, and non-temporal (whole lines used once
+        // stream past the caches; for half lines the cached path measured faster)
+        wf[t][b][0] = FOLD ? load16_stream(p) : load16(p);
         if (!FOLD) wf[t][b][1] = load16(p + 64);                   // bytes 64..127
       }
     }
@@ -319,7 +321,6 @@ template <int NT, int EPI, bool FOLD, int XP>
 static void launch_bf16_v(const LinearArgs& a, hipStream_t st) {
   constexpr int COLS = FOLD ? 8 : NT * 16;
   dim3 grid((a.N + COLS - 1) / COLS, (a.M + 15) / 16);
-  // plain (cacheable) weight loads: measured faster than non-temporal ones here
   if (a.gain != nullptr)
     PHOTON_LAUNCH(KC_SKINNY_GEMM, st, (fused_linear_bf16_kernel<NT, EPI, FOLD, XP, true>), grid, dim3(FL_THREADS), 0, st, a.x,
                   a.ldx, (const bf16_t*)a.W, a.gain, a.eps, a.bias, a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K);

@@ -43,15 +43,14 @@ __host__ __device__ constexpr int rl_group_pitch(int rows) { return rows * 16 + 
 __host__ __device__ constexpr int rl_chunk_bytes(int rows) { return 2 * 16 * rl_group_pitch(rows); }
 
 // EPI as in LinearEpilogue; XP: live slab pieces per lane (rows = 2*XP of the 16-row tile are live);
-// NORM: RMS pre-norm with gain; TMAX: units (MFMA tiles, register-resident accumulators) per workgroup.
+// NORM: RMS pre-norm with gain; TMAX: units per workgroup (register-resident accumulators).
 //
-// Columns are dealt in units of 8: workgroup g owns units [u0, u0 + cnt), one MFMA tile each.
-//   SwiGLU : tile rows 0..7 are the unit's gate rows, rows 8..15 the matching up rows; two loads per k block.
-//   else   : tile row r (and r + 8) is the unit's weight row r; lanes of rows 0..7 load the first 64 bytes of
-//            a block's line, lanes of rows 8..15 the second 64 (one load per k block).  The first MFMA of a
-//            block uses the registers as loaded, the second after a rotation by 8 lanes inside each row of
-//            16, which brings the second half under rows 0..7.  Accumulator rows 8..15 are meaningless there.
-// Either way the results of a unit's 8 columns sit in the accumulator rows 0..7 (lanes 0..31).
+// Columns are dealt in units of 8: workgroup g owns units [u0, u0 + cnt).  A unit's 8 weight rows form one MFMA
+// tile (SwiGLU: one tile of gate rows and one of the matching up rows): tile row r and r + 8 are weight row r;
+// lanes of rows 0..7 load the first 64 bytes of a k block's 128-byte line, lanes of rows 8..15 the second 64,
+// so one load per block fetches whole lines.  The first MFMA of a block uses the registers as loaded, the second
+// after a rotation by 8 lanes inside each row of 16, which brings the second half under rows 0..7.  Accumulator
+// rows 8..15 are meaningless; a unit's 8 columns sit in rows 0..7 (lanes 0..31).
 template <int EPI, int XP, bool NORM, int TMAX>
 __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
     const float* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ W, const float* __restrict__ gain, float eps,
@@ -61,8 +60,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   constexpr int ROWS = 2 * XP;
   constexpr int GP = rl_group_pitch(ROWS);
   constexpr int CHUNK_BYTES = rl_chunk_bytes(ROWS);
-  constexpr bool FOLD = (EPI != EPI_SWIGLU);
-  constexpr int WL = FOLD ? 1 : 2;                                 // weight loads per k block and tile
+  constexpr int TT = (EPI == EPI_SWIGLU) ? 2 * TMAX : TMAX;        // MFMA tiles: gate tiles first, then the up tiles
   extern __shared__ __align__(16) char smem[];                     // [8 waves][wave_bytes], then row statistics [8][16]
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -79,17 +77,13 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   const int n0 = u0 * 8;
 
   // weight row of this lane in every tile, as a byte offset from W (host checks that all of W is below 4 GiB)
-  uint32_t w_lane[TMAX];
+  uint32_t w_lane[TT];
 #pragma unroll
-  for (int t = 0; t < TMAX; ++t) {
-    const int tt = t < tiles ? t : tiles - 1;                      // surplus tiles repeat the last one (loaded, never stored)
-    const int c = n0 + tt * 8 + (lrow & 7);
-    if (FOLD) {
-      w_lane[t] = ((uint32_t)c * (uint32_t)K + (uint32_t)(lq + 4 * (lrow >> 3)) * 8u) * 2u;
-    } else {
-      const int n = lrow < 8 ? c : N + c;
-      w_lane[t] = ((uint32_t)n * (uint32_t)K + (uint32_t)lq * 8u) * 2u;
-    }
+  for (int t = 0; t < TT; ++t) {
+    const int u = t % TMAX;
+    const int uu = u < tiles ? u : tiles - 1;                      // surplus units repeat the last one (loaded, never stored)
+    const int n = (t < TMAX ? 0 : N) + n0 + uu * 8 + (lrow & 7);   // SwiGLU: the up rows follow the N gate rows
+    w_lane[t] = ((uint32_t)n * (uint32_t)K + (uint32_t)(lq + 4 * (lrow >> 3)) * 8u) * 2u;
   }
   const char* w_base = reinterpret_cast<const char*>(W);
 
@@ -97,15 +91,15 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   const int chunks = (total_blocks + CB - 1) / CB;
   const int n_my = wave < chunks ? (chunks - wave + RL_WAVES - 1) / RL_WAVES : 0;   // this wave contracts chunks wave, wave+8, ..
 
-  float4_t acc[TMAX];
+  float4_t acc[TT];
 #pragma unroll
-  for (int t = 0; t < TMAX; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
+  for (int t = 0; t < TT; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
   float ss[XP];
 #pragma unroll
   for (int i = 0; i < XP; ++i) ss[i] = 0.f;
 
   // ---- loads: unconditional, clamped into bounds, so that the load counter can be waited on exactly ----
-  auto load_w = [&](int j, uint4_t (&wf)[TMAX][CB][WL]) {
+  auto load_w = [&](int j, uint4_t (&wf)[TT][CB]) {
     const int chunk = wave + j * RL_WAVES;
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
@@ -113,10 +107,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
       blk = blk < total_blocks ? blk : total_blocks - 1;
       const char* wb = w_base + (int64_t)blk * (RL_KBLOCK * 2);
 #pragma unroll
-      for (int t = 0; t < TMAX; ++t) {
-        wf[t][b][0] = load16(wb + w_lane[t]);                      // folded: the whole line; else its bytes 0..63
-        if (!FOLD) wf[t][b][1] = load16(wb + w_lane[t] + 64);      // bytes 64..127
-      }
+      for (int t = 0; t < TT; ++t) wf[t][b] = load16_stream(wb + w_lane[t]);   // used once: keep it from displacing the activations
     }
   };
   // slab piece i of a lane: row i*2 + lane/32, k offset (lane%32)*4 inside the chunk
@@ -160,7 +151,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
     }
   };
   const int frag_row = (lrow & (ROWS - 1)) * 16;                   // dead rows read a live row's fragment: never stored
-  auto mma = [&](int j, const uint4_t (&wf)[TMAX][CB][WL]) {
+  auto mma = [&](int j, const uint4_t (&wf)[TT][CB]) {
     const int chunk = wave + j * RL_WAVES;
     const char* hi = my_area + j * CHUNK_BYTES;
     const char* lo = hi + 16 * GP;
@@ -173,8 +164,8 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
           const bf16x8_t bh = as_bf16x8(*reinterpret_cast<const uint4_t*>(hi + off));
           const bf16x8_t bl = as_bf16x8(*reinterpret_cast<const uint4_t*>(lo + off));
 #pragma unroll
-          for (int t = 0; t < TMAX; ++t) {
-            const bf16x8_t a = as_bf16x8(FOLD ? (half2 ? rotate8(wf[t][b][0]) : wf[t][b][0]) : wf[t][b][WL - 1 < half2 ? WL - 1 : half2]);
+          for (int t = 0; t < TT; ++t) {
+            const bf16x8_t a = as_bf16x8(half2 ? rotate8(wf[t][b]) : wf[t][b]);
             acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[t], 0, 0, 0);
             acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[t], 0, 0, 0);
           }
@@ -183,7 +174,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
     }
   };
 
-  uint4_t wa[TMAX][CB][WL], wb[TMAX][CB][WL];
+  uint4_t wa[TT][CB], wb[TT][CB];
   float4_t xa[XP + 1], xb[XP + 1];
   if (n_my > 0) {
     // Activations are requested before the weights: loads return in order, and the (cached) activations must
@@ -245,7 +236,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   __syncthreads();                                                 // every wave is done with its operands: the area is reused
   float4_t* red = reinterpret_cast<float4_t*>(my_area);
 #pragma unroll
-  for (int t = 0; t < TMAX; ++t) red[t * 64 + lane] = acc[t];
+  for (int t = 0; t < TT; ++t) red[t * 64 + lane] = acc[t];
   __syncthreads();
 
   // wave t finishes tile t: partial tiles added in wave order, 1/rms, epilogue.
@@ -254,7 +245,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   const int t = wave;
   const int m = m0 + lrow;
   if (m >= M) return;
-  if (lq >= 2) return;                                             // accumulator rows 8..15: up rows (read below) or meaningless
+  if (lq >= 2) return;                                             // accumulator rows 8..15 are meaningless
   const int n_out = n0 + t * 8 + lq * 4;
   float4_t extra = float4_t{0.f, 0.f, 0.f, 0.f};                   // bias and residual, fetched while the partials are added
   if (bias != nullptr) extra = *reinterpret_cast<const float4_t*>(bias + n_out);
@@ -265,7 +256,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   for (int w = 0; w < RL_WAVES; ++w) {
     const float4_t* rw = reinterpret_cast<const float4_t*>(smem + w * wave_bytes);
     y += rw[t * 64 + lane];
-    if (EPI == EPI_SWIGLU) yu += rw[t * 64 + lane + 32];
+    if (EPI == EPI_SWIGLU) yu += rw[(TMAX + t) * 64 + lane];
     tot += ssum[w * 16 + lrow];
   }
   if (NORM) {
@@ -346,7 +337,8 @@ bool launch_linear_resident(const LinearArgs& a, hipStream_t st) {
   const int chunks = (a.K / RL_KBLOCK + RL_CB - 1) / RL_CB;
   const int n_my_max = (chunks + RL_WAVES - 1) / RL_WAVES;
   int wave_bytes = n_my_max * rl_chunk_bytes(2 * xp);
-  if (wave_bytes < tmax * 1024) wave_bytes = tmax * 1024;          // the partial tiles reuse the area
+  const int tt = (a.epilogue == EPI_SWIGLU) ? 2 * tmax : tmax;
+  if (wave_bytes < tt * 1024) wave_bytes = tt * 1024;              // the partial tiles reuse the area
   const size_t lds = (size_t)RL_WAVES * wave_bytes + RL_WAVES * 16 * sizeof(float);
   if (lds > (size_t)RL_LDS_LIMIT) return false;
   switch (a.epilogue) {
