@@ -16,6 +16,7 @@ import argparse
 import json
 import math
 import os
+import re
 import sys
 import time
 
@@ -86,6 +87,21 @@ def cpu_baseline(wl, min_seconds=12.0, max_steps=120):
                   f"with {sample_layers} of {wl.cfg.n_layers} blocks per module: {dt:.1f} s measured, time scaled x{scale:g}",
         "seconds_measured": dt,
     }
+
+
+def counter_traffic(workload, kernel_class):
+    """HBM bytes per launch of the dominant kernel class from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE, each scaled by what the counter reads for a plain copy of known size);
+    None when no summary covers this workload and kernel."""
+    if workload != "cfg3_bf16_128k" or kernel_class != "linear_bf16_kernels":
+        return None
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "decode_step_cfg3_hbm_counters.md")
+    try:
+        with open(path) as f:
+            m = re.search(r"linear_traffic_bytes_per_launch:.*total=(\d+)", f.read())
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
 
 
 def main():
@@ -183,7 +199,7 @@ def main():
     kernels = {}
     for name, (n, ms) in prof.items():
         kernels[name] = {"launches_per_step": n / prof_steps, "us_per_launch": ms * 1e3 / n, "ms_per_step": ms / prof_steps}
-    alg_bytes = {"skinny_gemm_bf16_kernel": wbytes, "coarse_attn_kernel": kv_launch_bytes * nl}     # per step
+    alg_bytes = {"linear_bf16_kernels": wbytes, "coarse_attn_kernel": kv_launch_bytes * nl}     # per step
     for name, b in alg_bytes.items():
         if name in kernels:
             k = kernels[name]
@@ -193,7 +209,7 @@ def main():
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     dk = kernels[dominant]
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": dk.get("gbs"), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": dk.get("frac_of_hbm_peak"), "traffic": None, "bytes_per_launch": dk.get("bytes_per_launch"),
+                "frac": dk.get("frac_of_hbm_peak"), "traffic": counter_traffic(wl.name, dominant), "bytes_per_launch": dk.get("bytes_per_launch"),
                 "us_per_launch": dk["us_per_launch"], "launches_per_step": dk["launches_per_step"],
                 "share_of_kernel_time": dk["ms_per_step"] / sum(k["ms_per_step"] for k in kernels.values())}
     ca = kernels.get("coarse_attn_kernel", {})

@@ -30,7 +30,7 @@ struct ProfRec { int cls; hipEvent_t start, stop; };
 std::mutex g_prof_mu;
 std::vector<ProfRec> g_prof;
 const char* const kClassNames[KC_COUNT] = {
-    "coarse_attn_kernel", "coarse_merge_kernel", "local_attn_kernel", "skinny_gemm_bf16_kernel", "gemm_f32_kernel",
+    "coarse_attn_kernel", "coarse_merge_kernel", "local_attn_kernel", "linear_bf16_kernels", "gemm_f32_kernel",
     "reduce_splits_kernel", "chunker_gemm_bf16_kernel", "norm_rows_kernel", "rope_append_kernel", "silu_mul_kernel",
     "choose_token_kernel", "misc"};
 }  // namespace
