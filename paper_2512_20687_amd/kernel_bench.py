@@ -1,0 +1,154 @@
+"""Per-kernel throughput of the hot path's entry points at the shapes of the
+benchmark configurations, each against the roofline that bounds it.
+
+    python -m paper_2512_20687_amd.kernel_bench [--only a1,a2,a3,linear,probe]
+
+Prints one JSON object per line: a streaming-read ceiling (a trivial read-only
+kernel over 2 GiB), the chunker GEMM (bf16 MFMA peak), the coarse decode
+attention at the configuration-3 shape and over a flat 131072-key cache (HBM
+peak), chunk-local attention in tile mode (HBM peak) and the few-row linear
+maps of one block (HBM peak on weight bytes).  Inputs are seeded and synthetic,
+drawn on the GPU; buffers below 1 GiB are rotated so that no cache can serve a
+launch from the previous one.  Timing: HIP events on the launch stream around
+`iters` back-to-back launches after a warm-up, so a launch's time includes the
+gap to the next one (what a caller pays); rocprofv3's kernel durations are a
+few microseconds shorter.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+import torch
+
+from . import binding as ph
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
+
+
+def _time_us(fn, iters, warm=2):
+    for i in range(warm):
+        fn(i)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(iters):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters * 1e3
+
+
+def _emit(kernel, shape, us, *, bytes_=None, flops=None):
+    rec = {"kernel": kernel, "shape": shape, "us_per_launch": round(us, 2)}
+    if bytes_ is not None:
+        gbs = bytes_ / us / 1e3
+        rec.update(bound="hbm", algorithmic_bytes=int(bytes_), achieved=round(gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                   frac=round(gbs / HBM_PEAK_GBS, 4))
+    if flops is not None:
+        tf = flops / us / 1e6
+        rec.update(bound="mfma", algorithmic_flops=int(flops), achieved=round(tf, 1), peak=BF16_MFMA_PEAK_TFLOPS,
+                   unit="TFLOP/s", frac=round(tf / BF16_MFMA_PEAK_TFLOPS, 4))
+    print(json.dumps(rec), flush=True)
+    return rec
+
+
+def bench_probe():
+    """Achieved ceiling of a trivial read-only kernel (2 GiB, and the sizes of one block's weight matrices)."""
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    big = torch.empty(2 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    us = _time_us(lambda i: ph.photon_hbm_read_probe(big, sink), 10)
+    _emit("hbm_read_probe_kernel", "2 GiB", us, bytes_=big.numel())
+    for mb in (8.4, 25.2, 41.9, 131.1):
+        n = int(mb * 1e6) // 16 * 16
+        pool = 3 << 28                                    # 768 MiB window walked in steps of the buffer size
+        slots = max(2, pool // n)
+        us = _time_us(lambda i: ph.photon_hbm_read_probe(big[(i % slots) * n:(i % slots) * n + n], sink), 4 * slots, warm=slots)
+        _emit("hbm_read_probe_kernel", f"{mb} MB, rotating", us, bytes_=n)
+    del big
+
+
+def bench_a1():
+    """Chunker projection (Eq. 4) at prefill shapes: rows x (C*D) -> D, bf16."""
+    for rows, C_, D, N, what in ((32768, 8, 2048, 2048, "cfg5 level 1"), (4096, 8, 2048, 2048, "cfg5 level 2"),
+                                 (512, 8, 2048, 2048, "cfg5 level 3"), (8192, 4, 2048, 2048, "cfg3 token level, 32k tokens"),
+                                 (8192, 4, 1024, 1024, "cfg2/4 token level")):
+        x = torch.empty((rows * C_, D), device="cuda", dtype=torch.bfloat16).normal_()
+        w = (torch.empty((N, C_ * D), device="cuda", dtype=torch.float32).normal_() * 0.02).to(torch.bfloat16)
+        b = torch.zeros(N, device="cuda")
+        out = torch.empty((rows, N), device="cuda", dtype=torch.bfloat16)
+        us = _time_us(lambda i: ph.photon_chunker_project(x, w, b, out, C_), 5)
+        _emit("chunker_gemm_bf16_kernel", f"{what}: rows={rows} K={C_ * D} N={N}", us, flops=2.0 * rows * C_ * D * N)
+        del x, w, out
+
+
+def bench_a2():
+    """Coarse decode attention (Eq. 12-13): one query per (sequence, head) over the coarse cache."""
+    for Bt, H, S, nl, what in ((4, 32, 8320, 8, "cfg3: 131072 tokens / 16"), (4, 32, 131072, 2, "flat comparison: 131072 keys"),
+                               (256, 16, 2112, 2, "cfg4"), (16, 16, 640, 8, "cfg2 (cache-resident working set)")):
+        d_h = 64
+        k = torch.empty((nl, Bt, H, S, d_h), device="cuda", dtype=torch.bfloat16).normal_()
+        v = torch.empty_like(k).normal_()
+        q = torch.randn((Bt, H, d_h), device="cuda").to(torch.bfloat16)
+        o = torch.empty_like(q)
+        seq = torch.full((Bt,), S, dtype=torch.int32, device="cuda")
+        ns = ph.photon_coarse_decode_attn_auto_splits(Bt, H, S)
+        ws = torch.empty(max(ph.photon_coarse_decode_attn_workspace_bytes(Bt, H, d_h, max(ns, 2)), 16), dtype=torch.uint8, device="cuda")
+        us = _time_us(lambda i: ph.photon_coarse_decode_attn(q, k[i % nl], v[i % nl], seq, o, n_splits=ns, workspace=ws), 5 * nl, warm=nl)
+        _emit("coarse_attn_kernel + coarse_merge_kernel", f"{what}: Bt={Bt} H={H} S={S} d_h={d_h} splits={ns}", us,
+              bytes_=2 * Bt * H * S * d_h * 2)
+        del k, v
+
+
+def bench_a3():
+    """Chunk-local attention (Eq. 6-7), tile mode: every chunk's W x W causal window in one pass."""
+    for n, W, H, what in ((32768, 8, 32, "cfg5 level 1"), (131072, 4, 32, "cfg3 token level, slice"), (262144, 4, 16, "cfg4 slice"),
+                          (32768, 4, 16, "cfg2")):
+        d_h = 64
+        q = torch.empty((n, W, H, d_h), device="cuda", dtype=torch.bfloat16).normal_()
+        k = torch.empty_like(q).normal_()
+        v = torch.empty_like(q).normal_()
+        o = torch.empty_like(q)
+        us = _time_us(lambda i: ph.photon_chunk_local_attn(q, k, v, o), 5)
+        _emit("local_attn_kernel", f"{what}: chunks={n} W={W} H={H} d_h={d_h}", us, bytes_=4 * q.numel() * 2)
+        del q, k, v, o
+
+
+def bench_linear():
+    """Few-row linear maps of one configuration-3 block at the row counts of the decode sub-steps."""
+    shapes = ((6144, 2048, 0, True, "QKV + norm"), (2048, 2048, 1, False, "O + residual"), (5120, 2048, 2, True, "gate/up + norm + SwiGLU"),
+              (2048, 5120, 1, False, "down + residual"), (32000, 2048, 0, True, "LM head + final norm"))
+    for M in (4, 16):
+        for N, K, epi, norm, what in shapes:
+            rows_w = 2 * N if epi == 2 else N
+            nb = max(2, int(600e6 // (rows_w * K * 2)))
+            ws = [(torch.empty((rows_w, K), device="cuda").normal_() * 0.02).to(torch.bfloat16) for _ in range(nb)]
+            x = torch.randn(M, K, device="cuda")
+            out = torch.empty(M, N, device="cuda")
+            res = torch.randn(M, N, device="cuda") if epi == 1 else None
+            g = torch.rand(K, device="cuda") + 0.5 if norm else None
+            us = _time_us(lambda i: ph.photon_linear(x, ws[i % nb], out, gain=g, rms_eps=1e-5, res=res, epilogue=epi), 4 * nb, warm=nb)
+            _emit("linear_bf16_kernels", f"{what}: M={M} N={N} K={K}", us, bytes_=rows_w * K * 2)
+            del ws
+
+
+ALL = {"probe": bench_probe, "a1": bench_a1, "a2": bench_a2, "a3": bench_a3, "linear": bench_linear}
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--only", default=",".join(ALL), help="comma-separated subset of: " + ", ".join(ALL))
+    args = ap.parse_args(argv)
+    if not torch.cuda.is_available():
+        sys.exit("kernel_bench: no GPU visible; this benchmark runs the HIP kernels only")
+    ph.load_library()
+    torch.manual_seed(0)
+    for name in args.only.split(","):
+        ALL[name.strip()]()
+
+
+if __name__ == "__main__":
+    main()
