@@ -1,14 +1,18 @@
-// Context-chunker projection (paper Eq. 4) at many-row shapes: a dense bf16
-// contraction out[M,N] = x[M,K] * W[N,K]^T + bias on the matrix cores.
+// Dense bf16 contractions on the matrix cores: out[M,N] = x[M,K] * W[N,K]^T (+ bias, + residual).
+//   * the context-chunker projection (paper Eq. 4) at many-row shapes: bf16 in, bf16 out;
+//   * the block projections of a decode step once a level carries many rows (large batches, deep
+//     hierarchies): fp32 activations are normalised and split into a bf16 head and a bf16 remainder by a
+//     row kernel, and the contraction runs over [head | remainder] against [W | W], so the product is as
+//     accurate as fp32-activation x bf16-weight, as in the few-row kernels.
 //
-// One workgroup of 4 waves owns a 256x256 output tile; each wave owns a 128x128
-// quadrant as 4x4 MFMA 32x32x16 tiles (256 fp32 accumulators per lane).  K is
-// walked in 64-wide slabs, double-buffered in LDS (2 x 64 KB); the next slab is
-// moved global -> LDS directly (no staging registers) while the current slab's
-// MFMAs run, and operand fragments are double-buffered in registers.  LDS rows
-// are 128 bytes with the 16-byte column index XOR-ed by (row>>1)&7, which keeps
-// the 128-bit operand reads of 16 consecutive rows on distinct banks.  Workgroup ids are remapped so that the tiles resident on one
-// XCD at a time share x row-blocks and W column-blocks in that XCD's L2.
+// One workgroup of 4 waves owns a (64 WT) x (64 WT) output tile, each wave a quadrant of WT x WT
+// MFMA 32x32x16 tiles (WT = 4: 256x256 tile, 128x128 per wave, 256 fp32 accumulators per lane; WT = 2 and 1 for
+// problems with too few big tiles to fill the chip).  K is walked in 64-wide slabs, double-buffered in LDS;
+// the next slab is moved global -> LDS directly (no staging registers) while the current slab's MFMAs
+// run, and operand fragments are double-buffered in registers.  LDS rows are 128 bytes with the 16-byte
+// column index XOR-ed by (row>>1)&7, which keeps the 128-bit operand reads of 16 consecutive rows on
+// distinct banks.  Workgroup ids are remapped so that the tiles resident on one XCD at a time share x
+// row-blocks and W column-blocks in that XCD's L2.
 #include "photon_device.h"
 #include "photon_host.h"
 #include "photon_linear.h"
@@ -17,18 +21,26 @@ namespace photon {
 
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-constexpr int G_BM = 256, G_BN = 256, G_BK = 64;
+constexpr int G_BK = 64;
 constexpr int G_THREADS = 256;
-constexpr int G_TILE_BYTES = G_BM * G_BK * 2;          // 32 KB per operand slab
 
 __device__ __forceinline__ int swz(int row, int col16) { return row * 128 + ((col16 ^ ((row >> 1) & 7)) << 4); }
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-__global__ __launch_bounds__(G_THREADS) void chunker_gemm_bf16_kernel(
-    const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const float* __restrict__ bias, bf16_t* __restrict__ Cout,
-    int M, int N, int K, int tiles_m, int tiles_n) {
+enum GemmOut { GEMM_OUT_BF16 = 0, GEMM_OUT_F32 = 1 };
+
+// WT: MFMA tiles per wave and dimension (tile edge 64 WT).  A_lo != nullptr: second pass over K with the
+// remainders.  OUT bf16: Cout bf16 [M, ldc] = acc + bias.  OUT fp32: Cout fp32 [M, ldc] = acc + bias + res.
+template <int WT, int OUT>
+__global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ A_lo, const bf16_t* __restrict__ B, const float* __restrict__ bias,
+    const float* res, int64_t ldres, void* Cout, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n) {
+  constexpr int BM = 64 * WT;                                   // tile edge (rows and columns)
+  constexpr int WE = 32 * WT;                                   // wave quadrant edge
+  constexpr int TILE_BYTES = BM * G_BK * 2;                     // one operand slab
+  constexpr int ROUNDS = BM / 32;
   extern __shared__ __align__(16) char lds[];                   // [2 buffers][A slab | B slab]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
@@ -38,43 +50,47 @@ __global__ __launch_bounds__(G_THREADS) void chunker_gemm_bf16_kernel(
   const int id = blockIdx.x;
   const int logical = (total % 8 == 0) ? (id & 7) * (total / 8) + (id >> 3) : id;   // ragged tile count: plain order
   const int tm = logical / tiles_n, tn = logical % tiles_n;
-  const int m0 = tm * G_BM, n0 = tn * G_BN;
+  const int m0 = tm * BM, n0 = tn * BM;
 
   // global -> LDS without passing through registers: one instruction moves 64 lanes x 16 B = 8 slab rows;
   // lane l lands at LDS row l/8, 16-byte column l%8, so it fetches the logical column that the XOR
   // swizzle maps there.  Round i of wave w covers slab rows i*32 + w*8 .. +8.
   const int srow = lane >> 3, scol = lane & 7;
-  const bf16_t* aptr[8];
-  const bf16_t* bptr[8];
+  int64_t aoff[ROUNDS];
+  const bf16_t* bptr[ROUNDS];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
+  for (int i = 0; i < ROUNDS; ++i) {
     const int r = i * 32 + wave * 8 + srow;
     const int c = scol ^ ((r >> 1) & 7);
     int ra = m0 + r; ra = ra < M ? ra : M - 1;                   // clamped rows are never stored
     int rb = n0 + r; rb = rb < N ? rb : N - 1;
-    aptr[i] = A + (int64_t)ra * K + c * 8;
+    aoff[i] = (int64_t)ra * K + c * 8;
     bptr[i] = B + (int64_t)rb * K + c * 8;
   }
+  const int KT = K / G_BK;
+  const int KT2 = A_lo != nullptr ? 2 * KT : KT;                 // slabs walked: heads, then remainders against the same W
   auto stage = [&](int kt, int buf) {
-    char* sa = lds + buf * 2 * G_TILE_BYTES;
-    char* sb = sa + G_TILE_BYTES;
+    char* sa = lds + buf * 2 * TILE_BYTES;
+    char* sb = sa + TILE_BYTES;
+    const bf16_t* abase = kt < KT ? A : A_lo;
+    const int64_t kk = (int64_t)(kt < KT ? kt : kt - KT) * G_BK;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < ROUNDS; ++i) {
       const int off = (i * 32 + wave * 8) * 128;
-      __builtin_amdgcn_global_load_lds((gptr_t)(aptr[i] + (int64_t)kt * G_BK), (lptr_t)(sa + off), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(bptr[i] + (int64_t)kt * G_BK), (lptr_t)(sb + off), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(abase + aoff[i] + kk), (lptr_t)(sa + off), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(bptr[i] + kk), (lptr_t)(sb + off), 16, 0, 0);
     }
   };
 
-  float16_t acc[4][4];
+  float16_t acc[WT][WT];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < WT; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < WT; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;       // wave quadrant inside the tile
+  const int wm = (wave >> 1) * WE, wn = (wave & 1) * WE;         // wave quadrant inside the tile
   const int frow = lane & 31, fk = lane >> 5;                    // operand fragment: row, 8-wide k group
 
   // Pipeline over 64-wide K slabs with ONE barrier per slab, placed before the slab's last quarter:
@@ -83,31 +99,30 @@ __global__ __launch_bounds__(G_THREADS) void chunker_gemm_bf16_kernel(
   //     -> every wave has finished reading slab kt, so its buffer can take slab kt+2 right away
   //   issue slab kt+2, read the first fragments of slab kt+1, MFMA(ks=3 of slab kt)
   // so neither the load wait nor the first fragment reads of a slab leave the matrix cores idle.
-  const int KT = K / G_BK;
   constexpr int KS = G_BK / 16;
-  bf16x8_t af[2][4], bfr[2][4];
-  auto frags = [&](int buf, int ks, bf16x8_t (&a)[4], bf16x8_t (&b)[4]) {
-    const char* sa = lds + buf * 2 * G_TILE_BYTES;
-    const char* sb = sa + G_TILE_BYTES;
+  bf16x8_t af[2][WT], bfr[2][WT];
+  auto frags = [&](int buf, int ks, bf16x8_t (&a)[WT], bf16x8_t (&b)[WT]) {
+    const char* sa = lds + buf * 2 * TILE_BYTES;
+    const char* sb = sa + TILE_BYTES;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < WT; ++i) {
       a[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4_t*>(sa + swz(wm + i * 32 + frow, ks * 2 + fk)));
       b[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4_t*>(sb + swz(wn + i * 32 + frow, ks * 2 + fk)));
     }
   };
-  auto mfma16 = [&](const bf16x8_t (&a)[4], const bf16x8_t (&b)[4]) {
+  auto mfma16 = [&](const bf16x8_t (&a)[WT], const bf16x8_t (&b)[WT]) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < WT; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < WT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
   };
 
   stage(0, 0);
-  if (KT > 1) stage(1, 1);
+  if (KT2 > 1) stage(1, 1);
   __builtin_amdgcn_s_waitcnt(0);                                 // both slabs have landed (vmcnt(0))
   __syncthreads();
   frags(0, 0, af[0], bfr[0]);
-  for (int kt = 0; kt < KT; ++kt) {
+  for (int kt = 0; kt < KT2; ++kt) {
     const int buf = kt & 1;
 #pragma unroll
     for (int ks = 0; ks < KS - 1; ++ks) {
@@ -119,8 +134,8 @@ __global__ __launch_bounds__(G_THREADS) void chunker_gemm_bf16_kernel(
     // last quarter: slab kt is completely in registers / consumed from LDS
     __builtin_amdgcn_s_waitcnt(0);                               // slab kt+1 landed, own LDS reads done
     __syncthreads();
-    if (kt + 2 < KT) stage(kt + 2, buf);
-    if (kt + 1 < KT) frags(buf ^ 1, 0, af[KS & 1], bfr[KS & 1]);
+    if (kt + 2 < KT2) stage(kt + 2, buf);
+    if (kt + 1 < KT2) frags(buf ^ 1, 0, af[KS & 1], bfr[KS & 1]);
     __builtin_amdgcn_sched_barrier(0);
     mfma16(af[(KS - 1) & 1], bfr[(KS - 1) & 1]);
     __builtin_amdgcn_sched_barrier(0);
@@ -128,18 +143,71 @@ __global__ __launch_bounds__(G_THREADS) void chunker_gemm_bf16_kernel(
 
   // acc[i][j][v] of lane l: row m = wm + i*32 + 8*(v/4) + 4*(l/32) + v%4, column n = wn + j*32 + l%32
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < WT; ++j) {
     const int n = n0 + wn + j * 32 + (lane & 31);
     if (n >= N) continue;
     const float bv = bias != nullptr ? bias[n] : 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < WT; ++i) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (m < M) Cout[(int64_t)m * N + n] = from_f32<bf16_t>(acc[i][j][v] + bv);
+        if (m >= M) continue;
+        float y = acc[i][j][v] + bv;
+        if (OUT == GEMM_OUT_BF16) {
+          reinterpret_cast<bf16_t*>(Cout)[(int64_t)m * ldc + n] = from_f32<bf16_t>(y);
+        } else {
+          if (res != nullptr) y += res[(int64_t)m * ldres + n];
+          reinterpret_cast<float*>(Cout)[(int64_t)m * ldc + n] = y;
+        }
       }
     }
+  }
+}
+
+// Row kernel in front of the fp32-activation contraction: optional RMS norm with gain, then the split
+// x = head + remainder (both bf16, x - head - remainder = O(2^-17 x)).  One workgroup per row.
+__global__ __launch_bounds__(256) void norm_split_rows_kernel(const float* __restrict__ x, int64_t ldx, const float* __restrict__ gain,
+                                                              float eps, bf16_t* __restrict__ hi, bf16_t* __restrict__ lo, int K) {
+  const int tid = threadIdx.x;
+  const float* xr = x + (int64_t)blockIdx.x * ldx;
+  float r = 1.f;
+  if (gain != nullptr) {
+    float ss = 0.f;
+    for (int k = tid * 4; k < K; k += 1024) {
+      const float4_t v = *reinterpret_cast<const float4_t*>(xr + k);
+      ss = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss))));
+    }
+    ss = group_sum<32>(ss);
+    ss += __shfl_xor(ss, 32);
+    __shared__ float partsum[4];
+    if ((tid & 63) == 0) partsum[tid >> 6] = ss;
+    __syncthreads();
+    r = 1.0f / sqrtf(((partsum[0] + partsum[1]) + (partsum[2] + partsum[3])) / (float)K + eps);
+  }
+  uint2* ho = reinterpret_cast<uint2*>(hi + (int64_t)blockIdx.x * K);
+  uint2* lw = reinterpret_cast<uint2*>(lo + (int64_t)blockIdx.x * K);
+  for (int k = tid * 4; k < K; k += 1024) {
+    float4_t v = *reinterpret_cast<const float4_t*>(xr + k);    // second read of the row: it is in cache
+    if (gain != nullptr) v = v * *reinterpret_cast<const float4_t*>(gain + k) * r;
+    uint32_t h01, l01, h23, l23;
+    split_bf16x2(v.x, v.y, h01, l01);
+    split_bf16x2(v.z, v.w, h23, l23);
+    ho[k >> 2] = uint2{h01, h23};
+    lw[k >> 2] = uint2{l01, l23};
+  }
+}
+
+// out[m, n] = silu(gu[m, n]) * gu[m, N + n], gu fp32 [M, 2N].
+__global__ __launch_bounds__(256) void swiglu_rows_kernel(const float* __restrict__ gu, float* __restrict__ out, int64_t ldo, int N) {
+  const float* g = gu + (int64_t)blockIdx.x * 2 * N;
+  float* o = out + (int64_t)blockIdx.x * ldo;
+  for (int n = threadIdx.x * 4; n < N; n += 1024) {
+    const float4_t a = *reinterpret_cast<const float4_t*>(g + n);
+    const float4_t u = *reinterpret_cast<const float4_t*>(g + N + n);
+    float4_t y;
+    y.x = silu(a.x) * u.x; y.y = silu(a.y) * u.y; y.z = silu(a.z) * u.z; y.w = silu(a.w) * u.w;
+    *reinterpret_cast<float4_t*>(o + n) = y;
   }
 }
 
@@ -148,20 +216,69 @@ __global__ __launch_bounds__(256) void copy_bytes16_kernel(const uint4_t* __rest
   if (idx < n16) dst[idx] = src[idx];
 }
 
-static int32_t launch_chunker_gemm(const void* x, const void* w, const float* bias, void* out, int64_t M, int N, int K, hipStream_t st) {
-  const int tiles_m = (int)((M + G_BM - 1) / G_BM), tiles_n = (N + G_BN - 1) / G_BN;
+template <int WT, int OUT>
+static int32_t launch_gemm_t(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, const float* bias, const float* res,
+                             int64_t ldres, void* out, int64_t ldc, int64_t M, int N, int K, hipStream_t st) {
+  constexpr int BM = 64 * WT;
+  const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BM - 1) / BM;
   const int64_t grid = (int64_t)tiles_m * tiles_n;
-  static bool attr_set = false;
-  const size_t lds_bytes = 4 * G_TILE_BYTES;
+  const size_t lds_bytes = 4 * (size_t)BM * G_BK * 2;
+  static bool attr_set = false;                                  // more than 64 KiB of dynamic LDS has to be allowed once
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(chunker_gemm_bf16_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WT, OUT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return fail(PHOTON_ERR_HIP, "chunker gemm: cannot reserve %zu bytes of LDS: %s", lds_bytes, hipGetErrorString(e));
+    if (e != hipSuccess) return fail(PHOTON_ERR_HIP, "gemm: cannot reserve %zu bytes of LDS: %s", lds_bytes, hipGetErrorString(e));
     attr_set = true;
   }
-  PHOTON_LAUNCH(KC_CHUNKER_GEMM, st, chunker_gemm_bf16_kernel, dim3((unsigned)grid), dim3(G_THREADS), lds_bytes, st, (const bf16_t*)x,
-                     (const bf16_t*)w, bias, (bf16_t*)out, (int)M, N, K, tiles_m, tiles_n);
-  return check_launch("chunker_gemm_bf16_kernel");
+  PHOTON_LAUNCH(cls, st, (gemm_bf16_kernel<WT, OUT>), dim3((unsigned)grid), dim3(G_THREADS), lds_bytes, st, A, A_lo, B, bias, res, ldres,
+                out, ldc, (int)M, N, K, tiles_m, tiles_n);
+  return check_launch("gemm_bf16_kernel");
+}
+
+// Largest tile that still gives the chip enough workgroups.
+static int pick_tile(int64_t M, int N) {
+  auto tiles = [&](int wt) { return ((M + 64 * wt - 1) / (64 * wt)) * ((N + 64 * wt - 1) / (64 * wt)); };
+  if (tiles(4) >= 192) return 4;
+  if (tiles(2) >= 128) return 2;
+  return 1;
+}
+
+template <int OUT>
+static int32_t launch_gemm(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, const float* bias, const float* res,
+                           int64_t ldres, void* out, int64_t ldc, int64_t M, int N, int K, hipStream_t st) {
+  switch (pick_tile(M, N)) {
+    case 4: return launch_gemm_t<4, OUT>(cls, A, A_lo, B, bias, res, ldres, out, ldc, M, N, K, st);
+    case 2: return launch_gemm_t<2, OUT>(cls, A, A_lo, B, bias, res, ldres, out, ldc, M, N, K, st);
+    default: return launch_gemm_t<1, OUT>(cls, A, A_lo, B, bias, res, ldres, out, ldc, M, N, K, st);
+  }
+}
+
+static int32_t launch_chunker_gemm(const void* x, const void* w, const float* bias, void* out, int64_t M, int N, int K, hipStream_t st) {
+  return launch_gemm<GEMM_OUT_BF16>(KC_CHUNKER_GEMM, (const bf16_t*)x, nullptr, (const bf16_t*)w, bias, nullptr, 0, out, N, M, N, K, st);
+}
+
+size_t linear_many_workspace_bytes(int64_t rows, int K_max, int N2_max) {
+  // head and remainder of the activations (bf16 each), then the gate|up product rows (fp32)
+  return (size_t)rows * K_max * 2 * 2 + (size_t)rows * N2_max * sizeof(float);
+}
+
+int32_t launch_linear_many(const LinearArgs& a, void* workspace, int K_max, hipStream_t st) {
+  if (!a.w_bf16 || a.K % G_BK != 0 || a.K > K_max || a.ldx % 4 != 0)
+    return fail(PHOTON_ERR_UNSUPPORTED, "many-row linear: needs bf16 weights, K=%d a multiple of 64 and at most %d", a.K, K_max);
+  bf16_t* hi = reinterpret_cast<bf16_t*>(workspace);
+  bf16_t* lo = hi + (size_t)a.M * K_max;
+  float* gu = reinterpret_cast<float*>(lo + (size_t)a.M * K_max);
+  PHOTON_LAUNCH(KC_NORM, st, norm_split_rows_kernel, dim3(a.M), dim3(256), 0, st, a.x, a.ldx, a.gain, a.eps, hi, lo, a.K);
+  PHOTON_TRY(check_launch("norm_split_rows_kernel"));
+  if (a.epilogue == EPI_SWIGLU) {
+    if (a.N % 4 != 0) return fail(PHOTON_ERR_UNSUPPORTED, "many-row linear: SwiGLU width %d must be a multiple of 4", a.N);
+    PHOTON_TRY(launch_gemm<GEMM_OUT_F32>(KC_CHUNKER_GEMM, hi, lo, (const bf16_t*)a.W, nullptr, nullptr, 0, gu, 2 * (int64_t)a.N, a.M, 2 * a.N,
+                                         a.K, st));
+    PHOTON_LAUNCH(KC_SILU_MUL, st, swiglu_rows_kernel, dim3(a.M), dim3(256), 0, st, gu, a.out, a.ldo, a.N);
+    return check_launch("swiglu_rows_kernel");
+  }
+  return launch_gemm<GEMM_OUT_F32>(KC_CHUNKER_GEMM, hi, lo, (const bf16_t*)a.W, a.bias, a.epilogue == EPI_RESID ? a.res : nullptr, a.ldres,
+                                   a.out, a.ldo, a.M, a.N, a.K, st);
 }
 
 }  // namespace photon

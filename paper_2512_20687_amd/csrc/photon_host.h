@@ -36,6 +36,7 @@ struct ProfScope {
   ProfScope(int c, hipStream_t s) : cls(c), st(s), on(g_profile_on) { if (on) profile_mark(cls, st, true); }
   ~ProfScope() { if (on) profile_mark(cls, st, false); }
 };
+#define PHOTON_TRY(expr) do { const int32_t rc_ = (expr); if (rc_ != PHOTON_OK) return rc_; } while (0)
 #define PHOTON_LAUNCH(cls, stream, ...) \
   do { ::photon::ProfScope prof_scope_((cls), (stream)); hipLaunchKernelGGL(__VA_ARGS__); } while (0)
 

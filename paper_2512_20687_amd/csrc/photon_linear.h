@@ -34,4 +34,10 @@ int32_t launch_linear(const LinearArgs& a, hipStream_t st);
 // (the caller then takes the streaming kernel).  Arguments must have passed launch_linear's checks.
 bool launch_linear_resident(const LinearArgs& a, hipStream_t st);
 
+// Many rows (dozens and up) with bf16 weights: row kernel (norm, bf16 head/remainder split) + tiled MFMA
+// contraction + (SwiGLU) row kernel.  `workspace` holds linear_many_workspace_bytes(rows, K_max, N2_max)
+// bytes, K_max >= every K and N2_max >= every 2N of a SwiGLU call that will be issued with it.
+size_t linear_many_workspace_bytes(int64_t rows, int K_max, int N2_max);
+int32_t launch_linear_many(const LinearArgs& a, void* workspace, int K_max, hipStream_t st);
+
 }  // namespace photon

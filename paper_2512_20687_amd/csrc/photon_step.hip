@@ -155,6 +155,10 @@ static inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256
 
 // ------------------------------------------------------------------ workspace plan
 
+// From this many rows on a linear map goes to the tiled MFMA contraction instead of the few-row kernels
+// (which would re-read the weights once per 16 rows).
+constexpr int LINEAR_MANY_ROWS = 128;
+
 struct Plan {
   int L = 0;
   int64_t chunks[PHOTON_MAX_LEVELS + 1] = {0};   // chunks[l], l = 1..L: chunks decoded per step at level l
@@ -163,6 +167,8 @@ struct Plan {
   size_t coarse_ws = 0, coarse_ws_bytes = 0;
   size_t h = 0, attn = 0, qkv = 0, qrot = 0, act = 0, cond = 0, logits = 0, a_hat = 0;
   size_t h2 = 0, attn2 = 0, qkv2 = 0, qrot2 = 0, act2 = 0;   // second set (Bt rows) for the STEP branch that runs beside the lower levels
+  size_t many = 0, many2 = 0;                    // scratch of the many-row linear path (0 rows: absent), main and STEP branch
+  int many_K = 0;                                // widest contraction it is sized for
   size_t fresh[PHOTON_MAX_LEVELS] = {0};         // fresh[l]: new level-l units, l = 0..L-1
   size_t lk[PHOTON_MAX_LEVELS] = {0}, lv[PHOTON_MAX_LEVELS] = {0};   // local caches of level l (index l-1), all layers
   size_t total = 0;
@@ -202,6 +208,12 @@ static Plan make_plan(const photon_config& c, int Bt, int64_t S_max) {
   p.qkv2 = bump(cur, (size_t)Bt * 3 * D * f);
   p.qrot2 = bump(cur, (size_t)Bt * D * f);
   p.act2 = bump(cur, (size_t)Bt * F * f);
+  if (c.dt == PHOTON_BF16) {
+    p.many_K = (int)(D > F ? D : F);
+    if ((int64_t)c.C[c.L - 1] * D > p.many_K) p.many_K = (int)(c.C[c.L - 1] * D);   // the top chunker contracts over C_L * D
+    if (p.rows_max >= LINEAR_MANY_ROWS) p.many = bump(cur, linear_many_workspace_bytes(p.rows_max, p.many_K, (int)(2 * F)));
+    if (Bt >= LINEAR_MANY_ROWS) p.many2 = bump(cur, linear_many_workspace_bytes(Bt, p.many_K, (int)(2 * F)));
+  }
   for (int l = 1; l <= c.L; ++l) {
     p.fresh[l - 1] = bump(cur, (size_t)p.chunks[l] * c.C[l - 1] * D * f);
     const int W = c.R[l - 1] + c.C[l - 1] - 1;
@@ -253,11 +265,11 @@ struct Ctx {
   char* base;
   bool bf16;
   size_t o_h, o_attn, o_qkv, o_qrot, o_act;   // activation buffers of the branch this context drives
+  size_t o_many;                              // its many-row linear scratch
   bool overlap;                               // run the top-level update beside the lower levels
   float* f(size_t off) const { return reinterpret_cast<float*>(base + off); }
 };
 
-#define PHOTON_TRY(expr) do { const int32_t rc_ = (expr); if (rc_ != PHOTON_OK) return rc_; } while (0)
 
 // Rows entering a module pass: row i of the pass lives at in[i * ld] (D floats).
 struct RowsIn {
@@ -270,6 +282,8 @@ static int32_t linear(const Ctx& x, const float* in, int64_t ldx, const void* W,
   LinearArgs a;
   a.x = in; a.ldx = ldx; a.W = W; a.w_bf16 = x.bf16; a.gain = gain; a.eps = x.c->rms_eps; a.bias = bias; a.res = res;
   a.ldres = ldres; a.out = out; a.ldo = ldo; a.M = M; a.N = N; a.K = K; a.epilogue = epilogue;
+  if (x.bf16 && M >= LINEAR_MANY_ROWS && K <= x.p.many_K && (epilogue != EPI_SWIGLU || 2 * N <= 2 * x.c->d_ff))
+    return launch_linear_many(a, x.base + x.o_many, x.p.many_K, x.st);
   return launch_linear(a, x.st);
 }
 
@@ -426,7 +440,7 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
         return fail(PHOTON_ERR_HIP, "decode step: cannot fork the STEP branch");
       Ctx side = x;
       side.st = g_side;
-      side.o_h = x.p.h2; side.o_attn = x.p.attn2; side.o_qkv = x.p.qkv2; side.o_qrot = x.p.qrot2; side.o_act = x.p.act2;
+      side.o_h = x.p.h2; side.o_attn = x.p.attn2; side.o_qkv = x.p.qkv2; side.o_qrot = x.p.qrot2; side.o_act = x.p.act2; side.o_many = x.p.many2;
       PHOTON_TRY(chunk_and_step(side, units, tr));
       forked = true;
     }
@@ -498,7 +512,7 @@ extern "C" int32_t photon_decode_step(const photon_config* cfg, const photon_wei
   x.p = make_plan(c, Bt, st->S_max);
   x.bf16 = (c.dt == PHOTON_BF16);
   x.overlap = !g_profile_on;   // per-kernel timing wants one stream: concurrency would inflate the bracketed times
-  x.o_h = x.p.h; x.o_attn = x.p.attn; x.o_qkv = x.p.qkv; x.o_qrot = x.p.qrot; x.o_act = x.p.act;
+  x.o_h = x.p.h; x.o_attn = x.p.attn; x.o_qkv = x.p.qkv; x.o_qrot = x.p.qrot; x.o_act = x.p.act; x.o_many = x.p.many;
   PHOTON_REQUIRE(st->workspace != nullptr && aligned16(st->workspace) && st->workspace_bytes >= x.p.total, PHOTON_ERR_WORKSPACE,
                  "%s: workspace of %zu bytes needed (got %zu)", __func__, x.p.total, st->workspace_bytes);
   x.base = reinterpret_cast<char*>(st->workspace);

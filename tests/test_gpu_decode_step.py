@@ -109,6 +109,7 @@ def test_small_fp32_variants(kw):
     (dict(R=(2, 2)), 2),
     (dict(L=3, C=(2, 2, 4), R=(1, 1, 1), n_layers=1), 5),      # 80 rows at the token level: two row passes
     (dict(d_h=128, H=2, d_ff=0), 1),
+    (dict(C=(2, 2), n_layers=1), 130),                         # every level has enough rows for the tiled MFMA contraction
 ])
 def test_bf16_variants(kw, Bt):
     """bf16 weights and coarse cache, fp32 accumulation; tokens forced so that a
@@ -120,7 +121,7 @@ def test_bf16_variants(kw, Bt):
     w = si.make_weights(cfg, 33)
     S_max = 300
     st = si.make_decode_state(cfg, Bt, 257, S_max, seed=6)
-    st["seq_len"] = np.array([257 - 3 * b for b in range(Bt)], np.int32)
+    st["seq_len"] = np.array([257 - (3 * b) % 250 for b in range(Bt)], np.int32)
     forced = si.make_tokens(cfg.vocab, Bt, cfg.meta_context, 9)
     errs, _, _ = check_against_oracle(cfg, w, st, Bt, S_max, forced, TOL["bf16"])
     print(errs)
