@@ -119,6 +119,31 @@ PHOTON_API int32_t photon_chunk_local_attn(const void* q, const void* k, const v
                                 int64_t n_chunks, int32_t W, int32_t q_len, int32_t q_pos,
                                 int32_t H, int32_t d_h, float scale, photon_dtype dt, void* stream);
 
+/* --------------------------------------------------------------------------
+ * Causal self-attention of a context encoder over whole sequences: the
+ * prefill form of the encoder (paper Eq. 3; cost O(M_l^2) per level, Section
+ * 2.3.1).  Query i of sequence b attends to keys 0 .. i of the same sequence
+ * and head; q and k receive the rotary encoding at positions 0 .. M-1.
+ *   qkv  [Bt*M, 3*H*d_h]  fp32, device: rows b*M + i, columns [q | k | v],
+ *                         head h at columns h*d_h .. of each third
+ *   out  [Bt*M, H*d_h]    fp32, device
+ *   k_cache, v_cache      both NULL, or [Bt][H][S_max][d_h] in dt (device):
+ *                         receive the rotated keys and the values of positions
+ *                         0 .. M-1 (S_max >= M), i.e. the coarse cache a decode
+ *                         step continues from
+ *   workspace             photon_encoder_attn_workspace_bytes(...) bytes,
+ *                         device, caller-owned (0 bytes for fp32)
+ * dt PHOTON_BF16: matrix-core kernel, d_h = 64 only; scores from bf16 head +
+ * remainder operands, probabilities and values rounded to bf16.
+ * dt PHOTON_F32: fp32 vector kernel, d_h in {16, 32, 64}.
+ * Bt*H <= 65535.  Bt == 0 or M == 0 is a no-op.  Nothing is allocated or
+ * synchronised; errors are reported by status + photon_last_error().
+ * -------------------------------------------------------------------------- */
+PHOTON_API size_t photon_encoder_attn_workspace_bytes(int32_t Bt, int64_t M, int32_t H, int32_t d_h, photon_dtype dt);
+PHOTON_API int32_t photon_encoder_attn(const float* qkv, float* out, int32_t Bt, int64_t M, int32_t H, int32_t d_h,
+                                       float rope_theta, float scale, void* k_cache, void* v_cache, int64_t S_max,
+                                       void* workspace, size_t workspace_bytes, photon_dtype dt, void* stream);
+
 
 /* --------------------------------------------------------------------------
  * Few-row linear map with fused pre-norm and epilogue: the weight-streaming

@@ -19,6 +19,8 @@ from .binding import (  # noqa: F401
     photon_coarse_decode_attn_auto_splits,
     photon_coarse_decode_attn_workspace_bytes,
     photon_decode_step,
+    photon_encoder_attn,
+    photon_encoder_attn_workspace_bytes,
     photon_decode_step_workspace_bytes,
     photon_hbm_read_probe,
     photon_last_error,

@@ -130,6 +130,28 @@ def photon_chunk_local_attn(q, k, v, out, q_pos: int = 0, scale: Optional[float]
     return out
 
 
+def photon_encoder_attn_workspace_bytes(Bt: int, M: int, H: int, d_h: int, bf16: bool) -> int:
+    lib = load_library()
+    lib.photon_encoder_attn_workspace_bytes.argtypes = [C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int]
+    lib.photon_encoder_attn_workspace_bytes.restype = C.c_size_t
+    return int(lib.photon_encoder_attn_workspace_bytes(Bt, M, H, d_h, 1 if bf16 else 0))
+
+
+def photon_encoder_attn(qkv, out, Bt: int, M: int, H: int, d_h: int, rope_theta: float = 10000.0, scale: Optional[float] = None,
+                        k_cache=None, v_cache=None, workspace=None, bf16: bool = True):
+    """qkv fp32 [Bt*M, 3*H*d_h] -> out fp32 [Bt*M, H*d_h]; caches [Bt, H, S_max, d_h] (bf16 or fp32 per `bf16`)."""
+    lib = load_library()
+    lib.photon_encoder_attn.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_float, C.c_float,
+                                        C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]
+    lib.photon_encoder_attn.restype = C.c_int32
+    if scale is None:
+        scale = 1.0 / math.sqrt(d_h)
+    S_max = int(k_cache.shape[2]) if k_cache is not None else 0
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.photon_encoder_attn(_ptr(qkv), _ptr(out), Bt, M, H, d_h, rope_theta, scale, _ptr(k_cache), _ptr(v_cache), S_max,
+                                   _ptr(workspace), ws_bytes, 1 if bf16 else 0, _stream()))
+
+
 def photon_hbm_read_probe(buf: torch.Tensor, sink: torch.Tensor) -> None:
     lib = load_library()
     lib.photon_hbm_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]

@@ -115,6 +115,15 @@ __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4_t& v) { return __builtin_bit_cast(bf16x8_t, v); }
 
+// cos and sin of the rotary angle pos * theta^(-2i/d_h); the angle is formed in double because positions reach 10^5
+__device__ __forceinline__ void rope_angle(int pos, int i, int d_h, float theta, float& c, float& s) {
+  if (theta == 0.f) { c = 1.f; s = 0.f; return; }
+  const double inv_freq = exp2(-2.0 * (double)i / (double)d_h * log2((double)theta));
+  double sd, cd;
+  sincos((double)pos * inv_freq, &sd, &cd);
+  c = (float)cd; s = (float)sd;
+}
+
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float NEG_BIG = -1.0e30f;     // finite stand-in for -inf as running maximum
 

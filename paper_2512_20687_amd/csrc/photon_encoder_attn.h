@@ -1,0 +1,20 @@
+// Internal launch interface of the encoders' whole-sequence causal attention.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/photon.h"
+
+namespace photon {
+
+// Scratch the bf16 path needs (rotated, split and re-laid-out operands); 0 for fp32.
+size_t encoder_attn_workspace_bytes(int Bt, int64_t M, int H, int d_h, bool bf16);
+
+// out[b*M + i, h*d_h ..] = causal attention of query i over keys 0..i of (sequence b, head h), q and k rotated
+// at positions 0..M-1.  qkv fp32 [Bt*M, 3*H*d_h].  k_cache / v_cache (both or neither): [Bt][H][S_max][d_h] in the
+// configuration's storage type, receive the rotated keys and the values of positions 0..M-1.
+int32_t launch_encoder_attn(const float* qkv, float* out, int Bt, int64_t M, int H, int d_h, float theta, float scale, void* k_cache,
+                            void* v_cache, int64_t S_max, void* workspace, bool bf16, hipStream_t st);
+
+}  // namespace photon

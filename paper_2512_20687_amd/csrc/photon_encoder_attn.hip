@@ -1,0 +1,460 @@
+// Causal self-attention of a context encoder over whole sequences (the prefill
+// form of paper Eq. 3; Section 2.3.1 prices it at O(M_l^2) per level).
+//
+// Input is the fused projection output qkv fp32 [Bt*M, 3*H*d_h] (row = b*M +
+// position).  A row kernel applies the rotary encoding (module-local positions
+// 0..M-1) and lays the operands out per (sequence, head); the attention kernel
+// is a streaming-softmax tile kernel that never forms the M x M score matrix.
+//
+// bf16 configurations, d_h = 64: matrix cores.
+//   * S^T = K Q^T is computed (keys as MFMA rows, queries as columns) so that a
+//     lane owns ONE query and 16 of a tile's 32 keys: the row maximum and sum
+//     of the softmax are lane-local plus one exchange with lane^32.
+//   * q and k enter as bf16 head + bf16 remainder (K_h Q_h + K_h Q_l + K_l Q_h,
+//     three MFMAs) so that the scores carry fp32-level accuracy into the
+//     exponential; q is pre-scaled by scale*log2(e) and exp2 is used.
+//   * O^T = V^T P^T with P rounded to bf16 straight from the score registers:
+//     the k-slot order of that MFMA is chosen to be the order in which a lane
+//     already holds its 16 keys, and V is stored transposed ([d_h][key]) so the
+//     matching operand is two 8-byte LDS reads.  No data moves between lanes.
+//   * a workgroup = 4 waves = 128 queries of one (sequence, head); key blocks of
+//     64 (K head, K remainder, V^T: 24 KB) go global -> LDS directly, double
+//     buffered; tiles entirely above the diagonal are skipped per wave; the
+//     heavy (late) query blocks are scheduled first.
+// fp32 configuration: a plain fp32 tile kernel on the vector ALUs (small sizes).
+#include "photon_encoder_attn.h"
+
+#include "photon_device.h"
+#include "photon_host.h"
+
+namespace photon {
+
+namespace {
+
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+constexpr int EA_DH = 64;          // head size of the MFMA path
+constexpr int EA_BQ = 128;         // queries per workgroup (32 per wave)
+constexpr int EA_BK = 64;          // keys per block
+constexpr int EA_THREADS = 256;
+constexpr int EA_ARRAY = EA_BK * 128;                 // one staged array: 64 rows of 128 bytes
+constexpr int EA_STAGE = 3 * EA_ARRAY;                // K head | K remainder | V^T
+
+__host__ __device__ inline int64_t round_up64(int64_t m) { return (m + 63) / 64 * 64; }
+
+__device__ __forceinline__ int swz(int row, int col16) { return row * 128 + ((col16 ^ ((row >> 1) & 7)) << 4); }
+
+// 8 fp32 values -> packed bf16 heads and packed bf16 remainders
+__device__ __forceinline__ void split8(const float* x, uint4_t& hi, uint4_t& lo) {
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) split_bf16x2(x[2 * i], x[2 * i + 1], h[i], l[i]);
+  hi.x = h[0]; hi.y = h[1]; hi.z = h[2]; hi.w = h[3];
+  lo.x = l[0]; lo.y = l[1]; lo.z = l[2]; lo.w = l[3];
+}
+
+// ---- row kernel: rotary + operand layout ----------------------------------------------------------
+// One workgroup = 64 positions of one (sequence, head).  Thread t: position t/4, quarter t%4 of the pairs
+// (pairs i = quarter*8 .. +8, elements i and i + 32).
+// Outputs (bf16): qh, ql, kh, kl [Bt*H][Mp][64] (Mp = M rounded up to 64; rows >= M are zero), vt [Bt*H][64][Mp];
+// q is multiplied by qscale (= softmax scale * log2 e) before the split.  kc / vc (optional): the layer's
+// coarse cache [Bt][H][S_max][64], positions 0..M-1, K rotated.
+__global__ __launch_bounds__(256) void encoder_rope_split_kernel(const float* __restrict__ qkv, bf16_t* __restrict__ qh,
+                                                                 bf16_t* __restrict__ ql, bf16_t* __restrict__ kh,
+                                                                 bf16_t* __restrict__ kl, bf16_t* __restrict__ vt,
+                                                                 bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, int64_t M, int H,
+                                                                 int64_t S_max, float theta, float qscale) {
+  __shared__ bf16_t vtile[64][64 + 2];                // [d][position], padded
+  const int tid = threadIdx.x;
+  const int bh = blockIdx.y, b = bh / H, h = bh % H;
+  const int64_t Mp = round_up64(M);
+  const int64_t p0 = (int64_t)blockIdx.x * 64;
+  const int pl = tid >> 2, quarter = tid & 3;
+  const int64_t pos = p0 + pl;
+  const int D = H * EA_DH;
+  const bool live = pos < M;
+  float q[16], k[16], v[16];                          // elements quarter*8 .. +8, then 32 + quarter*8 .. +8
+#pragma unroll
+  for (int e = 0; e < 16; ++e) q[e] = k[e] = v[e] = 0.f;
+  if (live) {
+    const float* src = qkv + ((int64_t)b * M + pos) * 3 * D + h * EA_DH + quarter * 8;
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const float4_t a = *reinterpret_cast<const float4_t*>(src + half * 32 + c * 4);
+        const float4_t kk = *reinterpret_cast<const float4_t*>(src + D + half * 32 + c * 4);
+        const float4_t vv = *reinterpret_cast<const float4_t*>(src + 2 * D + half * 32 + c * 4);
+        const int e = half * 8 + c * 4;
+        q[e] = a.x; q[e + 1] = a.y; q[e + 2] = a.z; q[e + 3] = a.w;
+        k[e] = kk.x; k[e + 1] = kk.y; k[e + 2] = kk.z; k[e + 3] = kk.w;
+        v[e] = vv.x; v[e + 1] = vv.y; v[e + 2] = vv.z; v[e + 3] = vv.w;
+      }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float c, s;
+      rope_angle((int)pos, quarter * 8 + j, EA_DH, theta, c, s);
+      const float qa = q[j], qb = q[8 + j], ka = k[j], kb = k[8 + j];
+      q[j] = (qa * c - qb * s) * qscale; q[8 + j] = (qb * c + qa * s) * qscale;
+      k[j] = ka * c - kb * s; k[8 + j] = kb * c + ka * s;
+    }
+  }
+  const int64_t row = ((int64_t)bh * Mp + pos) * EA_DH;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    uint4_t h4, l4, kh4, kl4;
+    split8(q + half * 8, h4, l4);
+    split8(k + half * 8, kh4, kl4);
+    const int off = half * 32 + quarter * 8;
+    *reinterpret_cast<uint4_t*>(qh + row + off) = h4;
+    *reinterpret_cast<uint4_t*>(ql + row + off) = l4;
+    *reinterpret_cast<uint4_t*>(kh + row + off) = kh4;
+    *reinterpret_cast<uint4_t*>(kl + row + off) = kl4;
+    if (kc != nullptr && live && pos < S_max) {
+      uint4_t vv;
+      vv.x = pack_bf16x2(v[half * 8 + 0], v[half * 8 + 1]); vv.y = pack_bf16x2(v[half * 8 + 2], v[half * 8 + 3]);
+      vv.z = pack_bf16x2(v[half * 8 + 4], v[half * 8 + 5]); vv.w = pack_bf16x2(v[half * 8 + 6], v[half * 8 + 7]);
+      const int64_t slot = (((int64_t)b * H + h) * S_max + pos) * EA_DH + off;
+      *reinterpret_cast<uint4_t*>(kc + slot) = kh4;
+      *reinterpret_cast<uint4_t*>(vc + slot) = vv;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) vtile[half * 32 + quarter * 8 + j][pl] = from_f32<bf16_t>(v[half * 8 + j]);
+  }
+  __syncthreads();
+  // transposed tile out: 64 rows (d) of 64 positions = 128 bytes each; thread t writes two 16-byte pieces
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int piece = tid + r * 256;
+    const int d = piece >> 3, c8 = (piece & 7) * 8;
+    uint4_t o;
+    o.x = (uint32_t)vtile[d][c8 + 0] | ((uint32_t)vtile[d][c8 + 1] << 16); o.y = (uint32_t)vtile[d][c8 + 2] | ((uint32_t)vtile[d][c8 + 3] << 16);
+    o.z = (uint32_t)vtile[d][c8 + 4] | ((uint32_t)vtile[d][c8 + 5] << 16); o.w = (uint32_t)vtile[d][c8 + 6] | ((uint32_t)vtile[d][c8 + 7] << 16);
+    *reinterpret_cast<uint4_t*>(vt + ((int64_t)bh * EA_DH + d) * Mp + p0 + c8) = o;
+  }
+}
+
+// ---- attention kernel (matrix cores) -----------------------------------------------------------------
+__global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const bf16_t* __restrict__ qh, const bf16_t* __restrict__ ql,
+                                                                       const bf16_t* __restrict__ kh, const bf16_t* __restrict__ kl,
+                                                                       const bf16_t* __restrict__ vt, float* __restrict__ out, int64_t M,
+                                                                       int H, int n_qblocks) {
+  extern __shared__ __align__(16) char lds[];         // [2 stages][K head | K remainder | V^T]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int qb = n_qblocks - 1 - blockIdx.x;          // late query blocks carry the most keys: schedule them first
+  const int bh = blockIdx.y, b = bh / H, h = bh % H;
+  const int64_t Mp = round_up64(M);
+  const int64_t q0 = (int64_t)qb * EA_BQ + wave * 32; // this wave's first query
+  const int qcol = lane & 31, kg = lane >> 5;
+  const int64_t qpos = q0 + qcol;                     // this lane's query (may be >= M in the last block: computed, not stored)
+
+  // operand bases of this (sequence, head)
+  const bf16_t* khb = kh + (int64_t)bh * Mp * EA_DH;
+  const bf16_t* klb = kl + (int64_t)bh * Mp * EA_DH;
+  const bf16_t* vtb = vt + (int64_t)bh * EA_DH * Mp;
+
+  // this lane's query as MFMA B operand: Q[q][16 s + 8 kg .. +8] for the four k-steps s, head and remainder
+  bf16x8_t qfh[4], qfl[4];
+  {
+    const int64_t qrow = qpos < Mp ? qpos : Mp - 1;   // rows up to Mp exist (zero padded)
+    const bf16_t* qp = qh + ((int64_t)bh * Mp + qrow) * EA_DH + kg * 8;
+    const bf16_t* qq = ql + ((int64_t)bh * Mp + qrow) * EA_DH + kg * 8;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      qfh[s] = as_bf16x8(load16(qp + s * 16));
+      qfl[s] = as_bf16x8(load16(qq + s * 16));
+    }
+  }
+
+  // global -> LDS: one instruction moves 8 rows of 128 bytes; lane l lands at row l/8, 16-byte column l%8 and
+  // therefore fetches the logical column that the XOR swizzle maps there.  24 instructions per stage, 6 per wave.
+  const int srow = lane >> 3, scol = lane & 7;
+  auto stage = [&](int kb, int buf) {
+    char* base = lds + buf * EA_STAGE;
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+      const int inst = wave * 6 + i;                  // 0..23: array = inst / 8, row group = inst % 8
+      const int arr = inst >> 3, r = (inst & 7) * 8 + srow;
+      const int c = scol ^ ((r >> 1) & 7);
+      const bf16_t* src;
+      if (arr == 0) src = khb + ((int64_t)kb * EA_BK + r) * EA_DH + c * 8;
+      else if (arr == 1) src = klb + ((int64_t)kb * EA_BK + r) * EA_DH + c * 8;
+      else src = vtb + (int64_t)r * Mp + (int64_t)kb * EA_BK + c * 8;
+      __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(base + arr * EA_ARRAY + (inst & 7) * 8 * 128), 16, 0, 0);
+    }
+  };
+
+  float16_t o[2];                                     // O^T tiles: d = dt*32 + 8*(v/4) + 4*kg + v%4, query = lane%32
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
+  float m_run = NEG_BIG, l_run = 0.f;                 // running maximum (shared by both lane halves) and this half's partial sum
+
+  // key blocks 0 .. last block that holds a key <= the workgroup's last query
+  const int64_t wg_last_q = (int64_t)qb * EA_BQ + EA_BQ - 1;
+  const int64_t last_key = wg_last_q < M - 1 ? wg_last_q : M - 1;
+  const int n_kb = (int)(last_key / EA_BK) + 1;
+  const int64_t wave_last_q = q0 + 31;
+
+  stage(0, 0);
+  for (int kb = 0; kb < n_kb; ++kb) {
+    const int buf = kb & 1;
+    __builtin_amdgcn_s_waitcnt(0);                    // block kb has landed (vmcnt 0)
+    __syncthreads();                                  // ... for every wave, and everyone is done with the other buffer
+    if (kb + 1 < n_kb) stage(kb + 1, buf ^ 1);
+    const int64_t k0 = (int64_t)kb * EA_BK;
+    if (k0 > wave_last_q) continue;                   // block entirely above this wave's diagonal (uniform per wave)
+    const char* sk = lds + buf * EA_STAGE;
+    const char* sl = sk + EA_ARRAY;
+    const char* sv = sk + 2 * EA_ARRAY;
+
+    // scores: st[kt][v] = S^T[key = k0 + kt*32 + 8*(v/4) + 4*kg + v%4][query]
+    float16_t st[2];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) st[kt][e] = 0.f;
+      if (k0 + kt * 32 > wave_last_q) continue;       // tile above the diagonal: its scores are masked below anyway
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const int off = swz(kt * 32 + qcol, s * 2 + kg);
+        const bf16x8_t ah = as_bf16x8(*reinterpret_cast<const uint4_t*>(sk + off));
+        const bf16x8_t al = as_bf16x8(*reinterpret_cast<const uint4_t*>(sl + off));
+        st[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qfh[s], st[kt], 0, 0, 0);
+        st[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qfl[s], st[kt], 0, 0, 0);
+        st[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, qfh[s], st[kt], 0, 0, 0);
+      }
+    }
+    // causal mask (only blocks that reach the diagonal), block maximum
+    const bool diag = k0 + EA_BK - 1 > q0;            // some key of the block exceeds some query of the wave
+    float mx = NEG_BIG;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        if (diag) {
+          const int64_t key = k0 + kt * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+          if (key > qpos) st[kt][v] = NEG_BIG;
+        }
+        mx = fmaxf(mx, st[kt][v]);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = fast_exp2(m_run - m_new);     // first block: exp2(-huge) = 0 and the state is zero anyway
+    m_run = m_new;
+    float psum = 0.f;
+    bf16x8_t pf[2][2];                                // P^T operands: [key tile][k-step], 8 of the lane's keys each
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        uint4_t pk;
+        float p[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          // a masked score stays at -1e30: exp2 gives exactly 0 as long as the query sees at least one key (it sees key 0)
+          p[j] = fast_exp2(st[kt][8 * s + j] - m_new);
+          psum += p[j];
+        }
+        pk.x = pack_bf16x2(p[0], p[1]); pk.y = pack_bf16x2(p[2], p[3]); pk.z = pack_bf16x2(p[4], p[5]); pk.w = pack_bf16x2(p[6], p[7]);
+        pf[kt][s] = as_bf16x8(pk);
+      }
+    l_run = l_run * alpha + psum;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+    // O^T += V^T P^T: k-slot (kg, j) of step s stands for key kt*32 + 16 s + 8 (j/4) + 4 kg + j%4
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      if (k0 + kt * 32 > wave_last_q) continue;
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+          const int row = dt * 32 + qcol;             // d
+          const int c16 = kt * 4 + 2 * s + (kg >> 1);
+          const uint2 lo8 = *reinterpret_cast<const uint2*>(sv + swz(row, c16) + (kg & 1) * 8);
+          const uint2 hi8 = *reinterpret_cast<const uint2*>(sv + swz(row, c16 + 1) + (kg & 1) * 8);
+          uint4_t a4; a4.x = lo8.x; a4.y = lo8.y; a4.z = hi8.x; a4.w = hi8.y;
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a4), pf[kt][s], o[dt], 0, 0, 0);
+        }
+    }
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (qpos >= M) return;
+  const float inv = 1.0f / l_tot;
+  float* dst = out + ((int64_t)b * M + qpos) * (H * EA_DH) + h * EA_DH;
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      float4_t y;
+      y.x = o[dt][g4 * 4 + 0] * inv; y.y = o[dt][g4 * 4 + 1] * inv; y.z = o[dt][g4 * 4 + 2] * inv; y.w = o[dt][g4 * 4 + 3] * inv;
+      *reinterpret_cast<float4_t*>(dst + dt * 32 + 8 * g4 + 4 * kg) = y;
+    }
+}
+
+// ---- fp32 configuration: plain tile kernel -----------------------------------------------------------
+// One workgroup = 64 queries of one (sequence, head); thread t owns query t and streams the keys 0..q
+// through LDS tiles of 32 keys (rotated as they are staged).
+template <int DH>
+__global__ __launch_bounds__(64) void encoder_attn_f32_kernel(const float* __restrict__ qkv, float* __restrict__ out, float* __restrict__ kc,
+                                                              float* __restrict__ vc, int64_t M, int H, int64_t S_max, float theta,
+                                                              float scale) {
+  __shared__ float ks[32][DH + 1], vs[32][DH + 1];
+  const int t = threadIdx.x;
+  const int bh = blockIdx.y, b = bh / H, h = bh % H;
+  const int D = H * DH, half = DH / 2;
+  const int64_t q0 = (int64_t)blockIdx.x * 64;
+  const int64_t qpos = q0 + t;
+  const bool live = qpos < M;
+  float q[DH], acc[DH];
+#pragma unroll
+  for (int d = 0; d < DH; ++d) { q[d] = 0.f; acc[d] = 0.f; }
+  if (live) {
+    const float* src = qkv + ((int64_t)b * M + qpos) * 3 * D + h * DH;
+#pragma unroll
+    for (int i = 0; i < half; ++i) {
+      float c, s;
+      rope_angle((int)qpos, i, DH, theta, c, s);
+      const float a = src[i], bb = src[i + half];
+      q[i] = (a * c - bb * s) * scale * LOG2E;
+      q[i + half] = (bb * c + a * s) * scale * LOG2E;
+    }
+  }
+  float m_run = NEG_BIG, l_run = 0.f;
+  const int64_t last = (q0 + 63 < M - 1) ? q0 + 63 : M - 1;
+  for (int64_t k0 = 0; k0 <= last; k0 += 32) {
+    __syncthreads();
+    // 64 threads load 32 keys: thread t -> key t/2, half (t%2) of the pairs
+    {
+      const int kr = t >> 1, part = t & 1;
+      const int64_t kpos = k0 + kr;
+      if (kpos < M) {
+        const float* src = qkv + ((int64_t)b * M + kpos) * 3 * D + h * DH;
+        for (int i = part * (half / 2); i < (part + 1) * (half / 2); ++i) {
+          float c, s;
+          rope_angle((int)kpos, i, DH, theta, c, s);
+          const float a = src[D + i], bb = src[D + i + half];
+          const float ka = a * c - bb * s, kb = bb * c + a * s;
+          const float va = src[2 * D + i], vb = src[2 * D + i + half];
+          ks[kr][i] = ka; ks[kr][i + half] = kb;
+          vs[kr][i] = va; vs[kr][i + half] = vb;
+        }
+      } else {
+        for (int i = part * (half / 2); i < (part + 1) * (half / 2); ++i) { ks[kr][i] = ks[kr][i + half] = 0.f; vs[kr][i] = vs[kr][i + half] = 0.f; }
+      }
+    }
+    __syncthreads();
+    if (!live) continue;
+    for (int j = 0; j < 32; ++j) {
+      const int64_t kpos = k0 + j;
+      if (kpos > qpos) break;
+      float s = 0.f;
+#pragma unroll
+      for (int d = 0; d < DH; ++d) s = fmaf(q[d], ks[j][d], s);
+      const float m_new = fmaxf(m_run, s);
+      const float alpha = fast_exp2(m_run - m_new), p = fast_exp2(s - m_new);
+      m_run = m_new;
+      l_run = l_run * alpha + p;
+#pragma unroll
+      for (int d = 0; d < DH; ++d) acc[d] = fmaf(acc[d], alpha, p * vs[j][d]);
+    }
+  }
+  if (!live) return;
+  const float inv = 1.0f / l_run;
+  float* dst = out + ((int64_t)b * M + qpos) * D + h * DH;
+#pragma unroll
+  for (int d = 0; d < DH; ++d) dst[d] = acc[d] * inv;
+  if (kc != nullptr && qpos < S_max) {                // this thread's own position: rotated key and value into the cache
+    const float* src = qkv + ((int64_t)b * M + qpos) * 3 * D + h * DH;
+    float* kd = kc + (((int64_t)b * H + h) * S_max + qpos) * DH;
+    float* vd = vc + (((int64_t)b * H + h) * S_max + qpos) * DH;
+#pragma unroll
+    for (int i = 0; i < half; ++i) {
+      float c, s;
+      rope_angle((int)qpos, i, DH, theta, c, s);
+      const float a = src[D + i], bb = src[D + i + half];
+      kd[i] = a * c - bb * s; kd[i + half] = bb * c + a * s;
+      vd[i] = src[2 * D + i]; vd[i + half] = src[2 * D + i + half];
+    }
+  }
+}
+
+}  // namespace
+
+size_t encoder_attn_workspace_bytes(int Bt, int64_t M, int H, int d_h, bool bf16) {
+  if (!bf16) return 0;
+  return (size_t)5 * Bt * H * round_up64(M) * d_h * sizeof(bf16_t);   // q head, q remainder, k head, k remainder, V^T
+}
+
+int32_t launch_encoder_attn(const float* qkv, float* out, int Bt, int64_t M, int H, int d_h, float theta, float scale, void* k_cache,
+                            void* v_cache, int64_t S_max, void* workspace, bool bf16, hipStream_t st) {
+  if (Bt <= 0 || M <= 0) return PHOTON_OK;
+  if ((int64_t)Bt * H > 65535) return fail(PHOTON_ERR_UNSUPPORTED, "encoder attention: Bt*H=%lld exceeds 65535", (long long)Bt * H);
+  if (!bf16) {
+    dim3 grid((unsigned)((M + 63) / 64), Bt * H);
+#define PHOTON_EA_F32(DH)                                                                                                          \
+    PHOTON_LAUNCH(KC_LOCAL_ATTN, st, encoder_attn_f32_kernel<DH>, grid, dim3(64), 0, st, qkv, out, (float*)k_cache, (float*)v_cache, M, H, \
+                  S_max, theta, scale)
+    switch (d_h) {
+      case 16: PHOTON_EA_F32(16); break;
+      case 32: PHOTON_EA_F32(32); break;
+      case 64: PHOTON_EA_F32(64); break;
+      default: return fail(PHOTON_ERR_UNSUPPORTED, "encoder attention (fp32): head size %d not in {16, 32, 64}", d_h);
+    }
+#undef PHOTON_EA_F32
+    return check_launch("encoder_attn_f32_kernel");
+  }
+  if (d_h != EA_DH) return fail(PHOTON_ERR_UNSUPPORTED, "encoder attention (bf16): head size %d, only 64 is built", d_h);
+  const int64_t Mp = round_up64(M);
+  const size_t arr = (size_t)Bt * H * Mp * EA_DH;
+  bf16_t* qh = reinterpret_cast<bf16_t*>(workspace);
+  bf16_t *ql = qh + arr, *kh = ql + arr, *kl = kh + arr, *vt = kl + arr;
+  PHOTON_LAUNCH(KC_ROPE_APPEND, st, encoder_rope_split_kernel, dim3((unsigned)(Mp / 64), Bt * H), dim3(256), 0, st, qkv, qh, ql, kh, kl, vt,
+                (bf16_t*)k_cache, (bf16_t*)v_cache, M, H, S_max, theta, scale * LOG2E);
+  PHOTON_TRY(check_launch("encoder_rope_split_kernel"));
+  const int n_qblocks = (int)((M + EA_BQ - 1) / EA_BQ);
+  PHOTON_LAUNCH(KC_LOCAL_ATTN, st, encoder_attn_mfma_kernel, dim3(n_qblocks, Bt * H), dim3(EA_THREADS), 2 * EA_STAGE, st, qh, ql, kh, kl, vt,
+                out, M, H, n_qblocks);
+  return check_launch("encoder_attn_mfma_kernel");
+}
+
+}  // namespace photon
+
+using namespace photon;
+
+extern "C" size_t photon_encoder_attn_workspace_bytes(int32_t Bt, int64_t M, int32_t H, int32_t d_h, photon_dtype dt) {
+  if (Bt <= 0 || M <= 0 || H <= 0 || d_h <= 0) return 0;
+  return encoder_attn_workspace_bytes(Bt, M, H, d_h, dt == PHOTON_BF16);
+}
+
+extern "C" int32_t photon_encoder_attn(const float* qkv, float* out, int32_t Bt, int64_t M, int32_t H, int32_t d_h, float rope_theta,
+                                       float scale, void* k_cache, void* v_cache, int64_t S_max, void* workspace, size_t workspace_bytes,
+                                       photon_dtype dt, void* stream) {
+  clear_error();
+  PHOTON_REQUIRE(valid_dtype(dt), PHOTON_ERR_UNSUPPORTED, "%s: unknown dtype %d", __func__, (int)dt);
+  PHOTON_REQUIRE(Bt >= 0 && M >= 0 && H >= 1 && d_h >= 1, PHOTON_ERR_INVALID_ARG, "%s: Bt=%d M=%lld H=%d d_h=%d invalid", __func__, Bt,
+                 (long long)M, H, d_h);
+  PHOTON_REQUIRE(M <= (1 << 24), PHOTON_ERR_UNSUPPORTED, "%s: M=%lld exceeds 2^24 positions", __func__, (long long)M);
+  if (Bt == 0 || M == 0) return PHOTON_OK;
+  PHOTON_REQUIRE_PTR(qkv);
+  PHOTON_REQUIRE_PTR(out);
+  PHOTON_REQUIRE((k_cache == nullptr) == (v_cache == nullptr), PHOTON_ERR_INVALID_ARG, "%s: give both caches or neither", __func__);
+  if (k_cache != nullptr) {
+    PHOTON_REQUIRE(aligned16(k_cache) && aligned16(v_cache), PHOTON_ERR_INVALID_ARG, "%s: cache is misaligned", __func__);
+    PHOTON_REQUIRE(S_max >= M, PHOTON_ERR_INVALID_ARG, "%s: cache pitch S_max=%lld is shorter than M=%lld", __func__, (long long)S_max,
+                   (long long)M);
+  }
+  const size_t need = encoder_attn_workspace_bytes(Bt, M, H, d_h, dt == PHOTON_BF16);
+  PHOTON_REQUIRE(workspace_bytes >= need, PHOTON_ERR_INVALID_ARG, "%s: workspace holds %zu bytes, %zu needed", __func__, workspace_bytes, need);
+  if (need > 0) PHOTON_REQUIRE_PTR(workspace);
+  return launch_encoder_attn(qkv, out, Bt, M, H, d_h, rope_theta, scale, k_cache, v_cache, S_max, workspace, dt == PHOTON_BF16,
+                             (hipStream_t)stream);
+}

@@ -39,14 +39,6 @@ __global__ __launch_bounds__(256) void norm_rows_kernel(const float* __restrict_
   }
 }
 
-__device__ __forceinline__ void rope_angle(int pos, int i, int d_h, float theta, float& c, float& s) {
-  if (theta == 0.f) { c = 1.f; s = 0.f; return; }
-  const double inv_freq = exp2(-2.0 * (double)i / (double)d_h * log2((double)theta));
-  double sd, cd;
-  sincos((double)pos * inv_freq, &sd, &cd);
-  c = (float)cd; s = (float)sd;
-}
-
 // Top-level STEP: position of sequence b is seq_len[b]-1 (the count already includes the new entry);
 // k, v go to cache[b, h, pos, :] of this layer.
 template <typename TKV>
