@@ -253,6 +253,38 @@ PHOTON_API int32_t photon_decode_step(const photon_config* cfg, const photon_wei
                                       const photon_trace* trace, void* stream);
 
 /* --------------------------------------------------------------------------
+ * Hierarchical prefill of a batch of prompts (paper Section 2.3.3, first
+ * paragraph; encoder Eq. 3-4): embeds the tokens, runs chunker + encoder
+ * module of every level bottom-up over the whole prompt (whole-sequence causal
+ * attention, see photon_encoder_attn), and leaves in `st` exactly what a decode
+ * step continues from: the top-level K/V cache of all M_L = T / prod(C) units,
+ * seq_len = M_L, x_top = X^(L)_{M_L}, and for every level l < L the carry =
+ * last reconstructed level-l unit, obtained by a teacher-forced decode of the
+ * last chunk of every level l >= 2 (conditioned on the previous level-l unit,
+ * or on the level's learned start latent when the prompt holds a single one).
+ *   tokens  device int32 [Bt, T], T a positive multiple of prod(C),
+ *           T / prod(C) <= st->S_max (strictly less if decode steps follow)
+ *   ew      encoder-side parameters (host struct of device pointers)
+ *   st      as for photon_decode_step, its workspace included (the carry
+ *           decode runs on it); cache rows beyond M_L are left untouched
+ *   workspace  photon_prefill_workspace_bytes(cfg, Bt, T) bytes, device,
+ *           caller-owned, no initialisation needed
+ * Levels >= 2 need C_l >= 2.  Everything is enqueued on `stream`.
+ * -------------------------------------------------------------------------- */
+typedef struct photon_encoder_weights {
+  const void* E_enc;                            /* [vocab, D] dt: encoder-side embedding table */
+  const void* chunker_w[PHOTON_MAX_LEVELS];     /* index l-1: chunker of level l, [D, C_l * D] dt */
+  const float* chunker_b[PHOTON_MAX_LEVELS];    /* [D] fp32 or NULL */
+  photon_module_weights enc[PHOTON_MAX_LEVELS]; /* index l-1: encoder module of level l (enc[L-1] = photon_weights.top) */
+  const float* x0[PHOTON_MAX_LEVELS];           /* index l-1: start latent of the level-l decoder, [D] fp32 */
+} photon_encoder_weights;
+
+PHOTON_API size_t photon_prefill_workspace_bytes(const photon_config* cfg, int32_t Bt, int64_t T);
+PHOTON_API int32_t photon_prefill(const photon_config* cfg, const photon_weights* w, const photon_encoder_weights* ew,
+                                  const photon_state* st, int32_t Bt, const int32_t* tokens, int64_t T,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
  * Bandwidth probe for benchmarks: a trivial kernel that reads `bytes` bytes of
  * `buf` once with 128-bit non-temporal loads (2048 workgroups, grid-stride) and discards
  * them.  Timing it gives the streaming-read ceiling of the machine, which the

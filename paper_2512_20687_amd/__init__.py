@@ -25,6 +25,8 @@ from .binding import (  # noqa: F401
     photon_hbm_read_probe,
     photon_last_error,
     photon_linear,
+    photon_prefill,
+    photon_prefill_workspace_bytes,
     photon_profile_enable,
     photon_profile_get,
     photon_profile_reset,

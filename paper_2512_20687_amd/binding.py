@@ -219,6 +219,11 @@ class _Weights(C.Structure):
                 ("dec", _Module * MAX_LEVELS)]
 
 
+class _EncoderWeights(C.Structure):
+    _fields_ = [("E_enc", C.c_void_p), ("chunker_w", C.c_void_p * MAX_LEVELS), ("chunker_b", C.c_void_p * MAX_LEVELS),
+                ("enc", _Module * MAX_LEVELS), ("x0", C.c_void_p * MAX_LEVELS)]
+
+
 class _State(C.Structure):
     _fields_ = [("k_cache", C.c_void_p), ("v_cache", C.c_void_p), ("seq_len", C.c_void_p), ("x_top", C.c_void_p),
                 ("carry", C.c_void_p), ("S_max", C.c_int64), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
@@ -236,6 +241,11 @@ def _register_step(lib):
     lib.photon_decode_step.restype = C.c_int32
     lib.photon_decode_step.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(_State), C.c_int32,
                                        C.c_void_p, C.c_void_p, C.POINTER(_Trace), C.c_void_p]
+    lib.photon_prefill_workspace_bytes.restype = C.c_size_t
+    lib.photon_prefill_workspace_bytes.argtypes = [C.POINTER(_Config), C.c_int32, C.c_int64]
+    lib.photon_prefill.restype = C.c_int32
+    lib.photon_prefill.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(_EncoderWeights), C.POINTER(_State), C.c_int32,
+                                   C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
     lib._photon_step_registered = True
 
 
@@ -274,6 +284,17 @@ class PhotonModel:
             w.conv_b[l] = self._vec(d["converter"]["b"])
             self._fill_module(w.dec[l], d["module"])
         self.c_weights = w
+        self.c_encoder_weights = None
+        if "E_enc" in weights and all("module" in e for e in weights["enc"]):
+            ew = _EncoderWeights()
+            ew.E_enc = self._mat(weights["E_enc"])
+            for l in range(cfg.L):
+                enc = weights["enc"][l]
+                ew.chunker_w[l] = self._mat(enc["chunker"]["w"])
+                ew.chunker_b[l] = self._vec(enc["chunker"]["b"]) if "b" in enc["chunker"] else None
+                self._fill_module(ew.enc[l], enc["module"])
+                ew.x0[l] = self._vec(weights["dec"][l]["x0"])
+            self.c_encoder_weights = ew
 
     def _dev(self, a, dtype):
         t = a if isinstance(a, torch.Tensor) else torch.from_numpy(a)
@@ -354,6 +375,29 @@ def photon_decode_step_workspace_bytes(cfg, Bt: int, S_max: int) -> int:
     lib = load_library()
     _register_step(lib)
     return lib.photon_decode_step_workspace_bytes(C.byref(_c_config(cfg)), Bt, S_max)
+
+
+def photon_prefill_workspace_bytes(cfg, Bt: int, T: int) -> int:
+    lib = load_library()
+    _register_step(lib)
+    return lib.photon_prefill_workspace_bytes(C.byref(_c_config(cfg)), Bt, T)
+
+
+def photon_prefill(model: PhotonModel, state: PhotonState, tokens: torch.Tensor, workspace: Optional[torch.Tensor] = None):
+    """Hierarchical prefill of the prompts `tokens` (int32 [Bt, T] on the device) into `state`."""
+    lib = load_library()
+    _register_step(lib)
+    if model.c_encoder_weights is None:
+        raise PhotonError(-1, "the model was built without encoder-side weights")
+    Bt, T = int(tokens.shape[0]), int(tokens.shape[1])
+    if workspace is None:
+        n = lib.photon_prefill_workspace_bytes(C.byref(model.c_cfg), Bt, T)
+        if n == 0:
+            raise PhotonError(-1, lib.photon_last_error().decode())
+        workspace = torch.empty(n, dtype=torch.uint8, device=model.device)
+    _check(lib.photon_prefill(C.byref(model.c_cfg), C.byref(model.c_weights), C.byref(model.c_encoder_weights), C.byref(state.c_state), Bt,
+                              _ptr(tokens), T, _ptr(workspace), workspace.numel(), _stream()))
+    return workspace
 
 
 def photon_decode_step(model: PhotonModel, state: PhotonState, out_tokens: torch.Tensor,

@@ -4,6 +4,7 @@
 // sequence lengths and tokens stay in device memory, so the enqueue pattern does
 // not depend on data and the whole step can be captured in a HIP graph.
 #include "photon_attn.h"
+#include "photon_encoder_attn.h"
 #include "photon_device.h"
 #include "photon_host.h"
 #include "photon_linear.h"
@@ -37,6 +38,33 @@ __global__ __launch_bounds__(256) void norm_rows_kernel(const float* __restrict_
     const float4_t gv = *reinterpret_cast<const float4_t*>(g + d);
     *reinterpret_cast<float4_t*>(o + d) = xrow[d >> 2] * r * gv;
   }
+}
+
+// rows[i, :] = table[tokens[i], :] as fp32 (encoder-side embedding of the prompt).
+template <typename TE>
+__global__ __launch_bounds__(256) void embed_rows_kernel(const int32_t* __restrict__ tokens, const TE* __restrict__ table,
+                                                         float* __restrict__ rows, int64_t n, int D, int vocab) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;       // one thread per 4 elements
+  const int per_row = D / 4;
+  if (idx >= n * per_row) return;
+  const int64_t i = idx / per_row;
+  const int d = (int)(idx % per_row) * 4;
+  int t = tokens[i];
+  t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);                      // out-of-range ids are clamped, never read out of bounds
+  const TE* src = table + (int64_t)t * D + d;
+  float4_t v;
+  v.x = to_f32<TE>(src[0]); v.y = to_f32<TE>(src[1]); v.z = to_f32<TE>(src[2]); v.w = to_f32<TE>(src[3]);
+  *reinterpret_cast<float4_t*>(rows + i * D + d) = v;
+}
+
+__global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ dst, int32_t value, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = value;
+}
+
+__global__ __launch_bounds__(256) void broadcast_rows_kernel(const float* __restrict__ src, float* __restrict__ dst, int rows, int D) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx < (int64_t)rows * D) dst[idx] = src[idx % D];
 }
 
 // Top-level STEP: position of sequence b is seq_len[b]-1 (the count already includes the new entry);
@@ -462,10 +490,214 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
 
 using namespace photon;
 
+// ------------------------------------------------------------------ prefill
+
+struct PrefillPlan {
+  int64_t M[PHOTON_MAX_LEVELS + 1] = {0};        // M[l]: level-l units per sequence, M[0] = T
+  size_t X[PHOTON_MAX_LEVELS + 1] = {0};         // X[l]: level-l encoder states [Bt*M[l], D]; X[0] = embeddings; X[L] unused
+  size_t A = 0, h = 0, attn = 0, qkv = 0, act = 0, many = 0, ea = 0, pair = 0;
+  int many_K = 0;
+  size_t total = 0;
+};
+
+static PrefillPlan make_prefill_plan(const photon_config& c, int Bt, int64_t T) {
+  PrefillPlan p;
+  const int64_t D = c.D, F = c.d_ff;
+  const size_t f = sizeof(float);
+  p.M[0] = T;
+  for (int l = 1; l <= c.L; ++l) p.M[l] = p.M[l - 1] / c.C[l - 1];
+  size_t cur = 0;
+  for (int l = 0; l < c.L; ++l) p.X[l] = bump(cur, (size_t)Bt * p.M[l] * D * f);
+  const int64_t rows = (int64_t)Bt * p.M[1];     // the widest level
+  p.A = bump(cur, rows * D * f);
+  p.h = bump(cur, rows * D * f);
+  p.attn = bump(cur, rows * D * f);
+  p.qkv = bump(cur, rows * 3 * D * f);
+  p.act = bump(cur, rows * F * f);
+  p.pair = bump(cur, (size_t)2 * Bt * D * f);    // conditioning latent of the carry decode, and a spare
+  if (c.dt == PHOTON_BF16) {
+    p.many_K = (int)(D > F ? D : F);
+    for (int l = 1; l <= c.L; ++l)
+      if ((int64_t)c.C[l - 1] * D > p.many_K) p.many_K = (int)(c.C[l - 1] * D);
+    if (rows >= LINEAR_MANY_ROWS) p.many = bump(cur, linear_many_workspace_bytes(rows, p.many_K, (int)(2 * F)));
+  }
+  p.ea = bump(cur, encoder_attn_workspace_bytes(Bt, p.M[1], c.H, c.d_h, c.dt == PHOTON_BF16));
+  p.total = cur;
+  return p;
+}
+
+// Bottom-up encoder pass over the prompt, then the carries.  `x` is a decode-step context on the state's own
+// workspace (the carry decode is a teacher-forced run of the decode sub-steps); `e` drives the big buffers.
+static int32_t prefill_impl(const Ctx& x, Ctx e, const PrefillPlan& pp, const photon_encoder_weights& ew, const int32_t* tokens) {
+  const photon_config& c = *x.c;
+  const int D = c.D, L = c.L, Bt = x.Bt;
+  const float scale = 1.0f / sqrtf((float)c.d_h);
+  const size_t esz = dtype_size(c.dt);
+
+  // X^(0): encoder-side embeddings
+  float* X0 = e.f(pp.X[0]);
+  const int64_t n_tok = (int64_t)Bt * pp.M[0];
+  if (x.bf16)
+    PHOTON_LAUNCH(KC_MISC, x.st, embed_rows_kernel<bf16_t>, dim3(blocks_for(n_tok * (D / 4))), dim3(256), 0, x.st, tokens,
+                  (const bf16_t*)ew.E_enc, X0, n_tok, D, c.vocab);
+  else
+    PHOTON_LAUNCH(KC_MISC, x.st, embed_rows_kernel<float>, dim3(blocks_for(n_tok * (D / 4))), dim3(256), 0, x.st, tokens,
+                  (const float*)ew.E_enc, X0, n_tok, D, c.vocab);
+  PHOTON_TRY(check_launch("embed_rows_kernel"));
+
+  float *A = e.f(pp.A), *h = e.f(pp.h), *qkv = e.f(pp.qkv), *attn = e.f(pp.attn);
+  float* pair = e.f(pp.pair);
+  for (int l = 1; l <= L; ++l) {
+    const int C = c.C[l - 1];
+    const int64_t M = pp.M[l];
+    const int rows = (int)(Bt * M);
+    const photon_module_weights& mod = ew.enc[l - 1];
+    // Eq. 4: C consecutive level-(l-1) states are one row of C*D inputs (the states are contiguous per sequence)
+    PHOTON_TRY(linear(e, e.f(pp.X[l - 1]), (int64_t)C * D, ew.chunker_w[l - 1], nullptr, ew.chunker_b[l - 1], nullptr, 0, A, D, rows, D,
+                      C * D, EPI_PLAIN));
+    RowsIn in;
+    in.ptr = A; in.ld = D;
+    const size_t layer_cache = (size_t)Bt * c.H * x.s->S_max * c.d_h * esz;
+    for (int i = 0; i < c.n_layers; ++i) {
+      const photon_layer_weights& lw = mod.layers[i];
+      PHOTON_TRY(linear(e, in.ptr, in.ld, lw.wqkv, lw.g1, nullptr, nullptr, 0, qkv, 3 * D, rows, 3 * D, D, EPI_PLAIN));
+      char* kc = (l == L) ? reinterpret_cast<char*>(x.s->k_cache) + (size_t)i * layer_cache : nullptr;
+      char* vc = (l == L) ? reinterpret_cast<char*>(x.s->v_cache) + (size_t)i * layer_cache : nullptr;
+      PHOTON_TRY(launch_encoder_attn(qkv, attn, Bt, M, c.H, c.d_h, c.rope_theta, scale, kc, vc, x.s->S_max, e.base + pp.ea, x.bf16, x.st));
+      PHOTON_TRY(block_tail(e, lw, in, rows));
+      in.ptr = h; in.ld = D;
+    }
+    if (l < L) {
+      PHOTON_TRY(norm(e, in.ptr, 1, 0, mod.g_final, e.f(pp.X[l]), 1, 0, rows));
+    } else {
+      // only two rows of X^(L) are ever used: the last one (the top state) and the one before it (conditions the carry decode)
+      PHOTON_TRY(norm(e, in.ptr, (int)M, (int)M - 1, mod.g_final, x.s->x_top, 1, 0, Bt));
+      if (L >= 2) {
+        if (M >= 2) {
+          PHOTON_TRY(norm(e, in.ptr, (int)M, (int)M - 2, mod.g_final, pair, 1, 0, Bt));
+        } else {
+          PHOTON_LAUNCH(KC_MISC, x.st, broadcast_rows_kernel, dim3(blocks_for((int64_t)Bt * D)), dim3(256), 0, x.st, ew.x0[L - 1], pair, Bt, D);
+          PHOTON_TRY(check_launch("broadcast_rows_kernel"));
+        }
+      }
+    }
+  }
+  PHOTON_LAUNCH(KC_MISC, x.st, fill_i32_kernel, dim3(blocks_for(Bt)), dim3(256), 0, x.st, x.s->seq_len, (int32_t)pp.M[L], Bt);
+  PHOTON_TRY(check_launch("fill_i32_kernel"));
+
+  // Carries: teacher-forced decode of the last chunk of every level l >= 2 (one chunk per sequence), on the
+  // decode step's own buffers.  Inputs of sub-step j >= 1 are the encoder-side states of the chunk (reading G7).
+  const float* cond = pair;                                // level-l latent before the last one, one row per sequence
+  int64_t cond_ld = D;
+  float* dh = x.f(x.o_h);
+  float* units = x.f(x.p.fresh[0]);                        // [Bt * C, D] scratch: the items of the chunk
+  for (int l = L; l >= 2; --l) {
+    const int C = c.C[l - 1], R = c.R[l - 1];
+    const photon_module_weights& mod = x.w->dec[l - 1];
+    PHOTON_TRY(linear(x, cond, cond_ld, x.w->conv_w[l - 1], nullptr, x.w->conv_b[l - 1], nullptr, 0, dh, (int64_t)R * D, Bt, R * D, D,
+                      EPI_PLAIN));
+    RowsIn in;
+    in.ptr = dh; in.ld = D;
+    const float* teacher = e.f(pp.X[l - 1]) + (pp.M[l - 1] - C) * (int64_t)D;   // sequence b: + b * M[l-1] * D
+    for (int j = 0; j < C; ++j) {
+      const int q_len = (j == 0) ? R : 1;
+      const int q_pos = (j == 0) ? 0 : R + j - 1;
+      PHOTON_TRY(local_module_pass(x, l, Bt, q_len, q_pos, in));
+      PHOTON_TRY(norm(x, dh, q_len, q_len - 1, mod.g_final, units, C, j, Bt));
+      in.ptr = teacher + (int64_t)j * D; in.ld = pp.M[l - 1] * (int64_t)D;
+    }
+    // carry^(l-1) = the chunk's last item (C >= 2: the last sub-step had one row per sequence);
+    // the item before it conditions the last chunk of the level below
+    PHOTON_TRY(norm(x, dh, 1, 0, mod.g_final, x.s->carry + (size_t)(l - 2) * Bt * D, 1, 0, Bt));
+    cond = units + (int64_t)(C - 2) * D;
+    cond_ld = (int64_t)C * D;
+  }
+  return PHOTON_OK;
+}
+
 extern "C" size_t photon_decode_step_workspace_bytes(const photon_config* cfg, int32_t Bt, int64_t S_max) {
   clear_error();
   if (validate_config(cfg, Bt, S_max) != PHOTON_OK) return 0;
   return make_plan(*cfg, Bt, S_max).total;
+}
+
+static int32_t require_module(const photon_config& c, const photon_module_weights& mod, const char* what, int level) {
+  PHOTON_REQUIRE(mod.layers && mod.g_final, PHOTON_ERR_INVALID_ARG, "%s module of level %d missing", what, level);
+  for (int i = 0; i < c.n_layers; ++i) {
+    const photon_layer_weights& lw = mod.layers[i];
+    const bool ok = lw.g1 && lw.wqkv && aligned16(lw.wqkv) && lw.wo && aligned16(lw.wo) &&
+                    (c.d_ff == 0 || (lw.g2 && lw.wgu && aligned16(lw.wgu) && lw.wd && aligned16(lw.wd)));
+    PHOTON_REQUIRE(ok, PHOTON_ERR_INVALID_ARG, "%s module of level %d, layer %d has a null or misaligned weight", what, level, i);
+  }
+  return PHOTON_OK;
+}
+
+static int32_t validate_prefill(const photon_config& c, int Bt, int64_t T, int64_t S_max) {
+  int64_t meta = 1;
+  for (int l = 0; l < c.L; ++l) meta *= c.C[l];
+  PHOTON_REQUIRE(T >= meta && T % meta == 0, PHOTON_ERR_INVALID_ARG, "prefill: T=%lld must be a positive multiple of prod(C)=%lld",
+                 (long long)T, (long long)meta);
+  PHOTON_REQUIRE(T / meta <= S_max, PHOTON_ERR_INVALID_ARG, "prefill: %lld top-level units do not fit S_max=%lld", (long long)(T / meta),
+                 (long long)S_max);
+  PHOTON_REQUIRE((int64_t)Bt * (T / c.C[0]) <= (1 << 24), PHOTON_ERR_UNSUPPORTED, "prefill: %lld level-1 rows exceed 2^24",
+                 (long long)Bt * (T / c.C[0]));
+  for (int l = 2; l <= c.L; ++l)
+    PHOTON_REQUIRE(c.C[l - 1] >= 2, PHOTON_ERR_UNSUPPORTED, "prefill: level %d has C=%d; the carry decode needs C >= 2 above level 1", l,
+                   c.C[l - 1]);
+  return PHOTON_OK;
+}
+
+extern "C" size_t photon_prefill_workspace_bytes(const photon_config* cfg, int32_t Bt, int64_t T) {
+  clear_error();
+  if (cfg == nullptr || validate_config(cfg, Bt, 1) != PHOTON_OK) return 0;
+  if (validate_prefill(*cfg, Bt, T, (int64_t)1 << 40) != PHOTON_OK) return 0;
+  return make_prefill_plan(*cfg, Bt, T).total;
+}
+
+extern "C" int32_t photon_prefill(const photon_config* cfg, const photon_weights* w, const photon_encoder_weights* ew,
+                                  const photon_state* st, int32_t Bt, const int32_t* tokens, int64_t T, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  clear_error();
+  PHOTON_REQUIRE(cfg && w && ew && st, PHOTON_ERR_INVALID_ARG, "%s: cfg, w, ew and st must not be null", __func__);
+  PHOTON_TRY(validate_config(cfg, Bt, st->S_max));
+  const photon_config& c = *cfg;
+  PHOTON_TRY(validate_prefill(c, Bt, T, st->S_max));
+  PHOTON_REQUIRE(tokens != nullptr, PHOTON_ERR_INVALID_ARG, "%s: tokens is null", __func__);
+  PHOTON_REQUIRE_PTR(st->k_cache);
+  PHOTON_REQUIRE_PTR(st->v_cache);
+  PHOTON_REQUIRE_PTR(st->x_top);
+  PHOTON_REQUIRE(st->seq_len != nullptr, PHOTON_ERR_INVALID_ARG, "%s: state.seq_len is null", __func__);
+  PHOTON_REQUIRE(c.L == 1 || (st->carry != nullptr && aligned16(st->carry)), PHOTON_ERR_INVALID_ARG,
+                 "%s: state.carry must be a 16-byte aligned device pointer when L > 1", __func__);
+  PHOTON_REQUIRE_PTR(ew->E_enc);
+  for (int l = 1; l <= c.L; ++l) {
+    PHOTON_REQUIRE(ew->chunker_w[l - 1] && aligned16(ew->chunker_w[l - 1]), PHOTON_ERR_INVALID_ARG,
+                   "%s: chunker of level %d missing or misaligned", __func__, l);
+    PHOTON_TRY(require_module(c, ew->enc[l - 1], "encoder", l));
+    if (l >= 2) {
+      PHOTON_REQUIRE(ew->x0[l - 1] != nullptr, PHOTON_ERR_INVALID_ARG, "%s: start latent of level %d missing", __func__, l);
+      PHOTON_REQUIRE(w->conv_w[l - 1] && aligned16(w->conv_w[l - 1]) && w->conv_b[l - 1], PHOTON_ERR_INVALID_ARG,
+                     "%s: converter of level %d missing or misaligned", __func__, l);
+      PHOTON_TRY(require_module(c, w->dec[l - 1], "decoder", l));
+    }
+  }
+  Ctx x;
+  x.c = cfg; x.w = w; x.s = st; x.Bt = Bt; x.st = (hipStream_t)stream;
+  x.p = make_plan(c, Bt, st->S_max);
+  x.bf16 = (c.dt == PHOTON_BF16);
+  x.overlap = false;
+  x.o_h = x.p.h; x.o_attn = x.p.attn; x.o_qkv = x.p.qkv; x.o_qrot = x.p.qrot; x.o_act = x.p.act; x.o_many = x.p.many;
+  PHOTON_REQUIRE(st->workspace != nullptr && aligned16(st->workspace) && st->workspace_bytes >= x.p.total, PHOTON_ERR_WORKSPACE,
+                 "%s: state workspace of %zu bytes needed (got %zu)", __func__, x.p.total, st->workspace_bytes);
+  x.base = reinterpret_cast<char*>(st->workspace);
+  const PrefillPlan pp = make_prefill_plan(c, Bt, T);
+  PHOTON_REQUIRE(workspace != nullptr && aligned16(workspace) && workspace_bytes >= pp.total, PHOTON_ERR_WORKSPACE,
+                 "%s: workspace of %zu bytes needed (got %zu)", __func__, pp.total, workspace_bytes);
+  Ctx e = x;                                               // same configuration and stream, the big buffers
+  e.base = reinterpret_cast<char*>(workspace);
+  e.o_h = pp.h; e.o_attn = pp.attn; e.o_qkv = pp.qkv; e.o_qrot = 0; e.o_act = pp.act; e.o_many = pp.many;
+  e.p.many_K = pp.many_K;
+  return prefill_impl(x, e, pp, *ew, tokens);
 }
 
 extern "C" int32_t photon_decode_step(const photon_config* cfg, const photon_weights* w, const photon_state* st, int32_t Bt,

@@ -1,12 +1,13 @@
 """Per-kernel throughput of the hot path's entry points at the shapes of the
 benchmark configurations, each against the roofline that bounds it.
 
-    python -m paper_2512_20687_amd.kernel_bench [--only a1,a2,a3,linear,probe]
+    python -m paper_2512_20687_amd.kernel_bench [--only probe,a1,a2,a3,encoder,linear]
 
 Prints one JSON object per line: a streaming-read ceiling (a trivial read-only
 kernel over 2 GiB), the chunker GEMM (bf16 MFMA peak), the coarse decode
 attention at the configuration-3 shape and over a flat 131072-key cache (HBM
-peak), chunk-local attention in tile mode (HBM peak) and the few-row linear
+peak), chunk-local attention in tile mode (HBM peak), the encoders' whole-sequence causal
+attention (bf16 MFMA peak on the causal half's flops) and the few-row linear
 maps of one block (HBM peak on weight bytes).  Inputs are seeded and synthetic,
 drawn on the GPU; buffers below 1 GiB are rotated so that no cache can serve a
 launch from the previous one.  Timing: HIP events on the launch stream around
@@ -117,6 +118,20 @@ def bench_a3():
         del q, k, v, o
 
 
+def bench_encoder_attn():
+    """Whole-sequence causal attention of the encoders (prefill form of Eq. 3); flops counted on the causal half."""
+    for Bt, M, H, what in ((4, 8192, 32, "cfg3 level 2 (top encoder)"), (8, 4096, 32, "cfg5 level 1"), (4, 32768, 32, "cfg3 level 1"),
+                           (16, 2048, 16, "cfg2 level 1")):
+        d_h = 64
+        qkv = torch.empty((Bt * M, 3 * H * d_h), device="cuda").normal_()
+        out = torch.empty((Bt * M, H * d_h), device="cuda")
+        ws = torch.empty(max(ph.photon_encoder_attn_workspace_bytes(Bt, M, H, d_h, True), 16), dtype=torch.uint8, device="cuda")
+        us = _time_us(lambda i: ph.photon_encoder_attn(qkv, out, Bt, M, H, d_h, workspace=ws, bf16=True), 3, warm=1)
+        _emit("encoder_rope_split_kernel + encoder_attn_mfma_kernel", f"{what}: Bt={Bt} M={M} H={H} d_h={d_h}", us,
+              flops=2.0 * d_h * M * (M + 1) * Bt * H)
+        del qkv, out, ws
+
+
 def bench_linear():
     """Few-row linear maps of one configuration-3 block at the row counts of the decode sub-steps."""
     shapes = ((6144, 2048, 0, True, "QKV + norm"), (2048, 2048, 1, False, "O + residual"), (5120, 2048, 2, True, "gate/up + norm + SwiGLU"),
@@ -135,7 +150,7 @@ def bench_linear():
             del ws
 
 
-ALL = {"probe": bench_probe, "a1": bench_a1, "a2": bench_a2, "a3": bench_a3, "linear": bench_linear}
+ALL = {"probe": bench_probe, "a1": bench_a1, "a2": bench_a2, "a3": bench_a3, "encoder": bench_encoder_attn, "linear": bench_linear}
 
 
 def main(argv=None):

@@ -1,0 +1,117 @@
+"""GPU parity of photon_prefill (hierarchical prefill, Section 2.3.3) against
+the oracle's prefill, and of a decode step that continues from it."""
+import numpy as np
+import pytest
+import torch
+
+import seeded_inputs as si
+from oracle import photon_oracle as po
+from util import TOL, dev, nerr, require_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_prefill(cfg, w, toks, S_max):
+    import paper_2512_20687_amd as ph
+    Bt = toks.shape[0]
+    model = ph.PhotonModel(cfg, w)
+    state = ph.PhotonState(model, Bt, S_max)
+    # poison what the prefill must fill
+    state.x_top.fill_(float("nan"))
+    state.carry.fill_(float("nan"))
+    state.seq_len.fill_(-7)
+    ph.photon_prefill(model, state, dev(np.asarray(toks, np.int32)))
+    torch.cuda.synchronize()
+    return model, state
+
+
+def check_state(cfg, state, ost, Bt, tol, tol_kv):
+    G = int(ost["seq_len"][0])
+    errs = {"x_top": nerr(state.x_top, ost["x_top"]),
+            "k": nerr(state.k[:, :, :, :G].float(), ost["k"][:, :, :, :G]),
+            "v": nerr(state.v[:, :, :, :G].float(), ost["v"][:, :, :, :G])}
+    if cfg.L > 1:
+        errs["carry"] = nerr(state.carry, ost["carry"])
+    assert np.array_equal(state.seq_len.cpu().numpy(), ost["seq_len"].astype(np.int32))
+    assert float(state.k[:, :, :, G:].float().abs().max()) == 0.0       # rows beyond the prompt stay untouched
+    bad = {k: v for k, v in errs.items() if not v <= (tol_kv if k in ("k", "v") else tol)}
+    assert not bad, (bad, errs)
+    return errs
+
+
+def test_cfg1_prefill_fp32():
+    """Configuration 1: 256-token prompt, two levels, all fp32."""
+    require_gpu()
+    wl = si.WORKLOADS["cfg1_tiny_f32"]
+    cfg = wl.cfg
+    w = si.make_weights(cfg, 0)
+    toks = si.make_tokens(cfg.vocab, wl.Bt, wl.T, 0)
+    S_max = wl.S0 + 4
+    ost = po.prefill(cfg, po.weights_to_f64(w), toks, S_max)
+    model, state = gpu_prefill(cfg, w, toks, S_max)
+    check_state(cfg, state, ost, wl.Bt, 2 * TOL["f32"], 2 * TOL["f32"])
+
+
+@pytest.mark.parametrize("kw,Bt,T", [
+    (dict(), 2, 16 * 12),                                    # L=2, C=(4,4): 48 level-1 units, 12 top units
+    (dict(), 1, 16),                                         # a single top unit: the start latent conditions the carry
+    (dict(L=3, C=(2, 3, 2), R=(1, 2, 1)), 3, 12 * 7),
+    (dict(L=1, C=(4,), R=(2,)), 2, 4 * 37),                  # one level: no carries
+    (dict(R=(2, 2), d_ff=0), 2, 16 * 5),
+])
+def test_small_fp32_prefill(kw, Bt, T):
+    require_gpu()
+    base = dict(L=2, C=(4, 4), R=(1, 1), D=64, H=2, d_h=32, n_layers=2, d_ff=160, vocab=96, dtype="f32")
+    base.update(kw)
+    cfg = si.PhotonConfig(**base)
+    w = si.make_weights(cfg, 11)
+    toks = si.make_tokens(cfg.vocab, Bt, T, 3)
+    S_max = T // cfg.meta_context + 3
+    ost = po.prefill(cfg, po.weights_to_f64(w), toks, S_max)
+    model, state = gpu_prefill(cfg, w, toks, S_max)
+    check_state(cfg, state, ost, Bt, 2 * TOL["f32"], 2 * TOL["f32"])
+
+
+@pytest.mark.parametrize("kw,Bt,T", [
+    (dict(), 2, 16 * 40),                                    # 160 level-1 rows per sequence: tiled MFMA contraction + MFMA attention
+    (dict(L=3, C=(2, 2, 4), R=(1, 1, 1), n_layers=1), 1, 16 * 9),
+    (dict(n_layers=1), 3, 16 * 1),
+])
+def test_bf16_prefill_then_step(kw, Bt, T):
+    """bf16 weights and cache; then one decode step from the GPU-made state
+    against the oracle's step from the oracle-made state."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    base = dict(L=2, C=(4, 4), R=(1, 1), D=256, H=4, d_h=64, n_layers=2, d_ff=640, vocab=1024, dtype="bf16")
+    base.update(kw)
+    cfg = si.PhotonConfig(**base)
+    w = si.make_weights(cfg, 33)
+    toks = si.make_tokens(cfg.vocab, Bt, T, 5)
+    S_max = T // cfg.meta_context + 4
+    w64 = po.weights_to_f64(w)
+    ost = po.prefill(cfg, w64, toks, S_max)
+    model, state = gpu_prefill(cfg, w, toks, S_max)
+    errs = check_state(cfg, state, ost, Bt, TOL["bf16"], 2.0 ** -7)
+    print(errs)
+    # continue with one decode step on both sides
+    forced = si.make_tokens(cfg.vocab, Bt, cfg.meta_context, 9)
+    otr = po.decode_step(cfg, w64, ost, forced_tokens=forced)
+    out = torch.full((Bt, cfg.meta_context), -1, dtype=torch.int32, device="cuda")
+    logits = torch.full((Bt, cfg.meta_context, cfg.vocab), float("nan"), device="cuda")
+    ph.photon_decode_step(model, state, out, forced_tokens=dev(np.asarray(forced, np.int32)), trace={"logits": logits})
+    torch.cuda.synchronize()
+    assert nerr(logits, otr["logits"]) <= TOL["bf16"]
+    assert nerr(state.x_top, otr["x_top"]) <= TOL["bf16"]
+
+
+def test_prefill_rejects_bad_arguments():
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    cfg = si.PhotonConfig(L=2, C=(4, 4), R=(1, 1), D=64, H=2, d_h=32, n_layers=1, d_ff=0, vocab=96, dtype="f32")
+    w = si.make_weights(cfg, 1)
+    model = ph.PhotonModel(cfg, w)
+    state = ph.PhotonState(model, 1, 4)
+    with pytest.raises(ph.PhotonError):
+        ph.photon_prefill(model, state, torch.zeros((1, 24), dtype=torch.int32, device="cuda"))      # not a multiple of 16
+    with pytest.raises(ph.PhotonError):
+        ph.photon_prefill(model, state, torch.zeros((1, 16 * 5), dtype=torch.int32, device="cuda"))  # 5 units > S_max = 4
