@@ -1,7 +1,7 @@
 """Per-kernel throughput of the hot path's entry points at the shapes of the
 benchmark configurations, each against the roofline that bounds it.
 
-    python -m paper_2512_20687_amd.kernel_bench [--only probe,a1,a2,a3,encoder,linear]
+    python -m paper_2512_20687_amd.kernel_bench [--only probe,a1,a2,a3,encoder,prefill,linear]
 
 Prints one JSON object per line: a streaming-read ceiling (a trivial read-only
 kernel over 2 GiB), the chunker GEMM (bf16 MFMA peak), the coarse decode
@@ -132,6 +132,36 @@ def bench_encoder_attn():
         del qkv, out, ws
 
 
+def bench_prefill():
+    """Whole hierarchical prefill (photon_prefill) at the benchmark configurations; flops = every linear map at its row
+    count plus the causal half of the encoders' attention."""
+    import os
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import seeded_inputs as si
+    for name in ("cfg2_bf16_8k", "cfg5_bf16_3level", "cfg3_bf16_128k"):
+        wl = si.WORKLOADS[name]
+        cfg, Bt, T = wl.cfg, wl.Bt, wl.T
+        w = si.make_weights(cfg, 0, device="cuda")
+        model = ph.PhotonModel(cfg, w)
+        del w
+        S_max = T // cfg.meta_context + 8
+        state = ph.PhotonState(model, Bt, S_max)
+        toks = torch.randint(0, cfg.vocab, (Bt, T), dtype=torch.int32, device="cuda")
+        ws = torch.empty(ph.photon_prefill_workspace_bytes(cfg, Bt, T), dtype=torch.uint8, device="cuda")
+        us = _time_us(lambda i: ph.photon_prefill(model, state, toks, workspace=ws), 2, warm=1)
+        D, F = cfg.D, cfg.d_ff
+        flops, M = 0.0, T
+        for l in range(1, cfg.L + 1):
+            M //= cfg.C[l - 1]
+            rows = Bt * M
+            flops += 2.0 * rows * cfg.C[l - 1] * D * D
+            flops += cfg.n_layers * (2.0 * rows * (4 * D * D + 3 * D * F) + 2.0 * D * M * (M + 1) * Bt)
+        rec = _emit("photon_prefill", f"{name}: Bt={Bt} T={T} (workspace {ws.numel() / 2**30:.1f} GiB)", us, flops=flops)
+        print(json.dumps({"kernel": "photon_prefill", "shape": name, "prompt_tokens_per_s": round(Bt * T / us * 1e6)}), flush=True)
+        del model, state, ws, toks
+        torch.cuda.empty_cache()
+
+
 def bench_linear():
     """Few-row linear maps of one configuration-3 block at the row counts of the decode sub-steps."""
     shapes = ((6144, 2048, 0, True, "QKV + norm"), (2048, 2048, 1, False, "O + residual"), (5120, 2048, 2, True, "gate/up + norm + SwiGLU"),
@@ -150,7 +180,7 @@ def bench_linear():
             del ws
 
 
-ALL = {"probe": bench_probe, "a1": bench_a1, "a2": bench_a2, "a3": bench_a3, "encoder": bench_encoder_attn, "linear": bench_linear}
+ALL = {"probe": bench_probe, "a1": bench_a1, "a2": bench_a2, "a3": bench_a3, "encoder": bench_encoder_attn, "prefill": bench_prefill, "linear": bench_linear}
 
 
 def main(argv=None):
