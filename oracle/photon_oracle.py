@@ -312,17 +312,24 @@ def encode(cfg, w, tokens):
     """Hierarchical encoder on one sequence (Eq. 3-4): returns
     X = [X^(0), ..., X^(L)], A = [None, A^(1), ..., A^(L)] and the per-layer
     (K, V) of the top module."""
+    X, A, kv = encode_all(cfg, w, tokens)
+    return X, A, kv[cfg.L]
+
+
+def encode_all(cfg, w, tokens):
+    """As encode, but returns the per-layer (K, V) of every level's module:
+    kv = [None, kv^(1), ..., kv^(L)]."""
     X = [f64(w["E_enc"])[np.asarray(tokens)]]
     A = [None]
-    kv_top = None
+    kvs = [None]
     for l in range(1, cfg.L + 1):
         e = w["enc"][l - 1]
         a = chunker_project(X[l - 1], e["chunker"]["w"], e["chunker"].get("b"), cfg.C[l - 1])
         x, kv = module_full(a, np.arange(a.shape[0]), e["module"], cfg)
         A.append(a)
         X.append(x)
-        kv_top = kv
-    return X, A, kv_top
+        kvs.append(kv)
+    return X, A, kvs
 
 
 def teacher_forced_forward(cfg, w, tokens):
@@ -389,23 +396,16 @@ def top_step(cfg, w, a, state, counters=None):
     return x
 
 
-def decode_step(cfg, w, state, forced_tokens=None, bottleneck_override=None, counters=None):
-    """One recursive-generation step g -> g+1 for every sequence (Section
-    2.3.3, steps (i)-(iii); Appendix A, Definition 2).
-
-    (i) top-down: level L decodes C_L new level-(L-1) units from X^(L)_g; each
-    lower level l decodes one chunk per new level-l unit, the chunk being
-    conditioned on the *previous* level-l unit (Section 2.1.2, converter
-    paragraph), i.e. on [carry^(l), new_1, ..., new_{n-1}] (reading G10); level 1
-    emits the prod(C) tokens of meta-context g+1, feeding back the decoder-side
-    embedding of each chosen token.  Levels >= 2 feed back their own previous
-    output (Eq. 6 as written).  (ii) the top chunker summarises the new
-    level-(L-1) units.  (iii) STEP appends to KV^(L).
-
-    forced_tokens [Bt, prod(C)] replaces the argmax choice (the logits are still
-    returned).  bottleneck_override [Bt, C_L, D] replaces the reconstruction fed
-    to the chunker (used to check the exactness theorem).  state is updated in
-    place; returns a trace dict."""
+def top_down(cfg, w, state, forced_tokens=None):
+    """Step (i) of both decoding procedures (Appendix A, Definitions 1 and 2):
+    level L decodes C_L new level-(L-1) units from X^(L)_g; each lower level l
+    decodes one chunk per new level-l unit, the chunk being conditioned on the
+    *previous* level-l unit (Section 2.1.2, converter paragraph), i.e. on
+    [carry^(l), new_1, ..., new_{n-1}] (reading G10); level 1 emits the prod(C)
+    tokens of meta-context g+1, feeding back the decoder-side embedding of each
+    chosen token.  Levels >= 2 feed back their own previous output (Eq. 6 as
+    written).  Updates the carries in place; returns the trace and new[l] =
+    new level-l units [Bt, n_l, D]."""
     Bt = state["x_top"].shape[0]
     D = cfg.D
     trace = {"new": {}, "logits": None}
@@ -440,14 +440,104 @@ def decode_step(cfg, w, state, forced_tokens=None, bottleneck_override=None, cou
             prev = f64(state["carry"][l - 2])[:, None]                       # [Bt, 1, D]
             cond = np.concatenate([prev, new[l - 1][:, :-1]], axis=1).reshape(Bt * per_seq, D)
             state["carry"][l - 2] = new[l - 1][:, -1]
+    trace["tokens"] = tokens_out
+    return trace, new
+
+
+def _summarise_and_step(cfg, w, state, bott, trace, counters):
+    """Steps (ii)-(iii): the top chunker (Eq. 4) on the bottleneck block
+    [Bt, C_L, D], then STEP (Eq. 12-13)."""
+    Bt = state["x_top"].shape[0]
     top = w["enc"][cfg.L - 1]
-    bott = new[cfg.L - 1] if bottleneck_override is None else f64(bottleneck_override)
-    a_hat = chunker_project(bott.reshape(Bt * cfg.C[cfg.L - 1], D), top["chunker"]["w"],
+    a_hat = chunker_project(f64(bott).reshape(Bt * cfg.C[cfg.L - 1], cfg.D), top["chunker"]["w"],
                             top["chunker"].get("b"), cfg.C[cfg.L - 1])
     trace["a_hat"] = a_hat
     trace["x_top"] = top_step(cfg, w, a_hat, state, counters)
-    trace["tokens"] = tokens_out
     return trace
+
+
+def decode_step(cfg, w, state, forced_tokens=None, bottleneck_override=None, counters=None):
+    """One recursive-generation step g -> g+1 for every sequence (Section
+    2.3.3, steps (i)-(iii); Appendix A, Definition 2): (i) top_down, (ii) the
+    top chunker summarises the *reconstructed* new level-(L-1) units, (iii)
+    STEP appends to KV^(L).
+
+    forced_tokens [Bt, prod(C)] replaces the argmax choice (the logits are still
+    returned).  bottleneck_override [Bt, C_L, D] replaces the reconstruction fed
+    to the chunker (used to check the exactness theorem).  state is updated in
+    place; returns a trace dict."""
+    trace, new = top_down(cfg, w, state, forced_tokens)
+    bott = new[cfg.L - 1] if bottleneck_override is None else bottleneck_override
+    return _summarise_and_step(cfg, w, state, bott, trace, counters)
+
+
+def hier_prefill(cfg, w, tokens, S_max):
+    """Prefill for hierarchical generation (Appendix A, Definition 1: "initialize
+    all encoder-side states and caches"): the state of `prefill` plus, for every
+    level l < L, the K/V cache of that level's encoder over its M_l units:
+    enc_k[l-1], enc_v[l-1] [n_layers, Bt, H, S_max * prod(C_{l+1..L}), d_h] and
+    enc_len[l-1] [Bt]."""
+    tokens = np.asarray(tokens)
+    Bt, T = tokens.shape
+    state = prefill(cfg, w, tokens, S_max)
+    state["enc_k"], state["enc_v"], state["enc_len"] = [], [], []
+    cap = S_max
+    caps = [0] * (cfg.L + 1)
+    for l in range(cfg.L, 0, -1):
+        caps[l] = cap
+        cap *= cfg.C[l - 1]
+    for l in range(1, cfg.L):
+        state["enc_k"].append(np.zeros((cfg.n_layers, Bt, cfg.H, caps[l], cfg.d_h), F64))
+        state["enc_v"].append(np.zeros((cfg.n_layers, Bt, cfg.H, caps[l], cfg.d_h), F64))
+        state["enc_len"].append(np.zeros((Bt,), np.int64))
+    for b in range(Bt):
+        _, _, kvs = encode_all(cfg, w, tokens[b])
+        for l in range(1, cfg.L):
+            M = kvs[l][0][0].shape[1]
+            for i, (K, V) in enumerate(kvs[l]):
+                state["enc_k"][l - 1][i, b, :, :M] = K
+                state["enc_v"][l - 1][i, b, :, :M] = V
+            state["enc_len"][l - 1][b] = M
+    return state
+
+
+def hier_reencode(cfg, w, state, tokens, counters=None):
+    """Step 2 of hierarchical generation (Appendix A, Definition 1): the newly
+    generated tokens [Bt, prod(C)] are re-encoded bottom-up; every level l < L
+    advances its own stream one new unit at a time (STEP, Eq. 12-13, on that
+    level's cache).  Returns the encoder-side bottleneck block
+    X^(L-1) [Bt, C_L, D] of the new meta-context."""
+    tokens = np.asarray(tokens)
+    Bt = tokens.shape[0]
+    x = f64(w["E_enc"])[tokens]                                   # [Bt, prod(C), D]
+    for l in range(1, cfg.L):
+        e = w["enc"][l - 1]
+        C = cfg.C[l - 1]
+        n = x.shape[1] // C
+        a = chunker_project(x.reshape(Bt * n * C, cfg.D), e["chunker"]["w"], e["chunker"].get("b"), C).reshape(Bt, n, cfg.D)
+        caches = [(state["enc_k"][l - 1][i], state["enc_v"][l - 1][i]) for i in range(cfg.n_layers)]
+        out = np.empty((Bt, n, cfg.D), F64)
+        for j in range(n):
+            length = np.asarray(state["enc_len"][l - 1])
+            if counters is not None:
+                counters["kv_elems_read"] = counters.get("kv_elems_read", 0) + int(
+                    2 * cfg.n_layers * cfg.H * cfg.d_h * np.sum(length + 1))
+            out[:, j] = module_step(a[:, j], length, e["module"], caches, length, cfg)
+            state["enc_len"][l - 1] = length + 1
+        x = out
+    return x
+
+
+def hiergen_step(cfg, w, state, forced_tokens=None, counters=None):
+    """One step g -> g+1 of hierarchical generation (Appendix A, Definition 1):
+    (1) top_down as in recursive generation, (2) bottom-up re-encoding of the
+    generated tokens through every level's stream, (3) the top chunker on the
+    encoder-side bottleneck block, then STEP.  state comes from hier_prefill and
+    is updated in place."""
+    trace, new = top_down(cfg, w, state, forced_tokens)
+    bott = hier_reencode(cfg, w, state, trace["tokens"], counters)
+    trace["enc_bottleneck"] = bott
+    return _summarise_and_step(cfg, w, state, bott, trace, counters)
 
 
 # --------------------------------------------------------------------------

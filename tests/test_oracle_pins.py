@@ -396,6 +396,41 @@ def test_exactness_theorem(L, C):
     assert np.abs(probe["x_top"] - fresh["x_top"]).max() > 1e-6
 
 
+@pytest.mark.parametrize("L,C", [(2, (4, 4)), (3, (2, 3, 2))])
+def test_hiergen_equals_recomputation(L, C):
+    """Hierarchical generation (Definition 1) keeps a stream per level; after a
+    step every cache and the top state must equal what encoding prompt +
+    generated tokens from scratch gives (stream == batch at every level), and by
+    Theorem 1 a recursive step fed the same bottleneck block lands in the same
+    top state."""
+    cfg = tiny_cfg(L=L, C=C, R=(1,) * L, n_layers=2)
+    w = po.weights_to_f64(si.make_weights(cfg, 14))
+    B = cfg.meta_context
+    toks = si.make_tokens(cfg.vocab, 2, 2 * B, 7)
+    st = po.hier_prefill(cfg, w, toks, 6)
+    rec = {k: (v.copy() if hasattr(v, "copy") and not isinstance(v, list) else v) for k, v in po.prefill(cfg, w, toks, 6).items()}
+    tr = po.hiergen_step(cfg, w, st)
+    ext = np.concatenate([toks, tr["tokens"]], axis=1)
+    fresh = po.hier_prefill(cfg, w, ext, 6)
+    for key in ("x_top", "k", "v"):
+        np.testing.assert_allclose(st[key], fresh[key], atol=1e-10)
+    np.testing.assert_array_equal(st["seq_len"], fresh["seq_len"])
+    for l in range(1, L):
+        np.testing.assert_allclose(st["enc_k"][l - 1], fresh["enc_k"][l - 1], atol=1e-10)
+        np.testing.assert_allclose(st["enc_v"][l - 1], fresh["enc_v"][l - 1], atol=1e-10)
+        np.testing.assert_array_equal(st["enc_len"][l - 1], fresh["enc_len"][l - 1])
+    # the bottleneck block is the encoder state of the new tokens
+    for b in range(2):
+        np.testing.assert_allclose(tr["enc_bottleneck"][b], po.encode(cfg, w, ext[b])[0][L - 1][-C[-1]:], atol=1e-10)
+    # recursive generation with that block as its bottleneck: same tokens (same top-down pass), same top state
+    tr2 = po.decode_step(cfg, w, rec, forced_tokens=tr["tokens"], bottleneck_override=tr["enc_bottleneck"])
+    np.testing.assert_allclose(rec["x_top"], st["x_top"], atol=1e-10)
+    np.testing.assert_allclose(tr2["logits"], tr["logits"], atol=1e-10)
+    # cache sizes: the level streams hold M_l units each (box "Memory / Size")
+    total = sum(int(st["enc_len"][l - 1][0]) for l in range(1, L)) + int(st["seq_len"][0])
+    assert total == po.kv_cache_units(ext.shape[1], C, "hiergen")
+
+
 def test_batch_rows_are_independent():
     cfg = tiny_cfg(n_layers=1)
     w = po.weights_to_f64(si.make_weights(cfg, 13))
