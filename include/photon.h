@@ -279,10 +279,38 @@ typedef struct photon_encoder_weights {
   const float* x0[PHOTON_MAX_LEVELS];           /* index l-1: start latent of the level-l decoder, [D] fp32 */
 } photon_encoder_weights;
 
+/* Encoder streams of the levels below the top, kept only by hierarchical
+ * generation (Appendix A, Definition 1): index l-1 for level l = 1 .. L-1. */
+typedef struct photon_hier_state {
+  void* k_cache[PHOTON_MAX_LEVELS];     /* [n_layers, Bt, H, S_cap[l-1], d_h] dt: K/V of the level-l encoder */
+  void* v_cache[PHOTON_MAX_LEVELS];
+  int32_t* seq_len[PHOTON_MAX_LEVELS];  /* [Bt] units cached per sequence at level l */
+  int64_t S_cap[PHOTON_MAX_LEVELS];     /* capacity per sequence; a step appends prod(C_{l+1..L}) units */
+} photon_hier_state;
+
+/* hst: NULL for recursive generation; else the lower-level streams are filled
+ * too (all M_l units of every level l < L, seq_len = M_l; needs M_l <= S_cap). */
 PHOTON_API size_t photon_prefill_workspace_bytes(const photon_config* cfg, int32_t Bt, int64_t T);
 PHOTON_API int32_t photon_prefill(const photon_config* cfg, const photon_weights* w, const photon_encoder_weights* ew,
-                                  const photon_state* st, int32_t Bt, const int32_t* tokens, int64_t T,
-                                  void* workspace, size_t workspace_bytes, void* stream);
+                                  const photon_state* st, const photon_hier_state* hst, int32_t Bt,
+                                  const int32_t* tokens, int64_t T, void* workspace, size_t workspace_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
+ * One step of hierarchical generation (Appendix A, Definition 1), the schedule
+ * recursive generation is compared with (Section 2.3.3, Table 2): (1) the same
+ * top-down decode as photon_decode_step; (2) the generated tokens are
+ * re-encoded bottom-up: every level l < L advances its own stream by
+ * prod(C_{l+1..L}) units, one STEP (Eq. 12-13) per unit on that level's cache;
+ * (3) the top chunker (Eq. 4) summarises the ENCODER-side level-(L-1) block and
+ * the top stream advances.  Arguments as for photon_decode_step, plus the
+ * encoder-side weights and the lower-level streams (every level must have room
+ * for the units of one step).  trace->a_hat receives the encoder-side summary.
+ * Runs on `stream` only.
+ * -------------------------------------------------------------------------- */
+PHOTON_API int32_t photon_hiergen_step(const photon_config* cfg, const photon_weights* w, const photon_encoder_weights* ew,
+                                       const photon_state* st, const photon_hier_state* hst, int32_t Bt,
+                                       const int32_t* forced_tokens, int32_t* out_tokens, const photon_trace* trace,
+                                       void* stream);
 
 /* --------------------------------------------------------------------------
  * Bandwidth probe for benchmarks: a trivial kernel that reads `bytes` bytes of

@@ -9,6 +9,7 @@ raises.
 """
 from .binding import (  # noqa: F401
     PhotonError,
+    PhotonHierState,
     PhotonModel,
     PhotonState,
     lib_path,
@@ -23,6 +24,7 @@ from .binding import (  # noqa: F401
     photon_encoder_attn_workspace_bytes,
     photon_decode_step_workspace_bytes,
     photon_hbm_read_probe,
+    photon_hiergen_step,
     photon_last_error,
     photon_linear,
     photon_prefill,

@@ -229,6 +229,11 @@ class _State(C.Structure):
                 ("carry", C.c_void_p), ("S_max", C.c_int64), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
 
+class _HierState(C.Structure):
+    _fields_ = [("k_cache", C.c_void_p * MAX_LEVELS), ("v_cache", C.c_void_p * MAX_LEVELS), ("seq_len", C.c_void_p * MAX_LEVELS),
+                ("S_cap", C.c_int64 * MAX_LEVELS)]
+
+
 class _Trace(C.Structure):
     _fields_ = [("logits", C.c_void_p), ("new_units", C.c_void_p * MAX_LEVELS), ("a_hat", C.c_void_p)]
 
@@ -244,8 +249,11 @@ def _register_step(lib):
     lib.photon_prefill_workspace_bytes.restype = C.c_size_t
     lib.photon_prefill_workspace_bytes.argtypes = [C.POINTER(_Config), C.c_int32, C.c_int64]
     lib.photon_prefill.restype = C.c_int32
-    lib.photon_prefill.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(_EncoderWeights), C.POINTER(_State), C.c_int32,
-                                   C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.photon_prefill.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(_EncoderWeights), C.POINTER(_State),
+                                   C.POINTER(_HierState), C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.photon_hiergen_step.restype = C.c_int32
+    lib.photon_hiergen_step.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(_EncoderWeights), C.POINTER(_State),
+                                        C.POINTER(_HierState), C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(_Trace), C.c_void_p]
     lib._photon_step_registered = True
 
 
@@ -366,6 +374,39 @@ class PhotonState:
         self.c_state = s
 
 
+class PhotonHierState:
+    """Encoder streams of the levels below the top (hierarchical generation only): per level l = 1..L-1 a K/V
+    cache [n_layers, Bt, H, S_cap_l, d_h] and the per-sequence unit counts.  S_cap_l = S_max * prod(C_{l+1..L})."""
+
+    def __init__(self, model: PhotonModel, Bt: int, S_max: int, k=None, v=None, seq_len=None):
+        cfg, dev = model.cfg, model.device
+        self.k, self.v, self.seq_len, self.S_cap = [], [], [], []
+        h = _HierState()
+        cap = S_max
+        caps = {}
+        for l in range(cfg.L, 0, -1):
+            caps[l] = cap
+            cap *= cfg.C[l - 1]
+        for l in range(1, cfg.L):
+            shape = (cfg.n_layers, Bt, cfg.H, caps[l], cfg.d_h)
+
+            def put(a, dtype, shp):
+                if a is None:
+                    return torch.zeros(shp, dtype=dtype, device=dev)
+                t = a if isinstance(a, torch.Tensor) else torch.from_numpy(np_contig(a))
+                t = t.to(device=dev, dtype=dtype).contiguous()
+                assert tuple(t.shape) == tuple(shp), (t.shape, shp)
+                return t
+
+            self.k.append(put(None if k is None else k[l - 1], model.mat_dtype, shape))
+            self.v.append(put(None if v is None else v[l - 1], model.mat_dtype, shape))
+            self.seq_len.append(put(None if seq_len is None else seq_len[l - 1], torch.int32, (Bt,)))
+            self.S_cap.append(caps[l])
+            h.k_cache[l - 1], h.v_cache[l - 1] = self.k[-1].data_ptr(), self.v[-1].data_ptr()
+            h.seq_len[l - 1], h.S_cap[l - 1] = self.seq_len[-1].data_ptr(), caps[l]
+        self.c_state = h
+
+
 def np_contig(a):
     import numpy as np
     return np.ascontiguousarray(a)
@@ -383,8 +424,10 @@ def photon_prefill_workspace_bytes(cfg, Bt: int, T: int) -> int:
     return lib.photon_prefill_workspace_bytes(C.byref(_c_config(cfg)), Bt, T)
 
 
-def photon_prefill(model: PhotonModel, state: PhotonState, tokens: torch.Tensor, workspace: Optional[torch.Tensor] = None):
-    """Hierarchical prefill of the prompts `tokens` (int32 [Bt, T] on the device) into `state`."""
+def photon_prefill(model: PhotonModel, state: PhotonState, tokens: torch.Tensor, workspace: Optional[torch.Tensor] = None,
+                   hier: Optional["PhotonHierState"] = None):
+    """Hierarchical prefill of the prompts `tokens` (int32 [Bt, T] on the device) into `state` (and into the
+    lower-level streams `hier` when hierarchical generation is to follow)."""
     lib = load_library()
     _register_step(lib)
     if model.c_encoder_weights is None:
@@ -395,9 +438,31 @@ def photon_prefill(model: PhotonModel, state: PhotonState, tokens: torch.Tensor,
         if n == 0:
             raise PhotonError(-1, lib.photon_last_error().decode())
         workspace = torch.empty(n, dtype=torch.uint8, device=model.device)
-    _check(lib.photon_prefill(C.byref(model.c_cfg), C.byref(model.c_weights), C.byref(model.c_encoder_weights), C.byref(state.c_state), Bt,
-                              _ptr(tokens), T, _ptr(workspace), workspace.numel(), _stream()))
+    _check(lib.photon_prefill(C.byref(model.c_cfg), C.byref(model.c_weights), C.byref(model.c_encoder_weights), C.byref(state.c_state),
+                              C.byref(hier.c_state) if hier is not None else None, Bt, _ptr(tokens), T, _ptr(workspace),
+                              workspace.numel(), _stream()))
     return workspace
+
+
+def photon_hiergen_step(model: PhotonModel, state: PhotonState, hier: PhotonHierState, out_tokens: torch.Tensor,
+                        forced_tokens: Optional[torch.Tensor] = None, trace: Optional[dict] = None):
+    """One step of hierarchical generation: as photon_decode_step, but the generated tokens are re-encoded
+    bottom-up through the lower-level streams `hier` and the top stream advances on the encoder-side summary."""
+    lib = load_library()
+    _register_step(lib)
+    if model.c_encoder_weights is None:
+        raise PhotonError(-1, "the model was built without encoder-side weights")
+    tr = None
+    if trace is not None:
+        tr = _Trace()
+        tr.logits = _ptr(trace.get("logits"))
+        tr.a_hat = _ptr(trace.get("a_hat"))
+        for l, t in enumerate(trace.get("new_units", [])):
+            tr.new_units[l] = _ptr(t)
+    _check(lib.photon_hiergen_step(C.byref(model.c_cfg), C.byref(model.c_weights), C.byref(model.c_encoder_weights),
+                                   C.byref(state.c_state), C.byref(hier.c_state), state.Bt, _ptr(forced_tokens), _ptr(out_tokens),
+                                   C.byref(tr) if tr is not None else None, _stream()))
+    return out_tokens
 
 
 def photon_decode_step(model: PhotonModel, state: PhotonState, out_tokens: torch.Tensor,

@@ -188,6 +188,7 @@ struct Plan {
   size_t h = 0, attn = 0, qkv = 0, qrot = 0, act = 0, cond = 0, logits = 0, a_hat = 0;
   size_t h2 = 0, attn2 = 0, qkv2 = 0, qrot2 = 0, act2 = 0;   // second set (Bt rows) for the STEP branch that runs beside the lower levels
   size_t many = 0, many2 = 0;                    // scratch of the many-row linear path (0 rows: absent), main and STEP branch
+  size_t hx[PHOTON_MAX_LEVELS] = {0}, hA = 0;    // hierarchical generation: encoder-side new units of level l, chunker outputs
   int many_K = 0;                                // widest contraction it is sized for
   size_t fresh[PHOTON_MAX_LEVELS] = {0};         // fresh[l]: new level-l units, l = 0..L-1
   size_t lk[PHOTON_MAX_LEVELS] = {0}, lv[PHOTON_MAX_LEVELS] = {0};   // local caches of level l (index l-1), all layers
@@ -223,6 +224,7 @@ static Plan make_plan(const photon_config& c, int Bt, int64_t S_max) {
   p.cond = bump(cur, p.rows_max * D * f);
   p.logits = bump(cur, (size_t)p.chunks[1] * c.vocab * f);
   p.a_hat = bump(cur, (size_t)Bt * D * f);
+  p.hA = bump(cur, (size_t)p.chunks[1] * D * f);
   p.h2 = bump(cur, (size_t)Bt * D * f);
   p.attn2 = bump(cur, (size_t)Bt * D * f);
   p.qkv2 = bump(cur, (size_t)Bt * 3 * D * f);
@@ -236,6 +238,7 @@ static Plan make_plan(const photon_config& c, int Bt, int64_t S_max) {
   }
   for (int l = 1; l <= c.L; ++l) {
     p.fresh[l - 1] = bump(cur, (size_t)p.chunks[l] * c.C[l - 1] * D * f);
+    p.hx[l - 1] = bump(cur, (size_t)p.chunks[l] * c.C[l - 1] * D * f);
     const int W = c.R[l - 1] + c.C[l - 1] - 1;
     const size_t cache = (size_t)c.n_layers * p.chunks[l] * W * D * f;
     p.lk[l - 1] = bump(cur, cache);
@@ -287,6 +290,8 @@ struct Ctx {
   size_t o_h, o_attn, o_qkv, o_qrot, o_act;   // activation buffers of the branch this context drives
   size_t o_many;                              // its many-row linear scratch
   bool overlap;                               // run the top-level update beside the lower levels
+  const photon_encoder_weights* ew = nullptr; // encoder-side weights (prefill, hierarchical generation)
+  const photon_hier_state* hs = nullptr;      // lower-level encoder streams (hierarchical generation only)
   float* f(size_t off) const { return reinterpret_cast<float*>(base + off); }
 };
 
@@ -347,34 +352,80 @@ static int32_t local_module_pass(const Ctx& x, int level, int64_t n_chunks, int 
   return PHOTON_OK;
 }
 
-// STEP of the top-level encoder on the Bt rows `in`; leaves X^(L)_{g+1} in state.x_top.
-static int32_t top_step(const Ctx& x, RowsIn in) {
+// STEP (Eq. 12-13) of one encoder stream on the Bt rows `in` (one new unit per sequence): appends K/V to the
+// stream's cache at position seq_len - 1 (the count already includes the new unit) and writes the new state
+// of sequence b to out[(b * out_mul + out_off) * D].
+static int32_t stream_step(const Ctx& x, const photon_module_weights& mod, void* k_cache, void* v_cache, const int32_t* seq_len,
+                           int64_t S_cap, RowsIn in, float* out, int out_mul, int out_off) {
   const photon_config& c = *x.c;
-  const photon_module_weights& mod = x.w->top;
   const int rows = x.Bt;
   float *h = x.f(x.o_h), *qkv = x.f(x.o_qkv), *qrot = x.f(x.o_qrot), *attn = x.f(x.o_attn);
   const size_t esz = dtype_size(c.dt);
-  const size_t layer_cache = (size_t)x.Bt * c.H * x.s->S_max * c.d_h * esz;
+  const size_t layer_cache = (size_t)x.Bt * c.H * S_cap * c.d_h * esz;
   const float scale = 1.0f / sqrtf((float)c.d_h);
   for (int i = 0; i < c.n_layers; ++i) {
     const photon_layer_weights& lw = mod.layers[i];
-    char* kc = reinterpret_cast<char*>(x.s->k_cache) + (size_t)i * layer_cache;
-    char* vc = reinterpret_cast<char*>(x.s->v_cache) + (size_t)i * layer_cache;
+    char* kc = reinterpret_cast<char*>(k_cache) + (size_t)i * layer_cache;
+    char* vc = reinterpret_cast<char*>(v_cache) + (size_t)i * layer_cache;
     PHOTON_TRY(linear(x, in.ptr, in.ld, lw.wqkv, lw.g1, nullptr, nullptr, 0, qkv, 3 * c.D, rows, 3 * c.D, c.D, EPI_PLAIN));
     const int64_t n_el = (int64_t)rows * c.H * (c.d_h / 2);
     if (x.bf16)
       PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_coarse_kernel<bf16_t>, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot,
-                    (bf16_t*)kc, (bf16_t*)vc, x.s->seq_len, x.Bt, c.H, c.d_h, x.s->S_max, c.rope_theta);
+                    (bf16_t*)kc, (bf16_t*)vc, seq_len, x.Bt, c.H, c.d_h, S_cap, c.rope_theta);
     else
       PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_coarse_kernel<float>, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot,
-                    (float*)kc, (float*)vc, x.s->seq_len, x.Bt, c.H, c.d_h, x.s->S_max, c.rope_theta);
+                    (float*)kc, (float*)vc, seq_len, x.Bt, c.H, c.d_h, S_cap, c.rope_theta);
     PHOTON_TRY(check_launch("rope_append_coarse_kernel"));
-    PHOTON_TRY(launch_coarse_attn(x.bf16 ? KV_BF16 : KV_F32, true, c.d_h, qrot, kc, vc, x.s->seq_len, attn, x.Bt, c.H,
-                                  x.s->S_max, scale, x.p.n_splits, x.base + x.p.coarse_ws, x.st));
+    PHOTON_TRY(launch_coarse_attn(x.bf16 ? KV_BF16 : KV_F32, true, c.d_h, qrot, kc, vc, seq_len, attn, x.Bt, c.H, S_cap, scale,
+                                  x.p.n_splits, x.base + x.p.coarse_ws, x.st));
     PHOTON_TRY(block_tail(x, lw, in, rows));
     in.ptr = h; in.ld = c.D;
   }
-  return norm(x, h, 1, 0, mod.g_final, x.s->x_top, 1, 0, rows);
+  return norm(x, h, 1, 0, mod.g_final, out, out_mul, out_off, rows);
+}
+
+// STEP of the top-level encoder; leaves X^(L)_{g+1} in state.x_top.
+static int32_t top_step(const Ctx& x, RowsIn in) {
+  return stream_step(x, x.w->top, x.s->k_cache, x.s->v_cache, x.s->seq_len, x.s->S_max, in, x.s->x_top, 1, 0);
+}
+
+// Step 2 of hierarchical generation (Appendix A, Definition 1): re-encode the step's tokens bottom-up.  Every
+// level l < L advances its stream by its new units, one STEP per unit (they are causally ordered).  Returns the
+// encoder-side level-(L-1) block [Bt, C_L, D] (rows of sequence b contiguous).
+static int32_t hier_reencode(const Ctx& x, const int32_t* tokens, const float** bottleneck) {
+  const photon_config& c = *x.c;
+  const int D = c.D, L = c.L, Bt = x.Bt;
+  int64_t per_seq = 1;
+  for (int l = 0; l < L; ++l) per_seq *= c.C[l];
+  float* X = x.f(x.p.hx[0]);                               // encoder-side level-0 states of the new tokens
+  const int64_t n_tok = (int64_t)Bt * per_seq;
+  if (x.bf16)
+    PHOTON_LAUNCH(KC_MISC, x.st, embed_rows_kernel<bf16_t>, dim3(blocks_for(n_tok * (D / 4))), dim3(256), 0, x.st, tokens,
+                  (const bf16_t*)x.ew->E_enc, X, n_tok, D, c.vocab);
+  else
+    PHOTON_LAUNCH(KC_MISC, x.st, embed_rows_kernel<float>, dim3(blocks_for(n_tok * (D / 4))), dim3(256), 0, x.st, tokens,
+                  (const float*)x.ew->E_enc, X, n_tok, D, c.vocab);
+  PHOTON_TRY(check_launch("embed_rows_kernel"));
+  float* A = x.f(x.p.hA);
+  for (int l = 1; l < L; ++l) {
+    const int C = c.C[l - 1];
+    per_seq /= C;                                          // new level-l units per sequence
+    const int rows = (int)(Bt * per_seq);
+    PHOTON_TRY(linear(x, X, (int64_t)C * D, x.ew->chunker_w[l - 1], nullptr, x.ew->chunker_b[l - 1], nullptr, 0, A, D, rows, D, C * D,
+                      EPI_PLAIN));
+    float* Xl = x.f(x.p.hx[l]);
+    for (int j = 0; j < (int)per_seq; ++j) {
+      PHOTON_LAUNCH(KC_MISC, x.st, step_begin_kernel, dim3(blocks_for(Bt)), dim3(256), 0, x.st, x.hs->seq_len[l - 1], Bt);
+      PHOTON_TRY(check_launch("step_begin_kernel"));
+      RowsIn in;
+      in.ptr = A + (int64_t)j * D; in.ld = per_seq * (int64_t)D;
+      PHOTON_TRY(stream_step(x, x.ew->enc[l - 1], x.hs->k_cache[l - 1], x.hs->v_cache[l - 1], x.hs->seq_len[l - 1], x.hs->S_cap[l - 1], in,
+                             Xl, (int)per_seq, j));
+    }
+    X = Xl;
+  }
+  *bottleneck = X;
+  return PHOTON_OK;
 }
 
 // (ii) top chunker (Eq. 4) on the C_L new level-(L-1) units of every sequence, (iii) STEP (Eq. 13).
@@ -454,7 +505,7 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
         in.ptr = h; in.ld = D;
       }
     }
-    if (l == L && L >= 2 && x.overlap) {
+    if (l == L && L >= 2 && x.overlap && x.hs == nullptr) {
       PHOTON_TRY(ensure_side_stream());
       if (hipEventRecord(g_fork, x.st) != hipSuccess || hipStreamWaitEvent(g_side, g_fork, 0) != hipSuccess)
         return fail(PHOTON_ERR_HIP, "decode step: cannot fork the STEP branch");
@@ -478,7 +529,11 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
     }
   }
 
-  if (!forked) PHOTON_TRY(chunk_and_step(x, fresh[L - 1], tr));
+  if (x.hs != nullptr) {
+    const float* bott = nullptr;
+    PHOTON_TRY(hier_reencode(x, out_tokens, &bott));
+    PHOTON_TRY(chunk_and_step(x, bott, tr));
+  } else if (!forked) PHOTON_TRY(chunk_and_step(x, fresh[L - 1], tr));
   else {
     if (hipEventRecord(g_join, g_side) != hipSuccess || hipStreamWaitEvent(x.st, g_join, 0) != hipSuccess)
       return fail(PHOTON_ERR_HIP, "decode step: cannot join the STEP branch");
@@ -561,14 +616,27 @@ static int32_t prefill_impl(const Ctx& x, Ctx e, const PrefillPlan& pp, const ph
     for (int i = 0; i < c.n_layers; ++i) {
       const photon_layer_weights& lw = mod.layers[i];
       PHOTON_TRY(linear(e, in.ptr, in.ld, lw.wqkv, lw.g1, nullptr, nullptr, 0, qkv, 3 * D, rows, 3 * D, D, EPI_PLAIN));
-      char* kc = (l == L) ? reinterpret_cast<char*>(x.s->k_cache) + (size_t)i * layer_cache : nullptr;
-      char* vc = (l == L) ? reinterpret_cast<char*>(x.s->v_cache) + (size_t)i * layer_cache : nullptr;
-      PHOTON_TRY(launch_encoder_attn(qkv, attn, Bt, M, c.H, c.d_h, c.rope_theta, scale, kc, vc, x.s->S_max, e.base + pp.ea, x.bf16, x.st));
+      char *kc = nullptr, *vc = nullptr;
+      int64_t cap = x.s->S_max;
+      if (l == L) {
+        kc = reinterpret_cast<char*>(x.s->k_cache) + (size_t)i * layer_cache;
+        vc = reinterpret_cast<char*>(x.s->v_cache) + (size_t)i * layer_cache;
+      } else if (x.hs != nullptr) {                        // hierarchical generation keeps every level's stream
+        cap = x.hs->S_cap[l - 1];
+        const size_t lc = (size_t)Bt * c.H * cap * c.d_h * esz;
+        kc = reinterpret_cast<char*>(x.hs->k_cache[l - 1]) + (size_t)i * lc;
+        vc = reinterpret_cast<char*>(x.hs->v_cache[l - 1]) + (size_t)i * lc;
+      }
+      PHOTON_TRY(launch_encoder_attn(qkv, attn, Bt, M, c.H, c.d_h, c.rope_theta, scale, kc, vc, cap, e.base + pp.ea, x.bf16, x.st));
       PHOTON_TRY(block_tail(e, lw, in, rows));
       in.ptr = h; in.ld = D;
     }
     if (l < L) {
       PHOTON_TRY(norm(e, in.ptr, 1, 0, mod.g_final, e.f(pp.X[l]), 1, 0, rows));
+      if (x.hs != nullptr) {
+        PHOTON_LAUNCH(KC_MISC, x.st, fill_i32_kernel, dim3(blocks_for(Bt)), dim3(256), 0, x.st, x.hs->seq_len[l - 1], (int32_t)M, Bt);
+        PHOTON_TRY(check_launch("fill_i32_kernel"));
+      }
     } else {
       // only two rows of X^(L) are ever used: the last one (the top state) and the one before it (conditions the carry decode)
       PHOTON_TRY(norm(e, in.ptr, (int)M, (int)M - 1, mod.g_final, x.s->x_top, 1, 0, Bt));
@@ -654,9 +722,28 @@ extern "C" size_t photon_prefill_workspace_bytes(const photon_config* cfg, int32
   return make_prefill_plan(*cfg, Bt, T).total;
 }
 
+static int32_t require_hier_state(const photon_config& c, const photon_hier_state* hst) {
+  for (int l = 1; l < c.L; ++l) {
+    PHOTON_REQUIRE(hst->k_cache[l - 1] && aligned16(hst->k_cache[l - 1]) && hst->v_cache[l - 1] && aligned16(hst->v_cache[l - 1]) &&
+                       hst->seq_len[l - 1] && hst->S_cap[l - 1] > 0,
+                   PHOTON_ERR_INVALID_ARG, "stream of level %d: cache, seq_len or capacity missing or misaligned", l);
+  }
+  return PHOTON_OK;
+}
+
+static int32_t require_encoders(const photon_config& c, const photon_encoder_weights* ew) {
+  PHOTON_REQUIRE_PTR(ew->E_enc);
+  for (int l = 1; l <= c.L; ++l) {
+    PHOTON_REQUIRE(ew->chunker_w[l - 1] && aligned16(ew->chunker_w[l - 1]), PHOTON_ERR_INVALID_ARG,
+                   "chunker of level %d missing or misaligned", l);
+    PHOTON_TRY(require_module(c, ew->enc[l - 1], "encoder", l));
+  }
+  return PHOTON_OK;
+}
+
 extern "C" int32_t photon_prefill(const photon_config* cfg, const photon_weights* w, const photon_encoder_weights* ew,
-                                  const photon_state* st, int32_t Bt, const int32_t* tokens, int64_t T, void* workspace,
-                                  size_t workspace_bytes, void* stream) {
+                                  const photon_state* st, const photon_hier_state* hst, int32_t Bt, const int32_t* tokens, int64_t T,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
   clear_error();
   PHOTON_REQUIRE(cfg && w && ew && st, PHOTON_ERR_INVALID_ARG, "%s: cfg, w, ew and st must not be null", __func__);
   PHOTON_TRY(validate_config(cfg, Bt, st->S_max));
@@ -669,16 +756,20 @@ extern "C" int32_t photon_prefill(const photon_config* cfg, const photon_weights
   PHOTON_REQUIRE(st->seq_len != nullptr, PHOTON_ERR_INVALID_ARG, "%s: state.seq_len is null", __func__);
   PHOTON_REQUIRE(c.L == 1 || (st->carry != nullptr && aligned16(st->carry)), PHOTON_ERR_INVALID_ARG,
                  "%s: state.carry must be a 16-byte aligned device pointer when L > 1", __func__);
-  PHOTON_REQUIRE_PTR(ew->E_enc);
-  for (int l = 1; l <= c.L; ++l) {
-    PHOTON_REQUIRE(ew->chunker_w[l - 1] && aligned16(ew->chunker_w[l - 1]), PHOTON_ERR_INVALID_ARG,
-                   "%s: chunker of level %d missing or misaligned", __func__, l);
-    PHOTON_TRY(require_module(c, ew->enc[l - 1], "encoder", l));
-    if (l >= 2) {
-      PHOTON_REQUIRE(ew->x0[l - 1] != nullptr, PHOTON_ERR_INVALID_ARG, "%s: start latent of level %d missing", __func__, l);
-      PHOTON_REQUIRE(w->conv_w[l - 1] && aligned16(w->conv_w[l - 1]) && w->conv_b[l - 1], PHOTON_ERR_INVALID_ARG,
-                     "%s: converter of level %d missing or misaligned", __func__, l);
-      PHOTON_TRY(require_module(c, w->dec[l - 1], "decoder", l));
+  PHOTON_TRY(require_encoders(c, ew));
+  for (int l = 2; l <= c.L; ++l) {
+    PHOTON_REQUIRE(ew->x0[l - 1] != nullptr, PHOTON_ERR_INVALID_ARG, "%s: start latent of level %d missing", __func__, l);
+    PHOTON_REQUIRE(w->conv_w[l - 1] && aligned16(w->conv_w[l - 1]) && w->conv_b[l - 1], PHOTON_ERR_INVALID_ARG,
+                   "%s: converter of level %d missing or misaligned", __func__, l);
+    PHOTON_TRY(require_module(c, w->dec[l - 1], "decoder", l));
+  }
+  if (hst != nullptr) {
+    PHOTON_TRY(require_hier_state(c, hst));
+    int64_t M = T;
+    for (int l = 1; l < c.L; ++l) {
+      M /= c.C[l - 1];
+      PHOTON_REQUIRE(M <= hst->S_cap[l - 1], PHOTON_ERR_INVALID_ARG, "%s: %lld level-%d units do not fit its capacity %lld", __func__,
+                     (long long)M, l, (long long)hst->S_cap[l - 1]);
     }
   }
   Ctx x;
@@ -686,6 +777,7 @@ extern "C" int32_t photon_prefill(const photon_config* cfg, const photon_weights
   x.p = make_plan(c, Bt, st->S_max);
   x.bf16 = (c.dt == PHOTON_BF16);
   x.overlap = false;
+  x.ew = ew; x.hs = hst;
   x.o_h = x.p.h; x.o_attn = x.p.attn; x.o_qkv = x.p.qkv; x.o_qrot = x.p.qrot; x.o_act = x.p.act; x.o_many = x.p.many;
   PHOTON_REQUIRE(st->workspace != nullptr && aligned16(st->workspace) && st->workspace_bytes >= x.p.total, PHOTON_ERR_WORKSPACE,
                  "%s: state workspace of %zu bytes needed (got %zu)", __func__, x.p.total, st->workspace_bytes);
@@ -700,45 +792,58 @@ extern "C" int32_t photon_prefill(const photon_config* cfg, const photon_weights
   return prefill_impl(x, e, pp, *ew, tokens);
 }
 
-extern "C" int32_t photon_decode_step(const photon_config* cfg, const photon_weights* w, const photon_state* st, int32_t Bt,
-                                      const int32_t* forced_tokens, int32_t* out_tokens, const photon_trace* trace,
-                                      void* stream) {
-  clear_error();
-  PHOTON_REQUIRE(cfg && w && st, PHOTON_ERR_INVALID_ARG, "%s: cfg, w and st must not be null", __func__);
+static int32_t decode_entry(const char* fn, const photon_config* cfg, const photon_weights* w, const photon_encoder_weights* ew,
+                            const photon_state* st, const photon_hier_state* hst, int32_t Bt, const int32_t* forced_tokens,
+                            int32_t* out_tokens, const photon_trace* trace, void* stream) {
+  PHOTON_REQUIRE(cfg && w && st, PHOTON_ERR_INVALID_ARG, "%s: cfg, w and st must not be null", fn);
   PHOTON_TRY(validate_config(cfg, Bt, st->S_max));
   const photon_config& c = *cfg;
-  PHOTON_REQUIRE(out_tokens != nullptr, PHOTON_ERR_INVALID_ARG, "%s: out_tokens is null", __func__);
+  PHOTON_REQUIRE(out_tokens != nullptr, PHOTON_ERR_INVALID_ARG, "%s: out_tokens is null", fn);
   PHOTON_REQUIRE_PTR(st->k_cache);
   PHOTON_REQUIRE_PTR(st->v_cache);
   PHOTON_REQUIRE_PTR(st->x_top);
-  PHOTON_REQUIRE(st->seq_len != nullptr, PHOTON_ERR_INVALID_ARG, "%s: state.seq_len is null", __func__);
+  PHOTON_REQUIRE(st->seq_len != nullptr, PHOTON_ERR_INVALID_ARG, "%s: state.seq_len is null", fn);
   PHOTON_REQUIRE(c.L == 1 || (st->carry != nullptr && aligned16(st->carry)), PHOTON_ERR_INVALID_ARG,
-                 "%s: state.carry must be a 16-byte aligned device pointer when L > 1", __func__);
+                 "%s: state.carry must be a 16-byte aligned device pointer when L > 1", fn);
   PHOTON_REQUIRE_PTR(w->E_dec);
   PHOTON_REQUIRE_PTR(w->W_lm);
   PHOTON_REQUIRE_PTR(w->chunker_w);
-  PHOTON_REQUIRE(w->top.layers && w->top.g_final, PHOTON_ERR_INVALID_ARG, "%s: top module weights missing", __func__);
+  PHOTON_TRY(require_module(c, w->top, "top", c.L));
   for (int l = 0; l < c.L; ++l) {
-    PHOTON_REQUIRE(w->conv_w[l] && aligned16(w->conv_w[l]) && w->conv_b[l] && w->dec[l].layers && w->dec[l].g_final,
-                   PHOTON_ERR_INVALID_ARG, "%s: weights of decoder level %d missing or misaligned", __func__, l + 1);
+    PHOTON_REQUIRE(w->conv_w[l] && aligned16(w->conv_w[l]) && w->conv_b[l], PHOTON_ERR_INVALID_ARG,
+                   "%s: converter of level %d missing or misaligned", fn, l + 1);
+    PHOTON_TRY(require_module(c, w->dec[l], "decoder", l + 1));
   }
-  for (int m = 0; m <= c.L; ++m) {
-    const photon_module_weights& mod = (m == 0) ? w->top : w->dec[m - 1];
-    for (int i = 0; i < c.n_layers; ++i) {
-      const photon_layer_weights& lw = mod.layers[i];
-      const bool ok = lw.g1 && lw.wqkv && aligned16(lw.wqkv) && lw.wo && aligned16(lw.wo) &&
-                      (c.d_ff == 0 || (lw.g2 && lw.wgu && aligned16(lw.wgu) && lw.wd && aligned16(lw.wd)));
-      PHOTON_REQUIRE(ok, PHOTON_ERR_INVALID_ARG, "%s: module %d layer %d has a null or misaligned weight", __func__, m, i);
-    }
+  if (hst != nullptr) {
+    PHOTON_REQUIRE(ew != nullptr, PHOTON_ERR_INVALID_ARG, "%s: encoder-side weights are null", fn);
+    PHOTON_TRY(require_encoders(c, ew));
+    PHOTON_TRY(require_hier_state(c, hst));
   }
   Ctx x;
   x.c = cfg; x.w = w; x.s = st; x.Bt = Bt; x.st = (hipStream_t)stream;
   x.p = make_plan(c, Bt, st->S_max);
   x.bf16 = (c.dt == PHOTON_BF16);
   x.overlap = !g_profile_on;   // per-kernel timing wants one stream: concurrency would inflate the bracketed times
+  x.ew = ew; x.hs = hst;
   x.o_h = x.p.h; x.o_attn = x.p.attn; x.o_qkv = x.p.qkv; x.o_qrot = x.p.qrot; x.o_act = x.p.act; x.o_many = x.p.many;
   PHOTON_REQUIRE(st->workspace != nullptr && aligned16(st->workspace) && st->workspace_bytes >= x.p.total, PHOTON_ERR_WORKSPACE,
-                 "%s: workspace of %zu bytes needed (got %zu)", __func__, x.p.total, st->workspace_bytes);
+                 "%s: workspace of %zu bytes needed (got %zu)", fn, x.p.total, st->workspace_bytes);
   x.base = reinterpret_cast<char*>(st->workspace);
   return decode_step_impl(x, forced_tokens, out_tokens, trace);
+}
+
+extern "C" int32_t photon_decode_step(const photon_config* cfg, const photon_weights* w, const photon_state* st, int32_t Bt,
+                                      const int32_t* forced_tokens, int32_t* out_tokens, const photon_trace* trace,
+                                      void* stream) {
+  clear_error();
+  return decode_entry(__func__, cfg, w, nullptr, st, nullptr, Bt, forced_tokens, out_tokens, trace, stream);
+}
+
+extern "C" int32_t photon_hiergen_step(const photon_config* cfg, const photon_weights* w, const photon_encoder_weights* ew,
+                                       const photon_state* st, const photon_hier_state* hst, int32_t Bt,
+                                       const int32_t* forced_tokens, int32_t* out_tokens, const photon_trace* trace,
+                                       void* stream) {
+  clear_error();
+  PHOTON_REQUIRE(hst != nullptr, PHOTON_ERR_INVALID_ARG, "%s: the lower-level streams are null", __func__);
+  return decode_entry(__func__, cfg, w, ew, st, hst, Bt, forced_tokens, out_tokens, trace, stream);
 }

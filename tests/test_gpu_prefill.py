@@ -115,3 +115,61 @@ def test_prefill_rejects_bad_arguments():
         ph.photon_prefill(model, state, torch.zeros((1, 24), dtype=torch.int32, device="cuda"))      # not a multiple of 16
     with pytest.raises(ph.PhotonError):
         ph.photon_prefill(model, state, torch.zeros((1, 16 * 5), dtype=torch.int32, device="cuda"))  # 5 units > S_max = 4
+
+
+def check_hier(cfg, hier, ost, tol_kv):
+    for l in range(1, cfg.L):
+        n = int(ost["enc_len"][l - 1][0])
+        assert np.array_equal(hier.seq_len[l - 1].cpu().numpy(), ost["enc_len"][l - 1].astype(np.int32))
+        ek = nerr(hier.k[l - 1][:, :, :, :n].float(), ost["enc_k"][l - 1][:, :, :, :n])
+        ev = nerr(hier.v[l - 1][:, :, :, :n].float(), ost["enc_v"][l - 1][:, :, :, :n])
+        assert ek <= tol_kv and ev <= tol_kv, (l, ek, ev)
+        assert float(hier.k[l - 1][:, :, :, n:].float().abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("dtype,kw,Bt,T", [
+    ("f32", dict(), 2, 16 * 3),
+    ("f32", dict(L=3, C=(2, 3, 2), R=(1, 2, 1)), 2, 12 * 4),
+    ("f32", dict(L=1, C=(4,), R=(1,)), 2, 4 * 9),
+    ("bf16", dict(), 2, 16 * 10),
+    ("bf16", dict(L=3, C=(2, 2, 4), R=(1, 1, 1), n_layers=1), 3, 16 * 5),
+])
+def test_hierarchical_generation_two_steps(dtype, kw, Bt, T):
+    """Prefill with every level's stream kept, then two steps of hierarchical generation (Definition 1)
+    against the oracle: logits, encoder-side summary, top state, top cache and all lower-level streams."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    if dtype == "f32":
+        base = dict(L=2, C=(4, 4), R=(1, 1), D=64, H=2, d_h=32, n_layers=2, d_ff=160, vocab=96, dtype="f32")
+        tol, tol_kv = 2 * TOL["f32"], 2 * TOL["f32"]
+    else:
+        base = dict(L=2, C=(4, 4), R=(1, 1), D=256, H=4, d_h=64, n_layers=2, d_ff=640, vocab=1024, dtype="bf16")
+        tol, tol_kv = TOL["bf16"], 2.0 ** -7
+    base.update(kw)
+    cfg = si.PhotonConfig(**base)
+    w = si.make_weights(cfg, 17)
+    w64 = po.weights_to_f64(w)
+    toks = si.make_tokens(cfg.vocab, Bt, T, 2)
+    S_max = T // cfg.meta_context + 4
+    ost = po.hier_prefill(cfg, w64, toks, S_max)
+    model = ph.PhotonModel(cfg, w)
+    state = ph.PhotonState(model, Bt, S_max)
+    hier = ph.PhotonHierState(model, Bt, S_max)
+    ph.photon_prefill(model, state, dev(np.asarray(toks, np.int32)), hier=hier)
+    torch.cuda.synchronize()
+    check_state(cfg, state, ost, Bt, tol, tol_kv)
+    check_hier(cfg, hier, ost, tol_kv)
+    B = cfg.meta_context
+    for step in range(2):
+        forced = si.make_tokens(cfg.vocab, Bt, B, 20 + step)
+        otr = po.hiergen_step(cfg, w64, ost, forced_tokens=forced)
+        out = torch.full((Bt, B), -1, dtype=torch.int32, device="cuda")
+        trace = {"logits": torch.full((Bt, B, cfg.vocab), float("nan"), device="cuda"),
+                 "a_hat": torch.full((Bt, cfg.D), float("nan"), device="cuda")}
+        ph.photon_hiergen_step(model, state, hier, out, forced_tokens=dev(np.asarray(forced, np.int32)), trace=trace)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), forced)
+        assert nerr(trace["logits"], otr["logits"]) <= tol
+        assert nerr(trace["a_hat"], otr["a_hat"]) <= tol
+        check_state(cfg, state, ost, Bt, tol, tol_kv)
+        check_hier(cfg, hier, ost, tol_kv)
