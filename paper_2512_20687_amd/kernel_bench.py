@@ -1,7 +1,7 @@
 """Per-kernel throughput of the hot path's entry points at the shapes of the
 benchmark configurations, each against the roofline that bounds it.
 
-    python -m paper_2512_20687_amd.kernel_bench [--only probe,a1,a2,a3,encoder,prefill,linear]
+    python -m paper_2512_20687_amd.kernel_bench [--only probe,a1,a2,a3,encoder,prefill,schedules,linear]
 
 Prints one JSON object per line: a streaming-read ceiling (a trivial read-only
 kernel over 2 GiB), the chunker GEMM (bf16 MFMA peak), the coarse decode
@@ -162,6 +162,66 @@ def bench_prefill():
         torch.cuda.empty_cache()
 
 
+def bench_schedules():
+    """Recursive generation against hierarchical generation (Section 2.3.3, Table 2): one decode step of each,
+    replayed from a HIP graph on synthetic state (every level's cache filled with N(0,1) values at the lengths a
+    prompt of the configuration's context would leave)."""
+    import os
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import seeded_inputs as si
+    for name in ("cfg3_bf16_128k", "cfg2_bf16_8k"):
+        wl = si.WORKLOADS[name]
+        cfg, Bt, S0 = wl.cfg, wl.Bt, wl.S0
+        steps, warm = 24, 4
+        S_max = (S0 + 2 * (steps + warm) + 16 + 127) // 128 * 128
+        w = si.make_weights(cfg, 0, device="cuda")
+        model = ph.PhotonModel(cfg, w)
+        del w
+        out = torch.zeros((Bt, cfg.meta_context), dtype=torch.int32, device="cuda")
+        res = {}
+        for schedule in ("recgen", "hiergen"):
+            st0 = si.make_decode_state(cfg, Bt, S0, S_max, seed=0, device="cuda")
+            state = ph.PhotonState(model, Bt, S_max, **{k: st0[k] for k in ("k", "v", "seq_len", "x_top", "carry")})
+            del st0
+            hier, cache_bytes = None, state.k.numel() * 2 * state.k.element_size()
+            if schedule == "hiergen":
+                hier = ph.PhotonHierState(model, Bt, S_max)
+                units = S0
+                for l in range(cfg.L - 1, 0, -1):
+                    units *= cfg.C[l]                                   # level-l units of the prompt
+                    hier.k[l - 1].normal_(); hier.v[l - 1].normal_()
+                    hier.seq_len[l - 1].fill_(units)
+                    cache_bytes += hier.k[l - 1].numel() * 2 * hier.k[l - 1].element_size()
+                fn = lambda: ph.photon_hiergen_step(model, state, hier, out)
+            else:
+                fn = lambda: ph.photon_decode_step(model, state, out)
+            fn()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                fn()
+            us = _time_us(lambda i: g.replay(), steps, warm=warm)
+            # K/V bytes the global streams read in one step: every new unit of a level reads that level's whole cache per layer
+            e = state.k.element_size()
+            kv = 2.0 * Bt * cfg.H * cfg.d_h * e * cfg.n_layers * S0
+            if schedule == "hiergen":
+                units, n_new = S0, 1
+                for l in range(cfg.L - 1, 0, -1):
+                    units *= cfg.C[l]; n_new *= cfg.C[l]
+                    kv += 2.0 * Bt * cfg.H * cfg.d_h * e * cfg.n_layers * units * n_new
+            res[schedule] = {"ms_per_step": round(us / 1e3, 3), "tokens_per_s": round(Bt * cfg.meta_context / us * 1e6),
+                             "global_kv_read_bytes_per_step": int(kv), "global_kv_cache_bytes": int(cache_bytes)}
+            del state, hier, g
+            torch.cuda.empty_cache()
+        rec = {"kernel": "photon_decode_step vs photon_hiergen_step", "shape": name, **res,
+               "speedup_recgen_over_hiergen": round(res["hiergen"]["ms_per_step"] / res["recgen"]["ms_per_step"], 3),
+               "kv_read_ratio": round(res["hiergen"]["global_kv_read_bytes_per_step"] / res["recgen"]["global_kv_read_bytes_per_step"], 2),
+               "kv_size_ratio": round(res["hiergen"]["global_kv_cache_bytes"] / res["recgen"]["global_kv_cache_bytes"], 2)}
+        print(json.dumps(rec), flush=True)
+        del model
+        torch.cuda.empty_cache()
+
+
 def bench_linear():
     """Few-row linear maps of one configuration-3 block at the row counts of the decode sub-steps."""
     shapes = ((6144, 2048, 0, True, "QKV + norm"), (2048, 2048, 1, False, "O + residual"), (5120, 2048, 2, True, "gate/up + norm + SwiGLU"),
@@ -180,7 +240,7 @@ def bench_linear():
             del ws
 
 
-ALL = {"probe": bench_probe, "a1": bench_a1, "a2": bench_a2, "a3": bench_a3, "encoder": bench_encoder_attn, "prefill": bench_prefill, "linear": bench_linear}
+ALL = {"probe": bench_probe, "a1": bench_a1, "a2": bench_a2, "a3": bench_a3, "encoder": bench_encoder_attn, "prefill": bench_prefill, "schedules": bench_schedules, "linear": bench_linear}
 
 
 def main(argv=None):
