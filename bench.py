@@ -5,7 +5,7 @@
 
 A "step" is one photon_decode_step: one recursive-generation step (all chunk-
 local sub-steps of every level, LM head, top chunker, STEP over the coarse KV
-cache) for every sequence of the workload.  Default workload: BASELINE.json's
+cache) for every sequence of the workload.  Default workload: the benchmark's
 headline configuration (128k-token context, batch 4).  Inputs are seeded and
 synthetic (weights N(0,0.02), K/V ~ N(0,1)); they are resident in HBM before
 the timed region.  Prints ONE JSON line.

@@ -75,7 +75,7 @@ def _cfg(L, C, D, H, nl, vocab, dtype, R=None, d_ff=None):
                         vocab=vocab, dtype=dtype)
 
 
-# The five configurations of the benchmark spec.  d_ff = 2.5*D follows the ratio of
+# The five benchmark configurations.  d_ff = 2.5*D follows the ratio of
 # the paper's parameter tables (4096/1664, 4608/1792, 5120/1920); vocab 32000
 # is the paper's tokenizer size; R=1 makes the local window exactly C.
 WORKLOADS: Dict[str, Workload] = {
