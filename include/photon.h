@@ -322,9 +322,10 @@ PHOTON_API int32_t photon_hbm_read_probe(const void* buf, size_t bytes, void* si
 
 /* --------------------------------------------------------------------------
  * Per-kernel timing for benchmarks.  While enabled, every kernel launch of the
- * library is bracketed by a pair of HIP events on the launch stream (this
- * allocates events and must not be used under stream capture).  Kernels are
- * grouped in classes 0 .. photon_profile_num_classes()-1, named by
+ * library carries a pair of HIP events attached to the dispatch itself (start
+ * and end of the kernel as the command processor stamps them, on the launch
+ * stream); this allocates events and must not be used under stream capture.
+ * Kernels are grouped in classes 0 .. photon_profile_num_classes()-1, named by
  * photon_profile_class_name().  photon_profile_get() waits for the recorded
  * events of a class and returns the launch count and the summed elapsed
  * milliseconds; photon_profile_reset() drops all records.  While enabled,

@@ -35,16 +35,15 @@ const char* const kClassNames[KC_COUNT] = {
     "choose_token_kernel", "misc"};
 }  // namespace
 
-void profile_mark(int cls, hipStream_t st, bool begin) {
+bool profile_pair(int cls, hipEvent_t* start, hipEvent_t* stop) {
+  ProfRec r{cls, nullptr, nullptr};
+  if (hipEventCreate(&r.start) != hipSuccess) return false;
+  if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return false; }
   std::lock_guard<std::mutex> lk(g_prof_mu);
-  if (begin) {
-    ProfRec r{cls, nullptr, nullptr};
-    if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
-    (void)hipEventRecord(r.start, st);
-    g_prof.push_back(r);
-  } else if (!g_prof.empty()) {
-    (void)hipEventRecord(g_prof.back().stop, st);
-  }
+  g_prof.push_back(r);
+  *start = r.start;
+  *stop = r.stop;
+  return true;
 }
 
 }  // namespace photon

@@ -1,6 +1,7 @@
 // Host-side helpers of the C ABI: status/error reporting and argument checks.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdarg.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -30,15 +31,19 @@ enum KernelClass {
   KC_NORM, KC_ROPE_APPEND, KC_SILU_MUL, KC_CHOOSE_TOKEN, KC_MISC, KC_COUNT
 };
 extern bool g_profile_on;
-void profile_mark(int cls, hipStream_t st, bool begin);
-struct ProfScope {
-  int cls; hipStream_t st; bool on;
-  ProfScope(int c, hipStream_t s) : cls(c), st(s), on(g_profile_on) { if (on) profile_mark(cls, st, true); }
-  ~ProfScope() { if (on) profile_mark(cls, st, false); }
-};
+// A fresh event pair recorded under class `cls`; false when events cannot be created (the launch then goes untimed).
+bool profile_pair(int cls, hipEvent_t* start, hipEvent_t* stop);
 #define PHOTON_TRY(expr) do { const int32_t rc_ = (expr); if (rc_ != PHOTON_OK) return rc_; } while (0)
-#define PHOTON_LAUNCH(cls, stream, ...) \
-  do { ::photon::ProfScope prof_scope_((cls), (stream)); hipLaunchKernelGGL(__VA_ARGS__); } while (0)
+// Launch `kern` on `st`.  While profiling, the event pair is attached to the dispatch itself (start and end of the
+// kernel as the command processor stamps them), so the measured time is the kernel's, without the gap to its neighbours.
+#define PHOTON_LAUNCH(cls, stream, kern, grid, block, shmem, st, ...)                                              \
+  do {                                                                                                             \
+    hipEvent_t prof_a_ = nullptr, prof_b_ = nullptr;                                                               \
+    if (::photon::g_profile_on && ::photon::profile_pair((cls), &prof_a_, &prof_b_))                               \
+      hipExtLaunchKernelGGL(kern, grid, block, shmem, st, prof_a_, prof_b_, 0, __VA_ARGS__);                       \
+    else                                                                                                           \
+      hipLaunchKernelGGL(kern, grid, block, shmem, st, __VA_ARGS__);                                               \
+  } while (0)
 
 #define PHOTON_REQUIRE(cond, code, ...) \
   do { if (!(cond)) return ::photon::fail((code), __VA_ARGS__); } while (0)
