@@ -51,7 +51,7 @@ def test_chunker_no_rows():
                               torch.empty((0, 64), device="cuda"), 4)
 
 
-@pytest.mark.parametrize("level,rows", [(1, 32768), (3, 512)])
+@pytest.mark.parametrize("level,rows", [(1, 32768), (2, 4096), (3, 512)])      # 256-, 128- and 64-wide tiles
 def test_chunker_full_size_sampled_rows(level, rows):
     """Configuration 5's chunker GEMMs (8*2048 -> 2048) at their real row counts;
     the oracle computes a sample of output rows."""

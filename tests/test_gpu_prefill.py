@@ -104,6 +104,47 @@ def test_bf16_prefill_then_step(kw, Bt, T):
     assert nerr(state.x_top, otr["x_top"]) <= TOL["bf16"]
 
 
+def test_bf16_prefill_wide_rows():
+    """8 sequences x 1024 level-1 units: the linear maps of level 1 run on 256-wide and 128-wide MFMA tiles
+    (fp32 output, head + remainder activations), level 2 on 64-wide ones; the attention spans four query blocks."""
+    require_gpu()
+    cfg = si.PhotonConfig(L=2, C=(4, 4), R=(1, 1), D=512, H=8, d_h=64, n_layers=1, d_ff=1280, vocab=512, dtype="bf16")
+    w = si.make_weights(cfg, 41)
+    Bt, T = 8, 4096
+    toks = si.make_tokens(cfg.vocab, Bt, T, 8)
+    S_max = T // cfg.meta_context + 2
+    ost = po.prefill(cfg, po.weights_to_f64(w), toks, S_max)
+    model, state = gpu_prefill(cfg, w, toks, S_max)
+    errs = check_state(cfg, state, ost, Bt, TOL["bf16"], 2.0 ** -7)
+    print(errs)
+
+
+def test_encoder_attn_long_sequence_sampled_queries():
+    """8192 positions (the top encoder's length in configuration 3); the oracle computes a sample of the queries."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    Bt, M, H, d_h = 1, 8192, 2, 64
+    qkv = si.make_normal((Bt * M, 3 * H * d_h), 12, "f32")
+    out = torch.full((Bt * M, H * d_h), float("nan"), device="cuda")
+    ws = torch.empty(ph.photon_encoder_attn_workspace_bytes(Bt, M, H, d_h, True), dtype=torch.uint8, device="cuda")
+    ph.photon_encoder_attn(dev(qkv), out, Bt, M, H, d_h, workspace=ws, bf16=True)
+    torch.cuda.synchronize()
+    x = po.f64(qkv).reshape(M, 3, H, d_h)
+    pos = np.arange(M)
+    k = po.rope(x[:, 1], pos, 10000.0)
+    v = x[:, 2]
+    got = out.cpu().numpy().reshape(M, H, d_h)
+    rng = np.random.default_rng(0)
+    sample = sorted(set([0, 1, 63, 64, 255, 256, 257, M - 1] + list(rng.integers(0, M, 40))))
+    worst = 0.0
+    for i in sample:
+        q = po.rope(x[i:i + 1, 0], np.array([i]), 10000.0)[0]                       # [H, d_h]
+        ref = po.attend(q, k[: i + 1].transpose(1, 0, 2), v[: i + 1].transpose(1, 0, 2), 1.0 / np.sqrt(d_h))
+        worst = max(worst, float(np.abs(got[i] - ref).max() / np.abs(ref).max()))
+    assert worst <= TOL["bf16"], worst
+    assert not np.isnan(got).any()
+
+
 def test_prefill_rejects_bad_arguments():
     require_gpu()
     import paper_2512_20687_amd as ph
