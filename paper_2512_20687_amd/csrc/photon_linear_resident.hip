@@ -7,10 +7,10 @@
 // outweigh a tile's weights (32 B per k), and they are re-read, re-scaled and
 // re-split for every tile.  This kernel therefore
 //   * spreads the output columns evenly over (up to) one workgroup per compute
-//     unit, in units of 8 columns, several units per workgroup.  A unit is one
-//     MFMA tile: for SwiGLU its 8 gate rows and the 8 matching up rows; else
-//     its 8 weight rows with the two halves of every 128-byte line folded
-//     into the tile's two row halves (one load instruction then fetches whole
+//     unit, in units of 8 weight rows, several units per workgroup.  A unit is
+//     one MFMA tile: 8 output columns, or for SwiGLU the 4 gate rows and the 4
+//     matching up rows of 4 output columns; the two halves of every 128-byte
+//     line are folded into the tile's two row halves (one load instruction then fetches whole
 //     lines and no lane carries a duplicate: a compute unit's load path is the
 //     scarce resource, and a load that hits in cache costs it as much as one
 //     that misses);
@@ -45,12 +45,12 @@ __host__ __device__ constexpr int rl_chunk_bytes(int rows) { return 2 * 16 * rl_
 // EPI as in LinearEpilogue; XP: live slab pieces per lane (rows = 2*XP of the 16-row tile are live);
 // NORM: RMS pre-norm with gain; TMAX: units per workgroup (register-resident accumulators).
 //
-// Columns are dealt in units of 8: workgroup g owns units [u0, u0 + cnt).  A unit's 8 weight rows form one MFMA
-// tile (SwiGLU: one tile of gate rows and one of the matching up rows): tile row r and r + 8 are weight row r;
+// Columns are dealt in units of 8 (SwiGLU: 4): workgroup g owns units [u0, u0 + cnt).  A unit's 8 weight rows form one
+// MFMA tile (SwiGLU: 4 gate rows, then the 4 up rows of the same columns): tile row r and r + 8 are weight row r;
 // lanes of rows 0..7 load the first 64 bytes of a k block's 128-byte line, lanes of rows 8..15 the second 64,
 // so one load per block fetches whole lines.  The first MFMA of a block uses the registers as loaded, the second
 // after a rotation by 8 lanes inside each row of 16, which brings the second half under rows 0..7.  Accumulator
-// rows 8..15 are meaningless; a unit's 8 columns sit in rows 0..7 (lanes 0..31).
+// rows 8..15 are meaningless; a unit's 8 weight rows sit in rows 0..7 (lanes 0..31).
 template <int EPI, int XP, bool NORM, int TMAX>
 __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
     const float* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ W, const float* __restrict__ gain, float eps,
@@ -60,7 +60,8 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   constexpr int ROWS = 2 * XP;
   constexpr int GP = rl_group_pitch(ROWS);
   constexpr int CHUNK_BYTES = rl_chunk_bytes(ROWS);
-  constexpr int TT = (EPI == EPI_SWIGLU) ? 2 * TMAX : TMAX;        // MFMA tiles: gate tiles first, then the up tiles
+  constexpr int TT = TMAX;                                         // MFMA tiles, one per unit
+  constexpr int UC = (EPI == EPI_SWIGLU) ? 4 : 8;                  // output columns of a unit
   extern __shared__ __align__(16) char smem[];                     // [8 waves][wave_bytes], then row statistics [8][16]
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -74,15 +75,16 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   const int u_cnt = unit_base + (g < unit_rem ? 1 : 0);
   const int u0 = g * unit_base + (g < unit_rem ? g : unit_rem);
   const int tiles = u_cnt;                                         // 1 .. TMAX
-  const int n0 = u0 * 8;
+  const int n0 = u0 * UC;
 
   // weight row of this lane in every tile, as a byte offset from W (host checks that all of W is below 4 GiB)
   uint32_t w_lane[TT];
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
-    const int u = t % TMAX;
-    const int uu = u < tiles ? u : tiles - 1;                      // surplus units repeat the last one (loaded, never stored)
-    const int n = (t < TMAX ? 0 : N) + n0 + uu * 8 + (lrow & 7);   // SwiGLU: the up rows follow the N gate rows
+    const int uu = t < tiles ? t : tiles - 1;                      // surplus units repeat the last one (loaded, never stored)
+    const int r = lrow & 7;
+    // SwiGLU: tile rows 0..3 are gate rows, 4..7 the up rows of the same columns (stored after the N gate rows)
+    const int n = (EPI == EPI_SWIGLU) ? (r < 4 ? 0 : N) + n0 + uu * 4 + (r & 3) : n0 + uu * 8 + r;
     w_lane[t] = ((uint32_t)n * (uint32_t)K + (uint32_t)(lq + 4 * (lrow >> 3)) * 8u) * 2u;
   }
   const char* w_base = reinterpret_cast<const char*>(W);
@@ -245,8 +247,9 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   const int t = wave;
   const int m = m0 + lrow;
   if (m >= M) return;
-  if (lq >= 2) return;                                             // accumulator rows 8..15 are meaningless
-  const int n_out = n0 + t * 8 + lq * 4;
+  if (lq >= (EPI == EPI_SWIGLU ? 1 : 2)) return;                   // accumulator rows 8..15 are meaningless; SwiGLU: rows 4..7 are
+                                                                   // the up values, read from the lanes that hold them below
+  const int n_out = n0 + t * UC + lq * 4;
   float4_t extra = float4_t{0.f, 0.f, 0.f, 0.f};                   // bias and residual, fetched while the partials are added
   if (bias != nullptr) extra = *reinterpret_cast<const float4_t*>(bias + n_out);
   if (EPI == EPI_RESID) extra += *reinterpret_cast<const float4_t*>(res + (int64_t)m * ldres + n_out);
@@ -256,7 +259,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   for (int w = 0; w < RL_WAVES; ++w) {
     const float4_t* rw = reinterpret_cast<const float4_t*>(smem + w * wave_bytes);
     y += rw[t * 64 + lane];
-    if (EPI == EPI_SWIGLU) yu += rw[(TMAX + t) * 64 + lane];
+    if (EPI == EPI_SWIGLU) yu += rw[t * 64 + lane + 16];
     tot += ssum[w * 16 + lrow];
   }
   if (NORM) {
@@ -295,9 +298,9 @@ bool launch_resident_x(const LinearArgs& a, hipStream_t st, int tmax, int G, int
     case 2: return launch_resident_t<EPI, XP, NORM, 2>(a, st, G, ub, ur, wave_bytes, lds);
     case 3: return launch_resident_t<EPI, XP, NORM, 3>(a, st, G, ub, ur, wave_bytes, lds);
     case 4: return launch_resident_t<EPI, XP, NORM, 4>(a, st, G, ub, ur, wave_bytes, lds);
-    default:
-      if constexpr (EPI != EPI_SWIGLU) return launch_resident_t<EPI, XP, NORM, 8>(a, st, G, ub, ur, wave_bytes, lds);
-      return false;
+    case 5: return launch_resident_t<EPI, XP, NORM, 5>(a, st, G, ub, ur, wave_bytes, lds);
+    case 6: return launch_resident_t<EPI, XP, NORM, 6>(a, st, G, ub, ur, wave_bytes, lds);
+    default: return launch_resident_t<EPI, XP, NORM, 8>(a, st, G, ub, ur, wave_bytes, lds);
   }
 }
 
@@ -324,21 +327,22 @@ bool launch_linear_resident(const LinearArgs& a, hipStream_t st) {
   if (w_rows * a.K * 2 >= ((int64_t)1 << 32)) return false;       // 32-bit weight offsets
   const int rows_live = a.M < 16 ? a.M : 16;
   const int xp = rows_live <= 4 ? 2 : rows_live <= 8 ? 4 : 8;
-  const int units = a.N / 8;
+  // SwiGLU deals columns in units of 4 (a tile holds 4 gate rows and their 4 up rows): the same bytes per unit as
+  // 8 plain columns, and a finer deal, which evens out what the workgroups stream
+  const int units = a.N / ((a.epilogue == EPI_SWIGLU) ? 4 : 8);
   // one workgroup per compute unit when there are enough units; more rounds only when a workgroup would exceed the
-  // units its registers hold (8 folded tiles, or 4 gate/up tiles)
+  // 8 tiles its registers hold
   constexpr int CUS = 256;
-  const int cap = (a.epilogue == EPI_SWIGLU) ? 4 : 8;
+  const int cap = 8;
   const int rounds = (units + CUS * cap - 1) / (CUS * cap);
   const int G = units < CUS * rounds ? units : CUS * rounds;
   const int ub = units / G, ur = units % G;
   int tmax = ub + (ur ? 1 : 0);
-  if (tmax > 4) tmax = 8;                                          // instantiated: 1, 2, 3, 4, 8 (surplus tiles repeat the last)
+  if (tmax > 6) tmax = 8;                                          // instantiated: 1 .. 6 and 8 (surplus tiles repeat the last)
   const int chunks = (a.K / RL_KBLOCK + RL_CB - 1) / RL_CB;
   const int n_my_max = (chunks + RL_WAVES - 1) / RL_WAVES;
   int wave_bytes = n_my_max * rl_chunk_bytes(2 * xp);
-  const int tt = (a.epilogue == EPI_SWIGLU) ? 2 * tmax : tmax;
-  if (wave_bytes < tt * 1024) wave_bytes = tt * 1024;              // the partial tiles reuse the area
+  if (wave_bytes < tmax * 1024) wave_bytes = tmax * 1024;          // the partial tiles reuse the area
   const size_t lds = (size_t)RL_WAVES * wave_bytes + RL_WAVES * 16 * sizeof(float);
   if (lds > (size_t)RL_LDS_LIMIT) return false;
   switch (a.epilogue) {
