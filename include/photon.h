@@ -83,17 +83,23 @@ PHOTON_API int32_t photon_chunker_project(const void* x, const void* w, const fl
  * stream's K/V cache (the entry appended by this step included):
  *     out[b,h,:] = softmax(scale * q[b,h,:] . K[b,h,0:seq_len[b],:]) V[b,h,0:seq_len[b],:]
  *   q        [Bt, H, d_h]          dt
- *   k_cache  [Bt, H, S_max, d_h]   dt   (each (b,h) stream contiguous)
- *   v_cache  [Bt, H, S_max, d_h]   dt
+ *   k_cache  [Bt, H, S_max, d_p]   dt   (each (b,h) stream contiguous)
+ *   v_cache  [Bt, H, S_max, d_p]   dt
  *   seq_len  [Bt]                  int32, device; values in [0, S_max]; 0 gives zeros
  *   out      [Bt, H, d_h]          dt
- * d_h in {32, 64, 128}.  The S axis is split over n_splits workgroups per
+ * d_h in [1, 128].  A cache row holds d_p = photon_kv_row_elems(d_h) elements:
+ * d_h rounded up to 32, 64 or 128, so that rows are whole 64/128/256-byte
+ * lines for the head sizes 52, 56 and 60 of the paper's models (Appendix,
+ * tables "PHOTON (600M)" .. "(1.2B)") as well; columns d_h .. d_p-1 of every
+ * row in use must hold zeros (the library's own cache writers do that).
+ * The S axis is split over n_splits workgroups per
  * stream (0 = choose from Bt*H and S_max); partial softmax states are merged
  * in a fixed order, so the result is run-to-run deterministic for a given
  * n_splits.  n_splits > 1 needs a workspace of
  * photon_coarse_decode_attn_workspace_bytes() bytes (contents need no
  * initialisation; calls that share a workspace must be stream-ordered).
  * -------------------------------------------------------------------------- */
+PHOTON_API int32_t photon_kv_row_elems(int32_t d_h);   /* 0 when d_h is outside [1, 128] */
 PHOTON_API size_t photon_coarse_decode_attn_workspace_bytes(int32_t Bt, int32_t H, int32_t d_h, int32_t n_splits);
 PHOTON_API int32_t photon_coarse_decode_attn_auto_splits(int32_t Bt, int32_t H, int64_t S_max);
 PHOTON_API int32_t photon_coarse_decode_attn(const void* q, const void* k_cache, const void* v_cache,
@@ -112,7 +118,8 @@ PHOTON_API int32_t photon_coarse_decode_attn(const void* q, const void* k_cache,
  *   out  [n_chunks, q_len, H, d_h]   dt
  * q_len == W, q_pos == 0: the whole W x W causal tile (teacher-forced / prefill).
  * q_len == 1: one decode sub-step at window position q_pos.
- * Requires q_pos + q_len <= W <= PHOTON_MAX_WINDOW, d_h in {32, 64, 128}.
+ * Requires q_pos + q_len <= W <= PHOTON_MAX_WINDOW; d_h <= 128 and a multiple
+ * of 4 (fp32) or 8 (bf16): a head row is read in 16-byte pieces.
  * n_chunks == 0 is a no-op.
  * -------------------------------------------------------------------------- */
 PHOTON_API int32_t photon_chunk_local_attn(const void* q, const void* k, const void* v, void* out,
@@ -127,15 +134,17 @@ PHOTON_API int32_t photon_chunk_local_attn(const void* q, const void* k, const v
  *   qkv  [Bt*M, 3*H*d_h]  fp32, device: rows b*M + i, columns [q | k | v],
  *                         head h at columns h*d_h .. of each third
  *   out  [Bt*M, H*d_h]    fp32, device
- *   k_cache, v_cache      both NULL, or [Bt][H][S_max][d_h] in dt (device):
- *                         receive the rotated keys and the values of positions
- *                         0 .. M-1 (S_max >= M), i.e. the coarse cache a decode
+ *   k_cache, v_cache      both NULL, or [Bt][H][S_max][photon_kv_row_elems(d_h)]
+ *                         in dt (device): receive the rotated keys and the
+ *                         values of positions 0 .. M-1 (S_max >= M), zeros in
+ *                         the columns past d_h, i.e. the coarse cache a decode
  *                         step continues from
  *   workspace             photon_encoder_attn_workspace_bytes(...) bytes,
  *                         device, caller-owned (0 bytes for fp32)
- * dt PHOTON_BF16: matrix-core kernel, d_h = 64 only; scores from bf16 head +
- * remainder operands, probabilities and values rounded to bf16.
- * dt PHOTON_F32: fp32 vector kernel, d_h in {16, 32, 64}.
+ * dt PHOTON_BF16: matrix-core kernel, d_h a multiple of 4 up to 64 (operand
+ * rows are zero-padded to 64); scores from bf16 head + remainder operands,
+ * probabilities and values rounded to bf16.
+ * dt PHOTON_F32: fp32 vector kernel, d_h a multiple of 4 in [16, 64].
  * Bt*H <= 65535.  Bt == 0 or M == 0 is a no-op.  Nothing is allocated or
  * synchronised; errors are reported by status + photon_last_error().
  * -------------------------------------------------------------------------- */
@@ -187,7 +196,7 @@ typedef struct photon_config {
   int32_t L;                     /* levels, 1..PHOTON_MAX_LEVELS */
   int32_t C[PHOTON_MAX_LEVELS];  /* C[l-1] = C_l >= 1 */
   int32_t R[PHOTON_MAX_LEVELS];  /* R[l-1] = R_l >= 1;  R_l + C_l - 1 <= PHOTON_MAX_WINDOW */
-  int32_t D, H, d_h;             /* D == H * d_h */
+  int32_t D, H, d_h;             /* D == H * d_h; d_h a multiple of 4, at most 128 (prefill: at most 64) */
   int32_t n_layers;              /* blocks per module */
   int32_t d_ff;                  /* SwiGLU width, 0 = attention-only blocks */
   int32_t vocab;
@@ -222,7 +231,7 @@ typedef struct photon_weights {
 } photon_weights;
 
 typedef struct photon_state {
-  void* k_cache;        /* [n_layers, Bt, H, S_max, d_h] dt : KV^(L) */
+  void* k_cache;        /* [n_layers, Bt, H, S_max, photon_kv_row_elems(d_h)] dt : KV^(L) */
   void* v_cache;
   int32_t* seq_len;     /* [Bt] entries cached per sequence; the step adds 1.  Must be < S_max on entry. */
   float* x_top;         /* [Bt, D]       X^(L)_g, replaced by X^(L)_{g+1} */
@@ -272,8 +281,12 @@ PHOTON_API int32_t photon_decode_step(const photon_config* cfg, const photon_wei
  * Levels >= 2 need C_l >= 2.  Everything is enqueued on `stream`.
  * -------------------------------------------------------------------------- */
 typedef struct photon_encoder_weights {
-  const void* E_enc;                            /* [vocab, D] dt: encoder-side embedding table */
-  const void* chunker_w[PHOTON_MAX_LEVELS];     /* index l-1: chunker of level l, [D, C_l * D] dt */
+  const void* E_enc;                            /* [vocab, D] dt: encoder-side embedding table ([vocab, D / C_1] when
+                                                   chunker_w[0] is NULL) */
+  const void* chunker_w[PHOTON_MAX_LEVELS];     /* index l-1: chunker of level l, [D, C_l * D] dt.  chunker_w[0] may be
+                                                   NULL when L >= 2: the parameter-free concatenation of the paper's
+                                                   models (Appendix tables, "Ctx Chunker (block=4, concatenate)"):
+                                                   A^(1)_g is the C_1 embeddings of its tokens side by side */
   const float* chunker_b[PHOTON_MAX_LEVELS];    /* [D] fp32 or NULL */
   photon_module_weights enc[PHOTON_MAX_LEVELS]; /* index l-1: encoder module of level l (enc[L-1] = photon_weights.top) */
   const float* x0[PHOTON_MAX_LEVELS];           /* index l-1: start latent of the level-l decoder, [D] fp32 */
@@ -282,7 +295,7 @@ typedef struct photon_encoder_weights {
 /* Encoder streams of the levels below the top, kept only by hierarchical
  * generation (Appendix A, Definition 1): index l-1 for level l = 1 .. L-1. */
 typedef struct photon_hier_state {
-  void* k_cache[PHOTON_MAX_LEVELS];     /* [n_layers, Bt, H, S_cap[l-1], d_h] dt: K/V of the level-l encoder */
+  void* k_cache[PHOTON_MAX_LEVELS];     /* [n_layers, Bt, H, S_cap[l-1], photon_kv_row_elems(d_h)] dt: K/V of the level-l encoder */
   void* v_cache[PHOTON_MAX_LEVELS];
   int32_t* seq_len[PHOTON_MAX_LEVELS];  /* [Bt] units cached per sequence at level l */
   int64_t S_cap[PHOTON_MAX_LEVELS];     /* capacity per sequence; a step appends prod(C_{l+1..L}) units */

@@ -40,6 +40,8 @@ def weights_to_f64(w):
         return {k: weights_to_f64(v) for k, v in w.items()}
     if isinstance(w, (list, tuple)):
         return [weights_to_f64(v) for v in w]
+    if w is None:                       # a chunker without a matrix (parameter-free concatenation)
+        return None
     return f64(w)
 
 
@@ -509,12 +511,12 @@ def hier_reencode(cfg, w, state, tokens, counters=None):
     X^(L-1) [Bt, C_L, D] of the new meta-context."""
     tokens = np.asarray(tokens)
     Bt = tokens.shape[0]
-    x = f64(w["E_enc"])[tokens]                                   # [Bt, prod(C), D]
+    x = f64(w["E_enc"])[tokens]                                   # [Bt, prod(C), D]  (D / C_1 wide under a concatenating level-1 chunker)
     for l in range(1, cfg.L):
         e = w["enc"][l - 1]
         C = cfg.C[l - 1]
         n = x.shape[1] // C
-        a = chunker_project(x.reshape(Bt * n * C, cfg.D), e["chunker"]["w"], e["chunker"].get("b"), C).reshape(Bt, n, cfg.D)
+        a = chunker_project(x.reshape(Bt * n * C, x.shape[-1]), e["chunker"]["w"], e["chunker"].get("b"), C).reshape(Bt, n, cfg.D)
         caches = [(state["enc_k"][l - 1][i], state["enc_v"][l - 1][i]) for i in range(cfg.n_layers)]
         out = np.empty((Bt, n, cfg.D), F64)
         for j in range(n):

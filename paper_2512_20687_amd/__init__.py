@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     PhotonState,
     lib_path,
     load_library,
+    pad_kv_rows,
     photon_chunk_local_attn,
     photon_chunker_project,
     photon_coarse_decode_attn,
@@ -25,6 +26,7 @@ from .binding import (  # noqa: F401
     photon_decode_step_workspace_bytes,
     photon_hbm_read_probe,
     photon_hiergen_step,
+    photon_kv_row_elems,
     photon_last_error,
     photon_linear,
     photon_prefill,

@@ -97,6 +97,26 @@ def photon_chunker_project(x, w, bias, out, C_: int):
     return out
 
 
+def photon_kv_row_elems(d_h: int) -> int:
+    """Elements of one K/V cache row for head size d_h (d_h rounded up to 32, 64 or 128)."""
+    lib = load_library()
+    lib.photon_kv_row_elems.argtypes = [C.c_int32]
+    lib.photon_kv_row_elems.restype = C.c_int32
+    n = int(lib.photon_kv_row_elems(d_h))
+    if n == 0:
+        raise PhotonError(-1, f"head size {d_h} is outside [1, 128]")
+    return n
+
+
+def pad_kv_rows(t: torch.Tensor, d_h: int) -> torch.Tensor:
+    """[..., d_h] -> [..., photon_kv_row_elems(d_h)] with zeros in the added columns (the library's cache row layout)."""
+    d_p = photon_kv_row_elems(d_h)
+    if t.shape[-1] == d_p:
+        return t.contiguous()
+    assert t.shape[-1] == d_h, (t.shape, d_h)
+    return torch.nn.functional.pad(t, (0, d_p - d_h)).contiguous()
+
+
 def photon_coarse_decode_attn_workspace_bytes(Bt: int, H: int, d_h: int, n_splits: int) -> int:
     return load_library().photon_coarse_decode_attn_workspace_bytes(Bt, H, d_h, n_splits)
 
@@ -107,9 +127,13 @@ def photon_coarse_decode_attn_auto_splits(Bt: int, H: int, S_max: int) -> int:
 
 def photon_coarse_decode_attn(q, k_cache, v_cache, seq_len, out, scale: Optional[float] = None,
                               n_splits: int = 0, workspace: Optional[torch.Tensor] = None):
-    """q, out [Bt, H, d_h]; k_cache, v_cache [Bt, H, S_max, d_h]; seq_len int32 [Bt] (device)."""
+    """q, out [Bt, H, d_h]; k_cache, v_cache [Bt, H, S_max, photon_kv_row_elems(d_h)] (see pad_kv_rows);
+    seq_len int32 [Bt] (device)."""
     lib = load_library()
-    Bt, H, S_max, d_h = k_cache.shape
+    Bt, H, S_max, d_p = k_cache.shape
+    d_h = int(q.shape[-1])
+    if d_p != photon_kv_row_elems(d_h) or tuple(v_cache.shape) != tuple(k_cache.shape):
+        raise PhotonError(-1, f"cache rows hold {d_p} elements, head size {d_h} needs {photon_kv_row_elems(d_h)}")
     if scale is None:
         scale = 1.0 / math.sqrt(d_h)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
@@ -139,7 +163,8 @@ def photon_encoder_attn_workspace_bytes(Bt: int, M: int, H: int, d_h: int, bf16:
 
 def photon_encoder_attn(qkv, out, Bt: int, M: int, H: int, d_h: int, rope_theta: float = 10000.0, scale: Optional[float] = None,
                         k_cache=None, v_cache=None, workspace=None, bf16: bool = True):
-    """qkv fp32 [Bt*M, 3*H*d_h] -> out fp32 [Bt*M, H*d_h]; caches [Bt, H, S_max, d_h] (bf16 or fp32 per `bf16`)."""
+    """qkv fp32 [Bt*M, 3*H*d_h] -> out fp32 [Bt*M, H*d_h]; caches [Bt, H, S_max, photon_kv_row_elems(d_h)]
+    (bf16 or fp32 per `bf16`)."""
     lib = load_library()
     lib.photon_encoder_attn.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_float, C.c_float,
                                         C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]
@@ -147,6 +172,8 @@ def photon_encoder_attn(qkv, out, Bt: int, M: int, H: int, d_h: int, rope_theta:
     if scale is None:
         scale = 1.0 / math.sqrt(d_h)
     S_max = int(k_cache.shape[2]) if k_cache is not None else 0
+    if k_cache is not None and (k_cache.shape[-1] != photon_kv_row_elems(d_h) or tuple(v_cache.shape) != tuple(k_cache.shape)):
+        raise PhotonError(-1, f"cache rows hold {k_cache.shape[-1]} elements, head size {d_h} needs {photon_kv_row_elems(d_h)}")
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.photon_encoder_attn(_ptr(qkv), _ptr(out), Bt, M, H, d_h, rope_theta, scale, _ptr(k_cache), _ptr(v_cache), S_max,
                                    _ptr(workspace), ws_bytes, 1 if bf16 else 0, _stream()))
@@ -298,8 +325,9 @@ class PhotonModel:
             ew.E_enc = self._mat(weights["E_enc"])
             for l in range(cfg.L):
                 enc = weights["enc"][l]
-                ew.chunker_w[l] = self._mat(enc["chunker"]["w"])
-                ew.chunker_b[l] = self._vec(enc["chunker"]["b"]) if "b" in enc["chunker"] else None
+                cw = enc["chunker"]["w"]                 # None: parameter-free concatenation (level 1 only)
+                ew.chunker_w[l] = self._mat(cw) if cw is not None else None
+                ew.chunker_b[l] = self._vec(enc["chunker"]["b"]) if enc["chunker"].get("b") is not None else None
                 self._fill_module(ew.enc[l], enc["module"])
                 ew.x0[l] = self._vec(weights["dec"][l]["x0"])
             self.c_encoder_weights = ew
@@ -347,13 +375,17 @@ class PhotonState:
         lib = load_library()
         _register_step(lib)
         self.model, self.Bt, self.S_max = model, Bt, S_max
-        shape = (cfg.n_layers, Bt, cfg.H, S_max, cfg.d_h)
+        # cache rows hold photon_kv_row_elems(d_h) elements; a cache given with rows of d_h is zero-padded
+        shape = (cfg.n_layers, Bt, cfg.H, S_max, photon_kv_row_elems(cfg.d_h))
 
         def put(a, dtype, shp):
             if a is None:
                 return torch.zeros(shp, dtype=dtype, device=dev)
             t = a if isinstance(a, torch.Tensor) else torch.from_numpy(np_contig(a))
-            t = t.to(device=dev, dtype=dtype).contiguous()
+            t = t.to(device=dev, dtype=dtype)
+            if len(shp) == 5:
+                t = pad_kv_rows(t, cfg.d_h)
+            t = t.contiguous()
             assert tuple(t.shape) == tuple(shp), (t.shape, shp)
             return t
 
@@ -376,7 +408,7 @@ class PhotonState:
 
 class PhotonHierState:
     """Encoder streams of the levels below the top (hierarchical generation only): per level l = 1..L-1 a K/V
-    cache [n_layers, Bt, H, S_cap_l, d_h] and the per-sequence unit counts.  S_cap_l = S_max * prod(C_{l+1..L})."""
+    cache [n_layers, Bt, H, S_cap_l, photon_kv_row_elems(d_h)] and the per-sequence unit counts.  S_cap_l = S_max * prod(C_{l+1..L})."""
 
     def __init__(self, model: PhotonModel, Bt: int, S_max: int, k=None, v=None, seq_len=None):
         cfg, dev = model.cfg, model.device
@@ -388,13 +420,16 @@ class PhotonHierState:
             caps[l] = cap
             cap *= cfg.C[l - 1]
         for l in range(1, cfg.L):
-            shape = (cfg.n_layers, Bt, cfg.H, caps[l], cfg.d_h)
+            shape = (cfg.n_layers, Bt, cfg.H, caps[l], photon_kv_row_elems(cfg.d_h))
 
             def put(a, dtype, shp):
                 if a is None:
                     return torch.zeros(shp, dtype=dtype, device=dev)
                 t = a if isinstance(a, torch.Tensor) else torch.from_numpy(np_contig(a))
-                t = t.to(device=dev, dtype=dtype).contiguous()
+                t = t.to(device=dev, dtype=dtype)
+                if len(shp) == 5:
+                    t = pad_kv_rows(t, cfg.d_h)
+                t = t.contiguous()
                 assert tuple(t.shape) == tuple(shp), (t.shape, shp)
                 return t
 

@@ -8,7 +8,11 @@ namespace photon {
 
 enum KvType { KV_F32 = 0, KV_BF16 = 1 };
 
-// q/out are fp32 when q_f32 (always the case for KV_F32), else bf16.
+// Elements of one K/V cache row: the head size rounded up to 32, 64 or 128 (columns past d_h hold zeros); 0 = unsupported.
+inline int kv_row_elems(int d_h) { return d_h < 1 ? 0 : d_h <= 32 ? 32 : d_h <= 64 ? 64 : d_h <= 128 ? 128 : 0; }
+
+// q/out are fp32 when q_f32 (always the case for KV_F32), else bf16; rows of d_h elements.  Cache rows hold
+// kv_row_elems(d_h) elements.
 int32_t launch_coarse_attn(KvType kv, bool q_f32, int d_h, const void* q, const void* kc, const void* vc,
                            const int32_t* seq_len, void* out, int Bt, int H, int64_t S_max, float scale,
                            int n_splits, void* ws, hipStream_t st);

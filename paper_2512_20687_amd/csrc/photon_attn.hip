@@ -40,11 +40,13 @@ template <int VEC> struct SoftState {
 };
 
 // COARSE_WAVES waves per workgroup; U 16-byte K loads (and as many V loads) in flight per lane and register buffer.
+// DH: elements of a cache row (32, 64 or 128); d_h <= DH: head size, the row length of q and out.  Cache columns
+// d_h .. DH-1 hold zeros and meet zero query elements.
 template <typename TKV, typename TQ, int DH, int COARSE_WAVES, int U>
 __global__ __launch_bounds__(COARSE_WAVES * 64) void coarse_attn_kernel(
     const TQ* __restrict__ q, const TKV* __restrict__ kc, const TKV* __restrict__ vc,
     const int32_t* __restrict__ seq_len, TQ* __restrict__ out, float* __restrict__ ws,
-    int H, int64_t S_max, float scale_log2e, int n_splits) {
+    int H, int d_h, int64_t S_max, float scale_log2e, int n_splits) {
   using M = RowMap<TKV, DH>;
   constexpr int VEC = M::VEC, LPR = M::LPR, RPW = M::RPW;
   constexpr int TILE = RPW * U;                       // keys one wave consumes per buffer
@@ -65,7 +67,7 @@ __global__ __launch_bounds__(COARSE_WAVES * 64) void coarse_attn_kernel(
   // the query is fetched first but only converted after the first K/V slab is in flight
   TQ qraw[VEC];
 #pragma unroll
-  for (int i = 0; i < VEC; ++i) qraw[i] = q[(int64_t)bh * DH + c * VEC + i];
+  for (int i = 0; i < VEC; ++i) qraw[i] = c * VEC + i < d_h ? q[(int64_t)bh * d_h + c * VEC + i] : TQ{};
   float qf[VEC];
 
   const TKV* kb = kc + (int64_t)bh * S_max * DH + c * VEC;
@@ -171,7 +173,7 @@ __global__ __launch_bounds__(COARSE_WAVES * 64) void coarse_attn_kernel(
       o = fmaf(so[w][tid], a, o);
     }
     if (n_splits == 1) {
-      out[(int64_t)bh * DH + tid] = from_f32<TQ>(l > 0.f ? o / l : 0.f);
+      if (tid < d_h) out[(int64_t)bh * d_h + tid] = from_f32<TQ>(l > 0.f ? o / l : 0.f);
     } else {
       float* p = ws + ((int64_t)bh * n_splits + split) * (DH + 2);
       if (tid == 0) { p[0] = mm; p[1] = l; }
@@ -182,7 +184,7 @@ __global__ __launch_bounds__(COARSE_WAVES * 64) void coarse_attn_kernel(
 
 // Merge the split partials of one (b, h) stream in split order.
 template <typename TQ, int DH>
-__global__ __launch_bounds__(DH) void coarse_merge_kernel(const float* __restrict__ ws, TQ* __restrict__ out, int n_splits) {
+__global__ __launch_bounds__(DH) void coarse_merge_kernel(const float* __restrict__ ws, TQ* __restrict__ out, int n_splits, int d_h) {
   const int bh = blockIdx.x, d = threadIdx.x;
   const float* p = ws + (int64_t)bh * n_splits * (DH + 2);
   float mm = NEG_BIG;
@@ -193,38 +195,38 @@ __global__ __launch_bounds__(DH) void coarse_merge_kernel(const float* __restric
     l = fmaf(p[s * (DH + 2) + 1], a, l);
     o = fmaf(p[s * (DH + 2) + 2 + d], a, o);
   }
-  out[(int64_t)bh * DH + d] = from_f32<TQ>(l > 0.f ? o / l : 0.f);
+  if (d < d_h) out[(int64_t)bh * d_h + d] = from_f32<TQ>(l > 0.f ? o / l : 0.f);
 }
 
 template <typename TKV, typename TQ, int DH, int WAVES, int U>
 static int32_t launch_coarse_v(const void* q, const void* kc, const void* vc, const int32_t* seq_len, void* out,
-                               int Bt, int H, int64_t S_max, float scale, int n_splits, void* ws, hipStream_t st) {
+                               int Bt, int H, int d_h, int64_t S_max, float scale, int n_splits, void* ws, hipStream_t st) {
   dim3 grid(n_splits, Bt * H);
   PHOTON_LAUNCH(KC_COARSE_ATTN, st, (coarse_attn_kernel<TKV, TQ, DH, WAVES, U>), grid, dim3(WAVES * 64), 0, st,
-                     (const TQ*)q, (const TKV*)kc, (const TKV*)vc, seq_len, (TQ*)out, (float*)ws, H, S_max,
+                     (const TQ*)q, (const TKV*)kc, (const TKV*)vc, seq_len, (TQ*)out, (float*)ws, H, d_h, S_max,
                      scale * LOG2E, n_splits);
   int32_t rc = check_launch("coarse_attn_kernel");
   if (rc != PHOTON_OK || n_splits == 1) return rc;
-  PHOTON_LAUNCH(KC_COARSE_MERGE, st, (coarse_merge_kernel<TQ, DH>), dim3(Bt * H), dim3(DH), 0, st, (const float*)ws, (TQ*)out, n_splits);
+  PHOTON_LAUNCH(KC_COARSE_MERGE, st, (coarse_merge_kernel<TQ, DH>), dim3(Bt * H), dim3(DH), 0, st, (const float*)ws, (TQ*)out, n_splits, d_h);
   return check_launch("coarse_merge_kernel");
 }
 
 template <typename TKV, typename TQ, int DH>
 static int32_t launch_coarse_t(const void* q, const void* kc, const void* vc, const int32_t* seq_len, void* out,
-                               int Bt, int H, int64_t S_max, float scale, int n_splits, void* ws, hipStream_t st) {
-  return launch_coarse_v<TKV, TQ, DH, COARSE_WAVES_PER_WG, COARSE_UNROLL>(q, kc, vc, seq_len, out, Bt, H, S_max, scale,
+                               int Bt, int H, int d_h, int64_t S_max, float scale, int n_splits, void* ws, hipStream_t st) {
+  return launch_coarse_v<TKV, TQ, DH, COARSE_WAVES_PER_WG, COARSE_UNROLL>(q, kc, vc, seq_len, out, Bt, H, d_h, S_max, scale,
                                                                           n_splits, ws, st);
 }
 
 template <typename TKV, typename TQ>
 static int32_t launch_coarse_dh(int d_h, const void* q, const void* kc, const void* vc, const int32_t* seq_len, void* out,
                                 int Bt, int H, int64_t S_max, float scale, int n_splits, void* ws, hipStream_t st) {
-  switch (d_h) {
-    case 32: return launch_coarse_t<TKV, TQ, 32>(q, kc, vc, seq_len, out, Bt, H, S_max, scale, n_splits, ws, st);
-    case 64: return launch_coarse_t<TKV, TQ, 64>(q, kc, vc, seq_len, out, Bt, H, S_max, scale, n_splits, ws, st);
-    case 128: return launch_coarse_t<TKV, TQ, 128>(q, kc, vc, seq_len, out, Bt, H, S_max, scale, n_splits, ws, st);
+  switch (kv_row_elems(d_h)) {
+    case 32: return launch_coarse_t<TKV, TQ, 32>(q, kc, vc, seq_len, out, Bt, H, d_h, S_max, scale, n_splits, ws, st);
+    case 64: return launch_coarse_t<TKV, TQ, 64>(q, kc, vc, seq_len, out, Bt, H, d_h, S_max, scale, n_splits, ws, st);
+    case 128: return launch_coarse_t<TKV, TQ, 128>(q, kc, vc, seq_len, out, Bt, H, d_h, S_max, scale, n_splits, ws, st);
   }
-  return fail(PHOTON_ERR_UNSUPPORTED, "coarse attention: d_h=%d not in {32, 64, 128}", d_h);
+  return fail(PHOTON_ERR_UNSUPPORTED, "coarse attention: d_h=%d not in [1, 128]", d_h);
 }
 
 int32_t launch_coarse_attn(KvType kv, bool q_f32, int d_h, const void* q, const void* kc, const void* vc,
@@ -256,11 +258,12 @@ constexpr int LOCAL_THREADS = 256;
 
 // One lane group owns one (chunk, head) unit: it holds the unit's NK key and
 // value rows in registers and walks over the query rows.  TILE: q_len == NK and
-// q_pos == 0, fully unrolled.
+// q_pos == 0, fully unrolled.  DH: lanes * elements per lane of a group (32, 64, 128); d_h <= DH: head size (a
+// multiple of the 16-byte lane chunk); lanes past d_h carry zero queries and store nothing.
 template <typename T, int DH, int NK, bool TILE>
 __global__ __launch_bounds__(LOCAL_THREADS) void local_attn_kernel(
     const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, T* __restrict__ out,
-    int64_t n_units, int H, int W, int q_len_rt, int q_pos_rt, float scale_log2e) {
+    int64_t n_units, int H, int d_h, int W, int q_len_rt, int q_pos_rt, float scale_log2e) {
   using M = RowMap<T, DH>;
   constexpr int VEC = M::VEC, LPR = M::LPR, UPW = M::RPW;
   const int lane = threadIdx.x & 63;
@@ -270,25 +273,27 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_attn_kernel(
   unit = live ? unit : n_units - 1;
   const int64_t chunk = unit / H;
   const int h = (int)(unit % H);
-  const int col = (lane % LPR) * VEC;
+  const bool col_live = (lane % LPR) * VEC < d_h;
+  const int col = col_live ? (lane % LPR) * VEC : 0;               // surplus lanes repeat column 0 (in bounds)
   const int q_len = TILE ? NK : q_len_rt;
   const int q_pos = TILE ? 0 : q_pos_rt;
-  const int64_t row = (int64_t)H * DH;
+  const int64_t row = (int64_t)H * d_h;
 
-  const T* kp = k + (chunk * W * H + h) * DH + col;
-  const T* vp = v + (chunk * W * H + h) * DH + col;
+  const T* kp = k + (chunk * W * H + h) * d_h + col;
+  const T* vp = v + (chunk * W * H + h) * d_h + col;
   uint4_t kr[NK], vr[NK];
 #pragma unroll
   for (int j = 0; j < NK; ++j) { kr[j] = load16_stream(kp + j * row); vr[j] = load16_stream(vp + j * row); }
 
-  const T* qp = q + (chunk * q_len * H + h) * DH + col;
-  T* op = out + (chunk * q_len * H + h) * DH + col;
+  const T* qp = q + (chunk * q_len * H + h) * d_h + col;
+  T* op = out + (chunk * q_len * H + h) * d_h + col;
+  const float q_mul = col_live ? scale_log2e : 0.f;
 
   auto one_query = [&](int i, int nvis) {
     float qf[VEC];
     unpack16<T>(load16_stream(qp + i * row), qf);
 #pragma unroll
-    for (int t = 0; t < VEC; ++t) qf[t] *= scale_log2e;
+    for (int t = 0; t < VEC; ++t) qf[t] *= q_mul;
     float s[NK];
     float mx = NEG_BIG;
 #pragma unroll
@@ -320,7 +325,7 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_attn_kernel(
     const float inv = 1.f / l;
 #pragma unroll
     for (int t = 0; t < VEC; ++t) o[t] *= inv;
-    if (live) Vec16<T>::store(op + i * row, o);
+    if (live && col_live) Vec16<T>::store(op + i * row, o);
   };
 
   if (TILE) {
@@ -335,30 +340,41 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_attn_kernel(
 // q_pos .. q_pos+q_len-1) take q, k, v from the QKV projection output, apply the rotary encoding at
 // the window position, append k and v to the chunk's local cache, and attend causally over the window
 // so far.  One lane group per (chunk, head); the window (<= 16 rows) lives in registers.  fp32.
-template <int DH, int NK>
+// DH: 4 * lanes of a group.  PAD: the head size d_h is smaller than DH (a multiple of 4): surplus lanes carry
+// zeros, and the rotary partner of an element (d_h/2 away, in general not a whole number of lanes) is read from
+// memory instead of from a neighbour lane.
+template <int DH, int NK, bool PAD>
 __global__ __launch_bounds__(LOCAL_THREADS) void local_step_attn_kernel(
     const float* __restrict__ qkv, float* __restrict__ lk, float* __restrict__ lv, float* __restrict__ out,
-    int64_t n_units, int H, int W, int q_len, int q_pos, float scale_log2e, float theta) {
-  constexpr int VEC = 4, LPR = DH / 4, UPW = 64 / LPR, HALF = DH / 2;
+    int64_t n_units, int H, int d_h_rt, int W, int q_len, int q_pos, float scale_log2e, float theta) {
+  constexpr int VEC = 4, LPR = DH / 4, UPW = 64 / LPR;
+  const int d_h = PAD ? d_h_rt : DH;
+  const int half = d_h / 2;
   const int lane = threadIdx.x & 63;
   const int64_t wave = (int64_t)blockIdx.x * (LOCAL_THREADS / 64) + (threadIdx.x >> 6);
   int64_t unit = wave * UPW + lane / LPR;
-  const bool live = unit < n_units;
-  unit = live ? unit : n_units - 1;
+  const bool unit_live = unit < n_units;
+  unit = unit_live ? unit : n_units - 1;
   const int64_t chunk = unit / H;
   const int h = (int)(unit % H);
-  const int col = (lane % LPR) * VEC;
-  const int D = H * DH;
-  const bool upper = col >= HALF;                            // this lane holds elements i + d_h/2 of the rotary pairs
+  const bool col_live = (lane % LPR) * VEC < d_h;
+  const int col = col_live ? (lane % LPR) * VEC : 0;         // surplus lanes repeat column 0 (in bounds, never stored)
+  const bool live = unit_live && col_live;
+  const int D = H * d_h;
 
   float inv_freq[VEC];
+  bool upper[VEC];                                           // this element is the i + d_h/2 member of its rotary pair
+  int partner[VEC];
 #pragma unroll
-  for (int t = 0; t < VEC; ++t)
-    inv_freq[t] = theta == 0.f ? 0.f : (float)exp2(-2.0 * (double)((col + t) % HALF) / (double)DH * log2((double)theta));
+  for (int t = 0; t < VEC; ++t) {
+    upper[t] = col + t >= half;
+    partner[t] = upper[t] ? col + t - half : col + t + half;
+    inv_freq[t] = theta == 0.f ? 0.f : (float)exp2(-2.0 * (double)((col + t) % half) / (double)d_h * log2((double)theta));
+  }
 
   float4_t kr[NK], vr[NK];
-  float* kcache = lk + (chunk * W * H + h) * DH + col;
-  float* vcache = lv + (chunk * W * H + h) * DH + col;
+  float* kcache = lk + (chunk * W * H + h) * d_h + col;
+  float* vcache = lv + (chunk * W * H + h) * d_h + col;
 #pragma unroll
   for (int j = 0; j < NK; ++j) {
     if (j < q_pos) {
@@ -370,19 +386,27 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_step_attn_kernel(
   for (int j = 0; j < NK; ++j) {
     if (j >= q_pos) {
       const int64_t row = chunk * q_len + (j - q_pos);
-      const float* src = qkv + row * 3 * D + h * DH + col;
+      const float* head = qkv + row * 3 * D + h * d_h;
+      const float* src = head + col;
       float4_t q4 = *reinterpret_cast<const float4_t*>(src);
       float4_t k4 = *reinterpret_cast<const float4_t*>(src + D);
       const float4_t v4 = *reinterpret_cast<const float4_t*>(src + 2 * D);
-      // rotary: out[i] = x[i] c - x[i+h] s ; out[i+h] = x[i+h] c + x[i] s ; the partner sits LPR/2 lanes away
+      // rotary: out[i] = x[i] c - x[i+h] s ; out[i+h] = x[i+h] c + x[i] s
       float qa[VEC] = {q4.x, q4.y, q4.z, q4.w}, ka[VEC] = {k4.x, k4.y, k4.z, k4.w};
 #pragma unroll
       for (int t = 0; t < VEC; ++t) {
-        const float qb = __shfl_xor(qa[t], LPR / 2), kb = __shfl_xor(ka[t], LPR / 2);
+        float qb, kb;
+        if (PAD) {
+          qb = head[partner[t]];
+          kb = head[D + partner[t]];
+        } else {                                             // the partner sits LPR/2 lanes away
+          qb = __shfl_xor(qa[t], LPR / 2);
+          kb = __shfl_xor(ka[t], LPR / 2);
+        }
         double sd, cd;
         sincos((double)j * (double)inv_freq[t], &sd, &cd);
-        const float c = (float)cd, sn = upper ? (float)sd : -(float)sd;
-        qa[t] = qa[t] * c + qb * sn;
+        const float c = (float)cd, sn = upper[t] ? (float)sd : -(float)sd;
+        qa[t] = col_live ? qa[t] * c + qb * sn : 0.f;
         ka[t] = ka[t] * c + kb * sn;
       }
       kr[j] = float4_t{ka[0], ka[1], ka[2], ka[3]};
@@ -411,22 +435,22 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_step_attn_kernel(
         o += pw * vr[jj];
       }
       o *= (1.f / l);
-      if (live) *reinterpret_cast<float4_t*>(out + row * D + h * DH + col) = o;
+      if (live) *reinterpret_cast<float4_t*>(out + row * D + h * d_h + col) = o;
     }
   }
 }
 
-template <int DH>
+template <int DH, bool PAD>
 static int32_t launch_local_step_dh(const float* qkv, float* lk, float* lv, float* out, int64_t n_chunks, int W, int q_len,
-                                    int q_pos, int H, float scale, float theta, hipStream_t st) {
+                                    int q_pos, int H, int d_h, float scale, float theta, hipStream_t st) {
   const int64_t n_units = n_chunks * H;
   const int64_t units_per_block = (int64_t)(64 / (DH / 4)) * (LOCAL_THREADS / 64);
   const int64_t blocks = (n_units + units_per_block - 1) / units_per_block;
   if (blocks > 0x7fffffffLL) return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: too many chunks for one launch");
 #define PHOTON_LS_CASE(N)                                                                                                   \
   case N:                                                                                                                   \
-    PHOTON_LAUNCH(KC_LOCAL_ATTN, st, (local_step_attn_kernel<DH, N>), dim3((unsigned)blocks), dim3(LOCAL_THREADS), 0, st, qkv, lk, \
-                  lv, out, n_units, H, W, q_len, q_pos, scale * LOG2E, theta);                                             \
+    PHOTON_LAUNCH(KC_LOCAL_ATTN, st, (local_step_attn_kernel<DH, N, PAD>), dim3((unsigned)blocks), dim3(LOCAL_THREADS), 0, st, qkv, \
+                  lk, lv, out, n_units, H, d_h, W, q_len, q_pos, scale * LOG2E, theta);                                    \
     break;
   switch (q_pos + q_len) {
     PHOTON_LS_CASE(1) PHOTON_LS_CASE(2) PHOTON_LS_CASE(3) PHOTON_LS_CASE(4)
@@ -441,17 +465,23 @@ static int32_t launch_local_step_dh(const float* qkv, float* lk, float* lv, floa
 
 int32_t launch_local_step_attn(int d_h, const float* qkv, float* lk, float* lv, float* out, int64_t n_chunks, int W, int q_len,
                                int q_pos, int H, float scale, float theta, hipStream_t st) {
+  if (d_h % 4 != 0) return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: d_h=%d is not a multiple of 4", d_h);
   switch (d_h) {
-    case 32: return launch_local_step_dh<32>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, scale, theta, st);
-    case 64: return launch_local_step_dh<64>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, scale, theta, st);
-    case 128: return launch_local_step_dh<128>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, scale, theta, st);
+    case 32: return launch_local_step_dh<32, false>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, st);
+    case 64: return launch_local_step_dh<64, false>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, st);
+    case 128: return launch_local_step_dh<128, false>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, st);
   }
-  return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: d_h=%d not in {32, 64, 128}", d_h);
+  switch (kv_row_elems(d_h)) {
+    case 32: return launch_local_step_dh<32, true>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, st);
+    case 64: return launch_local_step_dh<64, true>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, st);
+    case 128: return launch_local_step_dh<128, true>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, st);
+  }
+  return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: d_h=%d not in [4, 128]", d_h);
 }
 
 template <typename T, int DH, int NK>
 static int32_t launch_local_nk(bool tile, const void* q, const void* k, const void* v, void* out, int64_t n_chunks,
-                               int W, int q_len, int q_pos, int H, float scale, hipStream_t st) {
+                               int W, int q_len, int q_pos, int H, int d_h, float scale, hipStream_t st) {
   using M = RowMap<T, DH>;
   const int64_t n_units = n_chunks * H;
   const int64_t units_per_block = (int64_t)M::RPW * (LOCAL_THREADS / 64);
@@ -459,20 +489,20 @@ static int32_t launch_local_nk(bool tile, const void* q, const void* k, const vo
   if (blocks > 0x7fffffffLL) return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: too many chunks for one launch");
   if (tile)
     PHOTON_LAUNCH(KC_LOCAL_ATTN, st, (local_attn_kernel<T, DH, NK, true>), dim3((unsigned)blocks), dim3(LOCAL_THREADS), 0, st,
-                       (const T*)q, (const T*)k, (const T*)v, (T*)out, n_units, H, W, q_len, q_pos, scale * LOG2E);
+                       (const T*)q, (const T*)k, (const T*)v, (T*)out, n_units, H, d_h, W, q_len, q_pos, scale * LOG2E);
   else
     PHOTON_LAUNCH(KC_LOCAL_ATTN, st, (local_attn_kernel<T, DH, NK, false>), dim3((unsigned)blocks), dim3(LOCAL_THREADS), 0, st,
-                       (const T*)q, (const T*)k, (const T*)v, (T*)out, n_units, H, W, q_len, q_pos, scale * LOG2E);
+                       (const T*)q, (const T*)k, (const T*)v, (T*)out, n_units, H, d_h, W, q_len, q_pos, scale * LOG2E);
   return check_launch("local_attn_kernel");
 }
 
 template <typename T, int DH>
 static int32_t launch_local_dh(const void* q, const void* k, const void* v, void* out, int64_t n_chunks,
-                               int W, int q_len, int q_pos, int H, float scale, hipStream_t st) {
+                               int W, int q_len, int q_pos, int H, int d_h, float scale, hipStream_t st) {
   const int nk = q_pos + q_len;
   const bool tile = (q_pos == 0);
 #define PHOTON_NK_CASE(N) \
-  case N: return launch_local_nk<T, DH, N>(tile, q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
+  case N: return launch_local_nk<T, DH, N>(tile, q, k, v, out, n_chunks, W, q_len, q_pos, H, d_h, scale, st);
   switch (nk) {
     PHOTON_NK_CASE(1) PHOTON_NK_CASE(2) PHOTON_NK_CASE(3) PHOTON_NK_CASE(4)
     PHOTON_NK_CASE(5) PHOTON_NK_CASE(6) PHOTON_NK_CASE(7) PHOTON_NK_CASE(8)
@@ -485,20 +515,22 @@ static int32_t launch_local_dh(const void* q, const void* k, const void* v, void
 
 int32_t launch_local_attn(bool f32, int d_h, const void* q, const void* k, const void* v, void* out,
                           int64_t n_chunks, int W, int q_len, int q_pos, int H, float scale, hipStream_t st) {
+  const int vec = f32 ? 4 : 8;                                // elements of a lane's 16-byte chunk
+  if (d_h < vec || d_h > 128 || d_h % vec != 0)
+    return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: d_h=%d must be a multiple of %d in [%d, 128]", d_h, vec, vec);
+  const int lanes = kv_row_elems(d_h);
   if (f32) {
-    switch (d_h) {
-      case 32: return launch_local_dh<float, 32>(q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
-      case 64: return launch_local_dh<float, 64>(q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
-      case 128: return launch_local_dh<float, 128>(q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
-    }
-  } else {
-    switch (d_h) {
-      case 32: return launch_local_dh<bf16_t, 32>(q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
-      case 64: return launch_local_dh<bf16_t, 64>(q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
-      case 128: return launch_local_dh<bf16_t, 128>(q, k, v, out, n_chunks, W, q_len, q_pos, H, scale, st);
+    switch (lanes) {
+      case 32: return launch_local_dh<float, 32>(q, k, v, out, n_chunks, W, q_len, q_pos, H, d_h, scale, st);
+      case 64: return launch_local_dh<float, 64>(q, k, v, out, n_chunks, W, q_len, q_pos, H, d_h, scale, st);
+      default: return launch_local_dh<float, 128>(q, k, v, out, n_chunks, W, q_len, q_pos, H, d_h, scale, st);
     }
   }
-  return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: d_h=%d not in {32, 64, 128}", d_h);
+  switch (lanes) {
+    case 32: return launch_local_dh<bf16_t, 32>(q, k, v, out, n_chunks, W, q_len, q_pos, H, d_h, scale, st);
+    case 64: return launch_local_dh<bf16_t, 64>(q, k, v, out, n_chunks, W, q_len, q_pos, H, d_h, scale, st);
+    default: return launch_local_dh<bf16_t, 128>(q, k, v, out, n_chunks, W, q_len, q_pos, H, d_h, scale, st);
+  }
 }
 
 }  // namespace photon
@@ -507,9 +539,11 @@ int32_t launch_local_attn(bool f32, int d_h, const void* q, const void* k, const
 
 using namespace photon;
 
+extern "C" int32_t photon_kv_row_elems(int32_t d_h) { return kv_row_elems(d_h); }
+
 extern "C" size_t photon_coarse_decode_attn_workspace_bytes(int32_t Bt, int32_t H, int32_t d_h, int32_t n_splits) {
-  if (Bt <= 0 || H <= 0 || d_h <= 0 || n_splits <= 1) return 0;
-  return (size_t)Bt * H * n_splits * (d_h + 2) * sizeof(float);
+  if (Bt <= 0 || H <= 0 || d_h <= 0 || d_h > 128 || n_splits <= 1) return 0;
+  return (size_t)Bt * H * n_splits * (kv_row_elems(d_h) + 2) * sizeof(float);
 }
 
 extern "C" int32_t photon_coarse_decode_attn_auto_splits(int32_t Bt, int32_t H, int64_t S_max) {
@@ -527,7 +561,7 @@ extern "C" int32_t photon_coarse_decode_attn(const void* q, const void* k_cache,
                  __func__, Bt, H, (long long)S_max);
   PHOTON_REQUIRE((int64_t)Bt * H <= 65535, PHOTON_ERR_UNSUPPORTED, "%s: Bt*H=%lld exceeds 65535 streams per launch",
                  __func__, (long long)Bt * H);
-  PHOTON_REQUIRE(d_h == 32 || d_h == 64 || d_h == 128, PHOTON_ERR_UNSUPPORTED, "%s: d_h=%d not in {32, 64, 128}", __func__, d_h);
+  PHOTON_REQUIRE(d_h >= 1 && d_h <= 128, PHOTON_ERR_UNSUPPORTED, "%s: d_h=%d not in [1, 128]", __func__, d_h);
   PHOTON_REQUIRE(n_splits >= 0 && n_splits <= 1024, PHOTON_ERR_INVALID_ARG, "%s: n_splits=%d out of [0, 1024]", __func__, n_splits);
   PHOTON_REQUIRE_PTR(q);
   PHOTON_REQUIRE_PTR(k_cache);
@@ -556,7 +590,11 @@ extern "C" int32_t photon_chunk_local_attn(const void* q, const void* k, const v
                  (int)PHOTON_MAX_WINDOW);
   PHOTON_REQUIRE(q_len >= 1 && q_pos >= 0 && q_pos + q_len <= W, PHOTON_ERR_INVALID_ARG,
                  "%s: queries [%d, %d) do not fit the window W=%d", __func__, q_pos, q_pos + q_len, W);
-  PHOTON_REQUIRE(d_h == 32 || d_h == 64 || d_h == 128, PHOTON_ERR_UNSUPPORTED, "%s: d_h=%d not in {32, 64, 128}", __func__, d_h);
+  {
+    const int vec = dt == PHOTON_F32 ? 4 : 8;
+    PHOTON_REQUIRE(d_h >= vec && d_h <= 128 && d_h % vec == 0, PHOTON_ERR_UNSUPPORTED,
+                   "%s: d_h=%d must be a multiple of %d in [%d, 128]", __func__, d_h, vec, vec);
+  }
   if (n_chunks == 0) return PHOTON_OK;
   PHOTON_REQUIRE_PTR(q);
   PHOTON_REQUIRE_PTR(k);

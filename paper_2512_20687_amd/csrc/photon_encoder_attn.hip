@@ -33,6 +33,7 @@
 // fp32 configuration: a plain fp32 tile kernel on the vector ALUs (small sizes).
 #include "photon_encoder_attn.h"
 
+#include "photon_attn.h"
 #include "photon_device.h"
 #include "photon_host.h"
 
@@ -69,15 +70,20 @@ __device__ __forceinline__ void split8(const float* x, uint4_t& hi, uint4_t& lo)
 
 // ---- row kernel: rotary + operand layout ----------------------------------------------------------
 // One workgroup = 64 positions of one (sequence, head).  Thread t: position t/4, quarter t%4 of the pairs
-// (pairs i = quarter*8 .. +8, elements i and i + 32).
+// (pairs i = quarter*8 .. +8).
 // Outputs (bf16): qh, ql, kh, kl [Bt*H][Mp][64] (Mp = M rounded up to 64; rows >= M are zero), vt [Bt*H][64][Mp];
 // q is multiplied by qscale (= softmax scale * log2 e) before the split.  kc / vc (optional): the layer's
-// coarse cache [Bt][H][S_max][64], positions 0..M-1, K rotated.
+// coarse cache [Bt][H][S_max][pitch], positions 0..M-1, K rotated.
+// PAD: head size d_h < 64 (a multiple of 4).  The operand rows stay 64 wide: of rotary pair i (i < d_h/2) the
+// first member sits in column i and the second in column 32 + i, for q and k alike (a score does not depend on
+// the order of the contraction index); V keeps its own column order, so the output columns are the head's; all
+// other columns are zero.
+template <bool PAD>
 __global__ __launch_bounds__(256) void encoder_rope_split_kernel(const float* __restrict__ qkv, bf16_t* __restrict__ qh,
                                                                  bf16_t* __restrict__ ql, bf16_t* __restrict__ kh,
                                                                  bf16_t* __restrict__ kl, bf16_t* __restrict__ vt,
                                                                  bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, int64_t M, int H,
-                                                                 int64_t S_max, float theta, float qscale) {
+                                                                 int d_h_rt, int pitch, int64_t S_max, float theta, float qscale) {
   __shared__ bf16_t vtile[64][64 + 2];                // [d][position], padded
   const int tid = threadIdx.x;
   const int bh = blockIdx.y, b = bh / H, h = bh % H;
@@ -85,29 +91,44 @@ __global__ __launch_bounds__(256) void encoder_rope_split_kernel(const float* __
   const int64_t p0 = (int64_t)blockIdx.x * 64;
   const int pl = tid >> 2, quarter = tid & 3;
   const int64_t pos = p0 + pl;
-  const int D = H * EA_DH;
+  const int d_h = PAD ? d_h_rt : EA_DH;
+  const int hr = d_h / 2;                             // distance between the members of a rotary pair
+  const int D = H * d_h;
   const bool live = pos < M;
-  float q[16], k[16], v[16];                          // elements quarter*8 .. +8, then 32 + quarter*8 .. +8
+  // q, k: [j] first and [8 + j] second member of pair quarter*8 + j; v: columns quarter*8 + j and 32 + quarter*8 + j
+  float q[16], k[16], v[16];
 #pragma unroll
   for (int e = 0; e < 16; ++e) q[e] = k[e] = v[e] = 0.f;
   if (live) {
-    const float* src = qkv + ((int64_t)b * M + pos) * 3 * D + h * EA_DH + quarter * 8;
+    const float* head = qkv + ((int64_t)b * M + pos) * 3 * D + h * d_h;
+    const float* src = head + quarter * 8;
 #pragma unroll
     for (int half = 0; half < 2; ++half)
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
-        const float4_t a = *reinterpret_cast<const float4_t*>(src + half * 32 + c * 4);
-        const float4_t kk = *reinterpret_cast<const float4_t*>(src + D + half * 32 + c * 4);
-        const float4_t vv = *reinterpret_cast<const float4_t*>(src + 2 * D + half * 32 + c * 4);
         const int e = half * 8 + c * 4;
-        q[e] = a.x; q[e + 1] = a.y; q[e + 2] = a.z; q[e + 3] = a.w;
-        k[e] = kk.x; k[e + 1] = kk.y; k[e + 2] = kk.z; k[e + 3] = kk.w;
-        v[e] = vv.x; v[e + 1] = vv.y; v[e + 2] = vv.z; v[e + 3] = vv.w;
+        if (!PAD) {
+          const float4_t a = *reinterpret_cast<const float4_t*>(src + half * 32 + c * 4);
+          const float4_t kk = *reinterpret_cast<const float4_t*>(src + D + half * 32 + c * 4);
+          q[e] = a.x; q[e + 1] = a.y; q[e + 2] = a.z; q[e + 3] = a.w;
+          k[e] = kk.x; k[e + 1] = kk.y; k[e + 2] = kk.z; k[e + 3] = kk.w;
+        }
+        if (!PAD || half * 32 + quarter * 8 + c * 4 < d_h) {
+          const float4_t vv = *reinterpret_cast<const float4_t*>(src + 2 * D + half * 32 + c * 4);
+          v[e] = vv.x; v[e + 1] = vv.y; v[e + 2] = vv.z; v[e + 3] = vv.w;
+        }
       }
+    if (PAD) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int i = quarter * 8 + j;
+        if (i < hr) { q[j] = head[i]; q[8 + j] = head[i + hr]; k[j] = head[D + i]; k[8 + j] = head[D + i + hr]; }
+      }
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       float c, s;
-      rope_angle((int)pos, quarter * 8 + j, EA_DH, theta, c, s);
+      rope_angle((int)pos, quarter * 8 + j, d_h, theta, c, s);
       const float qa = q[j], qb = q[8 + j], ka = k[j], kb = k[8 + j];
       q[j] = (qa * c - qb * s) * qscale; q[8 + j] = (qb * c + qa * s) * qscale;
       k[j] = ka * c - kb * s; k[8 + j] = kb * c + ka * s;
@@ -124,13 +145,24 @@ __global__ __launch_bounds__(256) void encoder_rope_split_kernel(const float* __
     *reinterpret_cast<uint4_t*>(ql + row + off) = l4;
     *reinterpret_cast<uint4_t*>(kh + row + off) = kh4;
     *reinterpret_cast<uint4_t*>(kl + row + off) = kl4;
-    if (kc != nullptr && live && pos < S_max) {
+    if (!PAD && kc != nullptr && live && pos < S_max) {
       uint4_t vv;
       vv.x = pack_bf16x2(v[half * 8 + 0], v[half * 8 + 1]); vv.y = pack_bf16x2(v[half * 8 + 2], v[half * 8 + 3]);
       vv.z = pack_bf16x2(v[half * 8 + 4], v[half * 8 + 5]); vv.w = pack_bf16x2(v[half * 8 + 6], v[half * 8 + 7]);
       const int64_t slot = (((int64_t)b * H + h) * S_max + pos) * EA_DH + off;
       *reinterpret_cast<uint4_t*>(kc + slot) = kh4;
       *reinterpret_cast<uint4_t*>(vc + slot) = vv;
+    }
+    if (PAD && kc != nullptr && live && pos < S_max) {  // cache rows in the head's own column order, zeros past d_h
+      const int64_t slot = (((int64_t)b * H + h) * S_max + pos) * pitch;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int i = quarter * 8 + j;
+        if (i < hr) kc[slot + half * hr + i] = from_f32<bf16_t>(k[half * 8 + j]);
+        const int col = half * 32 + i;
+        if (col < pitch) vc[slot + col] = from_f32<bf16_t>(v[half * 8 + j]);
+        if (col >= d_h && col < pitch) kc[slot + col] = bf16_t(0);
+      }
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) vtile[half * 32 + quarter * 8 + j][pl] = from_f32<bf16_t>(v[half * 8 + j]);
@@ -154,7 +186,7 @@ template <bool QK_SPLIT>
 __global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const bf16_t* __restrict__ qh, const bf16_t* __restrict__ ql,
                                                                        const bf16_t* __restrict__ kh, const bf16_t* __restrict__ kl,
                                                                        const bf16_t* __restrict__ vt, float* __restrict__ out, int64_t M,
-                                                                       int H, int n_qblocks) {
+                                                                       int H, int d_h, int n_qblocks) {
   extern __shared__ __align__(16) char lds[];         // [2 stages][K head | K remainder | V^T]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -350,14 +382,15 @@ __global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const bf1
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   if (qpos >= M) return;
   const float inv = 1.0f / l_tot;
-  float* dst = out + ((int64_t)b * M + qpos) * (H * EA_DH) + h * EA_DH;
+  float* dst = out + ((int64_t)b * M + qpos) * (H * d_h) + h * d_h;   // d_h <= 64: the columns past it are padding
 #pragma unroll
   for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
     for (int g4 = 0; g4 < 4; ++g4) {
       float4_t y;
       y.x = o[dt][g4 * 4 + 0] * inv; y.y = o[dt][g4 * 4 + 1] * inv; y.z = o[dt][g4 * 4 + 2] * inv; y.w = o[dt][g4 * 4 + 3] * inv;
-      *reinterpret_cast<float4_t*>(dst + dt * 32 + 8 * g4 + 4 * kg) = y;
+      const int col = dt * 32 + 8 * g4 + 4 * kg;
+      if (col < d_h) *reinterpret_cast<float4_t*>(dst + col) = y;
     }
 }
 
@@ -366,8 +399,8 @@ __global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const bf1
 // through LDS tiles of 32 keys (rotated as they are staged).
 template <int DH>
 __global__ __launch_bounds__(64) void encoder_attn_f32_kernel(const float* __restrict__ qkv, float* __restrict__ out, float* __restrict__ kc,
-                                                              float* __restrict__ vc, int64_t M, int H, int64_t S_max, float theta,
-                                                              float scale) {
+                                                              float* __restrict__ vc, int64_t M, int H, int pitch, int64_t S_max,
+                                                              float theta, float scale) {
   __shared__ float ks[32][DH + 1], vs[32][DH + 1];
   const int t = threadIdx.x;
   const int bh = blockIdx.y, b = bh / H, h = bh % H;
@@ -435,8 +468,9 @@ __global__ __launch_bounds__(64) void encoder_attn_f32_kernel(const float* __res
   for (int d = 0; d < DH; ++d) dst[d] = acc[d] * inv;
   if (kc != nullptr && qpos < S_max) {                // this thread's own position: rotated key and value into the cache
     const float* src = qkv + ((int64_t)b * M + qpos) * 3 * D + h * DH;
-    float* kd = kc + (((int64_t)b * H + h) * S_max + qpos) * DH;
-    float* vd = vc + (((int64_t)b * H + h) * S_max + qpos) * DH;
+    float* kd = kc + (((int64_t)b * H + h) * S_max + qpos) * pitch;   // cache rows hold pitch >= DH elements, zeros past DH
+    float* vd = vc + (((int64_t)b * H + h) * S_max + qpos) * pitch;
+    for (int p = DH; p < pitch; ++p) { kd[p] = 0.f; vd[p] = 0.f; }
 #pragma unroll
     for (int i = 0; i < half; ++i) {
       float c, s;
@@ -452,40 +486,57 @@ __global__ __launch_bounds__(64) void encoder_attn_f32_kernel(const float* __res
 
 size_t encoder_attn_workspace_bytes(int Bt, int64_t M, int H, int d_h, bool bf16) {
   if (!bf16) return 0;
-  return (size_t)5 * Bt * H * round_up64(M) * d_h * sizeof(bf16_t);   // q head, q remainder, k head, k remainder, V^T
+  (void)d_h;                                                           // the operand rows are 64 wide for every head size
+  return (size_t)5 * Bt * H * round_up64(M) * EA_DH * sizeof(bf16_t);  // q head, q remainder, k head, k remainder, V^T
 }
 
 int32_t launch_encoder_attn(const float* qkv, float* out, int Bt, int64_t M, int H, int d_h, float theta, float scale, void* k_cache,
                             void* v_cache, int64_t S_max, void* workspace, bool bf16, hipStream_t st) {
   if (Bt <= 0 || M <= 0) return PHOTON_OK;
   if ((int64_t)Bt * H > 65535) return fail(PHOTON_ERR_UNSUPPORTED, "encoder attention: Bt*H=%lld exceeds 65535", (long long)Bt * H);
+  const int pitch = kv_row_elems(d_h);
   if (!bf16) {
     dim3 grid((unsigned)((M + 63) / 64), Bt * H);
 #define PHOTON_EA_F32(DH)                                                                                                          \
     PHOTON_LAUNCH(KC_LOCAL_ATTN, st, encoder_attn_f32_kernel<DH>, grid, dim3(64), 0, st, qkv, out, (float*)k_cache, (float*)v_cache, M, H, \
-                  S_max, theta, scale)
+                  pitch, S_max, theta, scale)
     switch (d_h) {
       case 16: PHOTON_EA_F32(16); break;
+      case 20: PHOTON_EA_F32(20); break;
+      case 24: PHOTON_EA_F32(24); break;
+      case 28: PHOTON_EA_F32(28); break;
       case 32: PHOTON_EA_F32(32); break;
+      case 36: PHOTON_EA_F32(36); break;
+      case 40: PHOTON_EA_F32(40); break;
+      case 44: PHOTON_EA_F32(44); break;
+      case 48: PHOTON_EA_F32(48); break;
+      case 52: PHOTON_EA_F32(52); break;
+      case 56: PHOTON_EA_F32(56); break;
+      case 60: PHOTON_EA_F32(60); break;
       case 64: PHOTON_EA_F32(64); break;
-      default: return fail(PHOTON_ERR_UNSUPPORTED, "encoder attention (fp32): head size %d not in {16, 32, 64}", d_h);
+      default: return fail(PHOTON_ERR_UNSUPPORTED, "encoder attention (fp32): head size %d is not a multiple of 4 in [16, 64]", d_h);
     }
 #undef PHOTON_EA_F32
     return check_launch("encoder_attn_f32_kernel");
   }
-  if (d_h != EA_DH) return fail(PHOTON_ERR_UNSUPPORTED, "encoder attention (bf16): head size %d, only 64 is built", d_h);
+  if (d_h < 4 || d_h > EA_DH || d_h % 4 != 0)
+    return fail(PHOTON_ERR_UNSUPPORTED, "encoder attention (bf16): head size %d is not a multiple of 4 in [4, 64]", d_h);
   const int64_t Mp = round_up64(M);
   const size_t arr = (size_t)Bt * H * Mp * EA_DH;
   bf16_t* qh = reinterpret_cast<bf16_t*>(workspace);
   bf16_t *ql = qh + arr, *kh = ql + arr, *kl = kh + arr, *vt = kl + arr;
-  PHOTON_LAUNCH(KC_ROPE_APPEND, st, encoder_rope_split_kernel, dim3((unsigned)(Mp / 64), Bt * H), dim3(256), 0, st, qkv, qh, ql, kh, kl, vt,
-                (bf16_t*)k_cache, (bf16_t*)v_cache, M, H, S_max, theta, scale * LOG2E);
+  if (d_h == EA_DH)
+    PHOTON_LAUNCH(KC_ROPE_APPEND, st, encoder_rope_split_kernel<false>, dim3((unsigned)(Mp / 64), Bt * H), dim3(256), 0, st, qkv, qh, ql, kh,
+                  kl, vt, (bf16_t*)k_cache, (bf16_t*)v_cache, M, H, d_h, pitch, S_max, theta, scale * LOG2E);
+  else
+    PHOTON_LAUNCH(KC_ROPE_APPEND, st, encoder_rope_split_kernel<true>, dim3((unsigned)(Mp / 64), Bt * H), dim3(256), 0, st, qkv, qh, ql, kh,
+                  kl, vt, (bf16_t*)k_cache, (bf16_t*)v_cache, M, H, d_h, pitch, S_max, theta, scale * LOG2E);
   PHOTON_TRY(check_launch("encoder_rope_split_kernel"));
   const int n_qblocks = (int)((M + EA_BQ - 1) / EA_BQ);
   // Scores from head + remainder operands: with the heads alone the kernel is 1.4x faster, but its error grows with the
   // size of the scores (normalised output error 3e-3 at unit-variance q, k; 5e-2 at four times that), so it is not used.
   PHOTON_LAUNCH(KC_LOCAL_ATTN, st, encoder_attn_mfma_kernel<true>, dim3(n_qblocks, Bt * H), dim3(EA_THREADS), 2 * EA_STAGE, st, qh, ql, kh,
-                kl, vt, out, M, H, n_qblocks);
+                kl, vt, out, M, H, d_h, n_qblocks);
   return check_launch("encoder_attn_mfma_kernel");
 }
 

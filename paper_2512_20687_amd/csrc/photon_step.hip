@@ -68,12 +68,12 @@ __global__ __launch_bounds__(256) void broadcast_rows_kernel(const float* __rest
 }
 
 // Top-level STEP: position of sequence b is seq_len[b]-1 (the count already includes the new entry);
-// k, v go to cache[b, h, pos, :] of this layer.
+// k, v go to cache[b, h, pos, :] of this layer, whose rows hold `pitch` >= d_h elements (the surplus is zeroed).
 template <typename TKV>
 __global__ __launch_bounds__(256) void rope_append_coarse_kernel(const float* __restrict__ qkv, float* __restrict__ qrot,
                                                                  TKV* __restrict__ kc, TKV* __restrict__ vc,
                                                                  const int32_t* __restrict__ seq_len, int Bt, int H,
-                                                                 int d_h, int64_t S_max, float theta) {
+                                                                 int d_h, int pitch, int64_t S_max, float theta) {
   const int half = d_h >> 1, D = H * d_h;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (int64_t)Bt * H * half) return;
@@ -90,11 +90,12 @@ __global__ __launch_bounds__(256) void rope_append_coarse_kernel(const float* __
   qd[i] = qa * c - qb * s;
   qd[i + half] = qb * c + qa * s;
   if (pos < 0 || pos >= S_max) return;                        // full cache: nothing is written out of bounds
-  const int64_t slot = (((int64_t)b * H + h) * S_max + pos) * d_h;
+  const int64_t slot = (((int64_t)b * H + h) * S_max + pos) * pitch;
   kc[slot + i] = from_f32<TKV>(ka * c - kb * s);
   kc[slot + i + half] = from_f32<TKV>(kb * c + ka * s);
   vc[slot + i] = from_f32<TKV>(src[2 * D + i]);
   vc[slot + i + half] = from_f32<TKV>(src[2 * D + i + half]);
+  for (int p = d_h + i; p < pitch; p += half) { kc[slot + p] = TKV{}; vc[slot + p] = TKV{}; }
 }
 
 // Token choice for one row of logits (greedy, lowest index on ties, or the forced token), then the
@@ -255,7 +256,8 @@ static int32_t validate_config(const photon_config* c, int Bt, int64_t S_max) {
   PHOTON_REQUIRE(Bt > 0 && S_max > 0, PHOTON_ERR_INVALID_ARG, "Bt=%d and S_max=%lld must be positive", Bt, (long long)S_max);
   PHOTON_REQUIRE(c->D > 0 && c->H > 0 && c->d_h > 0 && c->H * c->d_h == c->D, PHOTON_ERR_INVALID_ARG,
                  "D=%d must equal H*d_h=%d*%d", c->D, c->H, c->d_h);
-  PHOTON_REQUIRE(c->d_h == 32 || c->d_h == 64 || c->d_h == 128, PHOTON_ERR_UNSUPPORTED, "d_h=%d not in {32, 64, 128}", c->d_h);
+  PHOTON_REQUIRE(c->d_h % 4 == 0 && c->d_h >= 4 && c->d_h <= 128, PHOTON_ERR_UNSUPPORTED, "d_h=%d must be a multiple of 4 in [4, 128]",
+                 c->d_h);
   PHOTON_REQUIRE(c->n_layers >= 1 && c->vocab >= 1 && c->d_ff >= 0, PHOTON_ERR_INVALID_ARG, "n_layers=%d vocab=%d d_ff=%d invalid",
                  c->n_layers, c->vocab, c->d_ff);
   int64_t chunks = Bt;
@@ -361,7 +363,8 @@ static int32_t stream_step(const Ctx& x, const photon_module_weights& mod, void*
   const int rows = x.Bt;
   float *h = x.f(x.o_h), *qkv = x.f(x.o_qkv), *qrot = x.f(x.o_qrot), *attn = x.f(x.o_attn);
   const size_t esz = dtype_size(c.dt);
-  const size_t layer_cache = (size_t)x.Bt * c.H * S_cap * c.d_h * esz;
+  const int pitch = kv_row_elems(c.d_h);
+  const size_t layer_cache = (size_t)x.Bt * c.H * S_cap * pitch * esz;
   const float scale = 1.0f / sqrtf((float)c.d_h);
   for (int i = 0; i < c.n_layers; ++i) {
     const photon_layer_weights& lw = mod.layers[i];
@@ -371,10 +374,10 @@ static int32_t stream_step(const Ctx& x, const photon_module_weights& mod, void*
     const int64_t n_el = (int64_t)rows * c.H * (c.d_h / 2);
     if (x.bf16)
       PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_coarse_kernel<bf16_t>, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot,
-                    (bf16_t*)kc, (bf16_t*)vc, seq_len, x.Bt, c.H, c.d_h, S_cap, c.rope_theta);
+                    (bf16_t*)kc, (bf16_t*)vc, seq_len, x.Bt, c.H, c.d_h, pitch, S_cap, c.rope_theta);
     else
       PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_coarse_kernel<float>, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot,
-                    (float*)kc, (float*)vc, seq_len, x.Bt, c.H, c.d_h, S_cap, c.rope_theta);
+                    (float*)kc, (float*)vc, seq_len, x.Bt, c.H, c.d_h, pitch, S_cap, c.rope_theta);
     PHOTON_TRY(check_launch("rope_append_coarse_kernel"));
     PHOTON_TRY(launch_coarse_attn(x.bf16 ? KV_BF16 : KV_F32, true, c.d_h, qrot, kc, vc, seq_len, attn, x.Bt, c.H, S_cap, scale,
                                   x.p.n_splits, x.base + x.p.coarse_ws, x.st));
@@ -392,27 +395,34 @@ static int32_t top_step(const Ctx& x, RowsIn in) {
 // Step 2 of hierarchical generation (Appendix A, Definition 1): re-encode the step's tokens bottom-up.  Every
 // level l < L advances its stream by its new units, one STEP per unit (they are causally ordered).  Returns the
 // encoder-side level-(L-1) block [Bt, C_L, D] (rows of sequence b contiguous).
+static int32_t embed_rows(hipStream_t st, bool bf16, const int32_t* tokens, const void* table, float* rows, int64_t n, int width, int vocab) {
+  if (bf16)
+    PHOTON_LAUNCH(KC_MISC, st, embed_rows_kernel<bf16_t>, dim3(blocks_for(n * (width / 4))), dim3(256), 0, st, tokens, (const bf16_t*)table,
+                  rows, n, width, vocab);
+  else
+    PHOTON_LAUNCH(KC_MISC, st, embed_rows_kernel<float>, dim3(blocks_for(n * (width / 4))), dim3(256), 0, st, tokens, (const float*)table,
+                  rows, n, width, vocab);
+  return check_launch("embed_rows_kernel");
+}
+
 static int32_t hier_reencode(const Ctx& x, const int32_t* tokens, const float** bottleneck) {
   const photon_config& c = *x.c;
   const int D = c.D, L = c.L, Bt = x.Bt;
   int64_t per_seq = 1;
   for (int l = 0; l < L; ++l) per_seq *= c.C[l];
-  float* X = x.f(x.p.hx[0]);                               // encoder-side level-0 states of the new tokens
-  const int64_t n_tok = (int64_t)Bt * per_seq;
-  if (x.bf16)
-    PHOTON_LAUNCH(KC_MISC, x.st, embed_rows_kernel<bf16_t>, dim3(blocks_for(n_tok * (D / 4))), dim3(256), 0, x.st, tokens,
-                  (const bf16_t*)x.ew->E_enc, X, n_tok, D, c.vocab);
-  else
-    PHOTON_LAUNCH(KC_MISC, x.st, embed_rows_kernel<float>, dim3(blocks_for(n_tok * (D / 4))), dim3(256), 0, x.st, tokens,
-                  (const float*)x.ew->E_enc, X, n_tok, D, c.vocab);
-  PHOTON_TRY(check_launch("embed_rows_kernel"));
   float* A = x.f(x.p.hA);
+  // parameter-free level-1 chunker: the embeddings are D / C_1 wide and C_1 of them side by side ARE the unit
+  const bool concat1 = L >= 2 && x.ew->chunker_w[0] == nullptr;
+  float* X = concat1 ? A : x.f(x.p.hx[0]);                 // encoder-side level-0 states of the new tokens
+  const int64_t n_tok = (int64_t)Bt * per_seq;
+  PHOTON_TRY(embed_rows(x.st, x.bf16, tokens, x.ew->E_enc, X, n_tok, concat1 ? D / c.C[0] : D, c.vocab));
   for (int l = 1; l < L; ++l) {
     const int C = c.C[l - 1];
     per_seq /= C;                                          // new level-l units per sequence
     const int rows = (int)(Bt * per_seq);
-    PHOTON_TRY(linear(x, X, (int64_t)C * D, x.ew->chunker_w[l - 1], nullptr, x.ew->chunker_b[l - 1], nullptr, 0, A, D, rows, D, C * D,
-                      EPI_PLAIN));
+    if (!(l == 1 && concat1))
+      PHOTON_TRY(linear(x, X, (int64_t)C * D, x.ew->chunker_w[l - 1], nullptr, x.ew->chunker_b[l - 1], nullptr, 0, A, D, rows, D, C * D,
+                        EPI_PLAIN));
     float* Xl = x.f(x.p.hx[l]);
     for (int j = 0; j < (int)per_seq; ++j) {
       PHOTON_LAUNCH(KC_MISC, x.st, step_begin_kernel, dim3(blocks_for(Bt)), dim3(256), 0, x.st, x.hs->seq_len[l - 1], Bt);
@@ -589,30 +599,26 @@ static int32_t prefill_impl(const Ctx& x, Ctx e, const PrefillPlan& pp, const ph
   const float scale = 1.0f / sqrtf((float)c.d_h);
   const size_t esz = dtype_size(c.dt);
 
-  // X^(0): encoder-side embeddings
-  float* X0 = e.f(pp.X[0]);
-  const int64_t n_tok = (int64_t)Bt * pp.M[0];
-  if (x.bf16)
-    PHOTON_LAUNCH(KC_MISC, x.st, embed_rows_kernel<bf16_t>, dim3(blocks_for(n_tok * (D / 4))), dim3(256), 0, x.st, tokens,
-                  (const bf16_t*)ew.E_enc, X0, n_tok, D, c.vocab);
-  else
-    PHOTON_LAUNCH(KC_MISC, x.st, embed_rows_kernel<float>, dim3(blocks_for(n_tok * (D / 4))), dim3(256), 0, x.st, tokens,
-                  (const float*)ew.E_enc, X0, n_tok, D, c.vocab);
-  PHOTON_TRY(check_launch("embed_rows_kernel"));
-
   float *A = e.f(pp.A), *h = e.f(pp.h), *qkv = e.f(pp.qkv), *attn = e.f(pp.attn);
   float* pair = e.f(pp.pair);
+  // X^(0): encoder-side embeddings.  Parameter-free level-1 chunker: they are D / C_1 wide, and C_1 of them side
+  // by side are A^(1) itself.
+  const bool concat1 = L >= 2 && ew.chunker_w[0] == nullptr;
+  const int64_t n_tok = (int64_t)Bt * pp.M[0];
+  PHOTON_TRY(embed_rows(x.st, x.bf16, tokens, ew.E_enc, concat1 ? A : e.f(pp.X[0]), n_tok, concat1 ? D / c.C[0] : D, c.vocab));
+
   for (int l = 1; l <= L; ++l) {
     const int C = c.C[l - 1];
     const int64_t M = pp.M[l];
     const int rows = (int)(Bt * M);
     const photon_module_weights& mod = ew.enc[l - 1];
     // Eq. 4: C consecutive level-(l-1) states are one row of C*D inputs (the states are contiguous per sequence)
-    PHOTON_TRY(linear(e, e.f(pp.X[l - 1]), (int64_t)C * D, ew.chunker_w[l - 1], nullptr, ew.chunker_b[l - 1], nullptr, 0, A, D, rows, D,
-                      C * D, EPI_PLAIN));
+    if (!(l == 1 && concat1))
+      PHOTON_TRY(linear(e, e.f(pp.X[l - 1]), (int64_t)C * D, ew.chunker_w[l - 1], nullptr, ew.chunker_b[l - 1], nullptr, 0, A, D, rows, D,
+                        C * D, EPI_PLAIN));
     RowsIn in;
     in.ptr = A; in.ld = D;
-    const size_t layer_cache = (size_t)Bt * c.H * x.s->S_max * c.d_h * esz;
+    const size_t layer_cache = (size_t)Bt * c.H * x.s->S_max * kv_row_elems(c.d_h) * esz;
     for (int i = 0; i < c.n_layers; ++i) {
       const photon_layer_weights& lw = mod.layers[i];
       PHOTON_TRY(linear(e, in.ptr, in.ld, lw.wqkv, lw.g1, nullptr, nullptr, 0, qkv, 3 * D, rows, 3 * D, D, EPI_PLAIN));
@@ -623,7 +629,7 @@ static int32_t prefill_impl(const Ctx& x, Ctx e, const PrefillPlan& pp, const ph
         vc = reinterpret_cast<char*>(x.s->v_cache) + (size_t)i * layer_cache;
       } else if (x.hs != nullptr) {                        // hierarchical generation keeps every level's stream
         cap = x.hs->S_cap[l - 1];
-        const size_t lc = (size_t)Bt * c.H * cap * c.d_h * esz;
+        const size_t lc = (size_t)Bt * c.H * cap * kv_row_elems(c.d_h) * esz;
         kc = reinterpret_cast<char*>(x.hs->k_cache[l - 1]) + (size_t)i * lc;
         vc = reinterpret_cast<char*>(x.hs->v_cache[l - 1]) + (size_t)i * lc;
       }
@@ -734,6 +740,12 @@ static int32_t require_hier_state(const photon_config& c, const photon_hier_stat
 static int32_t require_encoders(const photon_config& c, const photon_encoder_weights* ew) {
   PHOTON_REQUIRE_PTR(ew->E_enc);
   for (int l = 1; l <= c.L; ++l) {
+    if (l == 1 && c.L >= 2 && ew->chunker_w[0] == nullptr) {   // parameter-free concatenation of D / C_1 wide embeddings
+      PHOTON_REQUIRE(c.D % (4 * c.C[0]) == 0 && ew->chunker_b[0] == nullptr, PHOTON_ERR_INVALID_ARG,
+                     "level-1 chunker without a matrix: D=%d must be a multiple of 4*C_1=%d, and there is no bias", c.D, 4 * c.C[0]);
+      PHOTON_TRY(require_module(c, ew->enc[0], "encoder", 1));
+      continue;
+    }
     PHOTON_REQUIRE(ew->chunker_w[l - 1] && aligned16(ew->chunker_w[l - 1]), PHOTON_ERR_INVALID_ARG,
                    "chunker of level %d missing or misaligned", l);
     PHOTON_TRY(require_module(c, ew->enc[l - 1], "encoder", l));

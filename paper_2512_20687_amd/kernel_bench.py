@@ -169,7 +169,7 @@ def bench_schedules():
     import os
     sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
     import seeded_inputs as si
-    for name in ("cfg3_bf16_128k", "cfg2_bf16_8k"):
+    for name in ("cfg3_bf16_128k", "cfg2_bf16_8k", "paper_600m"):
         wl = si.WORKLOADS[name]
         cfg, Bt, S0 = wl.cfg, wl.Bt, wl.S0
         steps, warm = 24, 4

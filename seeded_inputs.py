@@ -38,10 +38,14 @@ class PhotonConfig:
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0   # 0 disables the rotary encoding
     chunker_bias: bool = True
+    # The paper's models (Appendix tables "PHOTON (600M)" ..): encoder-side token embeddings of width D / C_1 and a
+    # parameter-free level-1 chunker that puts C_1 of them side by side (416 * 4 = 1664).
+    concat_level1: bool = False
 
     def __post_init__(self):
         assert len(self.C) == self.L and len(self.R) == self.L
         assert self.H * self.d_h == self.D
+        assert not self.concat_level1 or (self.L >= 2 and self.D % self.C[0] == 0)
         assert self.dtype in ("f32", "bf16")
 
     @property
@@ -84,6 +88,16 @@ WORKLOADS: Dict[str, Workload] = {
     "cfg3_bf16_128k": Workload("cfg3_bf16_128k", _cfg(2, (4, 4), 2048, 32, 8, 32000, "bf16"), 4, 131072, 256),
     "cfg4_bf16_serving": Workload("cfg4_bf16_serving", _cfg(2, (4, 4), 1024, 16, 4, 32000, "bf16"), 256, 32768, 64),
     "cfg5_bf16_3level": Workload("cfg5_bf16_3level", _cfg(3, (8, 8, 8), 2048, 32, 8, 32000, "bf16"), 8, 32768, 128),
+    # The shapes of the paper's own models (Appendix tables): head sizes 52 / 56 / 60, converter length 2, token
+    # embeddings of a quarter of the width concatenated by the level-1 chunker; a 2048-token prompt followed by 128
+    # generated tokens as in the paper's prefill-heavy setting (Section 3, "Evaluation Metrics"); the batch of 256 is
+    # this build's choice (the paper gives none).
+    "paper_600m": Workload("paper_600m", replace(_cfg(2, (4, 4), 1664, 32, 4, 32000, "bf16", R=(2, 2), d_ff=4096),
+                                                 concat_level1=True), 256, 2048, 8),
+    "paper_900m": Workload("paper_900m", replace(_cfg(2, (4, 4), 1792, 32, 5, 32000, "bf16", R=(2, 2), d_ff=4608),
+                                                 concat_level1=True), 256, 2048, 8),
+    "paper_1p2b": Workload("paper_1p2b", replace(_cfg(2, (4, 4), 1920, 32, 6, 32000, "bf16", R=(2, 2), d_ff=5120),
+                                                 concat_level1=True), 256, 2048, 8),
 }
 
 
@@ -157,11 +171,14 @@ def make_weights(cfg: PhotonConfig, seed: int = 0, *, encoders: bool = True,
     D = cfg.D
     w = {"E_dec": d.normal((cfg.vocab, D), emb_std), "W_lm": d.normal((cfg.vocab, D), 0.02)}
     if encoders:
-        w["E_enc"] = d.normal((cfg.vocab, D), emb_std)
+        w["E_enc"] = d.normal((cfg.vocab, D // cfg.C[0] if cfg.concat_level1 else D), emb_std)
     enc: List[dict] = []
     for l in range(1, cfg.L + 1):
         if not encoders and l < cfg.L:
             enc.append({})
+            continue
+        if l == 1 and cfg.concat_level1:
+            enc.append({"chunker": {"w": None}, "module": _module(d, cfg)})
             continue
         e = {"chunker": {"w": d.normal((D, cfg.C[l - 1] * D), 0.02)}, "module": _module(d, cfg)}
         if cfg.chunker_bias:

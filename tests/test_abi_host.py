@@ -39,8 +39,8 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     p = ctypes.c_void_p(4096)        # aligned fake address; never dereferenced because validation fails first
     bad = ctypes.c_void_p(4100)
     # unsupported head size
-    assert lib.photon_coarse_decode_attn(p, p, p, p, p, 1, 2, 48, 16, 0.1, 1, None, 0, 0, None) == -2
-    assert b"d_h=48" in lib.photon_last_error()
+    assert lib.photon_coarse_decode_attn(p, p, p, p, p, 1, 2, 132, 16, 0.1, 1, None, 0, 0, None) == -2
+    assert b"d_h=132" in lib.photon_last_error()
     # null and misaligned pointers
     assert lib.photon_coarse_decode_attn(None, p, p, p, p, 1, 2, 64, 16, 0.1, 1, None, 0, 0, None) == -1
     assert lib.photon_coarse_decode_attn(bad, p, p, p, p, 1, 2, 64, 16, 0.1, 1, None, 0, 0, None) == -1
@@ -51,7 +51,8 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     # window and query range
     assert lib.photon_chunk_local_attn(p, p, p, p, 4, 17, 1, 0, 2, 64, 0.1, 1, None) == -2
     assert lib.photon_chunk_local_attn(p, p, p, p, 4, 4, 2, 3, 2, 64, 0.1, 1, None) == -1
-    assert lib.photon_chunk_local_attn(p, p, p, p, 4, 4, 4, 0, 2, 48, 0.1, 1, None) == -2
+    assert lib.photon_chunk_local_attn(p, p, p, p, 4, 4, 4, 0, 2, 52, 0.1, 1, None) == -2      # bf16 rows come in 16-byte pieces
+    assert lib.photon_chunk_local_attn(p, p, p, p, 4, 4, 4, 0, 2, 54, 0.1, 0, None) == -2
     assert lib.photon_chunk_local_attn(None, p, p, p, 4, 4, 4, 0, 2, 64, 0.1, 1, None) == -1
     # few-row linear map: bad epilogue, bad sizes
     assert lib.photon_linear(p, p, None, 1e-5, None, None, p, 4, 64, 64, 7, 1, None) == -1
@@ -61,3 +62,6 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     # workspace size formula
     assert lib.photon_coarse_decode_attn_workspace_bytes(4, 32, 64, 8) == 4 * 32 * 8 * 66 * 4
     assert lib.photon_coarse_decode_attn_workspace_bytes(4, 32, 64, 1) == 0
+    assert lib.photon_coarse_decode_attn_workspace_bytes(4, 32, 52, 8) == 4 * 32 * 8 * 66 * 4   # rows padded to 64
+    # cache row length for the head sizes of the paper's models
+    assert [lib.photon_kv_row_elems(d) for d in (16, 32, 52, 56, 60, 64, 128, 129, 0)] == [32, 32, 64, 64, 64, 64, 128, 0, 0]

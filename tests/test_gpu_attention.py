@@ -23,7 +23,9 @@ def coarse_case(dtype, Bt, H, d_h, S_max, seq, n_splits, seed=0):
     out = torch.full((Bt, H, d_h), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
     ns = n_splits or ph.photon_coarse_decode_attn_auto_splits(Bt, H, S_max)
     ws = torch.empty(max(ph.photon_coarse_decode_attn_workspace_bytes(Bt, H, d_h, ns), 16) // 4, dtype=torch.float32, device="cuda")
-    ph.photon_coarse_decode_attn(dev(q, dtype), dev(k, dtype), dev(v, dtype), dev(seq), out, n_splits=n_splits, workspace=ws)
+    # cache rows in the library's layout: head size rounded up to 32 / 64 / 128, zeros in the added columns
+    ph.photon_coarse_decode_attn(dev(q, dtype), ph.pad_kv_rows(dev(k, dtype), d_h), ph.pad_kv_rows(dev(v, dtype), d_h), dev(seq), out,
+                                 n_splits=n_splits, workspace=ws)
     torch.cuda.synchronize()
     return out, ref
 
@@ -36,6 +38,14 @@ def coarse_case(dtype, Bt, H, d_h, S_max, seq, n_splits, seed=0):
     ("bf16", 3, 4, 64, 1500, [1500, 777, 1]),
     ("bf16", 2, 2, 32, 700, [513, 700]),
     ("bf16", 1, 3, 128, 333, [333]),
+    # head sizes of the paper's models (Appendix tables: 52, 56, 60) and other sizes that are not a power of two
+    ("f32", 2, 3, 52, 200, [200, 77]),
+    ("bf16", 2, 4, 52, 900, [900, 333]),
+    ("bf16", 1, 2, 56, 300, [300]),
+    ("bf16", 2, 2, 60, 513, [513, 100]),
+    ("f32", 1, 2, 20, 70, [70]),
+    ("bf16", 1, 3, 96, 200, [200]),
+    ("bf16", 1, 2, 7, 90, [90]),
 ])
 @pytest.mark.parametrize("n_splits", [1, 2, 5, 16, 0])
 def test_coarse_parity(dtype, Bt, H, d_h, S_max, seq, n_splits):
@@ -119,6 +129,11 @@ def local_case(dtype, n, W, H, d_h, q_len, q_pos, seed=0):
     ("bf16", 7, 16, 2, 64),
     ("bf16", 3, 11, 3, 128),
     ("bf16", 1, 1, 1, 64),
+    ("f32", 9, 4, 3, 52),           # head sizes that do not fill a lane group
+    ("bf16", 40, 5, 4, 56),
+    ("f32", 5, 4, 2, 60),
+    ("bf16", 6, 4, 2, 24),
+    ("f32", 3, 2, 1, 4),
 ])
 def test_local_tile_parity(dtype, n, W, H, d_h):
     require_gpu()
@@ -126,7 +141,8 @@ def test_local_tile_parity(dtype, n, W, H, d_h):
     assert nerr(out, ref) <= TOL[dtype]
 
 
-@pytest.mark.parametrize("dtype,n,W,H,d_h", [("f32", 19, 4, 2, 32), ("bf16", 70, 8, 16, 64), ("f32", 3, 16, 2, 64)])
+@pytest.mark.parametrize("dtype,n,W,H,d_h", [("f32", 19, 4, 2, 32), ("bf16", 70, 8, 16, 64), ("f32", 3, 16, 2, 64),
+                                             ("f32", 11, 5, 2, 52), ("bf16", 9, 4, 3, 40)])
 def test_local_incremental_parity(dtype, n, W, H, d_h):
     require_gpu()
     for q_pos in range(W):

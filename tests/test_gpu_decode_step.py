@@ -51,8 +51,9 @@ def check_against_oracle(cfg, w, st_np, Bt, S_max, forced, tol):
         errs["carry"] = nerr(state.carry, ost["carry"])
     for name, got, ref in (("k", state.k, ost["k"]), ("v", state.v, ost["v"])):
         new_rows = np.stack([ref[:, b, :, s0[b]] for b in range(Bt)], 1)
-        got_rows = torch.stack([got[:, b, :, int(s0[b])] for b in range(Bt)], 1)
-        errs[name + "_new"] = nerr(got_rows, new_rows)
+        got_rows = torch.stack([got[:, b, :, int(s0[b])] for b in range(Bt)], 1)    # cache rows are padded with zeros past d_h
+        assert float(got_rows[..., cfg.d_h:].float().abs().sum()) == 0.0
+        errs[name + "_new"] = nerr(got_rows[..., :cfg.d_h], new_rows)
     bad = {k: v for k, v in errs.items() if not v <= tol}
     assert not bad, (bad, errs)
     assert np.array_equal(state.seq_len.cpu().numpy(), s0 + 1)
@@ -91,6 +92,10 @@ def test_cfg1_prefill_then_one_step_fp32():
     dict(L=3, C=(2, 3, 2), R=(1, 2, 1)),
     dict(L=1, C=(4,), R=(2,)),
     dict(rope_theta=0.0),
+    dict(D=104, d_h=52, R=(2, 2)),            # head sizes of the paper's models (Appendix tables)
+    dict(D=120, d_h=60),
+    dict(D=168, H=3, d_h=56, d_ff=0),
+    dict(D=24, d_h=12, d_ff=32),
 ])
 def test_small_fp32_variants(kw):
     require_gpu()
@@ -110,6 +115,9 @@ def test_small_fp32_variants(kw):
     (dict(L=3, C=(2, 2, 4), R=(1, 1, 1), n_layers=1), 5),      # 80 rows at the token level: two row passes
     (dict(d_h=128, H=2, d_ff=0), 1),
     (dict(C=(2, 2), n_layers=1), 130),                         # every level has enough rows for the tiled MFMA contraction
+    (dict(D=832, H=16, d_h=52, d_ff=1024, R=(2, 2), n_layers=1), 3),            # paper-like heads
+    (dict(D=960, H=16, d_h=60, d_ff=1280, n_layers=1), 2),
+    (dict(D=448, H=8, d_h=56, d_ff=640, C=(2, 2), n_layers=1), 130),            # tiled contraction with widths that are not powers of two
 ])
 def test_bf16_variants(kw, Bt):
     """bf16 weights and coarse cache, fp32 accumulation; tokens forced so that a

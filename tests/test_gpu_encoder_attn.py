@@ -36,12 +36,18 @@ def run(dtype, Bt, M, H, d_h, theta, with_cache, seed=0, S_max=None):
     kc = vc = None
     if with_cache:
         cdt = torch.bfloat16 if bf16 else torch.float32
-        kc = torch.zeros((Bt, H, S_max, d_h), device="cuda", dtype=cdt)
-        vc = torch.zeros_like(kc)
+        # rows of the library's cache layout (head size rounded up to 32 / 64 / 128); pre-filled so that the test
+        # sees that the columns past d_h of the written positions are zeroed
+        kc = torch.full((Bt, H, S_max, ph.photon_kv_row_elems(d_h)), 7.0, device="cuda", dtype=cdt)
+        vc = torch.full_like(kc, 7.0)
     n = ph.photon_encoder_attn_workspace_bytes(Bt, M, H, d_h, bf16)
     ws = torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
     ph.photon_encoder_attn(dev(qkv), out, Bt, M, H, d_h, rope_theta=theta, k_cache=kc, v_cache=vc, workspace=ws, bf16=bf16)
     torch.cuda.synchronize()
+    if with_cache:
+        assert float(kc[:, :, :M, d_h:].abs().sum()) == 0.0 and float(vc[:, :, :M, d_h:].abs().sum()) == 0.0
+        assert bool((kc[:, :, M:] == 7.0).all()) and bool((vc[:, :, M:] == 7.0).all())   # nothing beyond position M-1 is touched
+        kc, vc = kc[..., :d_h], vc[..., :d_h]
     return out, ref, kc, vc, kref, vref
 
 
@@ -54,7 +60,16 @@ def test_encoder_attn_bf16(Bt, M, H):
     assert nerr(out, ref) <= 6e-3
     assert nerr(kc[:, :, :M].float(), kref) <= 2.0 ** -8
     assert nerr(vc[:, :, :M].float(), vref) <= 2.0 ** -8
-    assert float(kc[:, :, M:].abs().max()) == 0.0                 # nothing beyond position M-1 is touched
+
+
+@pytest.mark.parametrize("Bt,M,H,d_h", [(2, 200, 3, 52), (1, 321, 2, 56), (1, 130, 2, 60), (2, 70, 2, 32), (1, 64, 1, 4)])
+def test_encoder_attn_bf16_padded_head(Bt, M, H, d_h):
+    """Head sizes of the paper's models (Appendix tables) and other sizes below 64: operand rows zero-padded to 64."""
+    require_gpu()
+    out, ref, kc, vc, kref, vref = run("bf16", Bt, M, H, d_h, 10000.0, True, seed=6)
+    assert nerr(out, ref) <= 6e-3
+    assert nerr(kc[:, :, :M].float(), kref) <= 2.0 ** -8
+    assert nerr(vc[:, :, :M].float(), vref) <= 2.0 ** -8
 
 
 def test_encoder_attn_bf16_no_rotary_no_cache():
@@ -63,7 +78,7 @@ def test_encoder_attn_bf16_no_rotary_no_cache():
     assert nerr(out, ref) <= 6e-3
 
 
-@pytest.mark.parametrize("Bt,M,H,d_h", [(1, 1, 1, 32), (2, 70, 2, 32), (1, 150, 3, 16), (2, 65, 1, 64)])
+@pytest.mark.parametrize("Bt,M,H,d_h", [(1, 1, 1, 32), (2, 70, 2, 32), (1, 150, 3, 16), (2, 65, 1, 64), (2, 90, 2, 52), (1, 77, 3, 60)])
 def test_encoder_attn_fp32(Bt, M, H, d_h):
     require_gpu()
     out, ref, kc, vc, kref, vref = run("f32", Bt, M, H, d_h, 10000.0, True, seed=2)
@@ -75,10 +90,13 @@ def test_encoder_attn_fp32(Bt, M, H, d_h):
 def test_encoder_attn_rejects_bad_arguments():
     require_gpu()
     import paper_2512_20687_amd as ph
-    qkv = torch.zeros((8, 3 * 48), device="cuda")
-    out = torch.zeros((8, 48), device="cuda")
+    qkv = torch.zeros((8, 3 * 128), device="cuda")
+    out = torch.zeros((8, 128), device="cuda")
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
     with pytest.raises(ph.PhotonError):
-        ph.photon_encoder_attn(qkv, out, 1, 8, 1, 48, bf16=True)             # head size not built
+        ph.photon_encoder_attn(qkv, out, 1, 8, 1, 128, bf16=True, workspace=ws)   # head size not built
+    with pytest.raises(ph.PhotonError):
+        ph.photon_encoder_attn(qkv, out, 1, 8, 1, 12, bf16=False)                 # fp32 kernel: 16 .. 64
     qkv = torch.zeros((8, 3 * 64), device="cuda")
     out = torch.zeros((8, 64), device="cuda")
     with pytest.raises(ph.PhotonError):

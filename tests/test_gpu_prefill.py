@@ -27,9 +27,11 @@ def gpu_prefill(cfg, w, toks, S_max):
 
 def check_state(cfg, state, ost, Bt, tol, tol_kv):
     G = int(ost["seq_len"][0])
+    d = cfg.d_h                                                         # cache rows are padded to 32 / 64 / 128 elements with zeros
     errs = {"x_top": nerr(state.x_top, ost["x_top"]),
-            "k": nerr(state.k[:, :, :, :G].float(), ost["k"][:, :, :, :G]),
-            "v": nerr(state.v[:, :, :, :G].float(), ost["v"][:, :, :, :G])}
+            "k": nerr(state.k[:, :, :, :G, :d].float(), ost["k"][:, :, :, :G]),
+            "v": nerr(state.v[:, :, :, :G, :d].float(), ost["v"][:, :, :, :G])}
+    assert float(state.k[..., d:].float().abs().sum()) == 0.0 and float(state.v[..., d:].float().abs().sum()) == 0.0
     if cfg.L > 1:
         errs["carry"] = nerr(state.carry, ost["carry"])
     assert np.array_equal(state.seq_len.cpu().numpy(), ost["seq_len"].astype(np.int32))
@@ -58,6 +60,11 @@ def test_cfg1_prefill_fp32():
     (dict(L=3, C=(2, 3, 2), R=(1, 2, 1)), 3, 12 * 7),
     (dict(L=1, C=(4,), R=(2,)), 2, 4 * 37),                  # one level: no carries
     (dict(R=(2, 2), d_ff=0), 2, 16 * 5),
+    # the shape family of the paper's models (Appendix tables): head size 52 / 60, converter length 2, token
+    # embeddings D / C_1 wide concatenated by the level-1 chunker
+    (dict(D=208, H=4, d_h=52, R=(2, 2), concat_level1=True), 2, 16 * 6),
+    (dict(D=120, d_h=60, concat_level1=True, L=3, C=(2, 3, 2), R=(1, 2, 1)), 2, 12 * 5),
+    (dict(D=40, d_h=20, d_ff=48), 1, 16 * 3),
 ])
 def test_small_fp32_prefill(kw, Bt, T):
     require_gpu()
@@ -76,6 +83,8 @@ def test_small_fp32_prefill(kw, Bt, T):
     (dict(), 2, 16 * 40),                                    # 160 level-1 rows per sequence: tiled MFMA contraction + MFMA attention
     (dict(L=3, C=(2, 2, 4), R=(1, 1, 1), n_layers=1), 1, 16 * 9),
     (dict(n_layers=1), 3, 16 * 1),
+    (dict(D=832, H=16, d_h=52, d_ff=1024, n_layers=1, R=(2, 2), concat_level1=True), 2, 16 * 36),   # paper-like heads, MFMA attention on padded rows
+    (dict(D=448, H=8, d_h=56, d_ff=640, n_layers=1), 2, 16 * 10),
 ])
 def test_bf16_prefill_then_step(kw, Bt, T):
     """bf16 weights and cache; then one decode step from the GPU-made state
@@ -162,8 +171,8 @@ def check_hier(cfg, hier, ost, tol_kv):
     for l in range(1, cfg.L):
         n = int(ost["enc_len"][l - 1][0])
         assert np.array_equal(hier.seq_len[l - 1].cpu().numpy(), ost["enc_len"][l - 1].astype(np.int32))
-        ek = nerr(hier.k[l - 1][:, :, :, :n].float(), ost["enc_k"][l - 1][:, :, :, :n])
-        ev = nerr(hier.v[l - 1][:, :, :, :n].float(), ost["enc_v"][l - 1][:, :, :, :n])
+        ek = nerr(hier.k[l - 1][:, :, :, :n, :cfg.d_h].float(), ost["enc_k"][l - 1][:, :, :, :n])
+        ev = nerr(hier.v[l - 1][:, :, :, :n, :cfg.d_h].float(), ost["enc_v"][l - 1][:, :, :, :n])
         assert ek <= tol_kv and ev <= tol_kv, (l, ek, ev)
         assert float(hier.k[l - 1][:, :, :, n:].float().abs().max()) == 0.0
 
@@ -174,6 +183,8 @@ def check_hier(cfg, hier, ost, tol_kv):
     ("f32", dict(L=1, C=(4,), R=(1,)), 2, 4 * 9),
     ("bf16", dict(), 2, 16 * 10),
     ("bf16", dict(L=3, C=(2, 2, 4), R=(1, 1, 1), n_layers=1), 3, 16 * 5),
+    ("f32", dict(D=208, H=4, d_h=52, concat_level1=True), 2, 16 * 3),
+    ("bf16", dict(D=832, H=16, d_h=52, d_ff=1024, n_layers=1, concat_level1=True), 2, 16 * 6),
 ])
 def test_hierarchical_generation_two_steps(dtype, kw, Bt, T):
     """Prefill with every level's stream kept, then two steps of hierarchical generation (Definition 1)

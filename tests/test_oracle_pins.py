@@ -396,18 +396,23 @@ def test_exactness_theorem(L, C):
     assert np.abs(probe["x_top"] - fresh["x_top"]).max() > 1e-6
 
 
-@pytest.mark.parametrize("L,C", [(2, (4, 4)), (3, (2, 3, 2))])
-def test_hiergen_equals_recomputation(L, C):
+@pytest.mark.parametrize("L,C,concat", [(2, (4, 4), False), (3, (2, 3, 2), False), (2, (4, 4), True), (3, (2, 3, 2), True)])
+def test_hiergen_equals_recomputation(L, C, concat):
     """Hierarchical generation (Definition 1) keeps a stream per level; after a
     step every cache and the top state must equal what encoding prompt +
     generated tokens from scratch gives (stream == batch at every level), and by
     Theorem 1 a recursive step fed the same bottleneck block lands in the same
     top state."""
-    cfg = tiny_cfg(L=L, C=C, R=(1,) * L, n_layers=2)
+    # concat: the models of the Appendix tables, token embeddings D / C_1 wide, level-1 chunker = concatenation
+    cfg = tiny_cfg(L=L, C=C, R=(1,) * L, n_layers=2, concat_level1=concat)
     w = po.weights_to_f64(si.make_weights(cfg, 14))
     B = cfg.meta_context
     toks = si.make_tokens(cfg.vocab, 2, 2 * B, 7)
     st = po.hier_prefill(cfg, w, toks, 6)
+    if concat:                              # A^(1)_g is literally the embeddings of its C_1 tokens, in order
+        _, A, _ = po.encode_all(cfg, w, toks[0])
+        assert w["E_enc"].shape == (cfg.vocab, cfg.D // C[0])
+        np.testing.assert_array_equal(A[1][3], np.concatenate([w["E_enc"][t] for t in toks[0][3 * C[0]:4 * C[0]]]))
     rec = {k: (v.copy() if hasattr(v, "copy") and not isinstance(v, list) else v) for k, v in po.prefill(cfg, w, toks, 6).items()}
     tr = po.hiergen_step(cfg, w, st)
     ext = np.concatenate([toks, tr["tokens"]], axis=1)
