@@ -21,10 +21,28 @@ namespace photon {
 
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-constexpr int G_BK = 64;
+constexpr int G_BK = 64;                                         // K must be a multiple of this
 constexpr int G_THREADS = 256;
 
-__device__ __forceinline__ int swz(int row, int col16) { return row * 128 + ((col16 ^ ((row >> 1) & 7)) << 4); }
+// Byte offset of (row, 16-byte column) in a staged slab whose rows hold BK bf16.  The column index is XOR-ed with row
+// bits so that the 16 rows one quarter-wave reads together fall on distinct 16-byte slots of the 256-byte bank line
+// (2 rows of 128 bytes, or 4 rows of 64 bytes, per line).
+template <int BK> __device__ __forceinline__ int swz(int row, int col16) {
+  if (BK == 64) return row * 128 + ((col16 ^ ((row >> 1) & 7)) << 4);
+  return row * 64 + ((col16 ^ ((row >> 2) & 3)) << 4);
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_base + 16 l (lds_base: byte offset in
+// LDS, wave-uniform).  Written as an instruction rather than through the compiler's builtin: the compiler treats
+// the builtin as an access to both memories that may complete out of order, and while one is in flight it makes
+// every wait for an LDS read a wait for ALL LDS reads, which serialises the operand prefetch below.  Completion is
+// tracked by hand (s_waitcnt vmcnt) at the one place per slab where it matters.
+__device__ __forceinline__ void load16_to_lds(const void* gsrc, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base) : "memory", "m0");
+}
+
+// s_waitcnt immediate: at most `vm` vector-memory operations outstanding, all LDS reads done
+constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 0xF) | ((vm >> 4) << 14) | (7 << 4); }
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -33,16 +51,21 @@ enum GemmOut { GEMM_OUT_BF16 = 0, GEMM_OUT_F32 = 1 };
 
 // WT: MFMA tiles per wave and dimension (tile edge 64 WT).  A_lo != nullptr: second pass over K with the
 // remainders.  OUT bf16: Cout bf16 [M, ldc] = acc + bias.  OUT fp32: Cout fp32 [M, ldc] = acc + bias + res.
-template <int WT, int OUT>
+// BK: k per slab (64 or 32); NB: slab buffers in LDS (NB - 1 slabs are in flight while one is contracted).
+template <int WT, int OUT, int BK, int NB>
 __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ A_lo, const bf16_t* __restrict__ B, const float* __restrict__ bias,
     const float* res, int64_t ldres, void* Cout, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n) {
   constexpr int BM = 64 * WT;                                   // tile edge (rows and columns)
   constexpr int WE = 32 * WT;                                   // wave quadrant edge
-  constexpr int TILE_BYTES = BM * G_BK * 2;                     // one operand slab
-  constexpr int ROUNDS = BM / 32;
-  extern __shared__ __align__(16) char lds[];                   // [2 buffers][A slab | B slab]
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  constexpr int TILE_BYTES = BM * BK * 2;                       // one operand slab
+  constexpr int CPR = BK / 8;                                   // 16-byte columns per slab row
+  constexpr int RPI = 64 / CPR;                                 // slab rows one load instruction covers
+  constexpr int ROUNDS = BM / (4 * RPI);
+  constexpr int LPS = 2 * ROUNDS;                               // load instructions per slab and wave
+  extern __shared__ __align__(16) char lds[];                   // [NB buffers][A slab | B slab]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // scalar: the LDS targets of the direct loads are wave-uniform
 
   // XCD-aware raster: ids are dealt round-robin to 8 XCDs; give each XCD a contiguous run of tiles,
   // column tiles fastest, so concurrent workgroups of an XCD share x row-blocks.
@@ -52,33 +75,36 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
   const int tm = logical / tiles_n, tn = logical % tiles_n;
   const int m0 = tm * BM, n0 = tn * BM;
 
-  // global -> LDS without passing through registers: one instruction moves 64 lanes x 16 B = 8 slab rows;
-  // lane l lands at LDS row l/8, 16-byte column l%8, so it fetches the logical column that the XOR
-  // swizzle maps there.  Round i of wave w covers slab rows i*32 + w*8 .. +8.
-  const int srow = lane >> 3, scol = lane & 7;
+  // global -> LDS without passing through registers: one instruction moves 64 lanes x 16 B = RPI slab rows;
+  // lane l lands at LDS row l/CPR, 16-byte column l%CPR, so it fetches the logical column that the XOR
+  // swizzle maps there.  Round i of wave w covers slab rows (i*4 + w)*RPI .. +RPI.
+  const int srow = lane / CPR, scol = lane % CPR;
   int64_t aoff[ROUNDS];
   const bf16_t* bptr[ROUNDS];
 #pragma unroll
   for (int i = 0; i < ROUNDS; ++i) {
-    const int r = i * 32 + wave * 8 + srow;
-    const int c = scol ^ ((r >> 1) & 7);
+    const int r = (i * 4 + wave) * RPI + srow;
+    const int c = (swz<BK>(r, scol) - r * (BK * 2)) >> 4;       // the swizzle is an involution on the column index
     int ra = m0 + r; ra = ra < M ? ra : M - 1;                   // clamped rows are never stored
     int rb = n0 + r; rb = rb < N ? rb : N - 1;
     aoff[i] = (int64_t)ra * K + c * 8;
     bptr[i] = B + (int64_t)rb * K + c * 8;
   }
-  const int KT = K / G_BK;
+  const int KT = K / BK;
   const int KT2 = A_lo != nullptr ? 2 * KT : KT;                 // slabs walked: heads, then remainders against the same W
+  // Always issues its loads (past the end: the last slab again, into a buffer nobody reads any more), so that the
+  // number of loads in flight at every wait is a compile-time constant.
   auto stage = [&](int kt, int buf) {
+    kt = kt < KT2 ? kt : KT2 - 1;
     char* sa = lds + buf * 2 * TILE_BYTES;
     char* sb = sa + TILE_BYTES;
     const bf16_t* abase = kt < KT ? A : A_lo;
-    const int64_t kk = (int64_t)(kt < KT ? kt : kt - KT) * G_BK;
+    const int64_t kk = (int64_t)(kt < KT ? kt : kt - KT) * BK;
 #pragma unroll
     for (int i = 0; i < ROUNDS; ++i) {
-      const int off = (i * 32 + wave * 8) * 128;
-      __builtin_amdgcn_global_load_lds((gptr_t)(abase + aoff[i] + kk), (lptr_t)(sa + off), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(bptr[i] + kk), (lptr_t)(sb + off), 16, 0, 0);
+      const int off = (i * 4 + wave) * 1024;
+      load16_to_lds(abase + aoff[i] + kk, (uint32_t)(uintptr_t)(lptr_t)(sa + off));
+      load16_to_lds(bptr[i] + kk, (uint32_t)(uintptr_t)(lptr_t)(sb + off));
     }
   };
 
@@ -93,53 +119,70 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
   const int wm = (wave >> 1) * WE, wn = (wave & 1) * WE;         // wave quadrant inside the tile
   const int frow = lane & 31, fk = lane >> 5;                    // operand fragment: row, 8-wide k group
 
-  // Pipeline over 64-wide K slabs with ONE barrier per slab, placed before the slab's last quarter:
-  //   MFMA(ks=0..2 of slab kt)  [reads of ks+1 issued ahead]
-  //   wait for slab kt+1 (its global->LDS loads were issued a whole slab ago), barrier
-  //     -> every wave has finished reading slab kt, so its buffer can take slab kt+2 right away
-  //   issue slab kt+2, read the first fragments of slab kt+1, MFMA(ks=3 of slab kt)
+  // Pipeline over the K slabs with ONE barrier per slab, placed before the slab's last 16-wide step:
+  //   MFMA(all steps but the last of slab kt)  [fragment reads of the next step issued ahead]
+  //   wait for slab kt+1 (NB-2 younger slabs may still be in flight), barrier
+  //     -> every wave has finished reading slab kt, so its buffer can take slab kt+NB right away
+  //   issue slab kt+NB, read the first fragments of slab kt+1, MFMA(last step of slab kt)
   // so neither the load wait nor the first fragment reads of a slab leave the matrix cores idle.
-  constexpr int KS = G_BK / 16;
+  constexpr int KS = BK / 16;
+  // The fragment reads of the next step are issued in two halves (x rows, then W rows) around the first row of
+  // MFMAs: the counter of outstanding LDS operations holds 15 at most, and with the 2 WT reads of the next step
+  // on top of the 2 WT of the current one the compiler could no longer wait for the older ones alone.
   bf16x8_t af[2][WT], bfr[2][WT];
-  auto frags = [&](int buf, int ks, bf16x8_t (&a)[WT], bf16x8_t (&b)[WT]) {
+  auto frags_a = [&](int buf, int ks, bf16x8_t (&a)[WT]) {
     const char* sa = lds + buf * 2 * TILE_BYTES;
-    const char* sb = sa + TILE_BYTES;
-#pragma unroll
-    for (int i = 0; i < WT; ++i) {
-      a[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4_t*>(sa + swz(wm + i * 32 + frow, ks * 2 + fk)));
-      b[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4_t*>(sb + swz(wn + i * 32 + frow, ks * 2 + fk)));
-    }
-  };
-  auto mfma16 = [&](const bf16x8_t (&a)[WT], const bf16x8_t (&b)[WT]) {
 #pragma unroll
     for (int i = 0; i < WT; ++i)
+      a[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4_t*>(sa + swz<BK>(wm + i * 32 + frow, ks * 2 + fk)));
+  };
+  auto frags_b = [&](int buf, int ks, bf16x8_t (&b)[WT]) {
+    const char* sb = lds + buf * 2 * TILE_BYTES + TILE_BYTES;
+#pragma unroll
+    for (int i = 0; i < WT; ++i)
+      b[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4_t*>(sb + swz<BK>(wn + i * 32 + frow, ks * 2 + fk)));
+  };
+  auto mfma_first = [&](const bf16x8_t (&a)[WT], const bf16x8_t (&b)[WT]) {
+#pragma unroll
+    for (int j = 0; j < WT; ++j) acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[j], acc[0][j], 0, 0, 0);
+  };
+  auto mfma_rest = [&](const bf16x8_t (&a)[WT], const bf16x8_t (&b)[WT]) {
+#pragma unroll
+    for (int i = 1; i < WT; ++i)
 #pragma unroll
       for (int j = 0; j < WT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
   };
+  // one 16-wide step: contract (a, b) while the fragments of the following step (buffer nbuf, step nks) arrive in (na, nb)
+  auto step = [&](const bf16x8_t (&a)[WT], const bf16x8_t (&b)[WT], int nbuf, int nks, bf16x8_t (&na)[WT], bf16x8_t (&nb)[WT]) {
+    frags_a(nbuf, nks, na);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_first(a, b);
+    __builtin_amdgcn_sched_barrier(0);
+    frags_b(nbuf, nks, nb);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_rest(a, b);
+    __builtin_amdgcn_sched_barrier(0);
+  };
 
-  stage(0, 0);
-  if (KT2 > 1) stage(1, 1);
-  __builtin_amdgcn_s_waitcnt(0);                                 // both slabs have landed (vmcnt(0))
-  __syncthreads();
-  frags(0, 0, af[0], bfr[0]);
-  for (int kt = 0; kt < KT2; ++kt) {
-    const int buf = kt & 1;
 #pragma unroll
-    for (int ks = 0; ks < KS - 1; ++ks) {
-      frags(buf, ks + 1, af[(ks + 1) & 1], bfr[(ks + 1) & 1]);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma16(af[ks & 1], bfr[ks & 1]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // last quarter: slab kt is completely in registers / consumed from LDS
-    __builtin_amdgcn_s_waitcnt(0);                               // slab kt+1 landed, own LDS reads done
+  for (int s = 0; s < NB; ++s) stage(s, s);
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NB - 1) * LPS)); // slab 0 has landed
+  __syncthreads();
+  frags_a(0, 0, af[0]);
+  frags_b(0, 0, bfr[0]);
+  int buf = 0;
+  for (int kt = 0; kt < KT2; ++kt) {
+    const int nxt = buf + 1 < NB ? buf + 1 : 0;
+#pragma unroll
+    for (int ks = 0; ks < KS - 1; ++ks) step(af[ks & 1], bfr[ks & 1], buf, ks + 1, af[(ks + 1) & 1], bfr[(ks + 1) & 1]);
+    // last step: slab kt is completely in registers / consumed from LDS
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NB - 2) * LPS)); // slab kt+1 landed, own LDS reads done
     __syncthreads();
-    if (kt + 2 < KT2) stage(kt + 2, buf);
-    if (kt + 1 < KT2) frags(buf ^ 1, 0, af[KS & 1], bfr[KS & 1]);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma16(af[(KS - 1) & 1], bfr[(KS - 1) & 1]);
-    __builtin_amdgcn_sched_barrier(0);
+    stage(kt + NB, buf);
+    step(af[(KS - 1) & 1], bfr[(KS - 1) & 1], nxt, 0, af[KS & 1], bfr[KS & 1]);   // after the last slab: a landed buffer, values unused
+    buf = nxt;
   }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));               // the surplus loads of the tail land before the workgroup ends
 
   // acc[i][j][v] of lane l: row m = wm + i*32 + 8*(v/4) + 4*(l/32) + v%4, column n = wn + j*32 + l%32
 #pragma unroll
@@ -216,23 +259,31 @@ __global__ __launch_bounds__(256) void copy_bytes16_kernel(const uint4_t* __rest
   if (idx < n16) dst[idx] = src[idx];
 }
 
-template <int WT, int OUT>
-static int32_t launch_gemm_t(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, const float* bias, const float* res,
+template <int WT, int OUT, int BK, int NB>
+static int32_t launch_gemm_v(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, const float* bias, const float* res,
                              int64_t ldres, void* out, int64_t ldc, int64_t M, int N, int K, hipStream_t st) {
   constexpr int BM = 64 * WT;
   const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BM - 1) / BM;
   const int64_t grid = (int64_t)tiles_m * tiles_n;
-  const size_t lds_bytes = 4 * (size_t)BM * G_BK * 2;
+  const size_t lds_bytes = (size_t)NB * 2 * BM * BK * 2;
   static bool attr_set = false;                                  // more than 64 KiB of dynamic LDS has to be allowed once
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WT, OUT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WT, OUT, BK, NB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return fail(PHOTON_ERR_HIP, "gemm: cannot reserve %zu bytes of LDS: %s", lds_bytes, hipGetErrorString(e));
     attr_set = true;
   }
-  PHOTON_LAUNCH(cls, st, (gemm_bf16_kernel<WT, OUT>), dim3((unsigned)grid), dim3(G_THREADS), lds_bytes, st, A, A_lo, B, bias, res, ldres,
-                out, ldc, (int)M, N, K, tiles_m, tiles_n);
+  PHOTON_LAUNCH(cls, st, (gemm_bf16_kernel<WT, OUT, BK, NB>), dim3((unsigned)grid), dim3(G_THREADS), lds_bytes, st, A, A_lo, B, bias, res,
+                ldres, out, ldc, (int)M, N, K, tiles_m, tiles_n);
   return check_launch("gemm_bf16_kernel");
+}
+
+// Measured: 64-wide slabs in two buffers.  32-wide slabs in three to five buffers (up to 128 KB in flight per
+// compute unit instead of 64 KB) are no faster at the large shapes and slower at the decode-step shapes.
+template <int WT, int OUT>
+static int32_t launch_gemm_t(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, const float* bias, const float* res,
+                             int64_t ldres, void* out, int64_t ldc, int64_t M, int N, int K, hipStream_t st) {
+  return launch_gemm_v<WT, OUT, 64, 2>(cls, A, A_lo, B, bias, res, ldres, out, ldc, M, N, K, st);
 }
 
 // Largest tile that still gives the chip enough workgroups.
