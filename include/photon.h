@@ -334,6 +334,18 @@ PHOTON_API int32_t photon_hiergen_step(const photon_config* cfg, const photon_we
 PHOTON_API int32_t photon_hbm_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
 
 /* --------------------------------------------------------------------------
+ * Matrix-core probe for benchmarks: 256 workgroups of 4 waves, each wave
+ * issuing iters x 16 independent bf16 MFMA 32x32x16 on register operands, no
+ * memory traffic.  Timing it gives the rate the matrix cores sustain on this
+ * machine (the clock under matrix load depends on the operand values:
+ * random_operands != 0 uses values spread like N(0,1) data, 0 small constants),
+ * which the MFMA kernels' TFLOP/s can be set against.  Returns the number of
+ * floating-point operations the launch performs (0.0 on error).
+ * sink: 4 writable device bytes.
+ * -------------------------------------------------------------------------- */
+PHOTON_API double photon_mfma_probe(int32_t iters, int32_t random_operands, void* sink, void* stream);
+
+/* --------------------------------------------------------------------------
  * Per-kernel timing for benchmarks.  While enabled, every kernel launch of the
  * library carries a pair of HIP events attached to the dispatch itself (start
  * and end of the kernel as the command processor stamps them, on the launch

@@ -29,6 +29,7 @@ from .binding import (  # noqa: F401
     photon_kv_row_elems,
     photon_last_error,
     photon_linear,
+    photon_mfma_probe,
     photon_prefill,
     photon_prefill_workspace_bytes,
     photon_profile_enable,

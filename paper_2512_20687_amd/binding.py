@@ -186,6 +186,17 @@ def photon_hbm_read_probe(buf: torch.Tensor, sink: torch.Tensor) -> None:
     _check(lib.photon_hbm_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()))
 
 
+def photon_mfma_probe(iters: int, random_operands: bool, sink: torch.Tensor) -> float:
+    """Enqueues the matrix-core probe; returns the floating-point operations of the launch."""
+    lib = load_library()
+    lib.photon_mfma_probe.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.photon_mfma_probe.restype = C.c_double
+    flops = float(lib.photon_mfma_probe(iters, 1 if random_operands else 0, _ptr(sink), _stream()))
+    if flops == 0.0:
+        raise PhotonError(-1, lib.photon_last_error().decode())
+    return flops
+
+
 def photon_profile_enable(on: bool) -> None:
     _check(load_library().photon_profile_enable(1 if on else 0))
 

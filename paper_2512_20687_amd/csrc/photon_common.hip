@@ -76,6 +76,54 @@ extern "C" int32_t photon_hbm_read_probe(const void* buf, size_t bytes, void* si
   return check_launch("hbm_read_probe_kernel");
 }
 
+// ---- matrix-core loop without memory traffic: the ceiling the MFMA kernels are compared with -------
+namespace photon {
+typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+// One wave per SIMD, 16 independent 32x32 accumulators, operands fixed in registers.  random_operands: values
+// spread like N(0,1) data in every lane and element (what a contraction of real activations toggles in the
+// multipliers) instead of small constants; the chip's clock under the two differs.
+__global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, int random_operands, float* __restrict__ sink) {
+  probe_f32x16 acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  probe_bf16x8 a, b;
+  uint32_t h = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    h = h * 1664525u + 1013904223u;
+    a[e] = random_operands ? (__bf16)(((int)(h >> 16) - 32768) / 16384.0f) : (__bf16)(float)(threadIdx.x & 3);
+    h = h * 1664525u + 1013904223u;
+    b[e] = random_operands ? (__bf16)(((int)(h >> 16) - 32768) / 16384.0f) : (__bf16)1.0f;
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s += acc[i][e];
+  if (s == 1.2345e-30f) sink[0] = s;           // practically never: keeps the accumulators alive
+}
+}  // namespace photon
+
+extern "C" double photon_mfma_probe(int32_t iters, int32_t random_operands, void* sink, void* stream) {
+  using namespace photon;
+  clear_error();
+  if (sink == nullptr || iters < 1 || iters > (1 << 24)) {
+    fail(PHOTON_ERR_INVALID_ARG, "%s: sink is null or iters=%d outside [1, 2^24]", __func__, iters);
+    return 0.0;
+  }
+  constexpr int WGS = 256;                     // one workgroup of 4 waves per compute unit
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(WGS), dim3(256), 0, (hipStream_t)stream, (int)iters, (int)random_operands, (float*)sink);
+  if (check_launch("mfma_probe_kernel") != PHOTON_OK) return 0.0;
+  return (double)WGS * 4 * iters * 16 * (2.0 * 32 * 32 * 16);
+}
+
 extern "C" int32_t photon_profile_enable(int32_t on) {
   photon::g_profile_on = (on != 0);
   return PHOTON_OK;

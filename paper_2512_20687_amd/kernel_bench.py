@@ -70,6 +70,14 @@ def bench_probe():
         us = _time_us(lambda i: ph.photon_hbm_read_probe(big[(i % slots) * n:(i % slots) * n + n], sink), 4 * slots, warm=slots)
         _emit("hbm_read_probe_kernel", f"{mb} MB, rotating", us, bytes_=n)
     del big
+    # matrix cores alone: the rate they sustain (and so the clock they run at) depends on the operand values
+    fsink = torch.zeros(4, device="cuda")
+    for rnd, what in ((False, "small constant operands"), (True, "operands spread like N(0,1) data")):
+        flops = [0.0]
+        def go(i, rnd=rnd):
+            flops[0] = ph.photon_mfma_probe(100000, rnd, fsink)
+        us = _time_us(go, 3, warm=1)
+        _emit("mfma_probe_kernel", f"16 x MFMA 32x32x16 bf16 per wave and iteration, 1 wave per SIMD, {what}", us, flops=flops[0])
 
 
 def bench_a1():
