@@ -2,7 +2,7 @@
 //   * the context-chunker projection (paper Eq. 4) at many-row shapes: bf16 in, bf16 out;
 //   * the block projections of a decode step once a level carries many rows (large batches, deep
 //     hierarchies): fp32 activations are normalised and split into a bf16 head and a bf16 remainder by a
-//     row kernel, and the contraction runs over [head | remainder] against [W | W], so the product is as
+//     row kernel, and every slab of W meets the slab of heads and the slab of remainders, so the product is as
 //     accurate as fp32-activation x bf16-weight, as in the few-row kernels.
 //
 // One workgroup of 4 waves owns a (64 WT) x (64 WT) output tile, each wave a quadrant of WT x WT
@@ -49,10 +49,12 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 
 enum GemmOut { GEMM_OUT_BF16 = 0, GEMM_OUT_F32 = 1 };
 
-// WT: MFMA tiles per wave and dimension (tile edge 64 WT).  A_lo != nullptr: second pass over K with the
-// remainders.  OUT bf16: Cout bf16 [M, ldc] = acc + bias.  OUT fp32: Cout fp32 [M, ldc] = acc + bias + res.
-// BK: k per slab (64 or 32); NB: slab buffers in LDS (NB - 1 slabs are in flight while one is contracted).
-template <int WT, int OUT, int BK, int NB>
+// WT: MFMA tiles per wave and dimension (tile edge 64 WT).  OUT bf16: Cout bf16 [M, ldc] = acc + bias.  OUT fp32:
+// Cout fp32 [M, ldc] = acc + bias + res.  BK: k per slab (64 or 32); NB: slab buffers in LDS (NB - 1 slabs are
+// in flight while one is contracted).  SPLIT: x is given as heads A and remainders A_lo; a slab holds both next to
+// ONE slab of W, whose fragments meet both in registers (what bounds the kernel is the bytes a compute unit takes
+// in per MFMA: two passes over K would fetch W twice).
+template <int WT, int OUT, int BK, int NB, bool SPLIT>
 __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ A_lo, const bf16_t* __restrict__ B, const float* __restrict__ bias,
     const float* res, int64_t ldres, void* Cout, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n) {
@@ -62,8 +64,11 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
   constexpr int CPR = BK / 8;                                   // 16-byte columns per slab row
   constexpr int RPI = 64 / CPR;                                 // slab rows one load instruction covers
   constexpr int ROUNDS = BM / (4 * RPI);
-  constexpr int LPS = 2 * ROUNDS;                               // load instructions per slab and wave
-  extern __shared__ __align__(16) char lds[];                   // [NB buffers][A slab | B slab]
+  constexpr int OPS = SPLIT ? 3 : 2;                            // operand slabs per buffer: x (heads), [x remainders], W
+  constexpr int STAGE_BYTES = OPS * TILE_BYTES;
+  constexpr int B_OFF = (OPS - 1) * TILE_BYTES;
+  constexpr int LPS = OPS * ROUNDS;                             // load instructions per slab and wave
+  extern __shared__ __align__(16) char lds[];                   // [NB buffers][A slab | (A_lo slab) | B slab]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // scalar: the LDS targets of the direct loads are wave-uniform
 
@@ -91,20 +96,19 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
     bptr[i] = B + (int64_t)rb * K + c * 8;
   }
   const int KT = K / BK;
-  const int KT2 = A_lo != nullptr ? 2 * KT : KT;                 // slabs walked: heads, then remainders against the same W
+  const int KT2 = KT;
   // Always issues its loads (past the end: the last slab again, into a buffer nobody reads any more), so that the
   // number of loads in flight at every wait is a compile-time constant.
   auto stage = [&](int kt, int buf) {
     kt = kt < KT2 ? kt : KT2 - 1;
-    char* sa = lds + buf * 2 * TILE_BYTES;
-    char* sb = sa + TILE_BYTES;
-    const bf16_t* abase = kt < KT ? A : A_lo;
-    const int64_t kk = (int64_t)(kt < KT ? kt : kt - KT) * BK;
+    char* sa = lds + buf * STAGE_BYTES;
+    const int64_t kk = (int64_t)kt * BK;
 #pragma unroll
     for (int i = 0; i < ROUNDS; ++i) {
       const int off = (i * 4 + wave) * 1024;
-      load16_to_lds(abase + aoff[i] + kk, (uint32_t)(uintptr_t)(lptr_t)(sa + off));
-      load16_to_lds(bptr[i] + kk, (uint32_t)(uintptr_t)(lptr_t)(sb + off));
+      load16_to_lds(A + aoff[i] + kk, (uint32_t)(uintptr_t)(lptr_t)(sa + off));
+      if (SPLIT) load16_to_lds(A_lo + aoff[i] + kk, (uint32_t)(uintptr_t)(lptr_t)(sa + TILE_BYTES + off));
+      load16_to_lds(bptr[i] + kk, (uint32_t)(uintptr_t)(lptr_t)(sa + B_OFF + off));
     }
   };
 
@@ -129,15 +133,15 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
   // The fragment reads of the next step are issued in two halves (x rows, then W rows) around the first row of
   // MFMAs: the counter of outstanding LDS operations holds 15 at most, and with the 2 WT reads of the next step
   // on top of the 2 WT of the current one the compiler could no longer wait for the older ones alone.
-  bf16x8_t af[2][WT], bfr[2][WT];
-  auto frags_a = [&](int buf, int ks, bf16x8_t (&a)[WT]) {
-    const char* sa = lds + buf * 2 * TILE_BYTES;
+  bf16x8_t af[2][WT], afl[2][WT], bfr[2][WT];
+  auto frags_a = [&](int buf, int ks, bf16x8_t (&a)[WT], int which = 0) {
+    const char* sa = lds + buf * STAGE_BYTES + which * TILE_BYTES;
 #pragma unroll
     for (int i = 0; i < WT; ++i)
       a[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4_t*>(sa + swz<BK>(wm + i * 32 + frow, ks * 2 + fk)));
   };
   auto frags_b = [&](int buf, int ks, bf16x8_t (&b)[WT]) {
-    const char* sb = lds + buf * 2 * TILE_BYTES + TILE_BYTES;
+    const char* sb = lds + buf * STAGE_BYTES + B_OFF;
 #pragma unroll
     for (int i = 0; i < WT; ++i)
       b[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4_t*>(sb + swz<BK>(wn + i * 32 + frow, ks * 2 + fk)));
@@ -152,16 +156,26 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
 #pragma unroll
       for (int j = 0; j < WT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
   };
-  // one 16-wide step: contract (a, b) while the fragments of the following step (buffer nbuf, step nks) arrive in (na, nb)
-  auto step = [&](const bf16x8_t (&a)[WT], const bf16x8_t (&b)[WT], int nbuf, int nks, bf16x8_t (&na)[WT], bf16x8_t (&nb)[WT]) {
-    frags_a(nbuf, nks, na);
+  // one 16-wide step of register set `cur`: contract (heads, W) [and (remainders, W)] while the fragments of the
+  // following step (buffer nbuf, step nks) arrive in the other register set
+  auto step = [&](int cur, int nbuf, int nks) {
+    const int nx = cur ^ 1;
+    frags_a(nbuf, nks, af[nx]);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_first(a, b);
+    mfma_first(af[cur], bfr[cur]);
     __builtin_amdgcn_sched_barrier(0);
-    frags_b(nbuf, nks, nb);
+    if (SPLIT) frags_a(nbuf, nks, afl[nx], 1); else frags_b(nbuf, nks, bfr[nx]);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_rest(a, b);
+    mfma_rest(af[cur], bfr[cur]);
     __builtin_amdgcn_sched_barrier(0);
+    if (SPLIT) {
+      mfma_first(afl[cur], bfr[cur]);
+      __builtin_amdgcn_sched_barrier(0);
+      frags_b(nbuf, nks, bfr[nx]);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_rest(afl[cur], bfr[cur]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
 
 #pragma unroll
@@ -169,17 +183,18 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NB - 1) * LPS)); // slab 0 has landed
   __syncthreads();
   frags_a(0, 0, af[0]);
+  if (SPLIT) frags_a(0, 0, afl[0], 1);
   frags_b(0, 0, bfr[0]);
   int buf = 0;
   for (int kt = 0; kt < KT2; ++kt) {
     const int nxt = buf + 1 < NB ? buf + 1 : 0;
 #pragma unroll
-    for (int ks = 0; ks < KS - 1; ++ks) step(af[ks & 1], bfr[ks & 1], buf, ks + 1, af[(ks + 1) & 1], bfr[(ks + 1) & 1]);
+    for (int ks = 0; ks < KS - 1; ++ks) step(ks & 1, buf, ks + 1);
     // last step: slab kt is completely in registers / consumed from LDS
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NB - 2) * LPS)); // slab kt+1 landed, own LDS reads done
     __syncthreads();
     stage(kt + NB, buf);
-    step(af[(KS - 1) & 1], bfr[(KS - 1) & 1], nxt, 0, af[KS & 1], bfr[KS & 1]);   // after the last slab: a landed buffer, values unused
+    step((KS - 1) & 1, nxt, 0);                                  // after the last slab: a landed buffer, values unused
     buf = nxt;
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));               // the surplus loads of the tail land before the workgroup ends
@@ -259,21 +274,21 @@ __global__ __launch_bounds__(256) void copy_bytes16_kernel(const uint4_t* __rest
   if (idx < n16) dst[idx] = src[idx];
 }
 
-template <int WT, int OUT, int BK, int NB>
+template <int WT, int OUT, int BK, int NB, bool SPLIT>
 static int32_t launch_gemm_v(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, const float* bias, const float* res,
                              int64_t ldres, void* out, int64_t ldc, int64_t M, int N, int K, hipStream_t st) {
   constexpr int BM = 64 * WT;
   const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BM - 1) / BM;
   const int64_t grid = (int64_t)tiles_m * tiles_n;
-  const size_t lds_bytes = (size_t)NB * 2 * BM * BK * 2;
+  const size_t lds_bytes = (size_t)NB * (SPLIT ? 3 : 2) * BM * BK * 2;
   static bool attr_set = false;                                  // more than 64 KiB of dynamic LDS has to be allowed once
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WT, OUT, BK, NB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WT, OUT, BK, NB, SPLIT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return fail(PHOTON_ERR_HIP, "gemm: cannot reserve %zu bytes of LDS: %s", lds_bytes, hipGetErrorString(e));
     attr_set = true;
   }
-  PHOTON_LAUNCH(cls, st, (gemm_bf16_kernel<WT, OUT, BK, NB>), dim3((unsigned)grid), dim3(G_THREADS), lds_bytes, st, A, A_lo, B, bias, res,
+  PHOTON_LAUNCH(cls, st, (gemm_bf16_kernel<WT, OUT, BK, NB, SPLIT>), dim3((unsigned)grid), dim3(G_THREADS), lds_bytes, st, A, A_lo, B, bias, res,
                 ldres, out, ldc, (int)M, N, K, tiles_m, tiles_n);
   return check_launch("gemm_bf16_kernel");
 }
@@ -283,7 +298,12 @@ static int32_t launch_gemm_v(int cls, const bf16_t* A, const bf16_t* A_lo, const
 template <int WT, int OUT>
 static int32_t launch_gemm_t(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, const float* bias, const float* res,
                              int64_t ldres, void* out, int64_t ldc, int64_t M, int N, int K, hipStream_t st) {
-  return launch_gemm_v<WT, OUT, 64, 2>(cls, A, A_lo, B, bias, res, ldres, out, ldc, M, N, K, st);
+  if constexpr (OUT == GEMM_OUT_F32) {
+    // heads and remainders in one pass: 32-wide slabs of three operands in three buffers (144 KB at the 256-wide
+    // tile); measured 5 % ahead of two buffers, and 14-16 % ahead of two passes over K on whole decode steps
+    if (A_lo != nullptr) return launch_gemm_v<WT, OUT, 32, 3, true>(cls, A, A_lo, B, bias, res, ldres, out, ldc, M, N, K, st);
+  }
+  return launch_gemm_v<WT, OUT, 64, 2, false>(cls, A, nullptr, B, bias, res, ldres, out, ldc, M, N, K, st);
 }
 
 // Largest tile that still gives the chip enough workgroups.
