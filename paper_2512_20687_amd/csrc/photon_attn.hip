@@ -238,12 +238,14 @@ int32_t launch_coarse_attn(KvType kv, bool q_f32, int d_h, const void* q, const 
 }
 
 int32_t coarse_auto_splits(int Bt, int H, int64_t S_max) {
-  // About 768 workgroups (3 per CU): measured 80 % of the HBM peak at 128 streams x 8200 keys for any cache
-  // pitch (one workgroup per CU is as fast only when the pitch S_max*d_h is a multiple of 16 KB: otherwise the
-  // streams start on skewed memory channels and few large splits collide; more splits lengthen the merge);
-  // every split still streams at least 512 keys.
+  // Short streams (the benchmark shape: 128 streams x 8200 keys): about 768 workgroups (3 per CU), measured 80 %
+  // of the HBM peak for any cache pitch (one workgroup per CU is as fast only when the pitch S_max*d_h is a
+  // multiple of 16 KB: otherwise the streams start on skewed memory channels and few large splits collide; more
+  // splits lengthen the merge).  Long streams (4096 keys or more per split): about 1024 workgroups (4 per CU, all
+  // resident at once), measured 87 % against 81 % at 128 streams x 131072 keys.  Every split streams at least 512 keys.
   const int64_t streams = (int64_t)Bt * H;
-  int64_t want = (768 + streams - 1) / streams;
+  int64_t want = (1024 + streams - 1) / streams;
+  if (S_max / want < 4096) want = (768 + streams - 1) / streams;
   int64_t cap = S_max / 512;
   if (cap < 1) cap = 1;
   if (want > cap) want = cap;
