@@ -142,8 +142,9 @@ PHOTON_API int32_t photon_chunk_local_attn(const void* q, const void* k, const v
  *   workspace             photon_encoder_attn_workspace_bytes(...) bytes,
  *                         device, caller-owned (0 bytes for fp32)
  * dt PHOTON_BF16: matrix-core kernel, d_h a multiple of 4 up to 64 (operand
- * rows are zero-padded to 64); scores from bf16 head + remainder operands,
- * probabilities and values rounded to bf16.
+ * rows are zero-padded to 64); q, k, v and the probabilities enter the
+ * matrix cores as fp16 (11 significant bits, values saturated at 65504),
+ * accumulation in fp32.
  * dt PHOTON_F32: fp32 vector kernel, d_h a multiple of 4 in [16, 64].
  * Bt*H <= 65535.  Bt == 0 or M == 0 is a no-op.  Nothing is allocated or
  * synchronised; errors are reported by status + photon_last_error().

@@ -113,6 +113,18 @@ __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g));
 
 // operand of the bf16 matrix-core instructions: 8 consecutive k of one row
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2_native __attribute__((ext_vector_type(2)));
+// Two fp32 values rounded to nearest-even fp16, saturated to the largest finite fp16, packed (lo in bits 0..15).
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+  const float2_native v = {fminf(fmaxf(lo, -65504.f), 65504.f), fminf(fmaxf(hi, -65504.f), 65504.f)};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_native));
+}
+// Same without the saturation, for values known to lie in [0, 1].
+__device__ __forceinline__ uint32_t pack_f16x2_unit(float lo, float hi) {
+  const float2_native v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_native));
+}
 __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4_t& v) { return __builtin_bit_cast(bf16x8_t, v); }
 
 // cos and sin of the rotary angle pos * theta^(-2i/d_h); the angle is formed in double because positions reach 10^5

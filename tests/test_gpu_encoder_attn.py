@@ -55,9 +55,9 @@ def run(dtype, Bt, M, H, d_h, theta, with_cache, seed=0, S_max=None):
 def test_encoder_attn_bf16(Bt, M, H):
     require_gpu()
     out, ref, kc, vc, kref, vref = run("bf16", Bt, M, H, 64, 10000.0, True)
-    # scores carry fp32-level accuracy; probabilities and values are rounded to bf16 (2^-9 each)
+    # q, k, v and the probabilities are rounded to fp16 (2^-12 each) on their way into the matrix cores
     assert nerr(out, ref) <= TOL["bf16"]
-    assert nerr(out, ref) <= 6e-3
+    assert nerr(out, ref) <= 1.5e-3
     assert nerr(kc[:, :, :M].float(), kref) <= 2.0 ** -8
     assert nerr(vc[:, :, :M].float(), vref) <= 2.0 ** -8
 
@@ -67,15 +67,32 @@ def test_encoder_attn_bf16_padded_head(Bt, M, H, d_h):
     """Head sizes of the paper's models (Appendix tables) and other sizes below 64: operand rows zero-padded to 64."""
     require_gpu()
     out, ref, kc, vc, kref, vref = run("bf16", Bt, M, H, d_h, 10000.0, True, seed=6)
-    assert nerr(out, ref) <= 6e-3
+    assert nerr(out, ref) <= 1.5e-3
     assert nerr(kc[:, :, :M].float(), kref) <= 2.0 ** -8
     assert nerr(vc[:, :, :M].float(), vref) <= 2.0 ** -8
+
+
+def test_encoder_attn_bf16_large_scores():
+    """Scores sixteen times the usual size (q, k of deviation 4): the fp16 roundings of q and k show, and stay far
+    inside the tolerance of a bf16 configuration; values beyond the fp16 range saturate instead of overflowing."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    Bt, M, H, d_h = 1, 500, 2, 64
+    qkv = 4.0 * si.make_normal((Bt * M, 3 * H * d_h), 21, "f32")
+    ref, _, _ = oracle_attn(qkv, Bt, M, H, d_h, 10000.0)
+    out = torch.full((Bt * M, H * d_h), float("nan"), device="cuda")
+    ws = torch.empty(ph.photon_encoder_attn_workspace_bytes(Bt, M, H, d_h, True), dtype=torch.uint8, device="cuda")
+    ph.photon_encoder_attn(dev(qkv), out, Bt, M, H, d_h, workspace=ws, bf16=True)
+    assert nerr(out, ref) <= 1e-2
+    qkv[:, 2 * H * d_h:] = 1e6                                      # v far outside the fp16 range: finite (saturated) output
+    ph.photon_encoder_attn(dev(qkv), out, Bt, M, H, d_h, workspace=ws, bf16=True)
+    assert bool(torch.isfinite(out).all()) and abs(float(out.max()) / 65504.0 - 1.0) < 1e-3
 
 
 def test_encoder_attn_bf16_no_rotary_no_cache():
     require_gpu()
     out, ref, *_ = run("bf16", 2, 300, 2, 64, 0.0, False, seed=4)
-    assert nerr(out, ref) <= 6e-3
+    assert nerr(out, ref) <= 1.5e-3
 
 
 @pytest.mark.parametrize("Bt,M,H,d_h", [(1, 1, 1, 32), (2, 70, 2, 32), (1, 150, 3, 16), (2, 65, 1, 64), (2, 90, 2, 52), (1, 77, 3, 60)])
