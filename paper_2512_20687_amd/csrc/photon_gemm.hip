@@ -47,10 +47,13 @@ constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 0xF) | ((vm >> 4) << 14) |
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-enum GemmOut { GEMM_OUT_BF16 = 0, GEMM_OUT_F32 = 1 };
+enum GemmOut { GEMM_OUT_BF16 = 0, GEMM_OUT_F32 = 1, GEMM_OUT_SWIGLU = 2 };
 
 // WT: MFMA tiles per wave and dimension (tile edge 64 WT).  OUT bf16: Cout bf16 [M, ldc] = acc + bias.  OUT fp32:
-// Cout fp32 [M, ldc] = acc + bias + res.  BK: k per slab (64 or 32); NB: slab buffers in LDS (NB - 1 slabs are
+// Cout fp32 [M, ldc] = acc + bias + res.  OUT SwiGLU (WT even): B has 2N rows, gate rows then up rows; a tile covers
+// 32 WT output columns and takes the gate rows of 32 columns into the even MFMA column tiles of a wave and the up
+// rows of the same columns into the odd ones, so that silu(gate) * up is formed in registers:
+// Cout fp32 [M, ldc] = silu(x Wg^T) * (x Wu^T).  BK: k per slab (64 or 32); NB: slab buffers in LDS (NB - 1 slabs are
 // in flight while one is contracted).  SPLIT: x is given as heads A and remainders A_lo; a slab holds both next to
 // ONE slab of W, whose fragments meet both in registers (what bounds the kernel is the bytes a compute unit takes
 // in per MFMA: two passes over K would fetch W twice).
@@ -78,7 +81,9 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
   const int id = blockIdx.x;
   const int logical = (total % 8 == 0) ? (id & 7) * (total / 8) + (id >> 3) : id;   // ragged tile count: plain order
   const int tm = logical / tiles_n, tn = logical % tiles_n;
-  const int m0 = tm * BM, n0 = tn * BM;
+  constexpr bool GU = (OUT == GEMM_OUT_SWIGLU);
+  static_assert(!GU || WT % 2 == 0, "the gate/up pairing needs an even number of column tiles per wave");
+  const int m0 = tm * BM, n0 = tn * (GU ? BM / 2 : BM);
 
   // global -> LDS without passing through registers: one instruction moves 64 lanes x 16 B = RPI slab rows;
   // lane l lands at LDS row l/CPR, 16-byte column l%CPR, so it fetches the logical column that the XOR
@@ -91,7 +96,14 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
     const int r = (i * 4 + wave) * RPI + srow;
     const int c = (swz<BK>(r, scol) - r * (BK * 2)) >> 4;       // the swizzle is an involution on the column index
     int ra = m0 + r; ra = ra < M ? ra : M - 1;                   // clamped rows are never stored
-    int rb = n0 + r; rb = rb < N ? rb : N - 1;
+    int rb = n0 + r;
+    if (GU) {                                                   // tile row -> output column and gate / up
+      const int rr = r % WE, jj = rr >> 5;
+      rb = n0 + (r / WE) * (WE / 2) + (jj >> 1) * 32 + (rr & 31);
+      rb = (rb < N ? rb : N - 1) + (jj & 1) * N;
+    } else {
+      rb = rb < N ? rb : N - 1;
+    }
     aoff[i] = (int64_t)ra * K + c * 8;
     bptr[i] = B + (int64_t)rb * K + c * 8;
   }
@@ -200,6 +212,23 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));               // the surplus loads of the tail land before the workgroup ends
 
   // acc[i][j][v] of lane l: row m = wm + i*32 + 8*(v/4) + 4*(l/32) + v%4, column n = wn + j*32 + l%32
+  if constexpr (GU) {
+#pragma unroll
+    for (int j = 0; j < WT; j += 2) {
+      const int n = n0 + (wn / WE) * (WE / 2) + (j >> 1) * 32 + (lane & 31);
+      if (n >= N) continue;
+#pragma unroll
+      for (int i = 0; i < WT; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          if (m >= M) continue;
+          reinterpret_cast<float*>(Cout)[(int64_t)m * ldc + n] = silu(acc[i][j][v]) * acc[i][j + 1][v];
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < WT; ++j) {
     const int n = n0 + wn + j * 32 + (lane & 31);
@@ -278,7 +307,8 @@ template <int WT, int OUT, int BK, int NB, bool SPLIT>
 static int32_t launch_gemm_v(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, const float* bias, const float* res,
                              int64_t ldres, void* out, int64_t ldc, int64_t M, int N, int K, hipStream_t st) {
   constexpr int BM = 64 * WT;
-  const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BM - 1) / BM;
+  constexpr int BN = (OUT == GEMM_OUT_SWIGLU) ? BM / 2 : BM;   // output columns of a tile
+  const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
   const int64_t grid = (int64_t)tiles_m * tiles_n;
   const size_t lds_bytes = (size_t)NB * (SPLIT ? 3 : 2) * BM * BK * 2;
   static bool attr_set = false;                                  // more than 64 KiB of dynamic LDS has to be allowed once
@@ -298,7 +328,7 @@ static int32_t launch_gemm_v(int cls, const bf16_t* A, const bf16_t* A_lo, const
 template <int WT, int OUT>
 static int32_t launch_gemm_t(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, const float* bias, const float* res,
                              int64_t ldres, void* out, int64_t ldc, int64_t M, int N, int K, hipStream_t st) {
-  if constexpr (OUT == GEMM_OUT_F32) {
+  if constexpr (OUT != GEMM_OUT_BF16) {
     // heads and remainders in one pass: 32-wide slabs of three operands in three buffers (144 KB at the 256-wide
     // tile); measured 5 % ahead of two buffers, and 14-16 % ahead of two passes over K on whole decode steps
     if (A_lo != nullptr) return launch_gemm_v<WT, OUT, 32, 3, true>(cls, A, A_lo, B, bias, res, ldres, out, ldc, M, N, K, st);
@@ -324,6 +354,18 @@ static int32_t launch_gemm(int cls, const bf16_t* A, const bf16_t* A_lo, const b
   }
 }
 
+// SwiGLU in the epilogue: N output columns from 2N rows of W.  Returns false when the problem is too small for a
+// tile with paired column tiles (the caller then contracts into a [M, 2N] buffer and applies SwiGLU by rows).
+static bool launch_gemm_swiglu(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, float* out, int64_t ldc, int64_t M, int N,
+                               int K, hipStream_t st, int32_t* rc) {
+  auto tiles = [&](int wt) { return ((M + 64 * wt - 1) / (64 * wt)) * ((N + 32 * wt - 1) / (32 * wt)); };
+  if (A_lo == nullptr) return false;
+  if (tiles(4) >= 192) *rc = launch_gemm_t<4, GEMM_OUT_SWIGLU>(cls, A, A_lo, B, nullptr, nullptr, 0, out, ldc, M, N, K, st);
+  else if (tiles(2) >= 128) *rc = launch_gemm_t<2, GEMM_OUT_SWIGLU>(cls, A, A_lo, B, nullptr, nullptr, 0, out, ldc, M, N, K, st);
+  else return false;
+  return true;
+}
+
 static int32_t launch_chunker_gemm(const void* x, const void* w, const float* bias, void* out, int64_t M, int N, int K, hipStream_t st) {
   return launch_gemm<GEMM_OUT_BF16>(KC_CHUNKER_GEMM, (const bf16_t*)x, nullptr, (const bf16_t*)w, bias, nullptr, 0, out, N, M, N, K, st);
 }
@@ -343,6 +385,8 @@ int32_t launch_linear_many(const LinearArgs& a, void* workspace, int K_max, hipS
   PHOTON_TRY(check_launch("norm_split_rows_kernel"));
   if (a.epilogue == EPI_SWIGLU) {
     if (a.N % 4 != 0) return fail(PHOTON_ERR_UNSUPPORTED, "many-row linear: SwiGLU width %d must be a multiple of 4", a.N);
+    int32_t rc = PHOTON_OK;
+    if (launch_gemm_swiglu(KC_CHUNKER_GEMM, hi, lo, (const bf16_t*)a.W, a.out, a.ldo, a.M, a.N, a.K, st, &rc)) return rc;
     PHOTON_TRY(launch_gemm<GEMM_OUT_F32>(KC_CHUNKER_GEMM, hi, lo, (const bf16_t*)a.W, nullptr, nullptr, 0, gu, 2 * (int64_t)a.N, a.M, 2 * a.N,
                                          a.K, st));
     PHOTON_LAUNCH(KC_SILU_MUL, st, swiglu_rows_kernel, dim3(a.M), dim3(256), 0, st, gu, a.out, a.ldo, a.N);
