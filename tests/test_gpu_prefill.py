@@ -128,6 +128,22 @@ def test_bf16_prefill_wide_rows():
     print(errs)
 
 
+def test_bf16_prefill_ragged_widths():
+    """Widths that are no multiples of the MFMA tile edges (448 = 7 x 64 columns, SwiGLU width 704 = 5.5 x 128), heads of
+    56: the last tile column of every linear map is partly empty, in the paired gate/up tiles as well."""
+    require_gpu()
+    cfg = si.PhotonConfig(L=2, C=(4, 4), R=(2, 2), D=448, H=8, d_h=56, n_layers=1, d_ff=704, vocab=512, dtype="bf16",
+                          concat_level1=True)
+    w = si.make_weights(cfg, 43)
+    Bt, T = 8, 4096
+    toks = si.make_tokens(cfg.vocab, Bt, T, 9)
+    S_max = T // cfg.meta_context + 2
+    ost = po.prefill(cfg, po.weights_to_f64(w), toks, S_max)
+    model, state = gpu_prefill(cfg, w, toks, S_max)
+    errs = check_state(cfg, state, ost, Bt, TOL["bf16"], 2.0 ** -7)
+    print(errs)
+
+
 def test_encoder_attn_long_sequence_sampled_queries():
     """8192 positions (the top encoder's length in configuration 3); the oracle computes a sample of the queries."""
     require_gpu()
