@@ -82,7 +82,7 @@ def test_coarse_is_deterministic_and_split_invariant():
     assert nerr(c, ref) <= TOL["bf16"] and nerr(a, ref) <= TOL["bf16"]
 
 
-@pytest.mark.parametrize("name,S", [("cfg3_bf16_128k", 8448), ("cfg2_bf16_8k", 640)])
+@pytest.mark.parametrize("name,S", [("cfg3_bf16_128k", 8448), ("cfg2_bf16_8k", 640), ("cfg4_bf16_serving", 2112)])
 def test_coarse_full_size_sampled_streams(name, S):
     """The configuration's real shape, in the launch configuration the bench uses
     (automatic split count); the oracle computes a sample of (b, h) streams."""
@@ -180,3 +180,25 @@ def test_local_tile_full_size_sampled_chunks(name, level):
     ti = torch.tensor(idx, device="cuda")
     ref = po.chunk_local_attn(q[ti].float().cpu().numpy(), k[ti].float().cpu().numpy(), v[ti].float().cpu().numpy(), 0, 1 / math.sqrt(d_h))
     assert nerr(out[ti], ref) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("n,W,H", [(32768, 8, 32), (131072, 4, 32)])      # configuration 5 level 1; configuration 3 token level (a slice)
+def test_local_tile_full_size_sampled_chunks(n, W, H):
+    """Tile mode at the configurations' real chunk counts (1 GiB per operand); the oracle computes a sample of chunks."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    d_h = 64
+    g = torch.Generator(device="cuda").manual_seed(17)
+    q = torch.randn((n, W, H, d_h), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    k = torch.randn((n, W, H, d_h), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn((n, W, H, d_h), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    ph.photon_chunk_local_attn(q, k, v, out, q_pos=0)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(1)
+    idx = sorted({0, n - 1} | {int(rng.integers(n)) for _ in range(30)})
+    sel = torch.tensor(idx, device="cuda")
+    ref = po.chunk_local_attn(q[sel].float().cpu().numpy(), k[sel].float().cpu().numpy(), v[sel].float().cpu().numpy(), 0, 1 / math.sqrt(d_h))
+    assert nerr(out[sel], ref) <= TOL["bf16"]
+    assert bool(torch.isfinite(out.float()).all())
+
