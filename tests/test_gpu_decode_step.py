@@ -227,3 +227,23 @@ def test_full_width_step_one_block_per_module():
     forced = si.make_tokens(cfg.vocab, wl.Bt, cfg.meta_context, 10)
     errs, _, _ = check_against_oracle(cfg, w, st, wl.Bt, S_max, forced, TOL["bf16"])
     assert errs["logits"] <= 1e-3, errs      # fp32 activations x bf16 weights: far inside the bf16 bar
+
+
+@pytest.mark.parametrize("name,Bt,S", [
+    ("cfg4_bf16_serving", 128, 2048),      # 128 sequences: every level, the top one included, runs the tiled MFMA contraction
+    ("cfg5_bf16_3level", 2, 64),           # three levels of 8: 128 rows at the token level, 16 and 2 above
+    ("paper_600m", 32, 128),               # the paper's 600M shape: heads of 52, converter length 2
+])
+def test_full_width_step_other_configurations(name, Bt, S):
+    """The other configurations at their real widths and vocabulary, one block per module and a reduced batch so
+    that the float64 oracle finishes in seconds; every intermediate is compared."""
+    require_gpu()
+    wl = si.WORKLOADS[name]
+    cfg = si.shrink(wl.cfg, n_layers=1)
+    w = si.make_weights(cfg, 18, encoders=False)
+    S_max = S + 64
+    st = si.make_decode_state(cfg, Bt, S, S_max, seed=19)
+    forced = si.make_tokens(cfg.vocab, Bt, cfg.meta_context, 20)
+    errs, _, _ = check_against_oracle(cfg, w, st, Bt, S_max, forced, TOL["bf16"])
+    assert errs["logits"] <= 1e-3, errs
+
