@@ -50,6 +50,54 @@ def weights_to_f64(w):
 # modules are LLaMA Transformer blocks; Appendix C.2 tables give their shape)
 # --------------------------------------------------------------------------
 
+# --------------------------------------------------------------------------
+# 8-bit storage of the coarse K/V cache (a variant beyond the paper, which
+# states no storage precision).  reading G17: the OCP 8-bit floating-point
+# format E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no
+# infinities, the all-ones pattern is NaN, largest finite value 448), round to
+# nearest even from the value being stored, saturating, no scale factor.
+# --------------------------------------------------------------------------
+
+def e4m3_decode(codes):
+    """Values of E4M3 bit patterns: (-1)^s 2^(e-7) (1 + m/8) for e > 0,
+    (-1)^s 2^(-6) (m/8) for e = 0; e = 15, m = 7 is NaN."""
+    c = np.asarray(codes).astype(np.int64)
+    s, e, m = c >> 7, (c >> 3) & 15, c & 7
+    v = np.where(e > 0, np.ldexp(1.0 + m / 8.0, e - 7), np.ldexp(m / 8.0, -6))
+    v = np.where((e == 15) & (m == 7), np.nan, v)
+    return np.where(s == 1, -v, v)
+
+
+def e4m3_encode(x):
+    """Nearest E4M3 value, ties to the even mantissa, magnitudes beyond 448
+    stored as 448 (NaN stays NaN).  Returns uint8 bit patterns."""
+    x = f64(x)
+    a = np.where(np.isnan(x), 0.0, np.minimum(np.abs(x), 448.0))
+    _, ex = np.frexp(a)                             # a = f * 2^ex with f in [0.5, 1): floor(log2 a) = ex - 1
+    e = np.maximum(ex - 1, -6)                      # below 2^-6 the spacing stays that of the smallest binade
+    q = np.rint(np.ldexp(a, 3 - e))                 # a in units of the spacing 2^(e-3); rint rounds ties to even
+    v = np.ldexp(q, e - 3)                          # may have stepped into the next binade: still a grid point
+    _, ex2 = np.frexp(v)
+    e2 = np.maximum(ex2 - 1, -6)
+    m = np.rint(np.ldexp(v, 3 - e2)).astype(np.int64)        # 8..15 for normal numbers, 0..7 for subnormal ones
+    normal = m >= 8
+    code = np.where(normal, ((e2 + 7) << 3) | (m - 8), m)
+    code = np.where(np.signbit(x), code | 0x80, code)
+    code = np.where(np.isnan(x), 0x7F, code)
+    return code.astype(np.uint8)
+
+
+def e4m3_round(x):
+    """x as it reads back from E4M3 storage."""
+    return e4m3_decode(e4m3_encode(x))
+
+
+def kv_store(cfg, x):
+    """What the coarse K/V cache holds for the value x: x itself, or its E4M3
+    rounding when the configuration stores the cache in 8 bits (reading G17)."""
+    return e4m3_round(x) if getattr(cfg, "kv_dtype", "") == "fp8" else f64(x)
+
+
 def rmsnorm(x, g, eps):
     """RMSNorm of the last axis: x * g / sqrt(mean(x^2) + eps).
     reading: eps inside the square root, default 1e-5 (the paper gives neither)."""
@@ -106,7 +154,7 @@ def _mlp(h, lay, cfg):
     return h + linear(act, lay["wd"])
 
 
-def block_step(x, pos, lay, kc, vc, length, cfg):
+def block_step(x, pos, lay, kc, vc, length, cfg, store=None):
     """One LLaMA block applied to one new vector per stream, with a KV cache.
 
     x [n, D]: the new input of each of n independent streams, at position
@@ -116,7 +164,8 @@ def block_step(x, pos, lay, kc, vc, length, cfg):
     Returns y [n, D].  The caller advances `length`.
     (STEP operator, Eq. 12 / Appendix A.1; block structure: reading G1 —
     pre-RMSNorm, multi-head attention with as many KV heads as heads, SwiGLU,
-    no biases — which is what reproduces the printed parameter counts.)"""
+    no biases — which is what reproduces the printed parameter counts.)
+    store: what the cache keeps of a value (identity if None; see kv_store)."""
     x = f64(x)
     n = x.shape[0]
     H, d_h = cfg.H, cfg.d_h
@@ -130,19 +179,19 @@ def block_step(x, pos, lay, kc, vc, length, cfg):
     o = np.empty((n, H, d_h), F64)
     for i in range(n):
         m = int(length[i])
-        kc[i, :, m] = k[i]
-        vc[i, :, m] = v[i]
+        kc[i, :, m] = k[i] if store is None else store(k[i])
+        vc[i, :, m] = v[i] if store is None else store(v[i])
         o[i] = attend(q[i], kc[i, :, : m + 1], vc[i, :, : m + 1], scale)
     h = x + linear(o.reshape(n, H * d_h), lay["wo"])
     return _mlp(h, lay, cfg)
 
 
-def module_step(x, pos, mod, caches, length, cfg):
+def module_step(x, pos, mod, caches, length, cfg, store=None):
     """All blocks of a module on one new vector per stream, then the module's
     final RMSNorm.  caches: list over layers of (kc, vc)."""
     h = f64(x)
     for lay, (kc, vc) in zip(mod["layers"], caches):
-        h = block_step(h, pos, lay, kc, vc, length, cfg)
+        h = block_step(h, pos, lay, kc, vc, length, cfg, store)
     return rmsnorm(h, mod["g_final"], cfg.rms_eps)
 
 
@@ -373,9 +422,9 @@ def prefill(cfg, w, tokens, S_max):
     carry = np.empty((max(cfg.L - 1, 0), Bt, cfg.D), F64)
     for b in range(Bt):
         r = teacher_forced_forward(cfg, w, tokens[b])
-        for i, (K, V) in enumerate(r["kv_top"]):
-            k[i, b, :, :G] = K
-            v[i, b, :, :G] = V
+        for i, (K, V) in enumerate(r["kv_top"]):        # the encoder attended to K, V as computed; the cache keeps kv_store of them
+            k[i, b, :, :G] = kv_store(cfg, K)
+            v[i, b, :, :G] = kv_store(cfg, V)
         x_top[b] = r["X"][cfg.L][-1]
         for l in range(1, cfg.L):
             carry[l - 1, b] = r["Xh"][l][-1]
@@ -392,7 +441,7 @@ def top_step(cfg, w, a, state, counters=None):
         # every layer reads K and V of all entries including the new one
         counters["kv_elems_read"] = counters.get("kv_elems_read", 0) + int(
             2 * cfg.n_layers * cfg.H * cfg.d_h * np.sum(length + 1))
-    x = module_step(a, length, mod, caches, length, cfg)
+    x = module_step(a, length, mod, caches, length, cfg, store=lambda t: kv_store(cfg, t))
     state["seq_len"] = length + 1
     state["x_top"] = x
     return x
@@ -497,8 +546,8 @@ def hier_prefill(cfg, w, tokens, S_max):
         for l in range(1, cfg.L):
             M = kvs[l][0][0].shape[1]
             for i, (K, V) in enumerate(kvs[l]):
-                state["enc_k"][l - 1][i, b, :, :M] = K
-                state["enc_v"][l - 1][i, b, :, :M] = V
+                state["enc_k"][l - 1][i, b, :, :M] = kv_store(cfg, K)
+                state["enc_v"][l - 1][i, b, :, :M] = kv_store(cfg, V)
             state["enc_len"][l - 1][b] = M
     return state
 
@@ -524,7 +573,7 @@ def hier_reencode(cfg, w, state, tokens, counters=None):
             if counters is not None:
                 counters["kv_elems_read"] = counters.get("kv_elems_read", 0) + int(
                     2 * cfg.n_layers * cfg.H * cfg.d_h * np.sum(length + 1))
-            out[:, j] = module_step(a[:, j], length, e["module"], caches, length, cfg)
+            out[:, j] = module_step(a[:, j], length, e["module"], caches, length, cfg, store=lambda t: kv_store(cfg, t))
             state["enc_len"][l - 1] = length + 1
         x = out
     return x

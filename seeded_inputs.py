@@ -41,11 +41,14 @@ class PhotonConfig:
     # The paper's models (Appendix tables "PHOTON (600M)" ..): encoder-side token embeddings of width D / C_1 and a
     # parameter-free level-1 chunker that puts C_1 of them side by side (416 * 4 = 1664).
     concat_level1: bool = False
+    # storage of the coarse K/V caches: "" = as `dtype`; "fp8" = 8-bit floating point (E4M3), with dtype "bf16" only
+    kv_dtype: str = ""
 
     def __post_init__(self):
         assert len(self.C) == self.L and len(self.R) == self.L
         assert self.H * self.d_h == self.D
         assert not self.concat_level1 or (self.L >= 2 and self.D % self.C[0] == 0)
+        assert self.kv_dtype in ("", "fp8") and (self.kv_dtype == "" or self.dtype == "bf16")
         assert self.dtype in ("f32", "bf16")
 
     @property

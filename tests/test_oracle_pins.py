@@ -480,3 +480,76 @@ def test_kv_byte_model():
         po.decode_step(cfg, w, st, counters=counters)
     assert counters["kv_elems_read"] == 2 * cfg.n_layers * cfg.D * 2 * po.kv_read_units(3, 3)
     assert list(st["seq_len"]) == [6, 6]
+
+
+# ---------------------------------------------------------------- 8-bit cache storage (reading G17)
+
+def _e4m3_table():
+    """All 256 bit patterns decoded field by field (sign, 4-bit exponent with bias 7, 3-bit mantissa), in plain Python."""
+    vals = []
+    for c in range(256):
+        s, e, m = c >> 7, (c >> 3) & 15, c & 7
+        if e == 15 and m == 7:
+            v = float("nan")
+        elif e == 0:
+            v = (m / 8.0) * 2.0 ** -6
+        else:
+            v = (1.0 + m / 8.0) * 2.0 ** (e - 7)
+        vals.append(-v if s else v)
+    return np.array(vals)
+
+
+def test_e4m3_codes_and_rounding():
+    tab = _e4m3_table()
+    codes = np.arange(256, dtype=np.uint8)
+    dec = po.e4m3_decode(codes)
+    assert np.array_equal(np.isnan(dec), np.isnan(tab)) and np.array_equal(dec[~np.isnan(tab)], tab[~np.isnan(tab)])
+    # landmarks of the format: 1.0, largest finite, smallest subnormal, smallest normal
+    assert dec[0x38] == 1.0 and dec[0x7E] == 448.0 and dec[0x01] == 2.0 ** -9 and dec[0x08] == 2.0 ** -6 and dec[0xB8] == -1.0
+    finite = ~np.isnan(tab)
+    # every representable value is a fixed point, bit pattern included (+0 and -0 both)
+    assert np.array_equal(po.e4m3_encode(tab[finite]), codes[finite])
+    # nearest value, found by brute force over the table, for a dense sweep; ties excluded here
+    pos = np.sort(tab[finite & (tab >= 0)])
+    x = np.concatenate([np.linspace(-460, 460, 20001), np.linspace(-0.05, 0.05, 20001), rng(3).normal(size=5000)])
+    d = np.abs(np.abs(x)[:, None] - pos[None, :])
+    best = np.sort(d, axis=1)
+    clear = best[:, 1] - best[:, 0] > 1e-12
+    want = np.sign(x) * pos[np.argmin(d, axis=1)]
+    got = po.e4m3_round(x)
+    assert np.array_equal(got[clear], want[clear])
+    # ties go to the even mantissa: the midpoint of neighbours a < b rounds to the one whose bit pattern is even
+    mid = (pos[:-1] + pos[1:]) / 2
+    pat = po.e4m3_encode(mid)
+    assert np.all(pat % 2 == 0)
+    assert np.all((po.e4m3_decode(pat) == pos[:-1]) | (po.e4m3_decode(pat) == pos[1:]))
+    assert po.e4m3_round(1.0625) == 1.0 and po.e4m3_round(1.1875) == 1.25 and po.e4m3_round(2.0 ** -10) == 0.0
+    assert po.e4m3_round(1.5 * 2.0 ** -10) == 2.0 ** -9
+    # saturation instead of overflow; order is preserved
+    assert po.e4m3_round(1e9) == 448.0 and po.e4m3_round(-465.0) == -448.0 and po.e4m3_round(449.0) == 448.0
+    xs = np.sort(rng(4).normal(size=4000) * 30)
+    assert np.all(np.diff(po.e4m3_round(xs)) >= 0)
+    assert np.isnan(po.e4m3_round(np.array([np.nan]))[0])
+    # relative error of a normal number: at most half a spacing = 2^-4 of its binade
+    xn = np.abs(rng(5).normal(size=4000)) + 2.0 ** -6
+    assert np.max(np.abs(po.e4m3_round(xn) - xn) / xn) <= 2.0 ** -4
+
+
+def test_fp8_cache_changes_only_what_is_stored():
+    """With 8-bit cache storage the step's own arithmetic is unchanged: the entries it appends are the E4M3 roundings
+    of the entries the unrounded configuration appends, as long as nothing read from the cache differs (first layer)."""
+    cfg = tiny_cfg(n_layers=1, dtype="bf16")
+    cfg8 = si.shrink(cfg, kv_dtype="fp8")
+    w = po.weights_to_f64(si.make_weights(cfg, 5))
+    st = si.make_decode_state(cfg, 2, 3, 8, seed=1)
+    # a cache that already holds representable values, so both configurations read the same numbers
+    st["k"], st["v"] = po.e4m3_round(st["k"]), po.e4m3_round(st["v"])
+    a, b = po.state_to_f64(st), po.state_to_f64(st)
+    forced = si.make_tokens(cfg.vocab, 2, cfg.meta_context, 2)
+    ta = po.decode_step(cfg, w, a, forced_tokens=forced)
+    tb = po.decode_step(cfg8, w, b, forced_tokens=forced)
+    np.testing.assert_array_equal(b["k"][0, :, :, 3], po.e4m3_round(a["k"][0, :, :, 3]))
+    np.testing.assert_array_equal(b["v"][0, :, :, 3], po.e4m3_round(a["v"][0, :, :, 3]))
+    np.testing.assert_array_equal(ta["logits"], tb["logits"])                 # the top-down pass never reads the coarse cache
+    assert np.abs(a["x_top"] - b["x_top"]).max() > 1e-6                      # the new state does: it saw its own rounded entry
+
