@@ -40,7 +40,9 @@ extern "C" {
 #define PHOTON_API
 #endif
 
-typedef enum { PHOTON_F32 = 0, PHOTON_BF16 = 1 } photon_dtype;
+/* PHOTON_FP8_E4M3: 8-bit floating point (OCP E4M3: bias 7, no infinities, largest finite value 448), accepted only
+ * as the storage type of a coarse K/V cache (photon_config.kv_dt, photon_coarse_decode_attn). */
+typedef enum { PHOTON_F32 = 0, PHOTON_BF16 = 1, PHOTON_FP8_E4M3 = 2 } photon_dtype;
 
 typedef enum {
   PHOTON_OK = 0,
@@ -95,7 +97,8 @@ PHOTON_API int32_t photon_chunker_project(const void* x, const void* w, const fl
  * The S axis is split over n_splits workgroups per
  * stream (0 = choose from Bt*H and S_max); partial softmax states are merged
  * in a fixed order, so the result is run-to-run deterministic for a given
- * n_splits.  n_splits > 1 needs a workspace of
+ * n_splits.  dt PHOTON_FP8_E4M3: the caches hold E4M3 bytes (1 byte per element, same row length d_p), q and
+ * out are fp32.  n_splits > 1 needs a workspace of
  * photon_coarse_decode_attn_workspace_bytes() bytes (contents need no
  * initialisation; calls that share a workspace must be stream-ordered).
  * -------------------------------------------------------------------------- */
@@ -201,7 +204,10 @@ typedef struct photon_config {
   int32_t n_layers;              /* blocks per module */
   int32_t d_ff;                  /* SwiGLU width, 0 = attention-only blocks */
   int32_t vocab;
-  photon_dtype dt;               /* storage of matrices, tables and the coarse K/V cache */
+  photon_dtype dt;               /* storage of matrices and tables */
+  photon_dtype kv_dt;            /* storage of the coarse K/V caches (state and hierarchical state): equal to dt, or
+                                    PHOTON_FP8_E4M3 with dt == PHOTON_BF16: entries are rounded to nearest even from their
+                                    fp32 values and saturate at +-448; no scale factor (a variant beyond the paper) */
   float rms_eps;
   float rope_theta;              /* 0 disables the rotary encoding */
 } photon_config;
@@ -232,7 +238,7 @@ typedef struct photon_weights {
 } photon_weights;
 
 typedef struct photon_state {
-  void* k_cache;        /* [n_layers, Bt, H, S_max, photon_kv_row_elems(d_h)] dt : KV^(L) */
+  void* k_cache;        /* [n_layers, Bt, H, S_max, photon_kv_row_elems(d_h)] kv_dt : KV^(L) */
   void* v_cache;
   int32_t* seq_len;     /* [Bt] entries cached per sequence; the step adds 1.  Must be < S_max on entry. */
   float* x_top;         /* [Bt, D]       X^(L)_g, replaced by X^(L)_{g+1} */
@@ -296,7 +302,7 @@ typedef struct photon_encoder_weights {
 /* Encoder streams of the levels below the top, kept only by hierarchical
  * generation (Appendix A, Definition 1): index l-1 for level l = 1 .. L-1. */
 typedef struct photon_hier_state {
-  void* k_cache[PHOTON_MAX_LEVELS];     /* [n_layers, Bt, H, S_cap[l-1], photon_kv_row_elems(d_h)] dt: K/V of the level-l encoder */
+  void* k_cache[PHOTON_MAX_LEVELS];     /* [n_layers, Bt, H, S_cap[l-1], photon_kv_row_elems(d_h)] kv_dt: K/V of the level-l encoder */
   void* v_cache[PHOTON_MAX_LEVELS];
   int32_t* seq_len[PHOTON_MAX_LEVELS];  /* [Bt] units cached per sequence at level l */
   int64_t S_cap[PHOTON_MAX_LEVELS];     /* capacity per sequence; a step appends prod(C_{l+1..L}) units */

@@ -11,7 +11,7 @@ import torch  # imported before the library so both share one HIP runtime
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB: Optional[C.CDLL] = None
 
-PHOTON_F32, PHOTON_BF16 = 0, 1
+PHOTON_F32, PHOTON_BF16, PHOTON_FP8_E4M3 = 0, 1, 2
 
 
 class PhotonError(RuntimeError):
@@ -58,6 +58,8 @@ def _dt(t: torch.Tensor) -> int:
         return PHOTON_F32
     if t.dtype == torch.bfloat16:
         return PHOTON_BF16
+    if t.dtype == torch.uint8:          # E4M3 bit patterns (coarse K/V caches only)
+        return PHOTON_FP8_E4M3
     raise PhotonError(-2, f"unsupported tensor dtype {t.dtype}")
 
 
@@ -137,6 +139,8 @@ def photon_coarse_decode_attn(q, k_cache, v_cache, seq_len, out, scale: Optional
     if scale is None:
         scale = 1.0 / math.sqrt(d_h)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    if k_cache.dtype == torch.uint8 and (q.dtype != torch.float32 or out.dtype != torch.float32):
+        raise PhotonError(-1, "8-bit caches go with fp32 queries and outputs")
     _check(lib.photon_coarse_decode_attn(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_len), _ptr(out), Bt, H, d_h,
                                          S_max, scale, n_splits, _ptr(workspace), ws_bytes, _dt(k_cache), _stream()))
     return out
@@ -238,7 +242,7 @@ MAX_LEVELS = 4
 class _Config(C.Structure):
     _fields_ = [("L", C.c_int32), ("C", C.c_int32 * MAX_LEVELS), ("R", C.c_int32 * MAX_LEVELS),
                 ("D", C.c_int32), ("H", C.c_int32), ("d_h", C.c_int32), ("n_layers", C.c_int32),
-                ("d_ff", C.c_int32), ("vocab", C.c_int32), ("dt", C.c_int32),
+                ("d_ff", C.c_int32), ("vocab", C.c_int32), ("dt", C.c_int32), ("kv_dt", C.c_int32),
                 ("rms_eps", C.c_float), ("rope_theta", C.c_float)]
 
 
@@ -302,6 +306,7 @@ def _c_config(cfg) -> _Config:
         c.C[i], c.R[i] = cfg.C[i], cfg.R[i]
     c.D, c.H, c.d_h, c.n_layers, c.d_ff, c.vocab = cfg.D, cfg.H, cfg.d_h, cfg.n_layers, cfg.d_ff, cfg.vocab
     c.dt = PHOTON_BF16 if cfg.dtype == "bf16" else PHOTON_F32
+    c.kv_dt = PHOTON_FP8_E4M3 if getattr(cfg, "kv_dtype", "") == "fp8" else c.dt
     c.rms_eps, c.rope_theta = cfg.rms_eps, cfg.rope_theta
     return c
 
@@ -315,6 +320,8 @@ class PhotonModel:
         self.cfg = cfg
         self.device = torch.device(device)
         self.mat_dtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        # coarse K/V caches: the matrices' type, or E4M3 bit patterns held as uint8
+        self.kv_dtype = torch.uint8 if getattr(cfg, "kv_dtype", "") == "fp8" else self.mat_dtype
         self._keep = []
         self.c_cfg = _c_config(cfg)
         w = _Weights()
@@ -393,6 +400,8 @@ class PhotonState:
             if a is None:
                 return torch.zeros(shp, dtype=dtype, device=dev)
             t = a if isinstance(a, torch.Tensor) else torch.from_numpy(np_contig(a))
+            if dtype == torch.uint8 and t.dtype != torch.uint8:
+                raise PhotonError(-1, "an 8-bit cache is given as E4M3 bit patterns (uint8)")
             t = t.to(device=dev, dtype=dtype)
             if len(shp) == 5:
                 t = pad_kv_rows(t, cfg.d_h)
@@ -400,8 +409,8 @@ class PhotonState:
             assert tuple(t.shape) == tuple(shp), (t.shape, shp)
             return t
 
-        self.k = put(k, model.mat_dtype, shape)
-        self.v = put(v, model.mat_dtype, shape)
+        self.k = put(k, model.kv_dtype, shape)
+        self.v = put(v, model.kv_dtype, shape)
         self.seq_len = put(seq_len, torch.int32, (Bt,))
         self.x_top = put(x_top, torch.float32, (Bt, cfg.D))
         self.carry = put(carry, torch.float32, (max(cfg.L - 1, 0), Bt, cfg.D))
@@ -437,6 +446,8 @@ class PhotonHierState:
                 if a is None:
                     return torch.zeros(shp, dtype=dtype, device=dev)
                 t = a if isinstance(a, torch.Tensor) else torch.from_numpy(np_contig(a))
+                if dtype == torch.uint8 and t.dtype != torch.uint8:
+                    raise PhotonError(-1, "an 8-bit cache is given as E4M3 bit patterns (uint8)")
                 t = t.to(device=dev, dtype=dtype)
                 if len(shp) == 5:
                     t = pad_kv_rows(t, cfg.d_h)
@@ -444,8 +455,8 @@ class PhotonHierState:
                 assert tuple(t.shape) == tuple(shp), (t.shape, shp)
                 return t
 
-            self.k.append(put(None if k is None else k[l - 1], model.mat_dtype, shape))
-            self.v.append(put(None if v is None else v[l - 1], model.mat_dtype, shape))
+            self.k.append(put(None if k is None else k[l - 1], model.kv_dtype, shape))
+            self.v.append(put(None if v is None else v[l - 1], model.kv_dtype, shape))
             self.seq_len.append(put(None if seq_len is None else seq_len[l - 1], torch.int32, (Bt,)))
             self.S_cap.append(caps[l])
             h.k_cache[l - 1], h.v_cache[l - 1] = self.k[-1].data_ptr(), self.v[-1].data_ptr()

@@ -6,7 +6,7 @@
 
 namespace photon {
 
-enum KvType { KV_F32 = 0, KV_BF16 = 1 };
+enum KvType { KV_F32 = 0, KV_BF16 = 1, KV_FP8 = 2 };   // KV_FP8: E4M3 bytes; q and out fp32
 
 // Elements of one K/V cache row: the head size rounded up to 32, 64 or 128 (columns past d_h hold zeros); 0 = unsupported.
 inline int kv_row_elems(int d_h) { return d_h < 1 ? 0 : d_h <= 32 ? 32 : d_h <= 64 ? 64 : d_h <= 128 ? 128 : 0; }

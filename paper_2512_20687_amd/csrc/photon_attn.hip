@@ -233,6 +233,7 @@ int32_t launch_coarse_attn(KvType kv, bool q_f32, int d_h, const void* q, const 
                            const int32_t* seq_len, void* out, int Bt, int H, int64_t S_max, float scale,
                            int n_splits, void* ws, hipStream_t st) {
   if (kv == KV_F32) return launch_coarse_dh<float, float>(d_h, q, kc, vc, seq_len, out, Bt, H, S_max, scale, n_splits, ws, st);
+  if (kv == KV_FP8) return launch_coarse_dh<fp8_t, float>(d_h, q, kc, vc, seq_len, out, Bt, H, S_max, scale, n_splits, ws, st);
   if (q_f32) return launch_coarse_dh<bf16_t, float>(d_h, q, kc, vc, seq_len, out, Bt, H, S_max, scale, n_splits, ws, st);
   return launch_coarse_dh<bf16_t, bf16_t>(d_h, q, kc, vc, seq_len, out, Bt, H, S_max, scale, n_splits, ws, st);
 }
@@ -558,7 +559,7 @@ extern "C" int32_t photon_coarse_decode_attn(const void* q, const void* k_cache,
                                              int64_t S_max, float scale, int32_t n_splits, void* workspace,
                                              size_t workspace_bytes, photon_dtype dt, void* stream) {
   clear_error();
-  PHOTON_REQUIRE(valid_dtype(dt), PHOTON_ERR_UNSUPPORTED, "%s: unknown dtype %d", __func__, (int)dt);
+  PHOTON_REQUIRE(valid_dtype(dt) || dt == PHOTON_FP8_E4M3, PHOTON_ERR_UNSUPPORTED, "%s: unknown dtype %d", __func__, (int)dt);
   PHOTON_REQUIRE(Bt > 0 && H > 0 && S_max > 0, PHOTON_ERR_INVALID_ARG, "%s: Bt=%d H=%d S_max=%lld must be positive",
                  __func__, Bt, H, (long long)S_max);
   PHOTON_REQUIRE((int64_t)Bt * H <= 65535, PHOTON_ERR_UNSUPPORTED, "%s: Bt*H=%lld exceeds 65535 streams per launch",
@@ -577,7 +578,7 @@ extern "C" int32_t photon_coarse_decode_attn(const void* q, const void* k_cache,
                    "%s: n_splits=%d needs a 16-byte aligned workspace of %zu bytes (got %zu)", __func__, n_splits, need,
                    workspace_bytes);
   }
-  return launch_coarse_attn(dt == PHOTON_F32 ? KV_F32 : KV_BF16, dt == PHOTON_F32, d_h, q, k_cache, v_cache, seq_len, out,
+  return launch_coarse_attn(dt == PHOTON_F32 ? KV_F32 : dt == PHOTON_BF16 ? KV_BF16 : KV_FP8, dt != PHOTON_BF16, d_h, q, k_cache, v_cache, seq_len, out,
                             Bt, H, S_max, scale, n_splits, workspace, (hipStream_t)stream);
 }
 

@@ -71,12 +71,33 @@ template <> __device__ __forceinline__ void unpack16<bf16_t>(const uint4_t& r, f
   v[4] = bf16_lo(r.z); v[5] = bf16_hi(r.z); v[6] = bf16_lo(r.w); v[7] = bf16_hi(r.w);
 }
 
+// ---- 8-bit floating point (OCP E4M3: bias 7, no infinities, largest finite value 448) for K/V cache storage ----
+struct fp8_t { uint8_t bits; };
+typedef float f32x2_native __attribute__((ext_vector_type(2)));
+// Two fp32 values -> two E4M3 bytes (lo in bits 0..7), nearest even.  The conversion instruction turns magnitudes
+// beyond the format's range into NaN; storage saturates instead, so the values are clamped first (NaN stays NaN).
+__device__ __forceinline__ uint32_t pack_fp8x2(float lo, float hi) {
+  lo = fminf(fmaxf(lo, -448.f), 448.f);
+  hi = fminf(fmaxf(hi, -448.f), 448.f);
+  return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(lo, hi, 0, false) & 0xffffu;
+}
+template <> __device__ __forceinline__ void unpack16<fp8_t>(const uint4_t& r, float* v) {
+  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const f32x2_native a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);
+    const f32x2_native b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);
+    v[4 * i] = a.x; v[4 * i + 1] = a.y; v[4 * i + 2] = b.x; v[4 * i + 3] = b.y;
+  }
+}
+
 template <typename T> __device__ __forceinline__ float to_f32(T x);
 template <> __device__ __forceinline__ float to_f32<float>(float x) { return x; }
 template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t x) { return __uint_as_float(uint32_t(x) << 16); }
 template <typename T> __device__ __forceinline__ T from_f32(float x);
 template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return bf16_t(f32_to_bf16_bits(x)); }
+template <> __device__ __forceinline__ fp8_t from_f32<fp8_t>(float x) { return fp8_t{(uint8_t)(pack_fp8x2(x, 0.f) & 0xffu)}; }
 
 // ---- cross-lane moves on the data-parallel-primitive path (no LDS traffic) ----
 template <int CTRL> __device__ __forceinline__ float dpp(float x) {

@@ -76,10 +76,11 @@ __device__ __forceinline__ int swz(int row, int col16) { return row * 128 + ((co
 // first member sits in column i and the second in column 32 + i, for q and k alike (a score does not depend on
 // the order of the contraction index); V keeps its own column order, so the output columns are the head's; all
 // other columns are zero.
-template <bool PAD>
+// TC: storage type of the cache (bf16_t or fp8_t).
+template <bool PAD, typename TC>
 __global__ __launch_bounds__(256) void encoder_rope_split_kernel(const float* __restrict__ qkv, uint16_t* __restrict__ qh,
                                                                  uint16_t* __restrict__ kh, uint16_t* __restrict__ vt,
-                                                                 bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, int64_t M, int H,
+                                                                 TC* __restrict__ kc, TC* __restrict__ vc, int64_t M, int H,
                                                                  int d_h_rt, int pitch, int64_t S_max, float theta, float qscale) {
   __shared__ uint16_t vtile[64][64 + 2];                // [d][position], padded
   const int tid = threadIdx.x;
@@ -142,24 +143,32 @@ __global__ __launch_bounds__(256) void encoder_rope_split_kernel(const float* __
     kh4.x = pack_f16x2(ks[0], ks[1]); kh4.y = pack_f16x2(ks[2], ks[3]); kh4.z = pack_f16x2(ks[4], ks[5]); kh4.w = pack_f16x2(ks[6], ks[7]);
     *reinterpret_cast<uint4_t*>(qh + row + off) = h4;
     *reinterpret_cast<uint4_t*>(kh + row + off) = kh4;
-    if (!PAD && kc != nullptr && live && pos < S_max) { // the cache holds bf16, rounded from the fp32 values
-      uint4_t vv, kk;
-      vv.x = pack_bf16x2(v[half * 8 + 0], v[half * 8 + 1]); vv.y = pack_bf16x2(v[half * 8 + 2], v[half * 8 + 3]);
-      vv.z = pack_bf16x2(v[half * 8 + 4], v[half * 8 + 5]); vv.w = pack_bf16x2(v[half * 8 + 6], v[half * 8 + 7]);
-      kk.x = pack_bf16x2(ks[0], ks[1]); kk.y = pack_bf16x2(ks[2], ks[3]); kk.z = pack_bf16x2(ks[4], ks[5]); kk.w = pack_bf16x2(ks[6], ks[7]);
+    if (!PAD && kc != nullptr && live && pos < S_max) { // the cache holds its own rounding of the fp32 values
+      const float* vs = v + half * 8;
       const int64_t slot = (((int64_t)b * H + h) * S_max + pos) * EA_DH + off;
-      *reinterpret_cast<uint4_t*>(kc + slot) = kk;
-      *reinterpret_cast<uint4_t*>(vc + slot) = vv;
+      if (sizeof(TC) == 2) {
+        uint4_t vv, kk;
+        vv.x = pack_bf16x2(vs[0], vs[1]); vv.y = pack_bf16x2(vs[2], vs[3]); vv.z = pack_bf16x2(vs[4], vs[5]); vv.w = pack_bf16x2(vs[6], vs[7]);
+        kk.x = pack_bf16x2(ks[0], ks[1]); kk.y = pack_bf16x2(ks[2], ks[3]); kk.z = pack_bf16x2(ks[4], ks[5]); kk.w = pack_bf16x2(ks[6], ks[7]);
+        *reinterpret_cast<uint4_t*>(kc + slot) = kk;
+        *reinterpret_cast<uint4_t*>(vc + slot) = vv;
+      } else {
+        uint2 vv, kk;
+        vv.x = pack_fp8x2(vs[0], vs[1]) | (pack_fp8x2(vs[2], vs[3]) << 16); vv.y = pack_fp8x2(vs[4], vs[5]) | (pack_fp8x2(vs[6], vs[7]) << 16);
+        kk.x = pack_fp8x2(ks[0], ks[1]) | (pack_fp8x2(ks[2], ks[3]) << 16); kk.y = pack_fp8x2(ks[4], ks[5]) | (pack_fp8x2(ks[6], ks[7]) << 16);
+        *reinterpret_cast<uint2*>(kc + slot) = kk;
+        *reinterpret_cast<uint2*>(vc + slot) = vv;
+      }
     }
     if (PAD && kc != nullptr && live && pos < S_max) {  // cache rows in the head's own column order, zeros past d_h
       const int64_t slot = (((int64_t)b * H + h) * S_max + pos) * pitch;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int i = quarter * 8 + j;
-        if (i < hr) kc[slot + half * hr + i] = from_f32<bf16_t>(k[half * 8 + j]);
+        if (i < hr) kc[slot + half * hr + i] = from_f32<TC>(k[half * 8 + j]);
         const int col = half * 32 + i;
-        if (col < pitch) vc[slot + col] = from_f32<bf16_t>(v[half * 8 + j]);
-        if (col >= d_h && col < pitch) kc[slot + col] = bf16_t(0);
+        if (col < pitch) vc[slot + col] = from_f32<TC>(v[half * 8 + j]);
+        if (col >= d_h && col < pitch) kc[slot + col] = TC{};
       }
     }
 #pragma unroll
@@ -475,7 +484,7 @@ size_t encoder_attn_workspace_bytes(int Bt, int64_t M, int H, int d_h, bool bf16
 }
 
 int32_t launch_encoder_attn(const float* qkv, float* out, int Bt, int64_t M, int H, int d_h, float theta, float scale, void* k_cache,
-                            void* v_cache, int64_t S_max, void* workspace, bool bf16, hipStream_t st) {
+                            void* v_cache, int64_t S_max, void* workspace, bool bf16, bool kv_fp8, hipStream_t st) {
   if (Bt <= 0 || M <= 0) return PHOTON_OK;
   if ((int64_t)Bt * H > 65535) return fail(PHOTON_ERR_UNSUPPORTED, "encoder attention: Bt*H=%lld exceeds 65535", (long long)Bt * H);
   const int pitch = kv_row_elems(d_h);
@@ -509,12 +518,12 @@ int32_t launch_encoder_attn(const float* qkv, float* out, int Bt, int64_t M, int
   const size_t arr = (size_t)Bt * H * Mp * EA_DH;
   uint16_t* qh = reinterpret_cast<uint16_t*>(workspace);
   uint16_t *kh = qh + arr, *vt = kh + arr;
-  if (d_h == EA_DH)
-    PHOTON_LAUNCH(KC_ROPE_APPEND, st, encoder_rope_split_kernel<false>, dim3((unsigned)(Mp / 64), Bt * H), dim3(256), 0, st, qkv, qh, kh, vt,
-                  (bf16_t*)k_cache, (bf16_t*)v_cache, M, H, d_h, pitch, S_max, theta, scale * LOG2E);
-  else
-    PHOTON_LAUNCH(KC_ROPE_APPEND, st, encoder_rope_split_kernel<true>, dim3((unsigned)(Mp / 64), Bt * H), dim3(256), 0, st, qkv, qh, kh, vt,
-                  (bf16_t*)k_cache, (bf16_t*)v_cache, M, H, d_h, pitch, S_max, theta, scale * LOG2E);
+#define PHOTON_EA_ROPE(PAD, TC)                                                                                                        \
+  PHOTON_LAUNCH(KC_ROPE_APPEND, st, (encoder_rope_split_kernel<PAD, TC>), dim3((unsigned)(Mp / 64), Bt * H), dim3(256), 0, st, qkv, qh, \
+                kh, vt, (TC*)k_cache, (TC*)v_cache, M, H, d_h, pitch, S_max, theta, scale * LOG2E)
+  if (d_h == EA_DH) { if (kv_fp8) PHOTON_EA_ROPE(false, fp8_t); else PHOTON_EA_ROPE(false, bf16_t); }
+  else { if (kv_fp8) PHOTON_EA_ROPE(true, fp8_t); else PHOTON_EA_ROPE(true, bf16_t); }
+#undef PHOTON_EA_ROPE
   PHOTON_TRY(check_launch("encoder_rope_split_kernel"));
   const int n_qblocks = (int)((M + EA_BQ - 1) / EA_BQ);
   PHOTON_LAUNCH(KC_LOCAL_ATTN, st, encoder_attn_mfma_kernel, dim3(n_qblocks, Bt * H), dim3(EA_THREADS), 2 * EA_STAGE, st, qh, kh, vt, out, M,
@@ -551,6 +560,6 @@ extern "C" int32_t photon_encoder_attn(const float* qkv, float* out, int32_t Bt,
   const size_t need = encoder_attn_workspace_bytes(Bt, M, H, d_h, dt == PHOTON_BF16);
   PHOTON_REQUIRE(workspace_bytes >= need, PHOTON_ERR_INVALID_ARG, "%s: workspace holds %zu bytes, %zu needed", __func__, workspace_bytes, need);
   if (need > 0) PHOTON_REQUIRE_PTR(workspace);
-  return launch_encoder_attn(qkv, out, Bt, M, H, d_h, rope_theta, scale, k_cache, v_cache, S_max, workspace, dt == PHOTON_BF16,
+  return launch_encoder_attn(qkv, out, Bt, M, H, d_h, rope_theta, scale, k_cache, v_cache, S_max, workspace, dt == PHOTON_BF16, false,
                              (hipStream_t)stream);
 }

@@ -15,7 +15,7 @@ int32_t fail(int32_t code, const char* fmt, ...) __attribute__((format(printf, 2
 void clear_error();
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-inline size_t dtype_size(photon_dtype dt) { return dt == PHOTON_BF16 ? 2 : 4; }
+inline size_t dtype_size(photon_dtype dt) { return dt == PHOTON_BF16 ? 2 : dt == PHOTON_FP8_E4M3 ? 1 : 4; }
 inline bool valid_dtype(photon_dtype dt) { return dt == PHOTON_F32 || dt == PHOTON_BF16; }
 
 // Report a launch failure of the kernel just enqueued (does not synchronise).

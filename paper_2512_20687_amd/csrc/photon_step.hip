@@ -252,6 +252,8 @@ static Plan make_plan(const photon_config& c, int Bt, int64_t S_max) {
 static int32_t validate_config(const photon_config* c, int Bt, int64_t S_max) {
   PHOTON_REQUIRE(c != nullptr, PHOTON_ERR_INVALID_ARG, "config is null");
   PHOTON_REQUIRE(valid_dtype(c->dt), PHOTON_ERR_UNSUPPORTED, "unknown dtype %d", (int)c->dt);
+  PHOTON_REQUIRE(c->kv_dt == c->dt || (c->dt == PHOTON_BF16 && c->kv_dt == PHOTON_FP8_E4M3), PHOTON_ERR_UNSUPPORTED,
+                 "kv_dt=%d must equal dt=%d, or be 8-bit with bf16 matrices", (int)c->kv_dt, (int)c->dt);
   PHOTON_REQUIRE(c->L >= 1 && c->L <= PHOTON_MAX_LEVELS, PHOTON_ERR_INVALID_ARG, "L=%d not in [1, %d]", c->L, (int)PHOTON_MAX_LEVELS);
   PHOTON_REQUIRE(Bt > 0 && S_max > 0, PHOTON_ERR_INVALID_ARG, "Bt=%d and S_max=%lld must be positive", Bt, (long long)S_max);
   PHOTON_REQUIRE(c->D > 0 && c->H > 0 && c->d_h > 0 && c->H * c->d_h == c->D, PHOTON_ERR_INVALID_ARG,
@@ -362,7 +364,7 @@ static int32_t stream_step(const Ctx& x, const photon_module_weights& mod, void*
   const photon_config& c = *x.c;
   const int rows = x.Bt;
   float *h = x.f(x.o_h), *qkv = x.f(x.o_qkv), *qrot = x.f(x.o_qrot), *attn = x.f(x.o_attn);
-  const size_t esz = dtype_size(c.dt);
+  const size_t esz = dtype_size(c.kv_dt);
   const int pitch = kv_row_elems(c.d_h);
   const size_t layer_cache = (size_t)x.Bt * c.H * S_cap * pitch * esz;
   const float scale = 1.0f / sqrtf((float)c.d_h);
@@ -372,14 +374,17 @@ static int32_t stream_step(const Ctx& x, const photon_module_weights& mod, void*
     char* vc = reinterpret_cast<char*>(v_cache) + (size_t)i * layer_cache;
     PHOTON_TRY(linear(x, in.ptr, in.ld, lw.wqkv, lw.g1, nullptr, nullptr, 0, qkv, 3 * c.D, rows, 3 * c.D, c.D, EPI_PLAIN));
     const int64_t n_el = (int64_t)rows * c.H * (c.d_h / 2);
-    if (x.bf16)
+    if (c.kv_dt == PHOTON_FP8_E4M3)
+      PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_coarse_kernel<fp8_t>, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot,
+                    (fp8_t*)kc, (fp8_t*)vc, seq_len, x.Bt, c.H, c.d_h, pitch, S_cap, c.rope_theta);
+    else if (x.bf16)
       PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_coarse_kernel<bf16_t>, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot,
                     (bf16_t*)kc, (bf16_t*)vc, seq_len, x.Bt, c.H, c.d_h, pitch, S_cap, c.rope_theta);
     else
       PHOTON_LAUNCH(KC_ROPE_APPEND, x.st, rope_append_coarse_kernel<float>, dim3(blocks_for(n_el)), dim3(256), 0, x.st, qkv, qrot,
                     (float*)kc, (float*)vc, seq_len, x.Bt, c.H, c.d_h, pitch, S_cap, c.rope_theta);
     PHOTON_TRY(check_launch("rope_append_coarse_kernel"));
-    PHOTON_TRY(launch_coarse_attn(x.bf16 ? KV_BF16 : KV_F32, true, c.d_h, qrot, kc, vc, seq_len, attn, x.Bt, c.H, S_cap, scale,
+    PHOTON_TRY(launch_coarse_attn(c.kv_dt == PHOTON_FP8_E4M3 ? KV_FP8 : x.bf16 ? KV_BF16 : KV_F32, true, c.d_h, qrot, kc, vc, seq_len, attn, x.Bt, c.H, S_cap, scale,
                                   x.p.n_splits, x.base + x.p.coarse_ws, x.st));
     PHOTON_TRY(block_tail(x, lw, in, rows));
     in.ptr = h; in.ld = c.D;
@@ -597,7 +602,7 @@ static int32_t prefill_impl(const Ctx& x, Ctx e, const PrefillPlan& pp, const ph
   const photon_config& c = *x.c;
   const int D = c.D, L = c.L, Bt = x.Bt;
   const float scale = 1.0f / sqrtf((float)c.d_h);
-  const size_t esz = dtype_size(c.dt);
+  const size_t esz = dtype_size(c.kv_dt);
 
   float *A = e.f(pp.A), *h = e.f(pp.h), *qkv = e.f(pp.qkv), *attn = e.f(pp.attn);
   float* pair = e.f(pp.pair);
@@ -633,7 +638,7 @@ static int32_t prefill_impl(const Ctx& x, Ctx e, const PrefillPlan& pp, const ph
         kc = reinterpret_cast<char*>(x.hs->k_cache[l - 1]) + (size_t)i * lc;
         vc = reinterpret_cast<char*>(x.hs->v_cache[l - 1]) + (size_t)i * lc;
       }
-      PHOTON_TRY(launch_encoder_attn(qkv, attn, Bt, M, c.H, c.d_h, c.rope_theta, scale, kc, vc, cap, e.base + pp.ea, x.bf16, x.st));
+      PHOTON_TRY(launch_encoder_attn(qkv, attn, Bt, M, c.H, c.d_h, c.rope_theta, scale, kc, vc, cap, e.base + pp.ea, x.bf16, c.kv_dt == PHOTON_FP8_E4M3, x.st));
       PHOTON_TRY(block_tail(e, lw, in, rows));
       in.ptr = h; in.ld = D;
     }

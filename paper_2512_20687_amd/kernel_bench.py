@@ -110,6 +110,19 @@ def bench_a2():
         _emit("coarse_attn_kernel + coarse_merge_kernel", f"{what}: Bt={Bt} H={H} S={S} d_h={d_h} splits={ns}", us,
               bytes_=2 * Bt * H * S * d_h * 2)
         del k, v
+    # the same kernel on an 8-bit (E4M3) cache: half the bytes per key
+    Bt, H, S, nl, d_h = 4, 32, 8320, 8, 64
+    k = (torch.randint(0, 256, (nl, Bt, H, S, d_h), device="cuda", dtype=torch.int32) & 0xB7).to(torch.uint8)   # finite, below 1 in magnitude
+    v = (torch.randint(0, 256, (nl, Bt, H, S, d_h), device="cuda", dtype=torch.int32) & 0xB7).to(torch.uint8)
+    q = torch.randn((Bt, H, d_h), device="cuda")
+    o = torch.empty_like(q)
+    seq = torch.full((Bt,), S, dtype=torch.int32, device="cuda")
+    ns = ph.photon_coarse_decode_attn_auto_splits(Bt, H, S)
+    ws = torch.empty(max(ph.photon_coarse_decode_attn_workspace_bytes(Bt, H, d_h, max(ns, 2)), 16), dtype=torch.uint8, device="cuda")
+    us = _time_us(lambda i: ph.photon_coarse_decode_attn(q, k[i % nl], v[i % nl], seq, o, n_splits=ns, workspace=ws), 5 * nl, warm=nl)
+    _emit("coarse_attn_kernel + coarse_merge_kernel", f"cfg3 with an 8-bit cache: Bt={Bt} H={H} S={S} d_h={d_h} splits={ns}", us,
+          bytes_=2 * Bt * H * S * d_h)
+    del k, v
 
 
 def bench_a3():
@@ -228,6 +241,30 @@ def bench_schedules():
         print(json.dumps(rec), flush=True)
         del model
         torch.cuda.empty_cache()
+    # recursive generation with the coarse cache held in 8 bits (E4M3), configuration 3
+    from dataclasses import replace
+    wl = si.WORKLOADS["cfg3_bf16_128k"]
+    cfg, Bt, S0 = replace(wl.cfg, kv_dtype="fp8"), wl.Bt, wl.S0
+    steps, warm = 24, 4
+    S_max = (S0 + 2 * (steps + warm) + 16 + 127) // 128 * 128
+    model = ph.PhotonModel(cfg, si.make_weights(cfg, 0, device="cuda"))
+    st0 = si.make_decode_state(wl.cfg, Bt, S0, S_max, seed=0, device="cuda")
+    shape = (cfg.n_layers, Bt, cfg.H, S_max, cfg.d_h)
+    codes = lambda: (torch.randint(0, 256, shape, device="cuda", dtype=torch.int32) & 0xB7).to(torch.uint8)
+    state = ph.PhotonState(model, Bt, S_max, k=codes(), v=codes(), seq_len=st0["seq_len"], x_top=st0["x_top"], carry=st0["carry"])
+    out = torch.zeros((Bt, cfg.meta_context), dtype=torch.int32, device="cuda")
+    fn = lambda: ph.photon_decode_step(model, state, out)
+    fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fn()
+    us = _time_us(lambda i: g.replay(), steps, warm=warm)
+    print(json.dumps({"kernel": "photon_decode_step", "shape": "cfg3_bf16_128k with an 8-bit (E4M3) coarse cache", "ms_per_step": round(us / 1e3, 3),
+                      "tokens_per_s": round(Bt * cfg.meta_context / us * 1e6),
+                      "global_kv_read_bytes_per_step": int(2.0 * Bt * cfg.H * cfg.d_h * cfg.n_layers * S0)}), flush=True)
+    del model, state, g
+    torch.cuda.empty_cache()
 
 
 def bench_linear():

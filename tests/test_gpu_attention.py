@@ -54,6 +54,33 @@ def test_coarse_parity(dtype, Bt, H, d_h, S_max, seq, n_splits):
     assert nerr(out, ref) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("Bt,H,d_h,S_max,seq", [(2, 3, 64, 700, [700, 333]), (1, 2, 52, 300, [257]), (2, 2, 128, 200, [200, 1]),
+                                               (3, 2, 32, 90, [90, 0, 17])])
+@pytest.mark.parametrize("n_splits", [1, 3, 0])
+def test_coarse_parity_8bit_cache(Bt, H, d_h, S_max, seq, n_splits):
+    """K/V held as E4M3 bit patterns (reading G17), queries and outputs fp32: the kernel must decode every one of the
+    bytes the way the format defines; the oracle attends over the decoded values."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    rng = np.random.default_rng(5)
+    # every finite bit pattern occurs: magnitudes from the smallest subnormal to 448, both signs, and both zeros
+    kc = rng.integers(0, 256, size=(Bt, H, S_max, d_h)).astype(np.uint8)
+    vc = rng.integers(0, 256, size=(Bt, H, S_max, d_h)).astype(np.uint8)
+    kc[(kc & 0x7F) == 0x7F] = 0x38                                      # no NaN patterns
+    vc[(vc & 0x7F) == 0x7F] = 0xB8
+    kc[:, :, :, 1::2] &= 0xB7                                           # keep most scores moderate: odd columns below 1 in magnitude
+    q = si.make_normal((Bt, H, d_h), 3, "f32", std=0.05)
+    seq = np.asarray(seq, np.int32)
+    ref = po.coarse_decode_attn(q, po.e4m3_decode(kc), po.e4m3_decode(vc), seq, 1 / math.sqrt(d_h))
+    out = torch.full((Bt, H, d_h), float("nan"), device="cuda")
+    ns = n_splits or ph.photon_coarse_decode_attn_auto_splits(Bt, H, S_max)
+    ws = torch.empty(max(ph.photon_coarse_decode_attn_workspace_bytes(Bt, H, d_h, ns), 16) // 4, dtype=torch.float32, device="cuda")
+    ph.photon_coarse_decode_attn(dev(q), ph.pad_kv_rows(torch.from_numpy(kc).cuda(), d_h), ph.pad_kv_rows(torch.from_numpy(vc).cuda(), d_h),
+                                 dev(seq), out, n_splits=n_splits, workspace=ws)
+    torch.cuda.synchronize()
+    assert nerr(out, ref) <= TOL["f32"]
+
+
 def test_coarse_empty_stream_and_unread_tail():
     require_gpu()
     import paper_2512_20687_amd as ph

@@ -247,3 +247,57 @@ def test_full_width_step_other_configurations(name, Bt, S):
     errs, _, _ = check_against_oracle(cfg, w, st, Bt, S_max, forced, TOL["bf16"])
     assert errs["logits"] <= 1e-3, errs
 
+
+def _adjacent_codes(got_codes, want_values):
+    """E4M3 bit patterns against the values the oracle stored: equal, or for a small fraction (the value sat within
+    rounding error of a tie: fp32 accumulation here, float64 there) the neighbouring representable value."""
+    got = po.e4m3_decode(got_codes)
+    want = np.asarray(want_values)
+    same = got == want
+    tab = np.sort(po.e4m3_decode(np.array([c for c in range(256) if (c & 0x7F) != 0x7F], np.uint8)))
+    tab = np.unique(tab)                                                  # -0 and +0 are one value
+    gi, wi = np.searchsorted(tab, got), np.searchsorted(tab, want)
+    assert np.all(np.abs(gi - wi)[~same] <= 1), "a stored value is more than one representable step off"
+    return float(same.mean())
+
+
+@pytest.mark.parametrize("kw,Bt", [(dict(), 3), (dict(D=832, H=16, d_h=52, d_ff=1024, R=(2, 2), n_layers=1), 2)])
+def test_bf16_step_with_8bit_cache(kw, Bt):
+    """Coarse K/V held in 8 bits (reading G17): the step reads E4M3 entries and appends the E4M3 rounding of the new
+    ones; everything else is as in the bf16 configurations."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    base = dict(L=2, C=(4, 4), R=(1, 1), D=256, H=4, d_h=64, n_layers=2, d_ff=640, vocab=1024, dtype="bf16", kv_dtype="fp8")
+    base.update(kw)
+    cfg = si.PhotonConfig(**base)
+    w = si.make_weights(cfg, 35)
+    S, S_max = 200, 230
+    st = si.make_decode_state(cfg, Bt, S, S_max, seed=7)
+    st["seq_len"] = np.array([S - 11 * b for b in range(Bt)], np.int32)
+    st["k"], st["v"] = po.e4m3_round(st["k"]), po.e4m3_round(st["v"])          # what an 8-bit cache can hold
+    forced = si.make_tokens(cfg.vocab, Bt, cfg.meta_context, 9)
+    ost = po.state_to_f64(st)
+    s0 = ost["seq_len"].copy()
+    otr = po.decode_step(cfg, po.weights_to_f64(w), ost, forced_tokens=forced)
+    model = ph.PhotonModel(cfg, w)
+    state = ph.PhotonState(model, Bt, S_max, k=po.e4m3_encode(st["k"]), v=po.e4m3_encode(st["v"]), seq_len=st["seq_len"],
+                           x_top=np.asarray(st["x_top"], np.float32), carry=np.asarray(st["carry"], np.float32))
+    assert state.k.dtype == torch.uint8 and state.k.element_size() == 1
+    B = cfg.meta_context
+    trace = {"logits": torch.full((Bt, B, cfg.vocab), float("nan"), device="cuda"), "a_hat": torch.full((Bt, cfg.D), float("nan"), device="cuda")}
+    toks = torch.full((Bt, B), -1, dtype=torch.int32, device="cuda")
+    ph.photon_decode_step(model, state, toks, forced_tokens=dev(np.asarray(forced, np.int32)), trace=trace)
+    torch.cuda.synchronize()
+    errs = {"logits": nerr(trace["logits"], otr["logits"]), "a_hat": nerr(trace["a_hat"], otr["a_hat"]),
+            "x_top": nerr(state.x_top, otr["x_top"]), "carry": nerr(state.carry, ost["carry"])}
+    assert all(v <= TOL["bf16"] for v in errs.values()), errs
+    for got, ref in ((state.k, ost["k"]), (state.v, ost["v"])):
+        g = got.cpu().numpy()
+        new_g = np.stack([g[:, b, :, int(s0[b]), :cfg.d_h] for b in range(Bt)], 1)
+        new_r = np.stack([ref[:, b, :, int(s0[b])] for b in range(Bt)], 1)
+        assert _adjacent_codes(new_g, new_r) >= 0.97
+        assert not g[..., cfg.d_h:].any()                                      # padding columns stay zero
+        old = np.stack([g[:, b, :, : int(s0[b]), :cfg.d_h] for b in range(1)], 1)
+        assert np.array_equal(po.e4m3_decode(old), np.stack([ref[:, b, :, : int(s0[b])] for b in range(1)], 1))   # nothing else is touched
+    assert np.array_equal(state.seq_len.cpu().numpy(), s0 + 1)
+

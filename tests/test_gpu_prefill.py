@@ -241,3 +241,36 @@ def test_hierarchical_generation_two_steps(dtype, kw, Bt, T):
         assert nerr(trace["a_hat"], otr["a_hat"]) <= tol
         check_state(cfg, state, ost, Bt, tol, tol_kv)
         check_hier(cfg, hier, ost, tol_kv)
+
+
+def test_bf16_prefill_with_8bit_cache_then_step():
+    """Prefill into an 8-bit (E4M3) coarse cache, then a decode step from it, against the oracle doing the same."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    cfg = si.PhotonConfig(L=2, C=(4, 4), R=(1, 1), D=256, H=4, d_h=64, n_layers=2, d_ff=640, vocab=1024, dtype="bf16", kv_dtype="fp8")
+    w = si.make_weights(cfg, 37)
+    Bt, T = 2, 16 * 30
+    toks = si.make_tokens(cfg.vocab, Bt, T, 6)
+    S_max = T // cfg.meta_context + 4
+    w64 = po.weights_to_f64(w)
+    ost = po.prefill(cfg, w64, toks, S_max)
+    model, state = gpu_prefill(cfg, w, toks, S_max)
+    G = T // cfg.meta_context
+    assert state.k.dtype == torch.uint8
+    for got, ref in ((state.k, ost["k"]), (state.v, ost["v"])):
+        gv = po.e4m3_decode(got.cpu().numpy()[:, :, :, :G, :cfg.d_h])
+        rv = ref[:, :, :, :G]
+        # entries are E4M3 roundings of values computed in fp32 here and float64 there: equal but for near-ties
+        assert (gv == rv).mean() >= 0.97
+        assert np.abs(gv - rv).max() <= 2.0 ** -3 * np.abs(rv).max()
+        assert not got.cpu().numpy()[:, :, :, G:].any()
+    assert nerr(state.x_top, ost["x_top"]) <= TOL["bf16"] and nerr(state.carry, ost["carry"]) <= TOL["bf16"]
+    forced = si.make_tokens(cfg.vocab, Bt, cfg.meta_context, 9)
+    otr = po.decode_step(cfg, w64, ost, forced_tokens=forced)
+    out = torch.full((Bt, cfg.meta_context), -1, dtype=torch.int32, device="cuda")
+    logits = torch.full((Bt, cfg.meta_context, cfg.vocab), float("nan"), device="cuda")
+    ph.photon_decode_step(model, state, out, forced_tokens=dev(np.asarray(forced, np.int32)), trace={"logits": logits})
+    torch.cuda.synchronize()
+    assert nerr(logits, otr["logits"]) <= TOL["bf16"]
+    assert nerr(state.x_top, otr["x_top"]) <= TOL["bf16"]
+
