@@ -7,12 +7,15 @@
 //
 // One workgroup of 4 waves owns a (64 WT) x (64 WT) output tile, each wave a quadrant of WT x WT
 // MFMA 32x32x16 tiles (WT = 4: 256x256 tile, 128x128 per wave, 256 fp32 accumulators per lane; WT = 2 and 1 for
-// problems with too few big tiles to fill the chip).  K is walked in 64-wide slabs, double-buffered in LDS;
-// the next slab is moved global -> LDS directly (no staging registers) while the current slab's MFMAs
-// run, and operand fragments are double-buffered in registers.  LDS rows are 128 bytes with the 16-byte
-// column index XOR-ed by (row>>1)&7, which keeps the 128-bit operand reads of 16 consecutive rows on
-// distinct banks.  Workgroup ids are remapped so that the tiles resident on one XCD at a time share x
-// row-blocks and W column-blocks in that XCD's L2.
+// problems with too few big tiles to fill the chip).  K is walked in slabs held in 2 or 3 LDS buffers (bf16
+// operands: 64 wide, x and W; fp32 activations: 32 wide, heads, remainders and W); the coming slabs are moved
+// global -> LDS directly (no staging registers) while the current slab's MFMAs run, and operand fragments are
+// double-buffered in registers.  LDS rows are 128 (64) bytes with the 16-byte column index XOR-ed with row bits,
+// which keeps the 128-bit operand reads of 16 consecutive rows on distinct banks.  Workgroup ids are remapped so
+// that the tiles resident on one XCD at a time share x row-blocks and W column-blocks in that XCD's L2.
+// What bounds the kernel is the rate at which a compute unit takes its slabs in (about 40 bytes per ns), not the
+// matrix cores: the tile is as large as the accumulator registers allow, W is fetched once per slab for heads and
+// remainders together, and the gate/up projection forms SwiGLU in the accumulators instead of writing both halves.
 #include "photon_device.h"
 #include "photon_host.h"
 #include "photon_linear.h"
