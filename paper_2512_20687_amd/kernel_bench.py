@@ -70,6 +70,12 @@ def bench_probe():
         us = _time_us(lambda i: ph.photon_hbm_read_probe(big[(i % slots) * n:(i % slots) * n + n], sink), 4 * slots, warm=slots)
         _emit("hbm_read_probe_kernel", f"{mb} MB, rotating", us, bytes_=n)
     del big
+    # a plain device-to-device copy (the runtime's own kernel): the ceiling of a stream that reads and writes
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    us = _time_us(lambda i: dst.copy_(src), 10)
+    _emit("device-to-device copy (runtime)", "1 GiB read + 1 GiB written", us, bytes_=2 * src.numel())
+    del src, dst
     # matrix cores alone: the rate they sustain (and so the clock they run at) depends on the operand values
     fsink = torch.zeros(4, device="cuda")
     for rnd, what in ((False, "small constant operands"), (True, "operands spread like N(0,1) data")):
