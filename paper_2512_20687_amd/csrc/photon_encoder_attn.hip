@@ -29,9 +29,12 @@
 //   * the score accumulators start from minus the running maximum (kept as a
 //     register vector that changes only when the maximum does), so the common
 //     path per score is exp2, one add into the row sum and the fp16 pack.
-//   * a workgroup = 8 waves = 256 queries of one (sequence, head) share every
+//   * a workgroup = 12 waves = 384 queries of one (sequence, head) share every
 //     key block of 64 (K, V^T: 16 KB = one 16-byte piece of each array per
-//     thread): what bounds the kernel is the K/V traffic into
+//     thread of the first 8 waves; three waves per SIMD is what the kernel's
+//     registers allow, and the phases of a wave - score MFMAs, softmax on the
+//     vector ALUs, value MFMAs - are serial, so every further wave fills gaps:
+//     measured +15 % at 32768 positions and +48 % at 8192 against 8 waves): what bounds the kernel is the K/V traffic into
 //     the compute unit, so the query block is as large as the wave count
 //     allows.  Blocks are requested two ahead into registers and written to a
 //     double-buffered, XOR-swizzled LDS image one ahead (memory latency spans
@@ -53,7 +56,8 @@ typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 constexpr int EA_DH = 64;          // head size of the MFMA path
-constexpr int EA_WAVES = 8;
+constexpr int EA_WAVES = 12;        // 3 per SIMD: what the kernel's registers allow
+constexpr int EA_MOVERS = 8;        // waves that move the key blocks: 512 threads = one 16-byte piece of each array
 constexpr int EA_BQ = EA_WAVES * 32; // queries per workgroup (32 per wave)
 constexpr int EA_BK = 64;          // keys per block
 constexpr int EA_THREADS = EA_WAVES * 64;
@@ -225,15 +229,17 @@ __global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const uin
 
   // A key block is 2 arrays of 64 rows x 128 bytes = 512 pieces of 16 bytes each: thread t moves piece (row t/8,
   // column t%8) of both arrays, global -> registers -> LDS (swizzled).
-  const int prow = tid >> 3, pcol = tid & 7;
+  const int prow = (tid >> 3) & 63, pcol = tid & 7;
   const int poff = swz(prow, pcol);
   struct Pieces { uint4_t kh, vt; };
   auto fetch = [&](int kb, int n_kb_, Pieces& r) __attribute__((always_inline)) {
+    if (wave >= EA_MOVERS) return;
     const int64_t k0 = (int64_t)(kb < n_kb_ ? kb : n_kb_ - 1) * EA_BK;      // past the end: the last block again (in bounds, unused)
     r.kh = load16(khb + (k0 + prow) * EA_DH + pcol * 8);
     r.vt = load16(vtb + (int64_t)prow * Mp + k0 + pcol * 8);
   };
   auto put = [&](const Pieces& r, int buf) __attribute__((always_inline)) {
+    if (wave >= EA_MOVERS) return;
     char* base = lds + buf * STAGE;
     *reinterpret_cast<uint4_t*>(base + poff) = r.kh;
     *reinterpret_cast<uint4_t*>(base + V_OFF + poff) = r.vt;
