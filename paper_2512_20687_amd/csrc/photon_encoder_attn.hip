@@ -34,7 +34,10 @@
 //     thread of the first 8 waves; three waves per SIMD is what the kernel's
 //     registers allow, and the phases of a wave - score MFMAs, softmax on the
 //     vector ALUs, value MFMAs - are serial, so every further wave fills gaps:
-//     measured +15 % at 32768 positions and +48 % at 8192 against 8 waves): what bounds the kernel is the K/V traffic into
+//     measured +15 % at 32768 positions and +48 % at 8192 against 8 waves;
+//     16 waves fit only with 128 registers per lane, which the compiler reaches
+//     - queries kept in LDS, one register stage - at the price of a slower
+//     schedule: 15 % behind 12 waves): what bounds the kernel is the K/V traffic into
 //     the compute unit, so the query block is as large as the wave count
 //     allows.  Blocks are requested two ahead into registers and written to a
 //     double-buffered, XOR-swizzled LDS image one ahead (memory latency spans
