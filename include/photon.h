@@ -171,10 +171,17 @@ PHOTON_API int32_t photon_encoder_attn(const float* qkv, float* out, int32_t Bt,
  *   gain [K], bias [N]   fp32 or NULL;   res [M, N] fp32 (epilogue 1)
  *   out  [M, N]          fp32
  * bf16 needs K % 64 == 0 and N % 16 == 0; fp32 needs K % 4 == 0.
+ * With dt = bf16 two flags may be added to `epilogue` (the decode step keeps the
+ * feed-forward's hidden rows, Eq. 6-7's SwiGLU product, in bf16 this way):
+ *   PHOTON_LINEAR_OUT_BF16: out holds bf16 values (the result rounded to nearest even);
+ *   PHOTON_LINEAR_X_BF16  : x holds bf16 values, which enter the matrix cores as they are;
+ *                           needs gain == NULL, epilogue 0 or 1, N % 8 == 0.
  * One kernel, no workspace; run-to-run deterministic.
  * -------------------------------------------------------------------------- */
-PHOTON_API int32_t photon_linear(const float* x, const void* w, const float* gain, float rms_eps, const float* bias,
-                                 const float* res, float* out, int32_t M, int32_t N, int32_t K, int32_t epilogue,
+#define PHOTON_LINEAR_X_BF16 0x10
+#define PHOTON_LINEAR_OUT_BF16 0x20
+PHOTON_API int32_t photon_linear(const void* x, const void* w, const float* gain, float rms_eps, const float* bias,
+                                 const float* res, void* out, int32_t M, int32_t N, int32_t K, int32_t epilogue,
                                  photon_dtype dt, void* stream);
 
 /* --------------------------------------------------------------------------
@@ -194,7 +201,11 @@ PHOTON_API int32_t photon_linear(const float* x, const void* w, const float* gai
  * module, SwiGLU feed-forward unless d_ff == 0), one final RMSNorm per module.
  *
  * Host structs below hold DEVICE pointers.  Matrices/tables are `dt`; gains,
- * biases and all state vectors are fp32.
+ * biases and all state vectors are fp32.  Arithmetic with dt = bf16: residual
+ * stream, norms, softmax and every accumulation in fp32; the feed-forward's
+ * hidden rows are kept in bf16, and so are the rows entering a projection once
+ * a pass holds 128 rows or more (below that they enter as a bf16 head plus a
+ * bf16 remainder, i.e. with fp32 accuracy).
  * -------------------------------------------------------------------------- */
 typedef struct photon_config {
   int32_t L;                     /* levels, 1..PHOTON_MAX_LEVELS */

@@ -222,12 +222,21 @@ def photon_profile_get() -> dict:
     return out
 
 
+PHOTON_LINEAR_X_BF16 = 0x10
+PHOTON_LINEAR_OUT_BF16 = 0x20
+
+
 def photon_linear(x, w, out, gain=None, rms_eps: float = 1e-5, bias=None, res=None, epilogue: int = 0):
-    """out[M, N] = epilogue(rmsnorm(x; gain) @ w^T); x, gain, bias, res, out fp32; w fp32 or bf16.
+    """out[M, N] = epilogue(rmsnorm(x; gain) @ w^T); gain, bias, res fp32; w fp32 or bf16; x and out fp32, or
+    (bf16 w only) bf16: the matching flag is added to the epilogue code.
     epilogue 0: + bias; 1: res + . + bias; 2: silu(gate) * up with w = [gate rows; up rows]."""
     lib = load_library()
     M, K = x.shape
     N = out.shape[1]
+    if x.dtype == torch.bfloat16:
+        epilogue |= PHOTON_LINEAR_X_BF16
+    if out.dtype == torch.bfloat16:
+        epilogue |= PHOTON_LINEAR_OUT_BF16
     _check(lib.photon_linear(_ptr(x), _ptr(w), _ptr(gain), rms_eps, _ptr(bias), _ptr(res), _ptr(out), M, N, K, epilogue,
                              _dt(w), _stream()))
     return out

@@ -1,21 +1,22 @@
 // Dense bf16 contractions on the matrix cores: out[M,N] = x[M,K] * W[N,K]^T (+ bias, + residual).
 //   * the context-chunker projection (paper Eq. 4) at many-row shapes: bf16 in, bf16 out;
-//   * the block projections of a decode step once a level carries many rows (large batches, deep
-//     hierarchies): fp32 activations are normalised and split into a bf16 head and a bf16 remainder by a
-//     row kernel, and every slab of W meets the slab of heads and the slab of remainders, so the product is as
-//     accurate as fp32-activation x bf16-weight, as in the few-row kernels.
+//   * the block projections of the prefill, and of a decode step once a level carries many rows (large
+//     batches, deep hierarchies): a row kernel normalises the fp32 activations and rounds them to bf16, the
+//     matrix cores' operand type (the few-row kernels keep a bf16 remainder as well; at many rows that second
+//     pass over the matrix cores costs a fifth of the prefill and of a large-batch step, for accuracy far
+//     beyond what bf16 matrices and a bf16 cache leave).
 //
 // One workgroup of 4 waves owns a (64 WT) x (64 WT) output tile, each wave a quadrant of WT x WT
 // MFMA 32x32x16 tiles (WT = 4: 256x256 tile, 128x128 per wave, 256 fp32 accumulators per lane; WT = 2 and 1 for
-// problems with too few big tiles to fill the chip).  K is walked in slabs held in 2 or 3 LDS buffers (bf16
-// operands: 64 wide, x and W; fp32 activations: 32 wide, heads, remainders and W); the coming slabs are moved
+// problems with too few big tiles to fill the chip).  K is walked in 64-wide slabs of x and W held in 2 LDS
+// buffers; the coming slabs are moved
 // global -> LDS directly (no staging registers) while the current slab's MFMAs run, and operand fragments are
 // double-buffered in registers.  LDS rows are 128 (64) bytes with the 16-byte column index XOR-ed with row bits,
 // which keeps the 128-bit operand reads of 16 consecutive rows on distinct banks.  Workgroup ids are remapped so
 // that the tiles resident on one XCD at a time share x row-blocks and W column-blocks in that XCD's L2.
 // What bounds the kernel is the rate at which a compute unit takes its slabs in (about 40 bytes per ns), not the
-// matrix cores: the tile is as large as the accumulator registers allow, W is fetched once per slab for heads and
-// remainders together, and the gate/up projection forms SwiGLU in the accumulators instead of writing both halves.
+// matrix cores: the tile is as large as the accumulator registers allow, and the gate/up projection forms SwiGLU
+// in the accumulators instead of writing both halves.
 #include "photon_device.h"
 #include "photon_host.h"
 #include "photon_linear.h"
@@ -56,13 +57,11 @@ enum GemmOut { GEMM_OUT_BF16 = 0, GEMM_OUT_F32 = 1, GEMM_OUT_SWIGLU = 2 };
 // Cout fp32 [M, ldc] = acc + bias + res.  OUT SwiGLU (WT even): B has 2N rows, gate rows then up rows; a tile covers
 // 32 WT output columns and takes the gate rows of 32 columns into the even MFMA column tiles of a wave and the up
 // rows of the same columns into the odd ones, so that silu(gate) * up is formed in registers:
-// Cout fp32 [M, ldc] = silu(x Wg^T) * (x Wu^T).  BK: k per slab (64 or 32); NB: slab buffers in LDS (NB - 1 slabs are
-// in flight while one is contracted).  SPLIT: x is given as heads A and remainders A_lo; a slab holds both next to
-// ONE slab of W, whose fragments meet both in registers (what bounds the kernel is the bytes a compute unit takes
-// in per MFMA: two passes over K would fetch W twice).
-template <int WT, int OUT, int BK, int NB, bool SPLIT>
+// Cout bf16 [M, ldc] = silu(x Wg^T) * (x Wu^T).  BK: k per slab (64 or 32); NB: slab buffers in LDS (NB - 1 slabs are
+// in flight while one is contracted).
+template <int WT, int OUT, int BK, int NB>
 __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
-    const bf16_t* __restrict__ A, const bf16_t* __restrict__ A_lo, const bf16_t* __restrict__ B, const float* __restrict__ bias,
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const float* __restrict__ bias,
     const float* res, int64_t ldres, void* Cout, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n) {
   constexpr int BM = 64 * WT;                                   // tile edge (rows and columns)
   constexpr int WE = 32 * WT;                                   // wave quadrant edge
@@ -70,11 +69,11 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
   constexpr int CPR = BK / 8;                                   // 16-byte columns per slab row
   constexpr int RPI = 64 / CPR;                                 // slab rows one load instruction covers
   constexpr int ROUNDS = BM / (4 * RPI);
-  constexpr int OPS = SPLIT ? 3 : 2;                            // operand slabs per buffer: x (heads), [x remainders], W
+  constexpr int OPS = 2;                                        // operand slabs per buffer: x, W
   constexpr int STAGE_BYTES = OPS * TILE_BYTES;
   constexpr int B_OFF = (OPS - 1) * TILE_BYTES;
   constexpr int LPS = OPS * ROUNDS;                             // load instructions per slab and wave
-  extern __shared__ __align__(16) char lds[];                   // [NB buffers][A slab | (A_lo slab) | B slab]
+  extern __shared__ __align__(16) char lds[];                   // [NB buffers][A slab | B slab]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // scalar: the LDS targets of the direct loads are wave-uniform
 
@@ -122,7 +121,6 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
     for (int i = 0; i < ROUNDS; ++i) {
       const int off = (i * 4 + wave) * 1024;
       load16_to_lds(A + aoff[i] + kk, (uint32_t)(uintptr_t)(lptr_t)(sa + off));
-      if (SPLIT) load16_to_lds(A_lo + aoff[i] + kk, (uint32_t)(uintptr_t)(lptr_t)(sa + TILE_BYTES + off));
       load16_to_lds(bptr[i] + kk, (uint32_t)(uintptr_t)(lptr_t)(sa + B_OFF + off));
     }
   };
@@ -148,9 +146,9 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
   // The fragment reads of the next step are issued in two halves (x rows, then W rows) around the first row of
   // MFMAs: the counter of outstanding LDS operations holds 15 at most, and with the 2 WT reads of the next step
   // on top of the 2 WT of the current one the compiler could no longer wait for the older ones alone.
-  bf16x8_t af[2][WT], afl[2][WT], bfr[2][WT];
-  auto frags_a = [&](int buf, int ks, bf16x8_t (&a)[WT], int which = 0) {
-    const char* sa = lds + buf * STAGE_BYTES + which * TILE_BYTES;
+  bf16x8_t af[2][WT], bfr[2][WT];
+  auto frags_a = [&](int buf, int ks, bf16x8_t (&a)[WT]) {
+    const char* sa = lds + buf * STAGE_BYTES;
 #pragma unroll
     for (int i = 0; i < WT; ++i)
       a[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4_t*>(sa + swz<BK>(wm + i * 32 + frow, ks * 2 + fk)));
@@ -171,7 +169,7 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
 #pragma unroll
       for (int j = 0; j < WT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
   };
-  // one 16-wide step of register set `cur`: contract (heads, W) [and (remainders, W)] while the fragments of the
+  // one 16-wide step of register set `cur`: contract (x, W) while the fragments of the
   // following step (buffer nbuf, step nks) arrive in the other register set
   auto step = [&](int cur, int nbuf, int nks) {
     const int nx = cur ^ 1;
@@ -179,18 +177,10 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
     __builtin_amdgcn_sched_barrier(0);
     mfma_first(af[cur], bfr[cur]);
     __builtin_amdgcn_sched_barrier(0);
-    if (SPLIT) frags_a(nbuf, nks, afl[nx], 1); else frags_b(nbuf, nks, bfr[nx]);
+    frags_b(nbuf, nks, bfr[nx]);
     __builtin_amdgcn_sched_barrier(0);
     mfma_rest(af[cur], bfr[cur]);
     __builtin_amdgcn_sched_barrier(0);
-    if (SPLIT) {
-      mfma_first(afl[cur], bfr[cur]);
-      __builtin_amdgcn_sched_barrier(0);
-      frags_b(nbuf, nks, bfr[nx]);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_rest(afl[cur], bfr[cur]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
   };
 
 #pragma unroll
@@ -198,7 +188,6 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NB - 1) * LPS)); // slab 0 has landed
   __syncthreads();
   frags_a(0, 0, af[0]);
-  if (SPLIT) frags_a(0, 0, afl[0], 1);
   frags_b(0, 0, bfr[0]);
   int buf = 0;
   for (int kt = 0; kt < KT2; ++kt) {
@@ -226,7 +215,7 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
         for (int v = 0; v < 16; ++v) {
           const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
           if (m >= M) continue;
-          reinterpret_cast<float*>(Cout)[(int64_t)m * ldc + n] = silu(acc[i][j][v]) * acc[i][j + 1][v];
+          reinterpret_cast<bf16_t*>(Cout)[(int64_t)m * ldc + n] = from_f32<bf16_t>(silu(acc[i][j][v]) * acc[i][j + 1][v]);
         }
       }
     }
@@ -255,10 +244,10 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
   }
 }
 
-// Row kernel in front of the fp32-activation contraction: optional RMS norm with gain, then the split
-// x = head + remainder (both bf16, x - head - remainder = O(2^-17 x)).  One workgroup per row.
-__global__ __launch_bounds__(256) void norm_split_rows_kernel(const float* __restrict__ x, int64_t ldx, const float* __restrict__ gain,
-                                                              float eps, bf16_t* __restrict__ hi, bf16_t* __restrict__ lo, int K) {
+// Row kernel in front of the contraction of fp32 activations: optional RMS norm with gain, then rounding to bf16
+// (nearest even).  One workgroup per row.
+__global__ __launch_bounds__(256) void norm_round_rows_kernel(const float* __restrict__ x, int64_t ldx, const float* __restrict__ gain,
+                                                              float eps, bf16_t* __restrict__ xb, int K) {
   const int tid = threadIdx.x;
   const float* xr = x + (int64_t)blockIdx.x * ldx;
   float r = 1.f;
@@ -275,29 +264,24 @@ __global__ __launch_bounds__(256) void norm_split_rows_kernel(const float* __res
     __syncthreads();
     r = 1.0f / sqrtf(((partsum[0] + partsum[1]) + (partsum[2] + partsum[3])) / (float)K + eps);
   }
-  uint2* ho = reinterpret_cast<uint2*>(hi + (int64_t)blockIdx.x * K);
-  uint2* lw = reinterpret_cast<uint2*>(lo + (int64_t)blockIdx.x * K);
+  uint2* o = reinterpret_cast<uint2*>(xb + (int64_t)blockIdx.x * K);
   for (int k = tid * 4; k < K; k += 1024) {
     float4_t v = *reinterpret_cast<const float4_t*>(xr + k);    // second read of the row: it is in cache
     if (gain != nullptr) v = v * *reinterpret_cast<const float4_t*>(gain + k) * r;
-    uint32_t h01, l01, h23, l23;
-    split_bf16x2(v.x, v.y, h01, l01);
-    split_bf16x2(v.z, v.w, h23, l23);
-    ho[k >> 2] = uint2{h01, h23};
-    lw[k >> 2] = uint2{l01, l23};
+    o[k >> 2] = uint2{pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
   }
 }
 
-// out[m, n] = silu(gu[m, n]) * gu[m, N + n], gu fp32 [M, 2N].
-__global__ __launch_bounds__(256) void swiglu_rows_kernel(const float* __restrict__ gu, float* __restrict__ out, int64_t ldo, int N) {
+// out[m, n] = silu(gu[m, n]) * gu[m, N + n], gu fp32 [M, 2N], out bf16.
+__global__ __launch_bounds__(256) void swiglu_rows_kernel(const float* __restrict__ gu, bf16_t* __restrict__ out, int64_t ldo, int N) {
   const float* g = gu + (int64_t)blockIdx.x * 2 * N;
-  float* o = out + (int64_t)blockIdx.x * ldo;
+  bf16_t* o = out + (int64_t)blockIdx.x * ldo;
   for (int n = threadIdx.x * 4; n < N; n += 1024) {
     const float4_t a = *reinterpret_cast<const float4_t*>(g + n);
     const float4_t u = *reinterpret_cast<const float4_t*>(g + N + n);
     float4_t y;
     y.x = silu(a.x) * u.x; y.y = silu(a.y) * u.y; y.z = silu(a.z) * u.z; y.w = silu(a.w) * u.w;
-    *reinterpret_cast<float4_t*>(o + n) = y;
+    *reinterpret_cast<uint2*>(o + n) = uint2{pack_bf16x2(y.x, y.y), pack_bf16x2(y.z, y.w)};
   }
 }
 
@@ -306,22 +290,22 @@ __global__ __launch_bounds__(256) void copy_bytes16_kernel(const uint4_t* __rest
   if (idx < n16) dst[idx] = src[idx];
 }
 
-template <int WT, int OUT, int BK, int NB, bool SPLIT>
-static int32_t launch_gemm_v(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, const float* bias, const float* res,
+template <int WT, int OUT, int BK, int NB>
+static int32_t launch_gemm_v(int cls, const bf16_t* A, const bf16_t* B, const float* bias, const float* res,
                              int64_t ldres, void* out, int64_t ldc, int64_t M, int N, int K, hipStream_t st) {
   constexpr int BM = 64 * WT;
   constexpr int BN = (OUT == GEMM_OUT_SWIGLU) ? BM / 2 : BM;   // output columns of a tile
   const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
   const int64_t grid = (int64_t)tiles_m * tiles_n;
-  const size_t lds_bytes = (size_t)NB * (SPLIT ? 3 : 2) * BM * BK * 2;
+  const size_t lds_bytes = (size_t)NB * 2 * BM * BK * 2;
   static bool attr_set = false;                                  // more than 64 KiB of dynamic LDS has to be allowed once
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WT, OUT, BK, NB, SPLIT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WT, OUT, BK, NB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return fail(PHOTON_ERR_HIP, "gemm: cannot reserve %zu bytes of LDS: %s", lds_bytes, hipGetErrorString(e));
     attr_set = true;
   }
-  PHOTON_LAUNCH(cls, st, (gemm_bf16_kernel<WT, OUT, BK, NB, SPLIT>), dim3((unsigned)grid), dim3(G_THREADS), lds_bytes, st, A, A_lo, B, bias, res,
+  PHOTON_LAUNCH(cls, st, (gemm_bf16_kernel<WT, OUT, BK, NB>), dim3((unsigned)grid), dim3(G_THREADS), lds_bytes, st, A, B, bias, res,
                 ldres, out, ldc, (int)M, N, K, tiles_m, tiles_n);
   return check_launch("gemm_bf16_kernel");
 }
@@ -329,14 +313,9 @@ static int32_t launch_gemm_v(int cls, const bf16_t* A, const bf16_t* A_lo, const
 // Measured: 64-wide slabs in two buffers.  32-wide slabs in three to five buffers (up to 128 KB in flight per
 // compute unit instead of 64 KB) are no faster at the large shapes and slower at the decode-step shapes.
 template <int WT, int OUT>
-static int32_t launch_gemm_t(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, const float* bias, const float* res,
-                             int64_t ldres, void* out, int64_t ldc, int64_t M, int N, int K, hipStream_t st) {
-  if constexpr (OUT != GEMM_OUT_BF16) {
-    // heads and remainders in one pass: 32-wide slabs of three operands in three buffers (144 KB at the 256-wide
-    // tile); measured 5 % ahead of two buffers, and 14-16 % ahead of two passes over K on whole decode steps
-    if (A_lo != nullptr) return launch_gemm_v<WT, OUT, 32, 3, true>(cls, A, A_lo, B, bias, res, ldres, out, ldc, M, N, K, st);
-  }
-  return launch_gemm_v<WT, OUT, 64, 2, false>(cls, A, nullptr, B, bias, res, ldres, out, ldc, M, N, K, st);
+static int32_t launch_gemm_t(int cls, const bf16_t* A, const bf16_t* B, const float* bias, const float* res, int64_t ldres, void* out,
+                             int64_t ldc, int64_t M, int N, int K, hipStream_t st) {
+  return launch_gemm_v<WT, OUT, 64, 2>(cls, A, B, bias, res, ldres, out, ldc, M, N, K, st);
 }
 
 // Largest tile that still gives the chip enough workgroups.
@@ -348,54 +327,62 @@ static int pick_tile(int64_t M, int N) {
 }
 
 template <int OUT>
-static int32_t launch_gemm(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, const float* bias, const float* res,
+static int32_t launch_gemm(int cls, const bf16_t* A, const bf16_t* B, const float* bias, const float* res,
                            int64_t ldres, void* out, int64_t ldc, int64_t M, int N, int K, hipStream_t st) {
   switch (pick_tile(M, N)) {
-    case 4: return launch_gemm_t<4, OUT>(cls, A, A_lo, B, bias, res, ldres, out, ldc, M, N, K, st);
-    case 2: return launch_gemm_t<2, OUT>(cls, A, A_lo, B, bias, res, ldres, out, ldc, M, N, K, st);
-    default: return launch_gemm_t<1, OUT>(cls, A, A_lo, B, bias, res, ldres, out, ldc, M, N, K, st);
+    case 4: return launch_gemm_t<4, OUT>(cls, A, B, bias, res, ldres, out, ldc, M, N, K, st);
+    case 2: return launch_gemm_t<2, OUT>(cls, A, B, bias, res, ldres, out, ldc, M, N, K, st);
+    default: return launch_gemm_t<1, OUT>(cls, A, B, bias, res, ldres, out, ldc, M, N, K, st);
   }
 }
 
 // SwiGLU in the epilogue: N output columns from 2N rows of W.  Returns false when the problem is too small for a
 // tile with paired column tiles (the caller then contracts into a [M, 2N] buffer and applies SwiGLU by rows).
-static bool launch_gemm_swiglu(int cls, const bf16_t* A, const bf16_t* A_lo, const bf16_t* B, float* out, int64_t ldc, int64_t M, int N,
+static bool launch_gemm_swiglu(int cls, const bf16_t* A, const bf16_t* B, bf16_t* out, int64_t ldc, int64_t M, int N,
                                int K, hipStream_t st, int32_t* rc) {
   auto tiles = [&](int wt) { return ((M + 64 * wt - 1) / (64 * wt)) * ((N + 32 * wt - 1) / (32 * wt)); };
-  if (A_lo == nullptr) return false;
-  if (tiles(4) >= 192) *rc = launch_gemm_t<4, GEMM_OUT_SWIGLU>(cls, A, A_lo, B, nullptr, nullptr, 0, out, ldc, M, N, K, st);
-  else if (tiles(2) >= 128) *rc = launch_gemm_t<2, GEMM_OUT_SWIGLU>(cls, A, A_lo, B, nullptr, nullptr, 0, out, ldc, M, N, K, st);
+  if (tiles(4) >= 192) *rc = launch_gemm_t<4, GEMM_OUT_SWIGLU>(cls, A, B, nullptr, nullptr, 0, out, ldc, M, N, K, st);
+  else if (tiles(2) >= 128) *rc = launch_gemm_t<2, GEMM_OUT_SWIGLU>(cls, A, B, nullptr, nullptr, 0, out, ldc, M, N, K, st);
   else return false;
   return true;
 }
 
 static int32_t launch_chunker_gemm(const void* x, const void* w, const float* bias, void* out, int64_t M, int N, int K, hipStream_t st) {
-  return launch_gemm<GEMM_OUT_BF16>(KC_CHUNKER_GEMM, (const bf16_t*)x, nullptr, (const bf16_t*)w, bias, nullptr, 0, out, N, M, N, K, st);
+  return launch_gemm<GEMM_OUT_BF16>(KC_CHUNKER_GEMM, (const bf16_t*)x, (const bf16_t*)w, bias, nullptr, 0, out, N, M, N, K, st);
 }
 
 size_t linear_many_workspace_bytes(int64_t rows, int K_max, int N2_max) {
-  // head and remainder of the activations (bf16 each), then the gate|up product rows (fp32)
-  return (size_t)rows * K_max * 2 * 2 + (size_t)rows * N2_max * sizeof(float);
+  // the activations as bf16, then the gate|up product rows (fp32) of the unfused SwiGLU
+  return (size_t)rows * K_max * 2 + (size_t)rows * N2_max * sizeof(float);
 }
 
 int32_t launch_linear_many(const LinearArgs& a, void* workspace, int K_max, hipStream_t st) {
   if (!a.w_bf16 || a.K % G_BK != 0 || a.K > K_max || a.ldx % 4 != 0)
     return fail(PHOTON_ERR_UNSUPPORTED, "many-row linear: needs bf16 weights, K=%d a multiple of 64 and at most %d", a.K, K_max);
-  bf16_t* hi = reinterpret_cast<bf16_t*>(workspace);
-  bf16_t* lo = hi + (size_t)a.M * K_max;
-  float* gu = reinterpret_cast<float*>(lo + (size_t)a.M * K_max);
-  PHOTON_LAUNCH(KC_NORM, st, norm_split_rows_kernel, dim3(a.M), dim3(256), 0, st, a.x, a.ldx, a.gain, a.eps, hi, lo, a.K);
-  PHOTON_TRY(check_launch("norm_split_rows_kernel"));
+  if (a.out_bf16 != (a.epilogue == EPI_SWIGLU))
+    return fail(PHOTON_ERR_UNSUPPORTED, "many-row linear: the SwiGLU product, and only it, is written as bf16");
+  if (a.x_bf16) {
+    // bf16 rows are the operand as they stand: one pass of the plain contraction
+    if (a.gain != nullptr || a.epilogue == EPI_SWIGLU || a.ldx != a.K)
+      return fail(PHOTON_ERR_UNSUPPORTED, "many-row linear: bf16 activations come dense, without norm or SwiGLU");
+    return launch_gemm<GEMM_OUT_F32>(KC_CHUNKER_GEMM, reinterpret_cast<const bf16_t*>(a.x), (const bf16_t*)a.W, a.bias,
+                                     a.epilogue == EPI_RESID ? a.res : nullptr, a.ldres, a.out, a.ldo, a.M, a.N, a.K, st);
+  }
+  bf16_t* xb = reinterpret_cast<bf16_t*>(workspace);
+  float* gu = reinterpret_cast<float*>(xb + (size_t)a.M * K_max);
+  PHOTON_LAUNCH(KC_NORM, st, norm_round_rows_kernel, dim3(a.M), dim3(256), 0, st, a.x, a.ldx, a.gain, a.eps, xb, a.K);
+  PHOTON_TRY(check_launch("norm_round_rows_kernel"));
   if (a.epilogue == EPI_SWIGLU) {
     if (a.N % 4 != 0) return fail(PHOTON_ERR_UNSUPPORTED, "many-row linear: SwiGLU width %d must be a multiple of 4", a.N);
     int32_t rc = PHOTON_OK;
-    if (launch_gemm_swiglu(KC_CHUNKER_GEMM, hi, lo, (const bf16_t*)a.W, a.out, a.ldo, a.M, a.N, a.K, st, &rc)) return rc;
-    PHOTON_TRY(launch_gemm<GEMM_OUT_F32>(KC_CHUNKER_GEMM, hi, lo, (const bf16_t*)a.W, nullptr, nullptr, 0, gu, 2 * (int64_t)a.N, a.M, 2 * a.N,
+    bf16_t* act = reinterpret_cast<bf16_t*>(a.out);
+    if (launch_gemm_swiglu(KC_CHUNKER_GEMM, xb, (const bf16_t*)a.W, act, a.ldo, a.M, a.N, a.K, st, &rc)) return rc;
+    PHOTON_TRY(launch_gemm<GEMM_OUT_F32>(KC_CHUNKER_GEMM, xb, (const bf16_t*)a.W, nullptr, nullptr, 0, gu, 2 * (int64_t)a.N, a.M, 2 * a.N,
                                          a.K, st));
-    PHOTON_LAUNCH(KC_SILU_MUL, st, swiglu_rows_kernel, dim3(a.M), dim3(256), 0, st, gu, a.out, a.ldo, a.N);
+    PHOTON_LAUNCH(KC_SILU_MUL, st, swiglu_rows_kernel, dim3(a.M), dim3(256), 0, st, gu, act, a.ldo, a.N);
     return check_launch("swiglu_rows_kernel");
   }
-  return launch_gemm<GEMM_OUT_F32>(KC_CHUNKER_GEMM, hi, lo, (const bf16_t*)a.W, a.bias, a.epilogue == EPI_RESID ? a.res : nullptr, a.ldres,
+  return launch_gemm<GEMM_OUT_F32>(KC_CHUNKER_GEMM, xb, (const bf16_t*)a.W, a.bias, a.epilogue == EPI_RESID ? a.res : nullptr, a.ldres,
                                    a.out, a.ldo, a.M, a.N, a.K, st);
 }
 

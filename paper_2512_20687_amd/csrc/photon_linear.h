@@ -13,8 +13,9 @@ enum LinearEpilogue { EPI_PLAIN = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
 //   EPI_RESID : out = res + y + bias            (out may alias res)
 //   EPI_SWIGLU: out = silu(y[:, :N]) * y[:, N:] (W has 2N rows: gate rows, then up rows)
 struct LinearArgs {
-  const float* x = nullptr;    // fp32 [M, K], row pitch ldx elements
+  const float* x = nullptr;    // fp32 [M, K], row pitch ldx elements (x_bf16: bf16 values behind the pointer)
   int64_t ldx = 0;
+  bool x_bf16 = false;         // bf16 weights only, no norm, plain or residual epilogue: x is the MFMA operand as it stands
   const void* W = nullptr;     // [N, K] (2N for EPI_SWIGLU) row-major, bf16 when w_bf16 else fp32
   bool w_bf16 = false;
   const float* gain = nullptr; // [K] or nullptr
@@ -24,6 +25,7 @@ struct LinearArgs {
   int64_t ldres = 0;
   float* out = nullptr;        // [M, N], row pitch ldo
   int64_t ldo = 0;
+  bool out_bf16 = false;       // bf16 weights only: out holds bf16 values (rounded to nearest even), ldo in elements
   int M = 0, N = 0, K = 0;
   int epilogue = EPI_PLAIN;
 };
@@ -34,7 +36,7 @@ int32_t launch_linear(const LinearArgs& a, hipStream_t st);
 // (the caller then takes the streaming kernel).  Arguments must have passed launch_linear's checks.
 bool launch_linear_resident(const LinearArgs& a, hipStream_t st);
 
-// Many rows (dozens and up) with bf16 weights: row kernel (norm, bf16 head/remainder split) + tiled MFMA
+// Many rows (dozens and up) with bf16 weights: row kernel (norm, rounding to bf16) + tiled MFMA
 // contraction + (SwiGLU) row kernel.  `workspace` holds linear_many_workspace_bytes(rows, K_max, N2_max)
 // bytes, K_max >= every K and N2_max >= every 2N of a SwiGLU call that will be issued with it.
 size_t linear_many_workspace_bytes(int64_t rows, int K_max, int N2_max);

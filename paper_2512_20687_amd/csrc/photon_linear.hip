@@ -68,7 +68,7 @@ constexpr int FL_STAGE_BYTES = FL_CB * 2 * 4 * FL_FRAG_PITCH;   // one of hi / l
 template <int NT, int EPI, bool FOLD, int XP, bool NORM>
 __global__ __launch_bounds__(FL_THREADS, (NT == 1 && EPI != EPI_SWIGLU && XP == 2) ? 4 : 2) void fused_linear_bf16_kernel(
     const float* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ W, const float* __restrict__ gain, float eps,
-    const float* __restrict__ bias, const float* res, int64_t ldres, float* out, int64_t ldo, int M, int N, int K) {
+    const float* __restrict__ bias, const float* res, int64_t ldres, float* out, int64_t ldo, int M, int N, int K, int out_bf16) {
   constexpr int CB = FL_CB;
   constexpr bool XPF = true;
   constexpr int TL = (EPI == EPI_SWIGLU) ? 2 * NT : NT;            // MFMA tiles per wave
@@ -257,7 +257,10 @@ __global__ __launch_bounds__(FL_THREADS, (NT == 1 && EPI != EPI_SWIGLU && XP == 
     y.x = silu(y.x) * yu.x; y.y = silu(y.y) * yu.y; y.z = silu(y.z) * yu.z; y.w = silu(y.w) * yu.w;
   }
   y += extra;
-  *reinterpret_cast<float4_t*>(out + (int64_t)m * ldo + n_out) = y;
+  if (out_bf16)
+    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(out) + (int64_t)m * ldo + n_out) = uint2{pack_bf16x2(y.x, y.y), pack_bf16x2(y.z, y.w)};
+  else
+    *reinterpret_cast<float4_t*>(out + (int64_t)m * ldo + n_out) = y;
 }
 
 // fp32 weights (the small all-fp32 configuration): one wave per output column, lanes stride over k
@@ -323,10 +326,10 @@ static void launch_bf16_v(const LinearArgs& a, hipStream_t st) {
   dim3 grid((a.N + COLS - 1) / COLS, (a.M + 15) / 16);
   if (a.gain != nullptr)
     PHOTON_LAUNCH(KC_SKINNY_GEMM, st, (fused_linear_bf16_kernel<NT, EPI, FOLD, XP, true>), grid, dim3(FL_THREADS), 0, st, a.x,
-                  a.ldx, (const bf16_t*)a.W, a.gain, a.eps, a.bias, a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K);
+                  a.ldx, (const bf16_t*)a.W, a.gain, a.eps, a.bias, a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K, a.out_bf16 ? 1 : 0);
   else
     PHOTON_LAUNCH(KC_SKINNY_GEMM, st, (fused_linear_bf16_kernel<NT, EPI, FOLD, XP, false>), grid, dim3(FL_THREADS), 0, st, a.x,
-                  a.ldx, (const bf16_t*)a.W, a.gain, a.eps, a.bias, a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K);
+                  a.ldx, (const bf16_t*)a.W, a.gain, a.eps, a.bias, a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K, a.out_bf16 ? 1 : 0);
 }
 
 template <int EPI, int XP>
@@ -356,6 +359,7 @@ int32_t launch_linear(const LinearArgs& a, hipStream_t st) {
     if (a.K % FL_KBLOCK != 0 || a.N % 16 != 0 || a.ldx % 4 != 0 || a.ldo % 4 != 0 || (a.res && a.ldres % 4 != 0))
       return fail(PHOTON_ERR_UNSUPPORTED, "linear (bf16): K=%d must be a multiple of 64, N=%d of 16, row pitches of 4", a.K, a.N);
     if (launch_linear_resident(a, st)) return check_launch("resident_linear_bf16_kernel");
+    if (a.x_bf16) return fail(PHOTON_ERR_UNSUPPORTED, "linear: bf16 activations need a plain or residual epilogue without norm, N=%d a multiple of 8", a.N);
     switch (a.epilogue) {
       case EPI_PLAIN: launch_bf16_e<EPI_PLAIN>(a, st); break;
       case EPI_RESID: launch_bf16_e<EPI_RESID>(a, st); break;
@@ -363,6 +367,7 @@ int32_t launch_linear(const LinearArgs& a, hipStream_t st) {
     }
     return check_launch("fused_linear_bf16_kernel");
   }
+  if (a.x_bf16 || a.out_bf16) return fail(PHOTON_ERR_UNSUPPORTED, "linear (fp32): activations are fp32");
   if (a.K % 4 != 0 || a.ldx % 4 != 0) return fail(PHOTON_ERR_UNSUPPORTED, "linear (fp32): K=%d and the row pitch must be multiples of 4", a.K);
   dim3 grid((a.N + 3) / 4, (a.M + F32_ROWS - 1) / F32_ROWS);
 #define PHOTON_F32_LAUNCH(E)                                                                                              \
@@ -381,10 +386,13 @@ int32_t launch_linear(const LinearArgs& a, hipStream_t st) {
 
 using namespace photon;
 
-extern "C" int32_t photon_linear(const float* x, const void* w, const float* gain, float rms_eps, const float* bias,
-                                 const float* res, float* out, int32_t M, int32_t N, int32_t K, int32_t epilogue,
+extern "C" int32_t photon_linear(const void* x, const void* w, const float* gain, float rms_eps, const float* bias,
+                                 const float* res, void* out, int32_t M, int32_t N, int32_t K, int32_t epilogue,
                                  photon_dtype dt, void* stream) {
   clear_error();
+  const bool x_bf16 = (epilogue & PHOTON_LINEAR_X_BF16) != 0, out_bf16 = (epilogue & PHOTON_LINEAR_OUT_BF16) != 0;
+  epilogue &= ~(PHOTON_LINEAR_X_BF16 | PHOTON_LINEAR_OUT_BF16);
+  PHOTON_REQUIRE(!(x_bf16 || out_bf16) || dt == PHOTON_BF16, PHOTON_ERR_UNSUPPORTED, "%s: bf16 rows need dt = bf16", __func__);
   PHOTON_REQUIRE(valid_dtype(dt), PHOTON_ERR_UNSUPPORTED, "%s: unknown dtype %d", __func__, (int)dt);
   PHOTON_REQUIRE(M >= 0 && N > 0 && K > 0, PHOTON_ERR_INVALID_ARG, "%s: M=%d N=%d K=%d invalid", __func__, M, N, K);
   if (M == 0) return PHOTON_OK;
@@ -395,7 +403,8 @@ extern "C" int32_t photon_linear(const float* x, const void* w, const float* gai
   PHOTON_REQUIRE(bias == nullptr || aligned16(bias), PHOTON_ERR_INVALID_ARG, "%s: bias is misaligned", __func__);
   PHOTON_REQUIRE(res == nullptr || aligned16(res), PHOTON_ERR_INVALID_ARG, "%s: res is misaligned", __func__);
   LinearArgs a;
-  a.x = x; a.ldx = K; a.W = w; a.w_bf16 = (dt == PHOTON_BF16); a.gain = gain; a.eps = rms_eps; a.bias = bias; a.res = res;
-  a.ldres = N; a.out = out; a.ldo = N; a.M = M; a.N = N; a.K = K; a.epilogue = epilogue;
+  a.x = reinterpret_cast<const float*>(x); a.x_bf16 = x_bf16; a.out_bf16 = out_bf16;
+  a.ldx = K; a.W = w; a.w_bf16 = (dt == PHOTON_BF16); a.gain = gain; a.eps = rms_eps; a.bias = bias; a.res = res;
+  a.ldres = N; a.out = reinterpret_cast<float*>(out); a.ldo = N; a.M = M; a.N = N; a.K = K; a.epilogue = epilogue;
   return launch_linear(a, (hipStream_t)stream);
 }

@@ -44,6 +44,10 @@ __host__ __device__ constexpr int rl_chunk_bytes(int rows) { return 2 * 16 * rl_
 
 // EPI as in LinearEpilogue; XP: live slab pieces per lane (rows = 2*XP of the 16-row tile are live);
 // NORM: RMS pre-norm with gain; TMAX: units per workgroup (register-resident accumulators).
+// XB: the activations are bf16 already (the feed-forward's hidden rows): they ARE the operand, so each lane
+// loads its fragments (8 consecutive k of its row, 16 bytes) straight from memory beside the weights of the
+// same chunk; nothing is staged, normalised or split, LDS only carries the final reduction, and K is not
+// limited by LDS.  Rows beyond M are not loaded (their accumulator columns are never stored).
 //
 // Columns are dealt in units of 8 (SwiGLU: 4): workgroup g owns units [u0, u0 + cnt).  A unit's 8 weight rows form one
 // MFMA tile (SwiGLU: 4 gate rows, then the 4 up rows of the same columns): tile row r and r + 8 are weight row r;
@@ -51,11 +55,12 @@ __host__ __device__ constexpr int rl_chunk_bytes(int rows) { return 2 * 16 * rl_
 // so one load per block fetches whole lines.  The first MFMA of a block uses the registers as loaded, the second
 // after a rotation by 8 lanes inside each row of 16, which brings the second half under rows 0..7.  Accumulator
 // rows 8..15 are meaningless; a unit's 8 weight rows sit in rows 0..7 (lanes 0..31).
-template <int EPI, int XP, bool NORM, int TMAX>
+template <int EPI, int XP, bool NORM, int TMAX, bool XB>
 __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
     const float* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ W, const float* __restrict__ gain, float eps,
     const float* __restrict__ bias, const float* res, int64_t ldres, float* out, int64_t ldo, int M, int N, int K,
-    int unit_base, int unit_rem, int wave_bytes) {
+    int unit_base, int unit_rem, int wave_bytes, int out_bf16) {
+  static_assert(!XB || !NORM, "bf16 activations come without a pre-norm");
   constexpr int CB = RL_CB;
   constexpr int ROWS = 2 * XP;
   constexpr int GP = rl_group_pitch(ROWS);
@@ -93,6 +98,10 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   const int chunks = (total_blocks + CB - 1) / CB;
   const int n_my = wave < chunks ? (chunks - wave + RL_WAVES - 1) / RL_WAVES : 0;   // this wave contracts chunks wave, wave+8, ..
 
+  struct Operands {
+    uint4_t w[TT][CB];                                             // weight fragments of one chunk
+    uint4_t xf[XB ? CB : 1][2];                                    // XB: its activation fragments
+  };
   float4_t acc[TT];
 #pragma unroll
   for (int t = 0; t < TT; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
@@ -101,15 +110,30 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   for (int i = 0; i < XP; ++i) ss[i] = 0.f;
 
   // ---- loads: unconditional, clamped into bounds, so that the load counter can be waited on exactly ----
-  auto load_w = [&](int j, uint4_t (&wf)[TT][CB]) {
+  // bf16 activations: fragment (block b, half) of this lane = k b*64 + half*32 + lq*8 .. +8 of row m0 + lrow
+  const bool xf_live = m0 + lrow < M;
+  const char* xf_lane = reinterpret_cast<const char*>(x) + ((int64_t)(m0 + (xf_live ? lrow : 0)) * ldx + lq * 8) * 2;
+  auto load_w = [&](int j, Operands& o) {
     const int chunk = wave + j * RL_WAVES;
+    if (XB) {                                                      // the (cached) activations first, as below
+#pragma unroll
+      for (int b = 0; b < CB; ++b) {
+        int blk = chunk * CB + b;
+        blk = blk < total_blocks ? blk : total_blocks - 1;
+#pragma unroll
+        for (int half2 = 0; half2 < 2; ++half2) {
+          o.xf[b][half2] = uint4_t{0u, 0u, 0u, 0u};
+          if (xf_live) o.xf[b][half2] = load16(xf_lane + (int64_t)blk * (RL_KBLOCK * 2) + half2 * 64);
+        }
+      }
+    }
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
       int blk = chunk * CB + b;
       blk = blk < total_blocks ? blk : total_blocks - 1;
       const char* wb = w_base + (int64_t)blk * (RL_KBLOCK * 2);
 #pragma unroll
-      for (int t = 0; t < TT; ++t) wf[t][b] = load16_stream(wb + w_lane[t]);   // used once: keep it from displacing the activations
+      for (int t = 0; t < TT; ++t) o.w[t][b] = load16_stream(wb + w_lane[t]);   // used once: keep it from displacing the activations
     }
   };
   // slab piece i of a lane: row i*2 + lane/32, k offset (lane%32)*4 inside the chunk
@@ -123,6 +147,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   }
   const char* x_tile = reinterpret_cast<const char*>(x + (int64_t)m0 * ldx);
   auto load_x = [&](int j, float4_t (&xr)[XP + 1]) {
+    if (XB) return;
     const int chunk = wave + j * RL_WAVES;
     int blk = chunk * CB + (c4 >> 4);
     blk = blk < total_blocks ? blk : total_blocks - 1;
@@ -133,6 +158,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   };
   // scale, split and store chunk j in operand order: group (block, half, q) holds k = b*64 + half*32 + q*8 .. +8 of every row
   auto stage = [&](int j, const float4_t (&xr)[XP + 1]) {
+    if (XB) return;
     const int chunk = wave + j * RL_WAVES;
     char* hi = my_area + j * CHUNK_BYTES;
     char* lo = hi + 16 * GP;
@@ -153,7 +179,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
     }
   };
   const int frag_row = (lrow & (ROWS - 1)) * 16;                   // dead rows read a live row's fragment: never stored
-  auto mma = [&](int j, const uint4_t (&wf)[TT][CB]) {
+  auto mma = [&](int j, const Operands& o) {
     const int chunk = wave + j * RL_WAVES;
     const char* hi = my_area + j * CHUNK_BYTES;
     const char* lo = hi + 16 * GP;
@@ -162,23 +188,50 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
       if (chunk * CB + b < total_blocks) {
 #pragma unroll
         for (int half2 = 0; half2 < 2; ++half2) {
-          const int off = ((b * 2 + half2) * 4 + lq) * GP + frag_row;
-          const bf16x8_t bh = as_bf16x8(*reinterpret_cast<const uint4_t*>(hi + off));
-          const bf16x8_t bl = as_bf16x8(*reinterpret_cast<const uint4_t*>(lo + off));
+          if constexpr (XB) {
+            const bf16x8_t bx = as_bf16x8(o.xf[b][half2]);
 #pragma unroll
-          for (int t = 0; t < TT; ++t) {
-            const bf16x8_t a = as_bf16x8(half2 ? rotate8(wf[t][b]) : wf[t][b]);
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[t], 0, 0, 0);
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[t], 0, 0, 0);
+            for (int t = 0; t < TT; ++t) {
+              const bf16x8_t a = as_bf16x8(half2 ? rotate8(o.w[t][b]) : o.w[t][b]);
+              acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bx, acc[t], 0, 0, 0);
+            }
+          } else {
+            const int off = ((b * 2 + half2) * 4 + lq) * GP + frag_row;
+            const bf16x8_t bh = as_bf16x8(*reinterpret_cast<const uint4_t*>(hi + off));
+            const bf16x8_t bl = as_bf16x8(*reinterpret_cast<const uint4_t*>(lo + off));
+#pragma unroll
+            for (int t = 0; t < TT; ++t) {
+              const bf16x8_t a = as_bf16x8(half2 ? rotate8(o.w[t][b]) : o.w[t][b]);
+              acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[t], 0, 0, 0);
+              acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[t], 0, 0, 0);
+            }
           }
         }
       }
     }
   };
 
-  uint4_t wa[TT][CB], wb[TT][CB];
+  if constexpr (XB) {
+    // Nothing is staged: a ring of NB chunks in flight per wave.  With one or two units per workgroup a chunk is only
+    // 2-3 KB per wave, and two of them per wave cannot cover the memory latency of a long contraction.
+    constexpr int NB = TT == 1 ? 4 : TT == 2 ? 3 : 2;
+    Operands ring[NB];
+#pragma unroll
+    for (int s = 0; s < NB; ++s)
+      if (s < n_my) load_w(s, ring[s]);
+    for (int j = 0; j < n_my; j += NB) {
+#pragma unroll
+      for (int s = 0; s < NB; ++s) {
+        if (j + s < n_my) {
+          mma(j + s, ring[s]);
+          if (j + s + NB < n_my) load_w(j + s + NB, ring[s]);
+        }
+      }
+    }
+  }
+  Operands wa, wb;
   float4_t xa[XP + 1], xb[XP + 1];
-  if (n_my > 0) {
+  if (!XB && n_my > 0) {
     // Activations are requested before the weights: loads return in order, and the (cached) activations must
     // not queue behind weight lines coming from HBM.  Both arms keep the number of loads in flight static.
     // The common depths (one or two chunks per wave) are written out straight.
@@ -271,12 +324,15 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
     y.x = silu(y.x) * yu.x; y.y = silu(y.y) * yu.y; y.z = silu(y.z) * yu.z; y.w = silu(y.w) * yu.w;
   }
   y += extra;
-  *reinterpret_cast<float4_t*>(out + (int64_t)m * ldo + n_out) = y;
+  if (out_bf16)
+    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(out) + (int64_t)m * ldo + n_out) = uint2{pack_bf16x2(y.x, y.y), pack_bf16x2(y.z, y.w)};
+  else
+    *reinterpret_cast<float4_t*>(out + (int64_t)m * ldo + n_out) = y;
 }
 
-template <int EPI, int XP, bool NORM, int TMAX>
+template <int EPI, int XP, bool NORM, int TMAX, bool XB = false>
 bool launch_resident_t(const LinearArgs& a, hipStream_t st, int G, int unit_base, int unit_rem, int wave_bytes, size_t lds) {
-  auto kern = resident_linear_bf16_kernel<EPI, XP, NORM, TMAX>;
+  auto kern = resident_linear_bf16_kernel<EPI, XP, NORM, TMAX, XB>;
   static bool attr_done = false;                                   // more than 64 KiB of dynamic LDS has to be allowed once
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, RL_LDS_LIMIT) != hipSuccess) {
@@ -287,7 +343,7 @@ bool launch_resident_t(const LinearArgs& a, hipStream_t st, int G, int unit_base
   }
   dim3 grid(G, (a.M + 15) / 16);
   PHOTON_LAUNCH(KC_SKINNY_GEMM, st, kern, grid, dim3(RL_THREADS), lds, st, a.x, a.ldx, (const bf16_t*)a.W, a.gain, a.eps, a.bias,
-                a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K, unit_base, unit_rem, wave_bytes);
+                a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K, unit_base, unit_rem, wave_bytes, a.out_bf16 ? 1 : 0);
   return true;
 }
 
@@ -301,6 +357,19 @@ bool launch_resident_x(const LinearArgs& a, hipStream_t st, int tmax, int G, int
     case 5: return launch_resident_t<EPI, XP, NORM, 5>(a, st, G, ub, ur, wave_bytes, lds);
     case 6: return launch_resident_t<EPI, XP, NORM, 6>(a, st, G, ub, ur, wave_bytes, lds);
     default: return launch_resident_t<EPI, XP, NORM, 8>(a, st, G, ub, ur, wave_bytes, lds);
+  }
+}
+
+// bf16 activations: one instantiation per epilogue and unit count (live rows are a run-time mask)
+template <int EPI>
+bool launch_resident_xb(const LinearArgs& a, hipStream_t st, int tmax, int G, int ub, int ur, int wave_bytes, size_t lds) {
+  switch (tmax) {
+    case 1: return launch_resident_t<EPI, 8, false, 1, true>(a, st, G, ub, ur, wave_bytes, lds);
+    case 2: return launch_resident_t<EPI, 8, false, 2, true>(a, st, G, ub, ur, wave_bytes, lds);
+    case 3: return launch_resident_t<EPI, 8, false, 3, true>(a, st, G, ub, ur, wave_bytes, lds);
+    case 4: return launch_resident_t<EPI, 8, false, 4, true>(a, st, G, ub, ur, wave_bytes, lds);
+    case 5: return launch_resident_t<EPI, 8, false, 5, true>(a, st, G, ub, ur, wave_bytes, lds);
+    default: return launch_resident_t<EPI, 8, false, 6, true>(a, st, G, ub, ur, wave_bytes, lds);
   }
 }
 
@@ -318,8 +387,9 @@ bool launch_resident_e(const LinearArgs& a, hipStream_t st, int xp, int tmax, in
 // Returns true when the launch was issued here; false leaves the case to the streaming kernel.
 bool launch_linear_resident(const LinearArgs& a, hipStream_t st) {
   if (!a.w_bf16 || a.K % RL_KBLOCK != 0 || a.N % 8 != 0) return false;
-  if (a.ldx % 4 != 0 || a.ldo % 4 != 0 || (a.res && a.ldres % 4 != 0)) return false;
+  if (a.ldx % (a.x_bf16 ? 8 : 4) != 0 || a.ldo % 4 != 0 || (a.res && a.ldres % 4 != 0)) return false;
   const bool norm = a.gain != nullptr;
+  if (a.x_bf16 && (norm || a.epilogue == EPI_SWIGLU)) return false;
   // instantiated combinations: the ones the decode path uses
   const bool combo = (a.epilogue == EPI_PLAIN) || (a.epilogue == EPI_RESID && !norm) || (a.epilogue == EPI_SWIGLU && norm);
   if (!combo) return false;
@@ -333,7 +403,7 @@ bool launch_linear_resident(const LinearArgs& a, hipStream_t st) {
   // one workgroup per compute unit when there are enough units; more rounds only when a workgroup would exceed the
   // 8 tiles its registers hold
   constexpr int CUS = 256;
-  const int cap = 8;
+  const int cap = a.x_bf16 ? 6 : 8;                               // bf16 activations: the fragments take registers too
   const int rounds = (units + CUS * cap - 1) / (CUS * cap);
   const int G = units < CUS * rounds ? units : CUS * rounds;
   const int ub = units / G, ur = units % G;
@@ -341,10 +411,13 @@ bool launch_linear_resident(const LinearArgs& a, hipStream_t st) {
   if (tmax > 6) tmax = 8;                                          // instantiated: 1 .. 6 and 8 (surplus tiles repeat the last)
   const int chunks = (a.K / RL_KBLOCK + RL_CB - 1) / RL_CB;
   const int n_my_max = (chunks + RL_WAVES - 1) / RL_WAVES;
-  int wave_bytes = n_my_max * rl_chunk_bytes(2 * xp);
+  int wave_bytes = a.x_bf16 ? 0 : n_my_max * rl_chunk_bytes(2 * xp);
   if (wave_bytes < tmax * 1024) wave_bytes = tmax * 1024;          // the partial tiles reuse the area
   const size_t lds = (size_t)RL_WAVES * wave_bytes + RL_WAVES * 16 * sizeof(float);
   if (lds > (size_t)RL_LDS_LIMIT) return false;
+  if (a.x_bf16)
+    return a.epilogue == EPI_RESID ? launch_resident_xb<EPI_RESID>(a, st, tmax, G, ub, ur, wave_bytes, lds)
+                                   : launch_resident_xb<EPI_PLAIN>(a, st, tmax, G, ub, ur, wave_bytes, lds);
   switch (a.epilogue) {
     case EPI_PLAIN:
       return norm ? launch_resident_e<EPI_PLAIN, true>(a, st, xp, tmax, G, ub, ur, wave_bytes, lds)

@@ -307,8 +307,10 @@ struct RowsIn {
 };
 
 static int32_t linear(const Ctx& x, const float* in, int64_t ldx, const void* W, const float* gain, const float* bias,
-                      const float* res, int64_t ldres, float* out, int64_t ldo, int M, int N, int K, int epilogue) {
+                      const float* res, int64_t ldres, float* out, int64_t ldo, int M, int N, int K, int epilogue,
+                      bool in_bf16 = false, bool out_bf16 = false) {
   LinearArgs a;
+  a.x_bf16 = in_bf16; a.out_bf16 = out_bf16;
   a.x = in; a.ldx = ldx; a.W = W; a.w_bf16 = x.bf16; a.gain = gain; a.eps = x.c->rms_eps; a.bias = bias; a.res = res;
   a.ldres = ldres; a.out = out; a.ldo = ldo; a.M = M; a.N = N; a.K = K; a.epilogue = epilogue;
   if (x.bf16 && M >= LINEAR_MANY_ROWS && K <= x.p.many_K && (epilogue != EPI_SWIGLU || 2 * N <= 2 * x.c->d_ff))
@@ -330,8 +332,9 @@ static int32_t block_tail(const Ctx& x, const photon_layer_weights& lw, RowsIn i
   float *h = x.f(x.o_h), *attn = x.f(x.o_attn), *act = x.f(x.o_act);
   PHOTON_TRY(linear(x, attn, c.D, lw.wo, nullptr, nullptr, in.ptr, in.ld, h, c.D, rows, c.D, c.D, EPI_RESID));
   if (c.d_ff == 0) return PHOTON_OK;
-  PHOTON_TRY(linear(x, h, c.D, lw.wgu, lw.g2, nullptr, nullptr, 0, act, c.d_ff, rows, c.d_ff, c.D, EPI_SWIGLU));
-  return linear(x, act, c.d_ff, lw.wd, nullptr, nullptr, h, c.D, h, c.D, rows, c.D, c.d_ff, EPI_RESID);
+  // with bf16 matrices the hidden rows are kept as bf16: they are the down projection's MFMA operand as they stand
+  PHOTON_TRY(linear(x, h, c.D, lw.wgu, lw.g2, nullptr, nullptr, 0, act, c.d_ff, rows, c.d_ff, c.D, EPI_SWIGLU, false, x.bf16));
+  return linear(x, act, c.d_ff, lw.wd, nullptr, nullptr, h, c.D, h, c.D, rows, c.D, c.d_ff, EPI_RESID, x.bf16, false);
 }
 
 // All blocks of the level-`level` local decoder on n_chunks * q_len rows (window positions

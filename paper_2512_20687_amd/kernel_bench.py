@@ -288,6 +288,10 @@ def bench_linear():
             g = torch.rand(K, device="cuda") + 0.5 if norm else None
             us = _time_us(lambda i: ph.photon_linear(x, ws[i % nb], out, gain=g, rms_eps=1e-5, res=res, epilogue=epi), 4 * nb, warm=nb)
             _emit("linear_bf16_kernels", f"{what}: M={M} N={N} K={K}", us, bytes_=rows_w * K * 2)
+            if epi == 1 and K > N:                      # as the decode step runs it: the hidden rows are bf16
+                xb = x.to(torch.bfloat16)
+                us = _time_us(lambda i: ph.photon_linear(xb, ws[i % nb], out, res=res, epilogue=epi), 4 * nb, warm=nb)
+                _emit("linear_bf16_kernels", f"{what}, bf16 rows in: M={M} N={N} K={K}", us, bytes_=rows_w * K * 2)
             del ws
 
 

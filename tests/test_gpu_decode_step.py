@@ -226,7 +226,8 @@ def test_full_width_step_one_block_per_module():
     st = si.make_decode_state(cfg, wl.Bt, S, S_max, seed=9)
     forced = si.make_tokens(cfg.vocab, wl.Bt, cfg.meta_context, 10)
     errs, _, _ = check_against_oracle(cfg, w, st, wl.Bt, S_max, forced, TOL["bf16"])
-    assert errs["logits"] <= 1e-3, errs      # fp32 activations x bf16 weights: far inside the bf16 bar
+    # fp32 residual stream x bf16 weights, bf16 cache rows and bf16 hidden rows of the feed-forward: far inside the bf16 bar
+    assert errs["logits"] <= 3e-3, errs
 
 
 @pytest.mark.parametrize("name,Bt,S", [
@@ -245,7 +246,7 @@ def test_full_width_step_other_configurations(name, Bt, S):
     st = si.make_decode_state(cfg, Bt, S, S_max, seed=19)
     forced = si.make_tokens(cfg.vocab, Bt, cfg.meta_context, 20)
     errs, _, _ = check_against_oracle(cfg, w, st, Bt, S_max, forced, TOL["bf16"])
-    assert errs["logits"] <= 1e-3, errs
+    assert errs["logits"] <= 8e-3, errs      # many rows: activations enter the tiled contraction rounded to bf16
 
 
 def _adjacent_codes(got_codes, want_values):

@@ -82,3 +82,64 @@ def test_linear_in_place_residual_and_determinism():
     assert torch.equal(a, b)
     ref = h0 + po.linear(x.cpu().numpy(), w.float().cpu().numpy())
     assert nerr(a, ref) <= 2 * TOL["f32"]
+
+
+def bf16_values(a):
+    """The values of `a` rounded to bf16 (nearest even), as float64."""
+    return torch.from_numpy(np.asarray(a, np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+@pytest.mark.parametrize("M,N,K,epilogue,bias", [
+    (1, 64, 64, 0, False), (4, 2048, 5120, 1, False), (16, 2048, 5120, 1, False), (16, 1664, 4096, 1, True),
+    (7, 208, 448, 0, True),          # odd number of k blocks, 26 units
+    (40, 272, 1024, 1, False),       # three row tiles, the last one ragged
+    (3, 16384, 192, 0, False),       # 2048 units: several per workgroup
+])
+def test_linear_bf16_rows_in(M, N, K, epilogue, bias):
+    """bf16 activations enter the matrix cores as they are: exact products of bf16 values, fp32 sums."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    x = bf16_values(si.make_normal((M, K), 5, "f32"))
+    w = si.make_normal((N, K), 6, "bf16", std=0.05)
+    b = si.make_normal((N,), 7, "f32", std=0.1) if bias else None
+    res = si.make_normal((M, N), 8, "f32") if epilogue == 1 else None
+    ref = oracle_linear(x, w, None, 1e-5, b, res, epilogue, N)
+    out = torch.full((M, N), float("nan"), device="cuda")
+    opt = lambda a: None if a is None else dev(np.asarray(a, np.float32))
+    ph.photon_linear(dev(x, "bf16"), dev(w, "bf16"), out, bias=opt(b), res=opt(res), epilogue=epilogue)
+    torch.cuda.synchronize()
+    assert nerr(out, ref) <= 2 * TOL["f32"]
+
+
+@pytest.mark.parametrize("M,N,K,norm", [(4, 5120, 2048, True), (16, 5120, 2048, True), (40, 272, 1024, True), (16, 96, 8192, False)])
+def test_linear_bf16_rows_out(M, N, K, norm):
+    """SwiGLU product stored as bf16: the fp32 result rounded once (the last shape takes the streaming kernel)."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    x = si.make_normal((M, K), 9, "f32")
+    w = si.make_normal((2 * N, K), 10, "bf16", std=0.05)
+    gain = si.make_normal((K,), 11, "f32", std=0.3) + 1.0 if norm else None
+    ref = oracle_linear(x, w, gain, 1e-5, None, None, 2, N)
+    out = torch.full((M, N), float("nan"), device="cuda", dtype=torch.bfloat16)
+    full = torch.full((M, N), float("nan"), device="cuda")
+    g = None if gain is None else dev(np.asarray(gain, np.float32))
+    ph.photon_linear(dev(x), dev(w, "bf16"), out, gain=g, rms_eps=1e-5, epilogue=2)
+    ph.photon_linear(dev(x), dev(w, "bf16"), full, gain=g, rms_eps=1e-5, epilogue=2)
+    torch.cuda.synchronize()
+    assert nerr(out, ref) <= 2.0 ** -8                       # half a unit in the last place of the largest value
+    assert torch.equal(out, full.to(torch.bfloat16))         # the same numbers, rounded to nearest even
+
+
+def test_linear_bf16_rows_rejected_where_unsupported():
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    x = torch.zeros((4, 64), device="cuda", dtype=torch.bfloat16)
+    w = torch.zeros((128, 64), device="cuda", dtype=torch.bfloat16)
+    out = torch.zeros((4, 64), device="cuda")
+    with pytest.raises(ph.PhotonError):
+        ph.photon_linear(x, w, out, epilogue=2)                                  # SwiGLU takes fp32 rows
+    with pytest.raises(ph.PhotonError):
+        ph.photon_linear(x, w[:64], out, gain=torch.ones(64, device="cuda"))     # as does the pre-norm
+    with pytest.raises(ph.PhotonError):
+        ph.photon_linear(x, w[:64].float(), out)                                 # fp32 matrices: fp32 rows
+
