@@ -17,6 +17,8 @@
 // What bounds the kernel is the rate at which a compute unit takes its slabs in (about 40 bytes per ns), not the
 // matrix cores: the tile is as large as the accumulator registers allow, and the gate/up projection forms SwiGLU
 // in the accumulators instead of writing both halves.
+#include <type_traits>
+
 #include "photon_device.h"
 #include "photon_host.h"
 #include "photon_linear.h"
@@ -62,7 +64,8 @@ enum GemmOut { GEMM_OUT_BF16 = 0, GEMM_OUT_F32 = 1, GEMM_OUT_SWIGLU = 2 };
 template <int WT, int OUT, int BK, int NB>
 __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const float* __restrict__ bias,
-    const float* res, int64_t ldres, void* Cout, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n) {
+    const float* __restrict__ res, int64_t ldres, void* __restrict__ Cout, int64_t ldc, int M, int N, int K, int tiles_m,
+    int tiles_n) {
   constexpr int BM = 64 * WT;                                   // tile edge (rows and columns)
   constexpr int WE = 32 * WT;                                   // wave quadrant edge
   constexpr int TILE_BYTES = BM * BK * 2;                       // one operand slab
@@ -221,27 +224,40 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(
     }
     return;
   }
+  // Row tiles that lie inside the matrix (all but a ragged last one) take the arm without per-row checks.
+  auto epilogue = [&](auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
-  for (int j = 0; j < WT; ++j) {
-    const int n = n0 + wn + j * 32 + (lane & 31);
-    if (n >= N) continue;
-    const float bv = bias != nullptr ? bias[n] : 0.f;
+    for (int j = 0; j < WT; ++j) {
+      const int n = n0 + wn + j * 32 + (lane & 31);
+      if (n >= N) continue;
+      const float bv = bias != nullptr ? bias[n] : 0.f;
 #pragma unroll
-    for (int i = 0; i < WT; ++i) {
+      for (int i = 0; i < WT; ++i) {
+        const int mb = m0 + wm + i * 32 + 4 * (lane >> 5);
+        // Residual values are requested in groups, ahead of the group's stores: res and Cout never overlap (the
+        // host checks), so nothing orders these loads behind the stores of the group before.
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (m >= M) continue;
-        float y = acc[i][j][v] + bv;
-        if (OUT == GEMM_OUT_BF16) {
-          reinterpret_cast<bf16_t*>(Cout)[(int64_t)m * ldc + n] = from_f32<bf16_t>(y);
-        } else {
-          if (res != nullptr) y += res[(int64_t)m * ldres + n];
-          reinterpret_cast<float*>(Cout)[(int64_t)m * ldc + n] = y;
+        for (int half = 0; half < 2; ++half) {                   // 8 at a time: the accumulators leave few registers
+          float rv[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int v = half * 8 + u, m = mb + 8 * (v >> 2) + (v & 3);
+            rv[u] = (OUT != GEMM_OUT_BF16 && res != nullptr && (FULL || m < M)) ? res[(int64_t)m * ldres + n] : 0.f;
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int v = half * 8 + u, m = mb + 8 * (v >> 2) + (v & 3);
+            if (!FULL && m >= M) continue;
+            const float y = acc[i][j][v] + bv + rv[u];
+            if (OUT == GEMM_OUT_BF16) reinterpret_cast<bf16_t*>(Cout)[(int64_t)m * ldc + n] = from_f32<bf16_t>(y);
+            else reinterpret_cast<float*>(Cout)[(int64_t)m * ldc + n] = y;
+          }
         }
       }
     }
-  }
+  };
+  if (m0 + BM <= M) epilogue(std::true_type{}); else epilogue(std::false_type{});
 }
 
 // Row kernel in front of the contraction of fp32 activations: optional RMS norm with gain, then rounding to bf16
@@ -359,6 +375,11 @@ size_t linear_many_workspace_bytes(int64_t rows, int K_max, int N2_max) {
 int32_t launch_linear_many(const LinearArgs& a, void* workspace, int K_max, hipStream_t st) {
   if (!a.w_bf16 || a.K % G_BK != 0 || a.K > K_max || a.ldx % 4 != 0)
     return fail(PHOTON_ERR_UNSUPPORTED, "many-row linear: needs bf16 weights, K=%d a multiple of 64 and at most %d", a.K, K_max);
+  if (a.epilogue == EPI_RESID) {
+    const char *r0 = reinterpret_cast<const char*>(a.res), *o0 = reinterpret_cast<const char*>(a.out);
+    const char *r1 = r0 + ((int64_t)(a.M - 1) * a.ldres + a.N) * 4, *o1 = o0 + ((int64_t)(a.M - 1) * a.ldo + a.N) * 4;
+    if (r0 < o1 && o0 < r1) return fail(PHOTON_ERR_INVALID_ARG, "many-row linear: the residual rows must not overlap the output");
+  }
   if (a.out_bf16 != (a.epilogue == EPI_SWIGLU))
     return fail(PHOTON_ERR_UNSUPPORTED, "many-row linear: the SwiGLU product, and only it, is written as bf16");
   if (a.x_bf16) {

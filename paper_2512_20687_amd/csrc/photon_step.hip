@@ -57,6 +57,11 @@ __global__ __launch_bounds__(256) void embed_rows_kernel(const int32_t* __restri
   *reinterpret_cast<float4_t*>(rows + i * D + d) = v;
 }
 
+__global__ __launch_bounds__(256) void copy_f32x4_kernel(const float4_t* __restrict__ src, float4_t* __restrict__ dst, int64_t n4) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n4) dst[i] = src[i];
+}
+
 __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ dst, int32_t value, int n) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < n) dst[i] = value;
@@ -325,16 +330,23 @@ static int32_t norm(const Ctx& x, const float* in, int in_mul, int in_off, const
   return check_launch("norm_rows_kernel");
 }
 
-// Tail of a block once the attention output sits in p.attn: O projection + residual into p.h, then the
-// SwiGLU sub-layer.  `in` is the block's input (the residual stream before the block).
+// Tail of a block once the attention output sits in p.attn: O projection + residual, then the SwiGLU sub-layer,
+// leaving the residual stream in p.h.  `in` is the block's input (the residual stream before the block: p.h from
+// the second block on).  The stream between the two sub-layers lives in the q/k/v buffer, which the attention
+// has finished with: no projection then adds a residual in place, which the many-row contraction does not allow
+// (it requests residual values ahead of the stores of the tile before).
 static int32_t block_tail(const Ctx& x, const photon_layer_weights& lw, RowsIn in, int rows) {
   const photon_config& c = *x.c;
-  float *h = x.f(x.o_h), *attn = x.f(x.o_attn), *act = x.f(x.o_act);
-  PHOTON_TRY(linear(x, attn, c.D, lw.wo, nullptr, nullptr, in.ptr, in.ld, h, c.D, rows, c.D, c.D, EPI_RESID));
-  if (c.d_ff == 0) return PHOTON_OK;
+  float *h = x.f(x.o_h), *attn = x.f(x.o_attn), *act = x.f(x.o_act), *mid = x.f(x.o_qkv);
+  PHOTON_TRY(linear(x, attn, c.D, lw.wo, nullptr, nullptr, in.ptr, in.ld, mid, c.D, rows, c.D, c.D, EPI_RESID));
+  if (c.d_ff == 0) {
+    PHOTON_LAUNCH(KC_MISC, x.st, copy_f32x4_kernel, dim3((unsigned)(((int64_t)rows * c.D / 4 + 255) / 256)), dim3(256), 0, x.st,
+                  reinterpret_cast<const float4_t*>(mid), reinterpret_cast<float4_t*>(h), (int64_t)rows * c.D / 4);
+    return check_launch("copy_f32x4_kernel");
+  }
   // with bf16 matrices the hidden rows are kept as bf16: they are the down projection's MFMA operand as they stand
-  PHOTON_TRY(linear(x, h, c.D, lw.wgu, lw.g2, nullptr, nullptr, 0, act, c.d_ff, rows, c.d_ff, c.D, EPI_SWIGLU, false, x.bf16));
-  return linear(x, act, c.d_ff, lw.wd, nullptr, nullptr, h, c.D, h, c.D, rows, c.D, c.d_ff, EPI_RESID, x.bf16, false);
+  PHOTON_TRY(linear(x, mid, c.D, lw.wgu, lw.g2, nullptr, nullptr, 0, act, c.d_ff, rows, c.d_ff, c.D, EPI_SWIGLU, false, x.bf16));
+  return linear(x, act, c.d_ff, lw.wd, nullptr, nullptr, mid, c.D, h, c.D, rows, c.D, c.d_ff, EPI_RESID, x.bf16, false);
 }
 
 // All blocks of the level-`level` local decoder on n_chunks * q_len rows (window positions
