@@ -9,8 +9,7 @@
 // One workgroup of 4 waves owns a (64 WT) x (64 WT) output tile, each wave a quadrant of WT x WT
 // MFMA 32x32x16 tiles (WT = 4: 256x256 tile, 128x128 per wave, 256 fp32 accumulators per lane; WT = 2 and 1 for
 // problems with too few big tiles to fill the chip).  K is walked in 64-wide slabs of x and W held in 2 LDS
-// buffers; the coming slabs are moved
-// global -> LDS directly (no staging registers) while the current slab's MFMAs run, and operand fragments are
+// buffers (4 at the smaller tiles); the coming slabs are moved global -> LDS directly (no staging registers) while the current slab's MFMAs run, and operand fragments are
 // double-buffered in registers.  LDS rows are 128 (64) bytes with the 16-byte column index XOR-ed with row bits,
 // which keeps the 128-bit operand reads of 16 consecutive rows on distinct banks.  Workgroup ids are remapped so
 // that the tiles resident on one XCD at a time share x row-blocks and W column-blocks in that XCD's L2.
@@ -326,11 +325,16 @@ static int32_t launch_gemm_v(int cls, const bf16_t* A, const bf16_t* B, const fl
   return check_launch("gemm_bf16_kernel");
 }
 
-// Measured: 64-wide slabs in two buffers.  32-wide slabs in three to five buffers (up to 128 KB in flight per
-// compute unit instead of 64 KB) are no faster at the large shapes and slower at the decode-step shapes.
+// The 256-wide tile, measured: 64-wide slabs in two buffers.  32-wide slabs in three to five buffers (up to 128 KB in
+// flight per compute unit instead of 64 KB) are no faster at the large shapes.
 template <int WT, int OUT>
 static int32_t launch_gemm_t(int cls, const bf16_t* A, const bf16_t* B, const float* bias, const float* res, int64_t ldres, void* out,
                              int64_t ldc, int64_t M, int N, int K, hipStream_t st) {
+  // Small tiles come with few rows (a decode sub-step of a large batch): few slabs' worth of MFMA work per workgroup
+  // and often fewer workgroups than compute units, so the wait for a slab is what a slab costs.  Four buffers
+  // (three slabs in flight) instead of two: +11-12 % on whole decode steps with 128-256 sequences; six or eight
+  // buffers at the 64-wide tile add nothing.
+  if constexpr (WT <= 2) return launch_gemm_v<WT, OUT, 64, 4>(cls, A, B, bias, res, ldres, out, ldc, M, N, K, st);
   return launch_gemm_v<WT, OUT, 64, 2>(cls, A, B, bias, res, ldres, out, ldc, M, N, K, st);
 }
 
