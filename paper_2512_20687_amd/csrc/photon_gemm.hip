@@ -334,6 +334,12 @@ static int32_t launch_gemm_t(int cls, const bf16_t* A, const bf16_t* B, const fl
   // and often fewer workgroups than compute units, so the wait for a slab is what a slab costs.  Four buffers
   // (three slabs in flight) instead of two: +11-12 % on whole decode steps with 128-256 sequences; six or eight
   // buffers at the 64-wide tile add nothing.
+  // With more 128-wide tiles than compute units two buffers are kept: two workgroups then share a unit's LDS, which
+  // hides the wait as well and fills the tail better.
+  if constexpr (WT == 2) {
+    constexpr int BN = (OUT == GEMM_OUT_SWIGLU) ? 64 : 128;
+    if (((M + 127) / 128) * ((N + BN - 1) / BN) > 256) return launch_gemm_v<WT, OUT, 64, 2>(cls, A, B, bias, res, ldres, out, ldc, M, N, K, st);
+  }
   if constexpr (WT <= 2) return launch_gemm_v<WT, OUT, 64, 4>(cls, A, B, bias, res, ldres, out, ldc, M, N, K, st);
   return launch_gemm_v<WT, OUT, 64, 2>(cls, A, B, bias, res, ldres, out, ldc, M, N, K, st);
 }
