@@ -212,9 +212,9 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   };
 
   if constexpr (XB) {
-    // Nothing is staged: a ring of NB chunks in flight per wave.  With one or two units per workgroup a chunk is only
-    // 2-3 KB per wave, and two of them per wave cannot cover the memory latency of a long contraction.
-    constexpr int NB = TT == 1 ? 4 : TT == 2 ? 3 : 2;
+    // Nothing is staged: a ring of NB chunks in flight per wave (measured at the 5120-long down projection: four
+    // instead of two change nothing).
+    constexpr int NB = 2;
     Operands ring[NB];
 #pragma unroll
     for (int s = 0; s < NB; ++s)
