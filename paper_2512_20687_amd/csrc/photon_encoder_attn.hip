@@ -69,9 +69,15 @@ constexpr int EA_STAGE = 2 * EA_ARRAY;                // K | V^T
 
 __host__ __device__ inline int64_t round_up64(int64_t m) { return (m + 63) / 64 * 64; }
 
-// 128-byte rows, 16-byte columns XOR-ed with row bits 1..3 and (into bit 2) row bit 4: the 16 rows one quarter-wave reads
-// together (consecutive rows, or the permuted key rows {0..7, 16..23} + 8j) then fall on distinct banks
-__device__ __forceinline__ int swz(int row, int col16) { return row * 128 + ((col16 ^ ((row >> 1) & 7) ^ ((row >> 2) & 4)) << 4); }
+// LDS layout of the staged arrays: 128-byte rows, the 16-byte column index XOR-ed with row bits.  A 128-bit LDS read
+// is conflict-free when (measured with a read-only probe: 256 bytes per clock and compute unit, against 154 otherwise)
+//   * the 16 lanes of a quarter-wave fall on distinct 16-byte slots of the 256-byte bank line, and
+//   * lanes j and j + 16 of a half-wave agree in address bits 6 and 7 (the same quarter of the bank line).
+// V^T is read by consecutive rows (lane j: row j of 32): XOR with row bits 1..3; rows r and r + 16 share the slot.
+// K is read by permuted rows (quarter-wave 0: rows {0..7, 16..23}, quarter-wave 1: the same + 8): XOR with row bits
+// 1..2 and, into bit 2, row bit 4; rows r and r + 8 share the slot.
+__device__ __forceinline__ int swz_v(int row, int col16) { return row * 128 + ((col16 ^ ((row >> 1) & 7)) << 4); }
+__device__ __forceinline__ int swz_k(int row, int col16) { return row * 128 + ((col16 ^ ((row >> 1) & 3) ^ ((row >> 2) & 4)) << 4); }
 
 // ---- row kernel: rotary + operand layout ----------------------------------------------------------
 // One workgroup = 64 positions of one (sequence, head).  Thread t: position t/4, quarter t%4 of the pairs
@@ -207,7 +213,7 @@ __global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const uin
                                                                        int H, int d_h, int n_qblocks) {
   constexpr int STAGE = EA_STAGE;
   constexpr int V_OFF = EA_ARRAY;
-  extern __shared__ __align__(16) char lds[];         // [2 stages][K | V^T]
+  extern __shared__ __align__(16) char lds[];         // [4 buffers][K | V^T]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qb = n_qblocks - 1 - blockIdx.x;          // late query blocks carry the most keys: schedule them first
@@ -233,7 +239,7 @@ __global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const uin
   // A key block is 2 arrays of 64 rows x 128 bytes = 512 pieces of 16 bytes each: thread t moves piece (row t/8,
   // column t%8) of both arrays, global -> registers -> LDS (swizzled).
   const int prow = (tid >> 3) & 63, pcol = tid & 7;
-  const int poff = swz(prow, pcol);
+  const int poff_k = swz_k(prow, pcol), poff_v = swz_v(prow, pcol);
   struct Pieces { uint4_t kh, vt; };
   auto fetch = [&](int kb, int n_kb_, Pieces& r) __attribute__((always_inline)) {
     if (wave >= EA_MOVERS) return;
@@ -244,8 +250,8 @@ __global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const uin
   auto put = [&](const Pieces& r, int buf) __attribute__((always_inline)) {
     if (wave >= EA_MOVERS) return;
     char* base = lds + buf * STAGE;
-    *reinterpret_cast<uint4_t*>(base + poff) = r.kh;
-    *reinterpret_cast<uint4_t*>(base + V_OFF + poff) = r.vt;
+    *reinterpret_cast<uint4_t*>(base + poff_k) = r.kh;
+    *reinterpret_cast<uint4_t*>(base + V_OFF + poff_v) = r.vt;
   };
 
   float16_t o[2];                                     // O^T tiles: d = dt*32 + 8*(v/4) + 4*kg + v%4, query = lane%32
@@ -278,7 +284,7 @@ __global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const uin
     if (two) {
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        const int o0 = swz(krow, s * 2 + kg), o1 = swz(32 + krow, s * 2 + kg);
+        const int o0 = swz_k(krow, s * 2 + kg), o1 = swz_k(32 + krow, s * 2 + kg);
         const uint4_t ah0 = *reinterpret_cast<const uint4_t*>(sk + o0);
         const uint4_t ah1 = *reinterpret_cast<const uint4_t*>(sk + o1);
         st[0] = ea_mfma(ah0, qfh[s], s == 0 ? negm : st[0]);
@@ -287,7 +293,7 @@ __global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const uin
     } else {
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        const int o0 = swz(krow, s * 2 + kg);
+        const int o0 = swz_k(krow, s * 2 + kg);
         const uint4_t ah0 = *reinterpret_cast<const uint4_t*>(sk + o0);
         st[0] = ea_mfma(ah0, qfh[s], s == 0 ? negm : st[0]);
       }
@@ -356,28 +362,30 @@ __global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const uin
       for (int s = 0; s < 2; ++s)
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) {
-          const uint4_t a = *reinterpret_cast<const uint4_t*>(sv + swz(dt * 32 + qcol, kt * 4 + 2 * kg + s));
+          const uint4_t a = *reinterpret_cast<const uint4_t*>(sv + swz_v(dt * 32 + qcol, kt * 4 + 2 * kg + s));
           o[dt] = ea_mfma(a, pf[kt][s], o[dt]);
         }
     }
   };
 
+  // Four buffers, one barrier per TWO key blocks: a round contracts the pair of buffers that the round before filled
+  // and fills the other pair (last read before the barrier that ended that round) with the two blocks after.
   Pieces ra, rb;
   fetch(0, n_kb, ra);
   fetch(1, n_kb, rb);
   put(ra, 0);
+  put(rb, 1);
   fetch(2, n_kb, ra);
+  fetch(3, n_kb, rb);
   __syncthreads();
   for (int kb = 0; kb < n_kb; kb += 2) {
-    // buffer 0 holds block kb, rb block kb + 1, ra block kb + 2 (in flight)
-    put(rb, 1);                                       // buffer 1 was last read before the barrier that ended the previous round
-    fetch(kb + 3, n_kb, rb);
-    compute(kb, 0);
-    __syncthreads();
-    if (kb + 1 >= n_kb) break;
-    put(ra, 0);
+    const int cur = (kb >> 1) & 1;                    // buffers 2 cur, 2 cur + 1 hold blocks kb, kb + 1
+    put(ra, 2 * (cur ^ 1));                           // blocks kb + 2, kb + 3
+    put(rb, 2 * (cur ^ 1) + 1);
     fetch(kb + 4, n_kb, ra);
-    compute(kb + 1, 1);
+    fetch(kb + 5, n_kb, rb);
+    compute(kb, 2 * cur);
+    if (kb + 1 < n_kb) compute(kb + 1, 2 * cur + 1);
     __syncthreads();
   }
 
@@ -535,7 +543,7 @@ int32_t launch_encoder_attn(const float* qkv, float* out, int Bt, int64_t M, int
 #undef PHOTON_EA_ROPE
   PHOTON_TRY(check_launch("encoder_rope_split_kernel"));
   const int n_qblocks = (int)((M + EA_BQ - 1) / EA_BQ);
-  PHOTON_LAUNCH(KC_LOCAL_ATTN, st, encoder_attn_mfma_kernel, dim3(n_qblocks, Bt * H), dim3(EA_THREADS), 2 * EA_STAGE, st, qh, kh, vt, out, M,
+  PHOTON_LAUNCH(KC_LOCAL_ATTN, st, encoder_attn_mfma_kernel, dim3(n_qblocks, Bt * H), dim3(EA_THREADS), 4 * EA_STAGE, st, qh, kh, vt, out, M,
                 H, d_h, n_qblocks);
   return check_launch("encoder_attn_mfma_kernel");
 }
