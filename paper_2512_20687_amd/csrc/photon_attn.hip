@@ -406,9 +406,9 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_step_attn_kernel(
           qb = __shfl_xor(qa[t], LPR / 2);
           kb = __shfl_xor(ka[t], LPR / 2);
         }
-        double sd, cd;
-        sincos((double)j * (double)inv_freq[t], &sd, &cd);
-        const float c = (float)cd, sn = upper[t] ? (float)sd : -(float)sd;
+        float sd, cd;                                        // window positions are small (j < 16): single precision is exact enough
+        sincosf((float)j * inv_freq[t], &sd, &cd);
+        const float c = cd, sn = upper[t] ? sd : -sd;
         qa[t] = col_live ? qa[t] * c + qb * sn : 0.f;
         ka[t] = ka[t] * c + kb * sn;
       }
