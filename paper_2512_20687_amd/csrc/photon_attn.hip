@@ -349,7 +349,7 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_attn_kernel(
 template <int DH, int NK, bool PAD>
 __global__ __launch_bounds__(LOCAL_THREADS) void local_step_attn_kernel(
     const float* __restrict__ qkv, float* __restrict__ lk, float* __restrict__ lv, float* __restrict__ out,
-    int64_t n_units, int H, int d_h_rt, int W, int q_len, int q_pos, float scale_log2e, float theta) {
+    int64_t n_units, int H, int d_h_rt, int W, int q_len, int q_pos, float scale_log2e, double freq_ratio) {
   constexpr int VEC = 4, LPR = DH / 4, UPW = 64 / LPR;
   const int d_h = PAD ? d_h_rt : DH;
   const int half = d_h / 2;
@@ -372,7 +372,17 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_step_attn_kernel(
   for (int t = 0; t < VEC; ++t) {
     upper[t] = col + t >= half;
     partner[t] = upper[t] ? col + t - half : col + t + half;
-    inv_freq[t] = theta == 0.f ? 0.f : (float)exp2(-2.0 * (double)((col + t) % half) / (double)d_h * log2((double)theta));
+    // rotary frequency theta^(-2i/d_h) = freq_ratio^i (freq_ratio = theta^(-2/d_h) from the host, 0 for no rotation):
+    // i < 64, six squarings in double instead of a double-precision logarithm and power per element
+    double base = freq_ratio, f = freq_ratio == 0.0 ? 0.0 : 1.0;
+    int e = (col + t) % half;
+#pragma unroll
+    for (int b = 0; b < 6; ++b) {
+      if (e & 1) f *= base;
+      base *= base;
+      e >>= 1;
+    }
+    inv_freq[t] = (float)f;
   }
 
   float4_t kr[NK], vr[NK];
@@ -446,6 +456,7 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_step_attn_kernel(
 template <int DH, bool PAD>
 static int32_t launch_local_step_dh(const float* qkv, float* lk, float* lv, float* out, int64_t n_chunks, int W, int q_len,
                                     int q_pos, int H, int d_h, float scale, float theta, hipStream_t st) {
+  const double freq_ratio = theta == 0.f ? 0.0 : pow((double)theta, -2.0 / (double)d_h);
   const int64_t n_units = n_chunks * H;
   const int64_t units_per_block = (int64_t)(64 / (DH / 4)) * (LOCAL_THREADS / 64);
   const int64_t blocks = (n_units + units_per_block - 1) / units_per_block;
@@ -453,7 +464,7 @@ static int32_t launch_local_step_dh(const float* qkv, float* lk, float* lv, floa
 #define PHOTON_LS_CASE(N)                                                                                                   \
   case N:                                                                                                                   \
     PHOTON_LAUNCH(KC_LOCAL_ATTN, st, (local_step_attn_kernel<DH, N, PAD>), dim3((unsigned)blocks), dim3(LOCAL_THREADS), 0, st, qkv, \
-                  lk, lv, out, n_units, H, d_h, W, q_len, q_pos, scale * LOG2E, theta);                                    \
+                  lk, lv, out, n_units, H, d_h, W, q_len, q_pos, scale * LOG2E, freq_ratio);                                    \
     break;
   switch (q_pos + q_len) {
     PHOTON_LS_CASE(1) PHOTON_LS_CASE(2) PHOTON_LS_CASE(3) PHOTON_LS_CASE(4)
