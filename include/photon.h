@@ -203,7 +203,8 @@ PHOTON_API int32_t photon_linear(const void* x, const void* w, const float* gain
  * Host structs below hold DEVICE pointers.  Matrices/tables are `dt`; gains,
  * biases and all state vectors are fp32.  Arithmetic with dt = bf16: residual
  * stream, norms, softmax and every accumulation in fp32; the feed-forward's
- * hidden rows are kept in bf16, and so are the rows entering a projection once
+ * hidden rows and the attention rows of the local decoders and of the prefill
+ * are kept in bf16, and so are the rows entering a projection once
  * a pass holds 128 rows or more (below that they enter as a bf16 head plus a
  * bf16 remainder, i.e. with fp32 accuracy).
  * -------------------------------------------------------------------------- */

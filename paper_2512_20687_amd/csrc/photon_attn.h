@@ -24,6 +24,6 @@ int32_t launch_local_attn(bool f32, int d_h, const void* q, const void* k, const
 // Fused decode sub-step of a local decoder: rotary + append to the local cache + causal attention for the
 // q_len new rows of every chunk, read straight from the QKV projection output [rows, 3*H*d_h] (fp32).
 int32_t launch_local_step_attn(int d_h, const float* qkv, float* lk, float* lv, float* out, int64_t n_chunks, int W, int q_len,
-                               int q_pos, int H, float scale, float theta, hipStream_t st);
+                               int q_pos, int H, float scale, float theta, bool out_bf16, hipStream_t st);
 
 }  // namespace photon

@@ -349,7 +349,7 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_attn_kernel(
 template <int DH, int NK, bool PAD>
 __global__ __launch_bounds__(LOCAL_THREADS) void local_step_attn_kernel(
     const float* __restrict__ qkv, float* __restrict__ lk, float* __restrict__ lv, float* __restrict__ out,
-    int64_t n_units, int H, int d_h_rt, int W, int q_len, int q_pos, float scale_log2e, double freq_ratio) {
+    int64_t n_units, int H, int d_h_rt, int W, int q_len, int q_pos, float scale_log2e, double freq_ratio, int out_bf16) {
   constexpr int VEC = 4, LPR = DH / 4, UPW = 64 / LPR;
   const int d_h = PAD ? d_h_rt : DH;
   const int half = d_h / 2;
@@ -448,14 +448,17 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_step_attn_kernel(
         o += pw * vr[jj];
       }
       o *= (1.f / l);
-      if (live) *reinterpret_cast<float4_t*>(out + row * D + h * d_h + col) = o;
+      if (live) {
+        if (out_bf16) *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(out) + row * D + h * d_h + col) = uint2{pack_bf16x2(o.x, o.y), pack_bf16x2(o.z, o.w)};
+        else *reinterpret_cast<float4_t*>(out + row * D + h * d_h + col) = o;
+      }
     }
   }
 }
 
 template <int DH, bool PAD>
 static int32_t launch_local_step_dh(const float* qkv, float* lk, float* lv, float* out, int64_t n_chunks, int W, int q_len,
-                                    int q_pos, int H, int d_h, float scale, float theta, hipStream_t st) {
+                                    int q_pos, int H, int d_h, float scale, float theta, bool out_bf16, hipStream_t st) {
   const double freq_ratio = theta == 0.f ? 0.0 : pow((double)theta, -2.0 / (double)d_h);
   const int64_t n_units = n_chunks * H;
   const int64_t units_per_block = (int64_t)(64 / (DH / 4)) * (LOCAL_THREADS / 64);
@@ -464,7 +467,7 @@ static int32_t launch_local_step_dh(const float* qkv, float* lk, float* lv, floa
 #define PHOTON_LS_CASE(N)                                                                                                   \
   case N:                                                                                                                   \
     PHOTON_LAUNCH(KC_LOCAL_ATTN, st, (local_step_attn_kernel<DH, N, PAD>), dim3((unsigned)blocks), dim3(LOCAL_THREADS), 0, st, qkv, \
-                  lk, lv, out, n_units, H, d_h, W, q_len, q_pos, scale * LOG2E, freq_ratio);                                    \
+                  lk, lv, out, n_units, H, d_h, W, q_len, q_pos, scale * LOG2E, freq_ratio, out_bf16 ? 1 : 0);                                    \
     break;
   switch (q_pos + q_len) {
     PHOTON_LS_CASE(1) PHOTON_LS_CASE(2) PHOTON_LS_CASE(3) PHOTON_LS_CASE(4)
@@ -478,17 +481,17 @@ static int32_t launch_local_step_dh(const float* qkv, float* lk, float* lv, floa
 }
 
 int32_t launch_local_step_attn(int d_h, const float* qkv, float* lk, float* lv, float* out, int64_t n_chunks, int W, int q_len,
-                               int q_pos, int H, float scale, float theta, hipStream_t st) {
+                               int q_pos, int H, float scale, float theta, bool out_bf16, hipStream_t st) {
   if (d_h % 4 != 0) return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: d_h=%d is not a multiple of 4", d_h);
   switch (d_h) {
-    case 32: return launch_local_step_dh<32, false>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, st);
-    case 64: return launch_local_step_dh<64, false>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, st);
-    case 128: return launch_local_step_dh<128, false>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, st);
+    case 32: return launch_local_step_dh<32, false>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, out_bf16, st);
+    case 64: return launch_local_step_dh<64, false>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, out_bf16, st);
+    case 128: return launch_local_step_dh<128, false>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, out_bf16, st);
   }
   switch (kv_row_elems(d_h)) {
-    case 32: return launch_local_step_dh<32, true>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, st);
-    case 64: return launch_local_step_dh<64, true>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, st);
-    case 128: return launch_local_step_dh<128, true>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, st);
+    case 32: return launch_local_step_dh<32, true>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, out_bf16, st);
+    case 64: return launch_local_step_dh<64, true>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, out_bf16, st);
+    case 128: return launch_local_step_dh<128, true>(qkv, lk, lv, out, n_chunks, W, q_len, q_pos, H, d_h, scale, theta, out_bf16, st);
   }
   return fail(PHOTON_ERR_UNSUPPORTED, "chunk-local attention: d_h=%d not in [4, 128]", d_h);
 }

@@ -210,7 +210,7 @@ __device__ __forceinline__ float16_t ea_mfma(const uint4_t& a, const uint4_t& b,
 
 __global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const uint16_t* __restrict__ qh, const uint16_t* __restrict__ kh,
                                                                        const uint16_t* __restrict__ vt, float* __restrict__ out, int64_t M,
-                                                                       int H, int d_h, int n_qblocks) {
+                                                                       int H, int d_h, int n_qblocks, int out_bf16) {
   constexpr int STAGE = EA_STAGE;
   constexpr int V_OFF = EA_ARRAY;
   extern __shared__ __align__(16) char lds[];         // [4 buffers][K | V^T]
@@ -392,7 +392,7 @@ __global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const uin
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   if (qpos >= M) return;
   const float inv = 1.0f / l_tot;
-  float* dst = out + ((int64_t)b * M + qpos) * (H * d_h) + h * d_h;   // d_h <= 64: the columns past it are padding
+  const int64_t dst_off = ((int64_t)b * M + qpos) * (H * d_h) + h * d_h;   // d_h <= 64: the columns past it are padding
 #pragma unroll
   for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
@@ -400,7 +400,9 @@ __global__ __launch_bounds__(EA_THREADS) void encoder_attn_mfma_kernel(const uin
       float4_t y;
       y.x = o[dt][g4 * 4 + 0] * inv; y.y = o[dt][g4 * 4 + 1] * inv; y.z = o[dt][g4 * 4 + 2] * inv; y.w = o[dt][g4 * 4 + 3] * inv;
       const int col = dt * 32 + 8 * g4 + 4 * kg;
-      if (col < d_h) *reinterpret_cast<float4_t*>(dst + col) = y;
+      if (col >= d_h) continue;
+      if (out_bf16) *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(out) + dst_off + col) = uint2{pack_bf16x2(y.x, y.y), pack_bf16x2(y.z, y.w)};
+      else *reinterpret_cast<float4_t*>(out + dst_off + col) = y;
     }
 }
 
@@ -501,8 +503,9 @@ size_t encoder_attn_workspace_bytes(int Bt, int64_t M, int H, int d_h, bool bf16
 }
 
 int32_t launch_encoder_attn(const float* qkv, float* out, int Bt, int64_t M, int H, int d_h, float theta, float scale, void* k_cache,
-                            void* v_cache, int64_t S_max, void* workspace, bool bf16, bool kv_fp8, hipStream_t st) {
+                            void* v_cache, int64_t S_max, void* workspace, bool bf16, bool kv_fp8, bool out_bf16, hipStream_t st) {
   if (Bt <= 0 || M <= 0) return PHOTON_OK;
+  if (out_bf16 && !bf16) return fail(PHOTON_ERR_UNSUPPORTED, "encoder attention: bf16 output rows come with the bf16 path only");
   if ((int64_t)Bt * H > 65535) return fail(PHOTON_ERR_UNSUPPORTED, "encoder attention: Bt*H=%lld exceeds 65535", (long long)Bt * H);
   const int pitch = kv_row_elems(d_h);
   if (!bf16) {
@@ -544,7 +547,7 @@ int32_t launch_encoder_attn(const float* qkv, float* out, int Bt, int64_t M, int
   PHOTON_TRY(check_launch("encoder_rope_split_kernel"));
   const int n_qblocks = (int)((M + EA_BQ - 1) / EA_BQ);
   PHOTON_LAUNCH(KC_LOCAL_ATTN, st, encoder_attn_mfma_kernel, dim3(n_qblocks, Bt * H), dim3(EA_THREADS), 4 * EA_STAGE, st, qh, kh, vt, out, M,
-                H, d_h, n_qblocks);
+                H, d_h, n_qblocks, out_bf16 ? 1 : 0);
   return check_launch("encoder_attn_mfma_kernel");
 }
 
@@ -577,6 +580,6 @@ extern "C" int32_t photon_encoder_attn(const float* qkv, float* out, int32_t Bt,
   const size_t need = encoder_attn_workspace_bytes(Bt, M, H, d_h, dt == PHOTON_BF16);
   PHOTON_REQUIRE(workspace_bytes >= need, PHOTON_ERR_INVALID_ARG, "%s: workspace holds %zu bytes, %zu needed", __func__, workspace_bytes, need);
   if (need > 0) PHOTON_REQUIRE_PTR(workspace);
-  return launch_encoder_attn(qkv, out, Bt, M, H, d_h, rope_theta, scale, k_cache, v_cache, S_max, workspace, dt == PHOTON_BF16, false,
+  return launch_encoder_attn(qkv, out, Bt, M, H, d_h, rope_theta, scale, k_cache, v_cache, S_max, workspace, dt == PHOTON_BF16, false, false,
                              (hipStream_t)stream);
 }

@@ -335,10 +335,10 @@ static int32_t norm(const Ctx& x, const float* in, int in_mul, int in_off, const
 // the second block on).  The stream between the two sub-layers lives in the q/k/v buffer, which the attention
 // has finished with: no projection then adds a residual in place, which the many-row contraction does not allow
 // (it requests residual values ahead of the stores of the tile before).
-static int32_t block_tail(const Ctx& x, const photon_layer_weights& lw, RowsIn in, int rows) {
+static int32_t block_tail(const Ctx& x, const photon_layer_weights& lw, RowsIn in, int rows, bool attn_bf16) {
   const photon_config& c = *x.c;
   float *h = x.f(x.o_h), *attn = x.f(x.o_attn), *act = x.f(x.o_act), *mid = x.f(x.o_qkv);
-  PHOTON_TRY(linear(x, attn, c.D, lw.wo, nullptr, nullptr, in.ptr, in.ld, mid, c.D, rows, c.D, c.D, EPI_RESID));
+  PHOTON_TRY(linear(x, attn, c.D, lw.wo, nullptr, nullptr, in.ptr, in.ld, mid, c.D, rows, c.D, c.D, EPI_RESID, attn_bf16, false));
   if (c.d_ff == 0) {
     PHOTON_LAUNCH(KC_MISC, x.st, copy_f32x4_kernel, dim3((unsigned)(((int64_t)rows * c.D / 4 + 255) / 256)), dim3(256), 0, x.st,
                   reinterpret_cast<const float4_t*>(mid), reinterpret_cast<float4_t*>(h), (int64_t)rows * c.D / 4);
@@ -364,8 +364,9 @@ static int32_t local_module_pass(const Ctx& x, int level, int64_t n_chunks, int 
     float* lk = x.f(x.p.lk[level - 1]) + (size_t)i * layer_cache;
     float* lv = x.f(x.p.lv[level - 1]) + (size_t)i * layer_cache;
     PHOTON_TRY(linear(x, in.ptr, in.ld, lw.wqkv, lw.g1, nullptr, nullptr, 0, qkv, 3 * c.D, rows, 3 * c.D, c.D, EPI_PLAIN));
-    PHOTON_TRY(launch_local_step_attn(c.d_h, qkv, lk, lv, attn, n_chunks, W, q_len, q_pos, c.H, scale, c.rope_theta, x.st));
-    PHOTON_TRY(block_tail(x, lw, in, rows));
+    // with bf16 matrices the attention rows are written as bf16: the O projection's MFMA operand as they stand
+    PHOTON_TRY(launch_local_step_attn(c.d_h, qkv, lk, lv, attn, n_chunks, W, q_len, q_pos, c.H, scale, c.rope_theta, x.bf16, x.st));
+    PHOTON_TRY(block_tail(x, lw, in, rows, x.bf16));
     in.ptr = h; in.ld = c.D;
   }
   return PHOTON_OK;
@@ -401,7 +402,7 @@ static int32_t stream_step(const Ctx& x, const photon_module_weights& mod, void*
     PHOTON_TRY(check_launch("rope_append_coarse_kernel"));
     PHOTON_TRY(launch_coarse_attn(c.kv_dt == PHOTON_FP8_E4M3 ? KV_FP8 : x.bf16 ? KV_BF16 : KV_F32, true, c.d_h, qrot, kc, vc, seq_len, attn, x.Bt, c.H, S_cap, scale,
                                   x.p.n_splits, x.base + x.p.coarse_ws, x.st));
-    PHOTON_TRY(block_tail(x, lw, in, rows));
+    PHOTON_TRY(block_tail(x, lw, in, rows, false));      // the coarse attention writes fp32 rows
     in.ptr = h; in.ld = c.D;
   }
   return norm(x, h, 1, 0, mod.g_final, out, out_mul, out_off, rows);
@@ -653,8 +654,8 @@ static int32_t prefill_impl(const Ctx& x, Ctx e, const PrefillPlan& pp, const ph
         kc = reinterpret_cast<char*>(x.hs->k_cache[l - 1]) + (size_t)i * lc;
         vc = reinterpret_cast<char*>(x.hs->v_cache[l - 1]) + (size_t)i * lc;
       }
-      PHOTON_TRY(launch_encoder_attn(qkv, attn, Bt, M, c.H, c.d_h, c.rope_theta, scale, kc, vc, cap, e.base + pp.ea, x.bf16, c.kv_dt == PHOTON_FP8_E4M3, x.st));
-      PHOTON_TRY(block_tail(e, lw, in, rows));
+      PHOTON_TRY(launch_encoder_attn(qkv, attn, Bt, M, c.H, c.d_h, c.rope_theta, scale, kc, vc, cap, e.base + pp.ea, x.bf16, c.kv_dt == PHOTON_FP8_E4M3, x.bf16, x.st));
+      PHOTON_TRY(block_tail(e, lw, in, rows, x.bf16));
       in.ptr = h; in.ld = D;
     }
     if (l < L) {
