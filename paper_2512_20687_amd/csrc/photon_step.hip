@@ -515,16 +515,23 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
       const int q_len = (j == 0) ? R : 1;
       const int q_pos = (j == 0) ? 0 : R + j - 1;
       PHOTON_TRY(local_module_pass(x, l, n, q_len, q_pos, in));
-      // item j = final norm of the last row of each chunk
-      PHOTON_TRY(norm(x, h, q_len, q_len - 1, mod.g_final, units, C, j, (int)n));
+      // item j = final norm of the last row of each chunk.  At the token level of a hierarchy the item only feeds the
+      // vocabulary projection, which then applies the norm itself (one launch less per sub-step) unless the caller
+      // asked to see the items.
+      const bool norm_in_head = (l == 1 && L >= 2 && !(tr && tr->new_units[0]));
+      if (!norm_in_head) PHOTON_TRY(norm(x, h, q_len, q_len - 1, mod.g_final, units, C, j, (int)n));
       if (l >= 2) {                                        // Eq. 6: the module's own output is the next input
         in.ptr = units + (int64_t)j * D; in.ld = (int64_t)C * D;
       } else {
         float* lg = (tr && tr->logits) ? tr->logits + (int64_t)j * c.vocab : x.f(x.p.logits);
         const int64_t ld = (tr && tr->logits) ? (int64_t)C * c.vocab : c.vocab;
         // logits of item j of every chunk: rows of `units` with pitch C*D
-        PHOTON_TRY(linear(x, units + (int64_t)j * D, (int64_t)C * D, x.w->W_lm, nullptr, nullptr, nullptr, 0, lg, ld, (int)n,
-                          c.vocab, D, EPI_PLAIN));
+        if (norm_in_head)
+          PHOTON_TRY(linear(x, h + (int64_t)(q_len - 1) * D, (int64_t)q_len * D, x.w->W_lm, mod.g_final, nullptr, nullptr, 0, lg, ld, (int)n,
+                            c.vocab, D, EPI_PLAIN));
+        else
+          PHOTON_TRY(linear(x, units + (int64_t)j * D, (int64_t)C * D, x.w->W_lm, nullptr, nullptr, nullptr, 0, lg, ld, (int)n,
+                            c.vocab, D, EPI_PLAIN));
         float* x_next = (j + 1 < C) ? h : nullptr;         // decoder-side embedding of the chosen token
         if (x.bf16)
           PHOTON_LAUNCH(KC_CHOOSE_TOKEN, x.st, choose_token_kernel<bf16_t>, dim3((unsigned)n), dim3(CHOOSE_THREADS), 0, x.st, lg, ld, c.vocab,

@@ -304,3 +304,37 @@ def test_bf16_step_with_8bit_cache(kw, Bt):
         assert np.array_equal(po.e4m3_decode(old), np.stack([ref[:, b, :, : int(s0[b])] for b in range(1)], 1))   # nothing else is touched
     assert np.array_equal(state.seq_len.cpu().numpy(), s0 + 1)
 
+
+
+@pytest.mark.parametrize("kw,Bt", [
+    (dict(dtype="f32", D=64, H=2, d_h=32, d_ff=160, vocab=96), 3),
+    (dict(R=(2, 2)), 2),                                       # first sub-step: the item is the second of two rows
+    (dict(C=(2, 2), n_layers=1), 130),                         # many rows: the norm runs in the row kernel of the contraction
+    (dict(L=3, C=(2, 2, 4), R=(1, 1, 1), n_layers=1), 5),
+])
+def test_logits_when_the_items_are_not_requested(kw, Bt):
+    """Without a request for the token-level items the vocabulary projection applies the final norm itself
+    (one launch less per sub-step): same logits, same tokens, same state."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    base = dict(L=2, C=(4, 4), R=(1, 1), D=256, H=4, d_h=64, n_layers=2, d_ff=640, vocab=1024, dtype="bf16")
+    base.update(kw)
+    cfg = si.PhotonConfig(**base)
+    tol = TOL["f32" if cfg.dtype == "f32" else "bf16"]
+    w = si.make_weights(cfg, 41)
+    S_max = 40
+    st = si.make_decode_state(cfg, Bt, 17, S_max, seed=12)
+    forced = si.make_tokens(cfg.vocab, Bt, cfg.meta_context, 13)
+    ost = po.state_to_f64(st)
+    otr = po.decode_step(cfg, po.weights_to_f64(w), ost, forced_tokens=forced)
+    model = ph.PhotonModel(cfg, w)
+    state = ph.PhotonState(model, Bt, S_max, k=np.asarray(st["k"], np.float32), v=np.asarray(st["v"], np.float32),
+                           seq_len=np.asarray(st["seq_len"], np.int32), x_top=np.asarray(st["x_top"], np.float32),
+                           carry=np.asarray(st["carry"], np.float32))
+    trace = {"logits": torch.full((Bt, cfg.meta_context, cfg.vocab), float("nan"), device="cuda")}
+    toks = torch.full((Bt, cfg.meta_context), -1, dtype=torch.int32, device="cuda")
+    ph.photon_decode_step(model, state, toks, forced_tokens=dev(np.asarray(forced, np.int32)), trace=trace)
+    torch.cuda.synchronize()
+    assert nerr(trace["logits"], otr["logits"]) <= tol
+    assert nerr(state.x_top, otr["x_top"]) <= tol and nerr(state.carry, ost["carry"]) <= tol
+    assert np.array_equal(toks.cpu().numpy(), np.asarray(forced))
