@@ -234,6 +234,8 @@ def test_full_width_step_one_block_per_module():
     ("cfg4_bf16_serving", 128, 2048),      # 128 sequences: every level, the top one included, runs the tiled MFMA contraction
     ("cfg5_bf16_3level", 2, 64),           # three levels of 8: 128 rows at the token level, 16 and 2 above
     ("paper_600m", 32, 128),               # the paper's 600M shape: heads of 52, converter length 2
+    ("paper_900m", 8, 64),                 # 900M shape: width 1792, heads of 56
+    ("paper_1p2b", 130, 64),               # 1.2B shape: width 1920, heads of 60; 130 sequences: every level on the tiled contraction
 ])
 def test_full_width_step_other_configurations(name, Bt, S):
     """The other configurations at their real widths and vocabulary, one block per module and a reduced batch so
