@@ -65,3 +65,17 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.photon_coarse_decode_attn_workspace_bytes(4, 32, 52, 8) == 4 * 32 * 8 * 66 * 4   # rows padded to 64
     # cache row length for the head sizes of the paper's models
     assert [lib.photon_kv_row_elems(d) for d in (16, 32, 52, 56, 60, 64, 128, 129, 0)] == [32, 32, 64, 64, 64, 64, 128, 0, 0]
+
+
+def test_binding_constants_match_the_header():
+    """The ctypes binding repeats a few constants of the header: they must agree."""
+    from paper_2512_20687_amd import binding as b
+    text = open(os.path.join(ROOT, "include", "photon.h")).read()
+    enum = dict((k, int(v)) for k, v in re.findall(r"\b(PHOTON_[A-Z0-9_]+)\s*=\s*(-?\d+)", text))
+    define = dict((k, int(v, 0)) for k, v in re.findall(r"#define\s+(PHOTON_[A-Z0-9_]+)\s+(0x[0-9a-fA-F]+|\d+)\s*$", text, re.M))
+    assert (enum["PHOTON_F32"], enum["PHOTON_BF16"], enum["PHOTON_FP8_E4M3"]) == (b.PHOTON_F32, b.PHOTON_BF16, b.PHOTON_FP8_E4M3)
+    assert enum["PHOTON_MAX_LEVELS"] == b.MAX_LEVELS
+    assert define["PHOTON_LINEAR_X_BF16"] == b.PHOTON_LINEAR_X_BF16
+    assert define["PHOTON_LINEAR_OUT_BF16"] == b.PHOTON_LINEAR_OUT_BF16
+    # the two flags stay clear of the epilogue codes 0..2
+    assert define["PHOTON_LINEAR_X_BF16"] & 3 == 0 and define["PHOTON_LINEAR_OUT_BF16"] & 3 == 0
