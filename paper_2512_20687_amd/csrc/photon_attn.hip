@@ -395,38 +395,64 @@ __global__ __launch_bounds__(LOCAL_THREADS) void local_step_attn_kernel(
       vr[j] = *reinterpret_cast<const float4_t*>(vcache + (int64_t)j * D);
     }
   }
+  // The new rows' q, k, v (and, for padded heads, the rotary partners) are requested one row ahead: the first one
+  // here, before the sine and cosine are formed, so that the arithmetic runs under the loads.
+  float4_t q4, k4, v4;
+  float qp[VEC], kp[VEC];
+  auto fetch_row = [&](int64_t r) {
+    const float* head = qkv + (chunk * q_len + r) * 3 * D + h * d_h;
+    q4 = *reinterpret_cast<const float4_t*>(head + col);
+    k4 = *reinterpret_cast<const float4_t*>(head + col + D);
+    v4 = *reinterpret_cast<const float4_t*>(head + col + 2 * D);
+    if (PAD) {
+#pragma unroll
+      for (int t = 0; t < VEC; ++t) { qp[t] = head[partner[t]]; kp[t] = head[D + partner[t]]; }
+    }
+  };
+  fetch_row(0);
+  // cosine and sine of the first new row's angle (window positions are small, j < 16: single precision is exact
+  // enough); further new rows (a first sub-step with several converter rows) follow by the angle-addition formulas,
+  // which keeps the unrolled row loop below free of the library routine.
+  float rc[VEC], rs[VEC], dc[VEC], ds[VEC];
+#pragma unroll
+  for (int t = 0; t < VEC; ++t) {
+    sincosf((float)q_pos * inv_freq[t], &rs[t], &rc[t]);
+    dc[t] = 1.f; ds[t] = 0.f;
+    if (q_len > 1) sincosf(inv_freq[t], &ds[t], &dc[t]);
+  }
 #pragma unroll
   for (int j = 0; j < NK; ++j) {
     if (j >= q_pos) {
       const int64_t row = chunk * q_len + (j - q_pos);
-      const float* head = qkv + row * 3 * D + h * d_h;
-      const float* src = head + col;
-      float4_t q4 = *reinterpret_cast<const float4_t*>(src);
-      float4_t k4 = *reinterpret_cast<const float4_t*>(src + D);
-      const float4_t v4 = *reinterpret_cast<const float4_t*>(src + 2 * D);
       // rotary: out[i] = x[i] c - x[i+h] s ; out[i+h] = x[i+h] c + x[i] s
       float qa[VEC] = {q4.x, q4.y, q4.z, q4.w}, ka[VEC] = {k4.x, k4.y, k4.z, k4.w};
+      const float4_t v_row = v4;
+      float qpr[VEC], kpr[VEC];
+#pragma unroll
+      for (int t = 0; t < VEC; ++t) { qpr[t] = PAD ? qp[t] : 0.f; kpr[t] = PAD ? kp[t] : 0.f; }
+      if (j + 1 < NK) fetch_row(j + 1 - q_pos);              // the row after this one (exists: NK = q_pos + q_len)
 #pragma unroll
       for (int t = 0; t < VEC; ++t) {
         float qb, kb;
         if (PAD) {
-          qb = head[partner[t]];
-          kb = head[D + partner[t]];
+          qb = qpr[t];
+          kb = kpr[t];
         } else {                                             // the partner sits LPR/2 lanes away
           qb = __shfl_xor(qa[t], LPR / 2);
           kb = __shfl_xor(ka[t], LPR / 2);
         }
-        float sd, cd;                                        // window positions are small (j < 16): single precision is exact enough
-        sincosf((float)j * inv_freq[t], &sd, &cd);
-        const float c = cd, sn = upper[t] ? sd : -sd;
+        const float c = rc[t], sn = upper[t] ? rs[t] : -rs[t];
         qa[t] = col_live ? qa[t] * c + qb * sn : 0.f;
         ka[t] = ka[t] * c + kb * sn;
+        const float c1 = rc[t] * dc[t] - rs[t] * ds[t];        // the next row's angle
+        rs[t] = rs[t] * dc[t] + rc[t] * ds[t];
+        rc[t] = c1;
       }
       kr[j] = float4_t{ka[0], ka[1], ka[2], ka[3]};
-      vr[j] = v4;
+      vr[j] = v_row;
       if (live) {
         *reinterpret_cast<float4_t*>(kcache + (int64_t)j * D) = kr[j];
-        *reinterpret_cast<float4_t*>(vcache + (int64_t)j * D) = v4;
+        *reinterpret_cast<float4_t*>(vcache + (int64_t)j * D) = v_row;
       }
       // attention of this row over window rows 0..j
       float s[NK], mx = NEG_BIG;
