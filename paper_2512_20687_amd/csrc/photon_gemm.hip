@@ -42,9 +42,14 @@ template <int BK> __device__ __forceinline__ int swz(int row, int col16) {
 // the builtin as an access to both memories that may complete out of order, and while one is in flight it makes
 // every wait for an LDS read a wait for ALL LDS reads, which serialises the operand prefetch below.  Completion is
 // tracked by hand (s_waitcnt vmcnt) at the one place per slab where it matters.
+// m0 (the LDS base of the load) is named as clobbered so that the compiler keeps no value of its own in it across the
+// statement; it notes that m0 is a reserved register, which is the point here.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void load16_to_lds(const void* gsrc, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // s_waitcnt immediate: at most `vm` vector-memory operations outstanding, all LDS reads done
 constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 0xF) | ((vm >> 4) << 14) | (7 << 4); }
