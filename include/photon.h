@@ -175,7 +175,8 @@ PHOTON_API int32_t photon_encoder_attn(const float* qkv, float* out, int32_t Bt,
  * feed-forward's hidden rows, Eq. 6-7's SwiGLU product, in bf16 this way):
  *   PHOTON_LINEAR_OUT_BF16: out holds bf16 values (the result rounded to nearest even);
  *   PHOTON_LINEAR_X_BF16  : x holds bf16 values, which enter the matrix cores as they are;
- *                           needs gain == NULL, epilogue 0 or 1, N % 8 == 0.
+ *                           needs gain == NULL; with more than 16 rows a workgroup takes two
+ *                           or four row tiles of 16, so the matrix is streamed once per 32-64 rows.
  * One kernel, no workspace; run-to-run deterministic.
  * -------------------------------------------------------------------------- */
 #define PHOTON_LINEAR_X_BF16 0x10
@@ -205,7 +206,7 @@ PHOTON_API int32_t photon_linear(const void* x, const void* w, const float* gain
  * stream, norms, softmax and every accumulation in fp32; the feed-forward's
  * hidden rows and the attention rows of the local decoders and of the prefill
  * are kept in bf16, and so are the rows entering a projection once
- * a pass holds 128 rows or more (below that they enter as a bf16 head plus a
+ * a pass holds 33 rows or more (below that they enter as a bf16 head plus a
  * bf16 remainder, i.e. with fp32 accuracy).
  * -------------------------------------------------------------------------- */
 typedef struct photon_config {

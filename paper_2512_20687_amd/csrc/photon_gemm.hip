@@ -387,6 +387,12 @@ size_t linear_many_workspace_bytes(int64_t rows, int K_max, int N2_max) {
   return (size_t)rows * K_max * 2 + (size_t)rows * N2_max * sizeof(float);
 }
 
+int32_t launch_norm_round_rows(const float* x, int64_t ldx, const float* gain, float eps, void* xb, int M, int K, hipStream_t st) {
+  if (K % 4 != 0 || ldx % 4 != 0) return fail(PHOTON_ERR_UNSUPPORTED, "row kernel: K=%d and the row pitch must be multiples of 4", K);
+  PHOTON_LAUNCH(KC_NORM, st, norm_round_rows_kernel, dim3(M), dim3(256), 0, st, x, ldx, gain, eps, reinterpret_cast<bf16_t*>(xb), K);
+  return check_launch("norm_round_rows_kernel");
+}
+
 int32_t launch_linear_many(const LinearArgs& a, void* workspace, int K_max, hipStream_t st) {
   if (!a.w_bf16 || a.K % G_BK != 0 || a.K > K_max || a.ldx % 4 != 0)
     return fail(PHOTON_ERR_UNSUPPORTED, "many-row linear: needs bf16 weights, K=%d a multiple of 64 and at most %d", a.K, K_max);

@@ -40,6 +40,8 @@ bool launch_linear_resident(const LinearArgs& a, hipStream_t st);
 // contraction + (SwiGLU) row kernel.  `workspace` holds linear_many_workspace_bytes(rows, K_max, N2_max)
 // bytes, K_max >= every K and N2_max >= every 2N of a SwiGLU call that will be issued with it.
 size_t linear_many_workspace_bytes(int64_t rows, int K_max, int N2_max);
+// The row kernel alone: xb[M, K] (dense bf16) = rmsnorm(x; gain, eps) (gain == nullptr: x), rounded to nearest even.
+int32_t launch_norm_round_rows(const float* x, int64_t ldx, const float* gain, float eps, void* xb, int M, int K, hipStream_t st);
 int32_t launch_linear_many(const LinearArgs& a, void* workspace, int K_max, hipStream_t st);
 
 }  // namespace photon

@@ -55,12 +55,15 @@ __host__ __device__ constexpr int rl_chunk_bytes(int rows) { return 2 * 16 * rl_
 // so one load per block fetches whole lines.  The first MFMA of a block uses the registers as loaded, the second
 // after a rotation by 8 lanes inside each row of 16, which brings the second half under rows 0..7.  Accumulator
 // rows 8..15 are meaningless; a unit's 8 weight rows sit in rows 0..7 (lanes 0..31).
-template <int EPI, int XP, bool NORM, int TMAX, bool XB>
+// RT (bf16 activations only): row tiles of 16 per workgroup.  With 32-127 rows every weight fragment, once in registers,
+// meets the fragments of RT row tiles, so the weights are streamed once per RT*16 rows instead of once per 16.
+template <int EPI, int XP, bool NORM, int TMAX, bool XB, int RT = 1>
 __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
     const float* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ W, const float* __restrict__ gain, float eps,
     const float* __restrict__ bias, const float* res, int64_t ldres, float* out, int64_t ldo, int M, int N, int K,
     int unit_base, int unit_rem, int wave_bytes, int out_bf16) {
   static_assert(!XB || !NORM, "bf16 activations come without a pre-norm");
+  static_assert(XB || RT == 1, "several row tiles per workgroup: bf16 activations only");
   constexpr int CB = RL_CB;
   constexpr int ROWS = 2 * XP;
   constexpr int GP = rl_group_pitch(ROWS);
@@ -72,7 +75,7 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lrow = lane & 15, lq = lane >> 4;
-  const int m0 = blockIdx.y * 16;
+  const int m0 = blockIdx.y * (16 * RT);
   char* my_area = smem + wave * wave_bytes;
   float* ssum = reinterpret_cast<float*>(smem + RL_WAVES * wave_bytes);
 
@@ -100,19 +103,26 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
 
   struct Operands {
     uint4_t w[TT][CB];                                             // weight fragments of one chunk
-    uint4_t xf[XB ? CB : 1][2];                                    // XB: its activation fragments
+    uint4_t xf[RT][XB ? CB : 1][2];                                // XB: its activation fragments, per row tile
   };
-  float4_t acc[TT];
+  float4_t acc[RT][TT];
 #pragma unroll
-  for (int t = 0; t < TT; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int t = 0; t < TT; ++t) acc[rt][t] = float4_t{0.f, 0.f, 0.f, 0.f};
   float ss[XP];
 #pragma unroll
   for (int i = 0; i < XP; ++i) ss[i] = 0.f;
 
   // ---- loads: unconditional, clamped into bounds, so that the load counter can be waited on exactly ----
   // bf16 activations: fragment (block b, half) of this lane = k b*64 + half*32 + lq*8 .. +8 of row m0 + lrow
-  const bool xf_live = m0 + lrow < M;
-  const char* xf_lane = reinterpret_cast<const char*>(x) + ((int64_t)(m0 + (xf_live ? lrow : 0)) * ldx + lq * 8) * 2;
+  bool xf_live[RT];
+  const char* xf_lane[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    xf_live[rt] = m0 + rt * 16 + lrow < M;
+    xf_lane[rt] = reinterpret_cast<const char*>(x) + ((int64_t)(xf_live[rt] ? m0 + rt * 16 + lrow : 0) * ldx + lq * 8) * 2;
+  }
   auto load_w = [&](int j, Operands& o) {
     const int chunk = wave + j * RL_WAVES;
     if (XB) {                                                      // the (cached) activations first, as below
@@ -121,10 +131,12 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
         int blk = chunk * CB + b;
         blk = blk < total_blocks ? blk : total_blocks - 1;
 #pragma unroll
-        for (int half2 = 0; half2 < 2; ++half2) {
-          o.xf[b][half2] = uint4_t{0u, 0u, 0u, 0u};
-          if (xf_live) o.xf[b][half2] = load16(xf_lane + (int64_t)blk * (RL_KBLOCK * 2) + half2 * 64);
-        }
+        for (int half2 = 0; half2 < 2; ++half2)
+#pragma unroll
+          for (int rt = 0; rt < RT; ++rt) {
+            o.xf[rt][b][half2] = uint4_t{0u, 0u, 0u, 0u};
+            if (xf_live[rt]) o.xf[rt][b][half2] = load16(xf_lane[rt] + (int64_t)blk * (RL_KBLOCK * 2) + half2 * 64);
+          }
       }
     }
 #pragma unroll
@@ -190,11 +202,12 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
 #pragma unroll
         for (int half2 = 0; half2 < 2; ++half2) {
           if constexpr (XB) {
-            const bf16x8_t bx = as_bf16x8(o.xf[b][half2]);
 #pragma unroll
             for (int t = 0; t < TT; ++t) {
               const bf16x8_t a = as_bf16x8(half2 ? rotate8(o.w[t][b]) : o.w[t][b]);
-              acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bx, acc[t], 0, 0, 0);
+#pragma unroll
+              for (int rt = 0; rt < RT; ++rt)
+                acc[rt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, as_bf16x8(o.xf[rt][b][half2]), acc[rt][t], 0, 0, 0);
             }
           } else {
             const int off = ((b * 2 + half2) * 4 + lq) * GP + frag_row;
@@ -203,8 +216,8 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
 #pragma unroll
             for (int t = 0; t < TT; ++t) {
               const bf16x8_t a = as_bf16x8(half2 ? rotate8(o.w[t][b]) : o.w[t][b]);
-              acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[t], 0, 0, 0);
-              acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[t], 0, 0, 0);
+              acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[0][t], 0, 0, 0);
+              acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[0][t], 0, 0, 0);
             }
           }
         }
@@ -292,48 +305,53 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   __syncthreads();                                                 // every wave is done with its operands: the area is reused
   float4_t* red = reinterpret_cast<float4_t*>(my_area);
 #pragma unroll
-  for (int t = 0; t < TT; ++t) red[t * 64 + lane] = acc[t];
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int t = 0; t < TT; ++t) red[(rt * TT + t) * 64 + lane] = acc[rt][t];
   __syncthreads();
 
-  // wave t finishes tile t: partial tiles added in wave order, 1/rms, epilogue.
+  // wave t finishes tile t (of every row tile): partial tiles added in wave order, 1/rms, epilogue.
   // acc of lane l holds y[row m0 + l%16][tile row (l/16)*4 + 0..3] (tile row = weight row = output column)
   if (wave >= TMAX || wave >= tiles) return;
   const int t = wave;
-  const int m = m0 + lrow;
-  if (m >= M) return;
   if (lq >= (EPI == EPI_SWIGLU ? 1 : 2)) return;                   // accumulator rows 8..15 are meaningless; SwiGLU: rows 4..7 are
                                                                    // the up values, read from the lanes that hold them below
   const int n_out = n0 + t * UC + lq * 4;
-  float4_t extra = float4_t{0.f, 0.f, 0.f, 0.f};                   // bias and residual, fetched while the partials are added
-  if (bias != nullptr) extra = *reinterpret_cast<const float4_t*>(bias + n_out);
-  if (EPI == EPI_RESID) extra += *reinterpret_cast<const float4_t*>(res + (int64_t)m * ldres + n_out);
-  float4_t y = float4_t{0.f, 0.f, 0.f, 0.f}, yu = float4_t{0.f, 0.f, 0.f, 0.f};
-  float tot = 0.f;
 #pragma unroll
-  for (int w = 0; w < RL_WAVES; ++w) {
-    const float4_t* rw = reinterpret_cast<const float4_t*>(smem + w * wave_bytes);
-    y += rw[t * 64 + lane];
-    if (EPI == EPI_SWIGLU) yu += rw[t * 64 + lane + 16];
-    tot += ssum[w * 16 + lrow];
+  for (int rt = 0; rt < RT; ++rt) {
+    const int m = m0 + rt * 16 + lrow;
+    if (m >= M) continue;
+    float4_t extra = float4_t{0.f, 0.f, 0.f, 0.f};                 // bias and residual, fetched while the partials are added
+    if (bias != nullptr) extra = *reinterpret_cast<const float4_t*>(bias + n_out);
+    if (EPI == EPI_RESID) extra += *reinterpret_cast<const float4_t*>(res + (int64_t)m * ldres + n_out);
+    float4_t y = float4_t{0.f, 0.f, 0.f, 0.f}, yu = float4_t{0.f, 0.f, 0.f, 0.f};
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < RL_WAVES; ++w) {
+      const float4_t* rw = reinterpret_cast<const float4_t*>(smem + w * wave_bytes);
+      y += rw[(rt * TT + t) * 64 + lane];
+      if (EPI == EPI_SWIGLU) yu += rw[(rt * TT + t) * 64 + lane + 16];
+      tot += ssum[w * 16 + lrow];
+    }
+    if (NORM) {
+      const float r = 1.0f / sqrtf(tot / (float)K + eps);
+      y *= r;
+      yu *= r;
+    }
+    if (EPI == EPI_SWIGLU) {
+      y.x = silu(y.x) * yu.x; y.y = silu(y.y) * yu.y; y.z = silu(y.z) * yu.z; y.w = silu(y.w) * yu.w;
+    }
+    y += extra;
+    if (out_bf16)
+      *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(out) + (int64_t)m * ldo + n_out) = uint2{pack_bf16x2(y.x, y.y), pack_bf16x2(y.z, y.w)};
+    else
+      *reinterpret_cast<float4_t*>(out + (int64_t)m * ldo + n_out) = y;
   }
-  if (NORM) {
-    const float r = 1.0f / sqrtf(tot / (float)K + eps);
-    y *= r;
-    yu *= r;
-  }
-  if (EPI == EPI_SWIGLU) {
-    y.x = silu(y.x) * yu.x; y.y = silu(y.y) * yu.y; y.z = silu(y.z) * yu.z; y.w = silu(y.w) * yu.w;
-  }
-  y += extra;
-  if (out_bf16)
-    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(out) + (int64_t)m * ldo + n_out) = uint2{pack_bf16x2(y.x, y.y), pack_bf16x2(y.z, y.w)};
-  else
-    *reinterpret_cast<float4_t*>(out + (int64_t)m * ldo + n_out) = y;
 }
 
-template <int EPI, int XP, bool NORM, int TMAX, bool XB = false>
+template <int EPI, int XP, bool NORM, int TMAX, bool XB = false, int RT = 1>
 bool launch_resident_t(const LinearArgs& a, hipStream_t st, int G, int unit_base, int unit_rem, int wave_bytes, size_t lds) {
-  auto kern = resident_linear_bf16_kernel<EPI, XP, NORM, TMAX, XB>;
+  auto kern = resident_linear_bf16_kernel<EPI, XP, NORM, TMAX, XB, RT>;
   static bool attr_done = false;                                   // more than 64 KiB of dynamic LDS has to be allowed once
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, RL_LDS_LIMIT) != hipSuccess) {
@@ -342,7 +360,7 @@ bool launch_resident_t(const LinearArgs& a, hipStream_t st, int G, int unit_base
     }
     attr_done = true;
   }
-  dim3 grid(G, (a.M + 15) / 16);
+  dim3 grid(G, (a.M + 16 * RT - 1) / (16 * RT));
   PHOTON_LAUNCH(KC_SKINNY_GEMM, st, kern, grid, dim3(RL_THREADS), lds, st, a.x, a.ldx, (const bf16_t*)a.W, a.gain, a.eps, a.bias,
                 a.res, a.ldres, a.out, a.ldo, a.M, a.N, a.K, unit_base, unit_rem, wave_bytes, a.out_bf16 ? 1 : 0);
   return true;
@@ -361,16 +379,31 @@ bool launch_resident_x(const LinearArgs& a, hipStream_t st, int tmax, int G, int
   }
 }
 
-// bf16 activations: one instantiation per epilogue and unit count (live rows are a run-time mask)
-template <int EPI>
-bool launch_resident_xb(const LinearArgs& a, hipStream_t st, int tmax, int G, int ub, int ur, int wave_bytes, size_t lds) {
+// bf16 activations: one instantiation per epilogue, unit count and row tiles per workgroup (live rows are a run-time
+// mask).  Four row tiles are instantiated up to three units, two up to six: what the registers hold.
+template <int EPI, int RT>
+bool launch_resident_xb_rt(const LinearArgs& a, hipStream_t st, int tmax, int G, int ub, int ur, int wave_bytes, size_t lds) {
   switch (tmax) {
-    case 1: return launch_resident_t<EPI, 8, false, 1, true>(a, st, G, ub, ur, wave_bytes, lds);
-    case 2: return launch_resident_t<EPI, 8, false, 2, true>(a, st, G, ub, ur, wave_bytes, lds);
-    case 3: return launch_resident_t<EPI, 8, false, 3, true>(a, st, G, ub, ur, wave_bytes, lds);
-    case 4: return launch_resident_t<EPI, 8, false, 4, true>(a, st, G, ub, ur, wave_bytes, lds);
-    case 5: return launch_resident_t<EPI, 8, false, 5, true>(a, st, G, ub, ur, wave_bytes, lds);
-    default: return launch_resident_t<EPI, 8, false, 6, true>(a, st, G, ub, ur, wave_bytes, lds);
+    case 1: return launch_resident_t<EPI, 8, false, 1, true, RT>(a, st, G, ub, ur, wave_bytes, lds);
+    case 2: return launch_resident_t<EPI, 8, false, 2, true, RT>(a, st, G, ub, ur, wave_bytes, lds);
+    case 3: return launch_resident_t<EPI, 8, false, 3, true, RT>(a, st, G, ub, ur, wave_bytes, lds);
+  }
+  if constexpr (RT <= 2) {
+    switch (tmax) {
+      case 4: return launch_resident_t<EPI, 8, false, 4, true, RT>(a, st, G, ub, ur, wave_bytes, lds);
+      case 5: return launch_resident_t<EPI, 8, false, 5, true, RT>(a, st, G, ub, ur, wave_bytes, lds);
+      default: return launch_resident_t<EPI, 8, false, 6, true, RT>(a, st, G, ub, ur, wave_bytes, lds);
+    }
+  }
+  return false;
+}
+
+template <int EPI>
+bool launch_resident_xb(const LinearArgs& a, hipStream_t st, int rt, int tmax, int G, int ub, int ur, int wave_bytes, size_t lds) {
+  switch (rt) {
+    case 4: return launch_resident_xb_rt<EPI, 4>(a, st, tmax, G, ub, ur, wave_bytes, lds);
+    case 2: return launch_resident_xb_rt<EPI, 2>(a, st, tmax, G, ub, ur, wave_bytes, lds);
+    default: return launch_resident_xb_rt<EPI, 1>(a, st, tmax, G, ub, ur, wave_bytes, lds);
   }
 }
 
@@ -390,9 +423,9 @@ bool launch_linear_resident(const LinearArgs& a, hipStream_t st) {
   if (!a.w_bf16 || a.K % RL_KBLOCK != 0 || a.N % 8 != 0) return false;
   if (a.ldx % (a.x_bf16 ? 8 : 4) != 0 || a.ldo % 4 != 0 || (a.res && a.ldres % 4 != 0)) return false;
   const bool norm = a.gain != nullptr;
-  if (a.x_bf16 && (norm || a.epilogue == EPI_SWIGLU)) return false;
+  if (a.x_bf16 && norm) return false;
   // instantiated combinations: the ones the decode path uses
-  const bool combo = (a.epilogue == EPI_PLAIN) || (a.epilogue == EPI_RESID && !norm) || (a.epilogue == EPI_SWIGLU && norm);
+  const bool combo = (a.epilogue == EPI_PLAIN) || (a.epilogue == EPI_RESID && !norm) || (a.epilogue == EPI_SWIGLU && (norm || a.x_bf16));
   if (!combo) return false;
   const int64_t w_rows = (a.epilogue == EPI_SWIGLU) ? 2 * (int64_t)a.N : a.N;
   if (w_rows * a.K * 2 >= ((int64_t)1 << 32)) return false;       // 32-bit weight offsets
@@ -412,13 +445,19 @@ bool launch_linear_resident(const LinearArgs& a, hipStream_t st) {
   if (tmax > 6) tmax = 8;                                          // instantiated: 1 .. 6 and 8 (surplus tiles repeat the last)
   const int chunks = (a.K / RL_KBLOCK + RL_CB - 1) / RL_CB;
   const int n_my_max = (chunks + RL_WAVES - 1) / RL_WAVES;
+  // bf16 activations with more than 16 rows: several row tiles per workgroup, as many as the registers hold
+  const int rt = !a.x_bf16 || a.M <= 16 ? 1 : (a.M > 32 && tmax <= 3) ? 4 : 2;
   int wave_bytes = a.x_bf16 ? 0 : n_my_max * rl_chunk_bytes(2 * xp);
-  if (wave_bytes < tmax * 1024) wave_bytes = tmax * 1024;          // the partial tiles reuse the area
+  if (wave_bytes < rt * tmax * 1024) wave_bytes = rt * tmax * 1024;   // the partial tiles reuse the area
   const size_t lds = (size_t)RL_WAVES * wave_bytes + RL_WAVES * 16 * sizeof(float);
   if (lds > (size_t)RL_LDS_LIMIT) return false;
-  if (a.x_bf16)
-    return a.epilogue == EPI_RESID ? launch_resident_xb<EPI_RESID>(a, st, tmax, G, ub, ur, wave_bytes, lds)
-                                   : launch_resident_xb<EPI_PLAIN>(a, st, tmax, G, ub, ur, wave_bytes, lds);
+  if (a.x_bf16) {
+    switch (a.epilogue) {
+      case EPI_PLAIN: return launch_resident_xb<EPI_PLAIN>(a, st, rt, tmax, G, ub, ur, wave_bytes, lds);
+      case EPI_RESID: return launch_resident_xb<EPI_RESID>(a, st, rt, tmax, G, ub, ur, wave_bytes, lds);
+      default: return launch_resident_xb<EPI_SWIGLU>(a, st, rt, tmax, G, ub, ur, wave_bytes, lds);
+    }
+  }
   switch (a.epilogue) {
     case EPI_PLAIN:
       return norm ? launch_resident_e<EPI_PLAIN, true>(a, st, xp, tmax, G, ub, ur, wave_bytes, lds)

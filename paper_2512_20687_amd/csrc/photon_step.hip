@@ -184,6 +184,10 @@ static inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256
 // From this many rows on a linear map goes to the tiled MFMA contraction instead of the few-row kernels
 // (which would re-read the weights once per 16 rows).
 constexpr int LINEAR_MANY_ROWS = 128;
+// Between the two, from this many rows on (three row tiles of 16 and more), the rows are normalised and rounded to
+// bf16 by the row kernel and the few-row kernel takes several row tiles per workgroup: the weights are then streamed
+// once per 32 or 64 rows instead of once per 16.
+constexpr int LINEAR_MID_ROWS = 33;
 
 struct Plan {
   int L = 0;
@@ -239,8 +243,8 @@ static Plan make_plan(const photon_config& c, int Bt, int64_t S_max) {
   if (c.dt == PHOTON_BF16) {
     p.many_K = (int)(D > F ? D : F);
     if ((int64_t)c.C[c.L - 1] * D > p.many_K) p.many_K = (int)(c.C[c.L - 1] * D);   // the top chunker contracts over C_L * D
-    if (p.rows_max >= LINEAR_MANY_ROWS) p.many = bump(cur, linear_many_workspace_bytes(p.rows_max, p.many_K, (int)(2 * F)));
-    if (Bt >= LINEAR_MANY_ROWS) p.many2 = bump(cur, linear_many_workspace_bytes(Bt, p.many_K, (int)(2 * F)));
+    if (p.rows_max >= LINEAR_MID_ROWS) p.many = bump(cur, linear_many_workspace_bytes(p.rows_max, p.many_K, (int)(2 * F)));
+    if (Bt >= LINEAR_MID_ROWS) p.many2 = bump(cur, linear_many_workspace_bytes(Bt, p.many_K, (int)(2 * F)));
   }
   for (int l = 1; l <= c.L; ++l) {
     p.fresh[l - 1] = bump(cur, (size_t)p.chunks[l] * c.C[l - 1] * D * f);
@@ -320,6 +324,15 @@ static int32_t linear(const Ctx& x, const float* in, int64_t ldx, const void* W,
   a.ldres = ldres; a.out = out; a.ldo = ldo; a.M = M; a.N = N; a.K = K; a.epilogue = epilogue;
   if (x.bf16 && M >= LINEAR_MANY_ROWS && K <= x.p.many_K && (epilogue != EPI_SWIGLU || 2 * N <= 2 * x.c->d_ff))
     return launch_linear_many(a, x.base + x.o_many, x.p.many_K, x.st);
+  const int64_t w_bytes = (int64_t)(epilogue == EPI_SWIGLU ? 2 : 1) * N * K * 2;
+  if (x.bf16 && M >= LINEAR_MID_ROWS && K <= x.p.many_K && w_bytes < ((int64_t)1 << 32)) {
+    if (!in_bf16) {                                          // norm and rounding once, in front of the bf16-row kernel
+      void* rows_bf16 = x.base + x.o_many;
+      PHOTON_TRY(launch_norm_round_rows(in, ldx, gain, x.c->rms_eps, rows_bf16, M, K, x.st));
+      a.x = reinterpret_cast<const float*>(rows_bf16); a.ldx = K; a.x_bf16 = true; a.gain = nullptr;
+    }
+    return launch_linear(a, x.st);
+  }
   return launch_linear(a, x.st);
 }
 
@@ -612,7 +625,7 @@ static PrefillPlan make_prefill_plan(const photon_config& c, int Bt, int64_t T) 
     p.many_K = (int)(D > F ? D : F);
     for (int l = 1; l <= c.L; ++l)
       if ((int64_t)c.C[l - 1] * D > p.many_K) p.many_K = (int)(c.C[l - 1] * D);
-    if (rows >= LINEAR_MANY_ROWS) p.many = bump(cur, linear_many_workspace_bytes(rows, p.many_K, (int)(2 * F)));
+    if (rows >= LINEAR_MID_ROWS) p.many = bump(cur, linear_many_workspace_bytes(rows, p.many_K, (int)(2 * F)));
   }
   p.ea = bump(cur, encoder_attn_workspace_bytes(Bt, p.M[1], c.H, c.d_h, c.dt == PHOTON_BF16));
   p.total = cur;

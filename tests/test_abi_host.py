@@ -59,10 +59,9 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.photon_linear(p, p, None, 1e-5, None, None, p, 4, 64, 100, 0, 1, None) == -2
     assert lib.photon_linear(p, p, None, 1e-5, None, None, p, 4, 64, 64, 1, 1, None) == -1      # residual without res
     assert lib.photon_linear(p, p, None, 1e-5, None, None, p, 0, 64, 64, 0, 1, None) == 0       # no rows: no-op
-    # bf16 rows in or out: bf16 matrices only; rows in come without norm and without SwiGLU
+    # bf16 rows in or out: bf16 matrices only; rows in come without norm
     assert lib.photon_linear(p, p, None, 1e-5, None, None, p, 4, 64, 64, 0x10, 0, None) == -2
     assert lib.photon_linear(p, p, None, 1e-5, None, None, p, 4, 64, 64, 0x20, 0, None) == -2
-    assert lib.photon_linear(p, p, None, 1e-5, None, None, p, 4, 64, 64, 0x10 | 2, 1, None) == -2
     assert lib.photon_linear(p, p, p, 1e-5, None, None, p, 4, 64, 64, 0x10, 1, None) == -2
     # workspace size formula
     assert lib.photon_coarse_decode_attn_workspace_bytes(4, 32, 64, 8) == 4 * 32 * 8 * 66 * 4

@@ -94,6 +94,10 @@ def bf16_values(a):
     (7, 208, 448, 0, True),          # odd number of k blocks, 26 units
     (40, 272, 1024, 1, False),       # three row tiles, the last one ragged
     (3, 16384, 192, 0, False),       # 2048 units: several per workgroup
+    (64, 2048, 2048, 1, False),      # 64 rows: four row tiles per workgroup
+    (100, 6144, 1024, 0, True),      # three units per workgroup, four row tiles, the second group of them ragged
+    (64, 10240, 512, 0, False),      # five units per workgroup: two row tiles per workgroup, two groups
+    (33, 96, 5120, 1, True),         # one row into the third row tile
 ])
 def test_linear_bf16_rows_in(M, N, K, epilogue, bias):
     """bf16 activations enter the matrix cores as they are: exact products of bf16 values, fp32 sums."""
@@ -137,9 +141,25 @@ def test_linear_bf16_rows_rejected_where_unsupported():
     w = torch.zeros((128, 64), device="cuda", dtype=torch.bfloat16)
     out = torch.zeros((4, 64), device="cuda")
     with pytest.raises(ph.PhotonError):
-        ph.photon_linear(x, w, out, epilogue=2)                                  # SwiGLU takes fp32 rows
-    with pytest.raises(ph.PhotonError):
         ph.photon_linear(x, w[:64], out, gain=torch.ones(64, device="cuda"))     # as does the pre-norm
     with pytest.raises(ph.PhotonError):
         ph.photon_linear(x, w[:64].float(), out)                                 # fp32 matrices: fp32 rows
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 5120, 2048), (48, 272, 1024), (100, 640, 256), (16, 1024, 512)])
+def test_linear_swiglu_on_bf16_rows(M, N, K):
+    """SwiGLU on rows that are bf16 already (the 33-127-row passes of a step: the row kernel has normalised and
+    rounded them): exact products, fp32 sums, product stored as bf16."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    x = bf16_values(si.make_normal((M, K), 21, "f32"))
+    w = si.make_normal((2 * N, K), 22, "bf16", std=0.05)
+    ref = oracle_linear(x, w, None, 1e-5, None, None, 2, N)
+    out = torch.full((M, N), float("nan"), device="cuda", dtype=torch.bfloat16)
+    full = torch.full((M, N), float("nan"), device="cuda")
+    ph.photon_linear(dev(x, "bf16"), dev(w, "bf16"), out, epilogue=2)
+    ph.photon_linear(dev(x, "bf16"), dev(w, "bf16"), full, epilogue=2)
+    torch.cuda.synchronize()
+    assert nerr(full, ref) <= 2 * TOL["f32"]
+    assert torch.equal(out, full.to(torch.bfloat16))
 
