@@ -206,7 +206,7 @@ PHOTON_API int32_t photon_linear(const void* x, const void* w, const float* gain
  * stream, norms, softmax and every accumulation in fp32; the feed-forward's
  * hidden rows and the attention rows of the local decoders and of the prefill
  * are kept in bf16, and so are the rows entering a projection once
- * a pass holds 33 rows or more (below that they enter as a bf16 head plus a
+ * a pass holds 17 rows or more (below that they enter as a bf16 head plus a
  * bf16 remainder, i.e. with fp32 accuracy).
  * -------------------------------------------------------------------------- */
 typedef struct photon_config {
