@@ -189,7 +189,7 @@ def test_local_no_chunks_is_a_noop():
 
 
 @pytest.mark.parametrize("name,level", [("cfg5_bf16_3level", 1), ("cfg2_bf16_8k", 1)])
-def test_local_tile_full_size_sampled_chunks(name, level):
+def test_local_tile_full_size_by_workload(name, level):
     """All token-level chunk tiles of the configuration's prompt in one launch;
     the oracle computes a sample of chunks."""
     require_gpu()
@@ -210,7 +210,7 @@ def test_local_tile_full_size_sampled_chunks(name, level):
 
 
 @pytest.mark.parametrize("n,W,H", [(32768, 8, 32), (131072, 4, 32)])      # configuration 5 level 1; configuration 3 token level (a slice)
-def test_local_tile_full_size_sampled_chunks(n, W, H):
+def test_local_tile_full_size_by_shape(n, W, H):
     """Tile mode at the configurations' real chunk counts (1 GiB per operand); the oracle computes a sample of chunks."""
     require_gpu()
     import paper_2512_20687_amd as ph

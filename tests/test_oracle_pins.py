@@ -553,3 +553,96 @@ def test_fp8_cache_changes_only_what_is_stored():
     np.testing.assert_array_equal(ta["logits"], tb["logits"])                 # the top-down pass never reads the coarse cache
     assert np.abs(a["x_top"] - b["x_top"]).max() > 1e-6                      # the new state does: it saw its own rounded entry
 
+
+
+# ---------------------------------------------------------------- prefill carries and the start latent
+
+@pytest.mark.parametrize("L,C,R", [(2, (4, 4), (1, 1)), (3, (2, 3, 2), (1, 2, 1))])
+def test_prefill_carry_continues_the_teacher_forced_forward(L, C, R):
+    """Which unit prefill keeps as the carry (Section 2.3.3, first paragraph; Section 2.1.2, converter paragraph:
+    chunk g hangs off the previous latent g-1): a decode step that continues a prompt with forced tokens must agree
+    with the teacher-forced forward (Eq. 8) of prompt + forced tokens wherever both are conditioned on prompt-only
+    quantities -- the first C_1 logits (first token chunk, hanging off the last reconstructed level-1 unit of the
+    prompt) and the first new unit of every level >= 1 (item 1 of a chunk depends on its conditioning latent alone).
+    A carry taken from the encoder side, or one unit early, breaks this."""
+    cfg = tiny_cfg(L=L, C=C, R=R, n_layers=1)
+    w = po.weights_to_f64(si.make_weights(cfg, 21))
+    B = cfg.meta_context
+    T = 2 * B
+    toks = si.make_tokens(cfg.vocab, 2, T, 8)
+    forced = si.make_tokens(cfg.vocab, 2, B, 9)
+    st = po.prefill(cfg, w, toks, 8)
+    tr = po.decode_step(cfg, w, st, forced_tokens=forced)
+    for b in range(2):
+        ref = po.teacher_forced_forward(cfg, w, np.concatenate([toks[b], forced[b]]))
+        np.testing.assert_allclose(tr["logits"][b, : C[0]], ref["logits"][T: T + C[0]], atol=1e-10)
+        M = T
+        for l in range(1, L):                                   # first new level-l unit = X-hat^(l)_{M_l + 1}
+            M //= C[l - 1]
+            np.testing.assert_allclose(tr["new"][l][b, 0], ref["Xh"][l][M], atol=1e-10)
+        # the carry the prompt left behind is the last reconstruction of the prompt itself (causality of Eq. 8)
+        M = T
+        for l in range(1, L):
+            M //= C[l - 1]
+            np.testing.assert_allclose(po.prefill(cfg, w, toks[b: b + 1], 8)["carry"][l - 1][0], ref["Xh"][l][M - 1], atol=1e-10)
+    # the reconstruction is not the encoder-side state, so the two candidates for the carry are distinguishable
+    r0 = po.teacher_forced_forward(cfg, w, toks[0])
+    assert np.abs(r0["Xh"][1][-1] - r0["X"][1][-1]).max() > 1e-3
+    assert np.abs(r0["Xh"][1][-1] - r0["Xh"][1][-2]).max() > 1e-3
+
+
+@pytest.mark.parametrize("L,C,R", [(2, (4, 4), (1, 1)), (3, (2, 3, 2), (2, 1, 2))])
+def test_start_latent_conditions_exactly_the_first_chunk(L, C, R):
+    """Section 2.1.2 (converter paragraph): chunk 1 of every level has no previous latent and is conditioned on the
+    level's learned start latent.  On a prompt of one meta-context, chunk 1 of level l must equal a stand-alone chunk
+    decode (Eq. 6) from x0 with the teacher inputs of Eq. 8; moving x0 of level l moves chunk 1 of that level and
+    nothing else at that level, and at the token level exactly the chunks that hang off the moved units."""
+    cfg = tiny_cfg(L=L, C=C, R=R, n_layers=1)
+    w = po.weights_to_f64(si.make_weights(cfg, 22))
+    B = cfg.meta_context
+    toks = si.make_tokens(cfg.vocab, 1, B, 10)[0]
+    base = po.teacher_forced_forward(cfg, w, toks)
+    for l in range(1, L + 1):
+        Cl = C[l - 1]
+        dec_l = w["dec"][l - 1]
+        lower = base["X"][l - 1] if l >= 2 else w["E_dec"][toks]
+        items = po.local_decode(cfg, l, dec_l, po.f64(dec_l["x0"])[None], lambda j, item: lower[j - 1: j])
+        np.testing.assert_allclose(items[0], base["Xh"][l - 1][:Cl], atol=1e-10)
+        # perturb this level's start latent only
+        w2 = dict(w)
+        w2["dec"] = list(w["dec"])
+        w2["dec"][l - 1] = dict(dec_l, x0=po.f64(dec_l["x0"]) + 0.3)
+        alt = po.teacher_forced_forward(cfg, w2, toks)
+        moved = np.abs(alt["Xh"][l - 1] - base["Xh"][l - 1]).max(axis=-1) > 1e-9
+        assert moved[:Cl].all() and not moved[Cl:].any()
+        for m in range(l, L + 1):                                # levels at and above l are untouched
+            np.testing.assert_array_equal(alt["Xh"][m], base["Xh"][m])
+        # token level: unit u of level l-1 (u < C_l moved) conditions the chunk after it; chunk 1 hangs off x0 of level 1
+        span = 1
+        for m in range(1, l):
+            span *= C[m - 1]                                     # tokens per level-(l-1) unit
+        tok_moved = np.abs(alt["logits"] - base["logits"]).max(axis=-1) > 1e-9
+        want = np.zeros(B, bool)
+        if l == 1:
+            want[:Cl] = True
+        else:
+            # the moved level-(l-1) units 0..C_l-1 each condition the level-(l-1)-chunk that follows them; everything
+            # decoded below those chunks moves, except what hangs off an unmoved start latent or unit
+            lo_units = np.zeros(base["Xh"][l - 1].shape[0] + 1, bool)
+            lo_units[1: Cl + 1] = True                           # chunk index g (0-based) at level l-1 is conditioned on unit g-1
+            cur = lo_units[: base["Xh"][l - 1].shape[0]]         # which level-(l-1) chunks move
+            for m in range(l - 1, 0, -1):
+                units = np.repeat(cur, C[m - 1])                 # all units of a moved chunk move
+                if m == 1:
+                    want = units
+                else:
+                    nxt = np.zeros(units.shape[0], bool)
+                    nxt[1:] = units[:-1]                         # chunk g of level m-1 hangs off unit g-1 of level m-1 ... moved if that unit moved
+                    cur = nxt
+        np.testing.assert_array_equal(tok_moved, want)
+    # prefill of a one-meta-context prompt keeps the last unit of those first chunks as the carry
+    st = po.prefill(cfg, w, toks[None], 4)
+    M = B
+    for l in range(1, L):
+        M //= C[l - 1]
+        np.testing.assert_allclose(st["carry"][l - 1][0], base["Xh"][l][M - 1], atol=1e-12)
