@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--workload", default="cfg3_bf16_128k")
     ap.add_argument("--no-graph", action="store_true", help="enqueue every step instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (CPU baseline) leg")
+    ap.add_argument("--no-persistent", action="store_true",
+                    help="run every module pass as separate launches instead of one persistent launch (comparison)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known traffic) so that counter runs can be calibrated")
     return ap.parse_args()
@@ -82,7 +84,7 @@ def cpu_baseline(wl, min_seconds=12.0, max_steps=120):
     dt = time.perf_counter() - t0
     scale = wl.cfg.n_layers / sample_layers
     return {
-        "value": n * Bt * cfg.meta_context / (dt * scale), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "value": n * Bt * cfg.meta_context / (dt * scale), "unit": "tokens/s", "cores": int(threads), "kind": "oracle-numpy",
         "sample": f"{n} oracle decode steps at {wl.name} shapes (D={cfg.D}, H={cfg.H}, Bt={Bt}, coarse S={S}, vocab={cfg.vocab}) "
                   f"with {sample_layers} of {wl.cfg.n_layers} blocks per module: {dt:.1f} s measured, time scaled x{scale:g}",
         "seconds_measured": dt,
@@ -93,12 +95,12 @@ def counter_traffic(workload, kernel_class):
     """HBM bytes per launch of the dominant kernel class from the committed rocprofv3 counter summary
     (FETCH_SIZE + WRITE_SIZE, each scaled by what the counter reads for a plain copy of known size);
     None when no summary covers this workload and kernel."""
-    if workload != "cfg3_bf16_128k" or kernel_class != "linear_bf16_kernels":
+    if workload != "cfg3_bf16_128k":
         return None
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "decode_step_cfg3_hbm_counters.md")
     try:
         with open(path) as f:
-            m = re.search(r"linear_traffic_bytes_per_launch:.*total=(\d+)", f.read())
+            m = re.search(re.escape(kernel_class) + r"_traffic_bytes_per_launch:.*total=(\d+)", f.read())
         return float(m.group(1)) if m else None
     except OSError:
         return None
@@ -118,6 +120,8 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     ph.load_library()
+    if args.no_persistent:
+        ph.photon_set_persistent(False)
     wl = si.WORKLOADS[args.workload]
     cfg = wl.cfg
     dev = "cuda"
@@ -199,7 +203,11 @@ def main():
     kernels = {}
     for name, (n, ms) in prof.items():
         kernels[name] = {"launches_per_step": n / prof_steps, "us_per_launch": ms * 1e3 / n, "ms_per_step": ms / prof_steps}
-    alg_bytes = {"linear_bf16_kernels": wbytes, "coarse_attn_kernel": kv_launch_bytes * nl}     # per step
+    # a persistent launch streams the matrices of one module once; the other linear kernels stream the rest
+    module_bytes = nl * (4 * cfg.D * cfg.D + 3 * cfg.D * cfg.d_ff) * esz
+    pm_bytes = kernels.get("persistent_module_kernel", {}).get("launches_per_step", 0.0) * module_bytes
+    alg_bytes = {"linear_bf16_kernels": wbytes - pm_bytes, "persistent_module_kernel": pm_bytes,
+                 "coarse_attn_kernel": kv_launch_bytes * nl}     # per step
     for name, b in alg_bytes.items():
         if name in kernels:
             k = kernels[name]
@@ -246,7 +254,8 @@ def main():
         "config": {"workload": wl.name, "L": cfg.L, "C": list(cfg.C), "R": list(cfg.R), "d_model": cfg.D, "heads": cfg.H,
                    "head_dim": cfg.d_h, "layers_per_module": cfg.n_layers, "d_ff": cfg.d_ff, "vocab": cfg.vocab,
                    "batch": Bt, "context_tokens": wl.T, "coarse_kv_len_start": S0, "coarse_kv_len_end": S_end,
-                   "tokens_per_step": tokens_per_step, "mode": mode},
+                   "tokens_per_step": tokens_per_step, "mode": mode,
+                   "schedule": "separate_launches" if args.no_persistent else "persistent_module_passes"},
         "kv_read_gbs": kv_gbs, "kv_read_frac_of_hbm_peak": kv_gbs / HBM_PEAK_GBS,
         "kv_read_isolated": {"gbs": kv_iso_gbs, "frac_of_hbm_peak": kv_iso_gbs / HBM_PEAK_GBS, "us_per_launch": iso_us,
                              "bytes_per_launch": iso_bytes, "n_splits": ns, "launches": iso[0]},

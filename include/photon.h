@@ -253,13 +253,27 @@ typedef struct photon_weights {
 typedef struct photon_state {
   void* k_cache;        /* [n_layers, Bt, H, S_max, photon_kv_row_elems(d_h)] kv_dt : KV^(L) */
   void* v_cache;
-  int32_t* seq_len;     /* [Bt] entries cached per sequence; the step adds 1.  Must be < S_max on entry. */
+  int32_t* seq_len;     /* [Bt] entries cached per sequence; the step adds 1.  Must be < S_max on entry (else see status). */
   float* x_top;         /* [Bt, D]       X^(L)_g, replaced by X^(L)_{g+1} */
   float* carry;         /* [L-1, Bt, D]  carry[l-1] = last reconstructed level-l unit, updated */
   int64_t S_max;
   void* workspace;      /* photon_decode_step_workspace_bytes(); contents need no initialisation */
   size_t workspace_bytes;
+  int32_t* status;      /* NULL, or a device word the step ORs photon_step_status bits into (never cleared by the library) */
+  void* side_stream;    /* NULL, or a hipStream_t other than the call's stream, owned by the caller and used by one state
+                           at a time: with both events given, the top-level update (ii)-(iii) of an L >= 2 model runs on
+                           it beside the lower levels and is joined back before the call's work ends */
+  void* fork_event;     /* hipEvent_t (timing may be disabled), recorded and waited on by the step; NULL: no side stream */
+  void* join_event;     /* hipEvent_t, likewise */
 } photon_state;
+
+/* Bits of photon_state.status. */
+typedef enum {
+  PHOTON_STATUS_CACHE_FULL = 1,       /* a sequence had seq_len == S_max on entry: its count stays, its new K/V entry
+                                         overwrites the last one and its results of the step are not valid */
+  PHOTON_STATUS_BARRIER_TIMEOUT = 2   /* a grid-barrier wait of a persistent launch ran out (see photon_set_persistent):
+                                         every workgroup left the kernel; the step's results are not valid */
+} photon_step_status;
 
 /* Optional outputs for inspection (each pointer may be NULL). */
 typedef struct photon_trace {
@@ -272,14 +286,27 @@ PHOTON_API size_t photon_decode_step_workspace_bytes(const photon_config* cfg, i
 
 /* forced_tokens: device int32 [Bt, prod(C)] or NULL; out_tokens: device int32
  * [Bt, prod(C)].  cfg, w, st and trace are host structs, read during the call
- * only.  All work is enqueued on `stream`; tokens stay on the device.  For
- * L >= 2 the top-level update (ii)-(iii) runs on an internal second stream
- * beside the lower levels and is joined back into `stream` before the call
- * returns its work (created on first use: the first call of a process must not
- * be made under stream capture; later calls may be captured). */
+ * only.  All work is enqueued on `stream` (and, between a fork and a join that
+ * both happen inside the call, on st->side_stream when the caller lends one);
+ * tokens stay on the device.  The library creates no stream or event, so any
+ * call may be made under stream capture. */
 PHOTON_API int32_t photon_decode_step(const photon_config* cfg, const photon_weights* w, const photon_state* st,
                                       int32_t Bt, const int32_t* forced_tokens, int32_t* out_tokens,
                                       const photon_trace* trace, void* stream);
+
+/* Schedule of a local decoder's module pass (all blocks of G^(l) on the rows of one decode sub-step, Eq. 6-7) when
+ * it holds at most 16 rows of a bf16 configuration: on != 0 (the default) runs it as ONE persistent launch, one
+ * workgroup per compute unit, whose phases meet at grid barriers (bounded waits; needs head size 64 or 128, a window
+ * of at most 8 positions, at most 16 blocks per module and one of the compiled width classes, else the separate
+ * launches are used); on == 0 always uses separate launches.  Process-wide; results agree to the last bit.
+ * At most two persistent launches can be resident on a GPU at a time: steps of more than two states issued
+ * concurrently on different streams serialise on the barrier waits (and fail with the error word set after 10 s). */
+PHOTON_API int32_t photon_set_persistent(int32_t on);
+
+/* Bound of a grid-barrier wait inside a persistent launch, in ticks of the device's constant 100 MHz clock (default
+ * 10^9 = 10 s; process-wide).  A wait that runs out sets PHOTON_STATUS_BARRIER_TIMEOUT and makes every workgroup
+ * leave the kernel normally.  Meant for tests of that path (a limit of a few ticks makes the first real wait run out). */
+PHOTON_API int32_t photon_set_barrier_wait_limit(int64_t ticks);
 
 /* --------------------------------------------------------------------------
  * Hierarchical prefill of a batch of prompts (paper Section 2.3.3, first

@@ -35,5 +35,7 @@ from .binding import (  # noqa: F401
     photon_profile_enable,
     photon_profile_get,
     photon_profile_reset,
+    photon_set_barrier_wait_limit,
+    photon_set_persistent,
     photon_version,
 )

@@ -201,6 +201,22 @@ def photon_mfma_probe(iters: int, random_operands: bool, sink: torch.Tensor) -> 
     return flops
 
 
+def photon_set_persistent(on: bool) -> None:
+    """Module passes of at most 16 rows as one persistent launch (default) or as separate launches."""
+    lib = load_library()
+    lib.photon_set_persistent.argtypes = [C.c_int32]
+    lib.photon_set_persistent.restype = C.c_int32
+    _check(lib.photon_set_persistent(1 if on else 0))
+
+
+def photon_set_barrier_wait_limit(ticks: int) -> None:
+    """Bound of a grid-barrier wait of a persistent launch in 10 ns ticks (default 10**9)."""
+    lib = load_library()
+    lib.photon_set_barrier_wait_limit.argtypes = [C.c_int64]
+    lib.photon_set_barrier_wait_limit.restype = C.c_int32
+    _check(lib.photon_set_barrier_wait_limit(int(ticks)))
+
+
 def photon_profile_enable(on: bool) -> None:
     _check(load_library().photon_profile_enable(1 if on else 0))
 
@@ -277,7 +293,8 @@ class _EncoderWeights(C.Structure):
 
 class _State(C.Structure):
     _fields_ = [("k_cache", C.c_void_p), ("v_cache", C.c_void_p), ("seq_len", C.c_void_p), ("x_top", C.c_void_p),
-                ("carry", C.c_void_p), ("S_max", C.c_int64), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+                ("carry", C.c_void_p), ("S_max", C.c_int64), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("status", C.c_void_p), ("side_stream", C.c_void_p), ("fork_event", C.c_void_p), ("join_event", C.c_void_p)]
 
 
 class _HierState(C.Structure):
@@ -397,7 +414,10 @@ class PhotonState:
     """Decode state on the device: coarse K/V cache, per-sequence lengths, top
     state, carries, and the step's workspace."""
 
-    def __init__(self, model: PhotonModel, Bt: int, S_max: int, k=None, v=None, seq_len=None, x_top=None, carry=None):
+    def __init__(self, model: PhotonModel, Bt: int, S_max: int, k=None, v=None, seq_len=None, x_top=None, carry=None,
+                 side_stream: bool = True):
+        """side_stream: lend the step a second stream and two events (torch's) so that the top-level update of an
+        L >= 2 model runs beside the lower levels; False keeps the whole step on the caller's stream."""
         cfg, dev = model.cfg, model.device
         lib = load_library()
         _register_step(lib)
@@ -432,6 +452,17 @@ class PhotonState:
         s.x_top = self.x_top.data_ptr()
         s.carry = self.carry.data_ptr() if cfg.L > 1 else None
         s.S_max, s.workspace, s.workspace_bytes = S_max, self.workspace.data_ptr(), nbytes
+        self.status = torch.zeros(1, dtype=torch.int32, device=dev)
+        s.status = self.status.data_ptr()
+        self.side_stream = self.fork_event = self.join_event = None
+        if side_stream and cfg.L >= 2:
+            self.side_stream = torch.cuda.Stream(device=dev)
+            self.fork_event, self.join_event = torch.cuda.Event(), torch.cuda.Event()
+            for ev in (self.fork_event, self.join_event):      # torch creates the HIP event on first use
+                ev.record(self.side_stream)
+            self.side_stream.synchronize()
+            s.side_stream = self.side_stream.cuda_stream
+            s.fork_event, s.join_event = self.fork_event.cuda_event, self.join_event.cuda_event
         self.c_state = s
 
 

@@ -32,7 +32,7 @@ std::vector<ProfRec> g_prof;
 const char* const kClassNames[KC_COUNT] = {
     "coarse_attn_kernel", "coarse_merge_kernel", "local_attn_kernel", "linear_bf16_kernels", "gemm_f32_kernel",
     "reduce_splits_kernel", "chunker_gemm_bf16_kernel", "norm_rows_kernel", "rope_append_kernel", "silu_mul_kernel",
-    "choose_token_kernel", "misc"};
+    "choose_token_kernel", "misc", "persistent_module_kernel"};
 }  // namespace
 
 bool profile_pair(int cls, hipEvent_t* start, hipEvent_t* stop) {

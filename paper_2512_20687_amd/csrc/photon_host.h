@@ -28,7 +28,7 @@ inline int32_t check_launch(const char* what) {
 // ---- optional per-kernel-class timing with HIP events (photon_profile_* entry points) ----
 enum KernelClass {
   KC_COARSE_ATTN = 0, KC_COARSE_MERGE, KC_LOCAL_ATTN, KC_SKINNY_GEMM, KC_GEMM_F32, KC_REDUCE_SPLITS, KC_CHUNKER_GEMM,
-  KC_NORM, KC_ROPE_APPEND, KC_SILU_MUL, KC_CHOOSE_TOKEN, KC_MISC, KC_COUNT
+  KC_NORM, KC_ROPE_APPEND, KC_SILU_MUL, KC_CHOOSE_TOKEN, KC_MISC, KC_PERSISTENT, KC_COUNT
 };
 extern bool g_profile_on;
 // A fresh event pair recorded under class `cls`; false when events cannot be created (the launch then goes untimed).

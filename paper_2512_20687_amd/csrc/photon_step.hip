@@ -8,6 +8,7 @@
 #include "photon_device.h"
 #include "photon_host.h"
 #include "photon_linear.h"
+#include "photon_persistent.h"
 
 namespace photon {
 
@@ -171,11 +172,28 @@ __global__ __launch_bounds__(256) void update_carry_kernel(const float* __restri
   carry[idx] = fresh[((int64_t)b * n + n - 1) * D + d];
 }
 
-// Start of a step: count the entry this step will append to every sequence's coarse cache.
-__global__ __launch_bounds__(256) void step_begin_kernel(int32_t* __restrict__ seq_len, int Bt) {
+// Start of a step: count the entry this step will append to every sequence's coarse cache, and clear the barrier
+// counters (and the error word behind them) of the step's persistent launches.
+// A sequence whose cache is full (seq_len == S_cap on entry) keeps its count: its new entry then overwrites the last
+// one, in bounds, and the caller's status word gets bit 0 (its results of this step are not valid).
+__global__ __launch_bounds__(256) void step_begin_kernel(int32_t* __restrict__ seq_len, int Bt, int64_t S_cap, int32_t* __restrict__ status,
+                                                         unsigned* __restrict__ bar, int bar_words) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
-  if (idx < Bt) seq_len[idx] += 1;
+  if (seq_len != nullptr && idx < Bt) {
+    const int32_t n = seq_len[idx];
+    if (n < S_cap) seq_len[idx] = n + 1;
+    else if (status != nullptr) atomicOr(status, PHOTON_STATUS_CACHE_FULL);
+  }
+  for (int i = idx; i < bar_words; i += gridDim.x * 256) bar[i] = 0u;
 }
+
+// End of a step: a barrier wait of a persistent launch that ran out is reported in the caller's status word.
+__global__ void step_end_kernel(const unsigned* __restrict__ err, int32_t* __restrict__ status) {
+  if (threadIdx.x == 0 && blockIdx.x == 0 && err[0] != 0u) atomicOr(status, PHOTON_STATUS_BARRIER_TIMEOUT);
+}
+
+// Test and measurement switch: run every module pass as separate launches (photon_set_option).
+bool g_no_persistent = false;
 
 static inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
 
@@ -200,6 +218,8 @@ struct Plan {
   size_t many = 0, many2 = 0;                    // scratch of the many-row linear path (0 rows: absent), main and STEP branch
   size_t hx[PHOTON_MAX_LEVELS] = {0}, hA = 0;    // hierarchical generation: encoder-side new units of level l, chunker outputs
   int many_K = 0;                                // widest contraction it is sized for
+  size_t bar = 0;                                // barrier slots of the persistent launches of one step, then the error word
+  int bar_slots = 0;
   size_t fresh[PHOTON_MAX_LEVELS] = {0};         // fresh[l]: new level-l units, l = 0..L-1
   size_t lk[PHOTON_MAX_LEVELS] = {0}, lv[PHOTON_MAX_LEVELS] = {0};   // local caches of level l (index l-1), all layers
   size_t total = 0;
@@ -254,6 +274,8 @@ static Plan make_plan(const photon_config& c, int Bt, int64_t S_max) {
     p.lk[l - 1] = bump(cur, cache);
     p.lv[l - 1] = bump(cur, cache);
   }
+  for (int l = 1; l <= c.L; ++l) p.bar_slots += c.C[l - 1];       // one launch per decode sub-step
+  p.bar = bump(cur, ((size_t)p.bar_slots * PM_BAR_WORDS + 64) * sizeof(unsigned));
   p.total = cur;
   return p;
 }
@@ -305,6 +327,9 @@ struct Ctx {
   bool overlap;                               // run the top-level update beside the lower levels
   const photon_encoder_weights* ew = nullptr; // encoder-side weights (prefill, hierarchical generation)
   const photon_hier_state* hs = nullptr;      // lower-level encoder streams (hierarchical generation only)
+  int* bar_next = nullptr;                    // next unused barrier slot (cleared slots: see step_begin_kernel); nullptr: none
+  unsigned* bar_words() const { return reinterpret_cast<unsigned*>(base + p.bar); }
+  int bar_word_count() const { return p.bar_slots * PM_BAR_WORDS + 64; }
   float* f(size_t off) const { return reinterpret_cast<float*>(base + off); }
 };
 
@@ -364,7 +389,10 @@ static int32_t block_tail(const Ctx& x, const photon_layer_weights& lw, RowsIn i
 
 // All blocks of the level-`level` local decoder on n_chunks * q_len rows (window positions
 // q_pos .. q_pos+q_len-1 of every chunk).  Leaves the residual stream in p.h.
-static int32_t local_module_pass(const Ctx& x, int level, int64_t n_chunks, int q_len, int q_pos, RowsIn in) {
+// alone: nothing else runs beside this pass (no STEP branch on the side stream).  The persistent kernel holds every
+// compute unit's registers and most of its LDS, so kernels of another stream cannot run beside it: where the
+// top-level update overlaps the lower levels, those levels keep the separate launches.
+static int32_t local_module_pass(const Ctx& x, int level, int64_t n_chunks, int q_len, int q_pos, RowsIn in, bool alone = true) {
   const photon_config& c = *x.c;
   const photon_module_weights& mod = x.w->dec[level - 1];
   const int W = c.R[level - 1] + c.C[level - 1] - 1;
@@ -372,6 +400,23 @@ static int32_t local_module_pass(const Ctx& x, int level, int64_t n_chunks, int 
   float *h = x.f(x.o_h), *qkv = x.f(x.o_qkv), *attn = x.f(x.o_attn);
   const size_t layer_cache = (size_t)n_chunks * W * c.D;
   const float scale = 1.0f / sqrtf((float)c.d_h);
+  if (alone && x.bf16 && c.d_ff > 0 && rows <= PM_MAX_ROWS && x.bar_next != nullptr && *x.bar_next < x.p.bar_slots && !g_no_persistent) {
+    // all blocks in one launch, the projections meeting at grid barriers instead of kernel boundaries
+    PersistentModule pm;
+    pm.layers = mod.layers; pm.n_layers = c.n_layers;
+    pm.x_in = in.ptr; pm.ld_in = in.ld;
+    pm.h = h; pm.qkv = qkv; pm.attn = attn; pm.act = x.f(x.o_act);
+    pm.lk = x.f(x.p.lk[level - 1]); pm.lv = x.f(x.p.lv[level - 1]); pm.layer_cache = layer_cache;
+    pm.bar = x.bar_words() + (size_t)(*x.bar_next) * PM_BAR_WORDS;
+    pm.err = x.bar_words() + (size_t)x.p.bar_slots * PM_BAR_WORDS;
+    pm.M = rows; pm.D = c.D; pm.F = c.d_ff; pm.H = c.H; pm.d_h = c.d_h;
+    pm.n_chunks = n_chunks; pm.W = W; pm.q_len = q_len; pm.q_pos = q_pos;
+    pm.eps = c.rms_eps; pm.scale = scale; pm.theta = c.rope_theta;
+    if (persistent_module_supported(pm)) {
+      ++*x.bar_next;
+      return launch_persistent_module(pm, x.st);
+    }
+  }
   for (int i = 0; i < c.n_layers; ++i) {
     const photon_layer_weights& lw = mod.layers[i];
     float* lk = x.f(x.p.lk[level - 1]) + (size_t)i * layer_cache;
@@ -459,7 +504,8 @@ static int32_t hier_reencode(const Ctx& x, const int32_t* tokens, const float** 
                         EPI_PLAIN));
     float* Xl = x.f(x.p.hx[l]);
     for (int j = 0; j < (int)per_seq; ++j) {
-      PHOTON_LAUNCH(KC_MISC, x.st, step_begin_kernel, dim3(blocks_for(Bt)), dim3(256), 0, x.st, x.hs->seq_len[l - 1], Bt);
+      PHOTON_LAUNCH(KC_MISC, x.st, step_begin_kernel, dim3(blocks_for(Bt)), dim3(256), 0, x.st, x.hs->seq_len[l - 1], Bt, x.hs->S_cap[l - 1],
+                    x.s->status, (unsigned*)nullptr, 0);
       PHOTON_TRY(check_launch("step_begin_kernel"));
       RowsIn in;
       in.ptr = A + (int64_t)j * D; in.ld = per_seq * (int64_t)D;
@@ -484,29 +530,17 @@ static int32_t chunk_and_step(const Ctx& x, const float* bottleneck, const photo
   return top_step(x, top_in);
 }
 
-// The top-level update depends only on the level-L decoder's output, not on the lower levels that turn
-// it into tokens, so for L >= 2 it runs on a second stream beside them (fork after level L, join at
-// the end of the step).  The stream and its two events are created on first use and live for the process.
-static hipStream_t g_side = nullptr;
-static hipEvent_t g_fork = nullptr, g_join = nullptr;
-static int32_t ensure_side_stream() {
-  if (g_side != nullptr) return PHOTON_OK;
-  if (hipStreamCreateWithFlags(&g_side, hipStreamNonBlocking) != hipSuccess ||
-      hipEventCreateWithFlags(&g_fork, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&g_join, hipEventDisableTiming) != hipSuccess) {
-    g_side = nullptr;
-    return fail(PHOTON_ERR_HIP, "decode step: cannot create the side stream");
-  }
-  return PHOTON_OK;
-}
-
+// The top-level update depends only on the level-L decoder's output, not on the lower levels that turn it into
+// tokens, so for L >= 2 it can run on a second stream beside them (fork after level L, join at the end of the
+// step).  That stream and the two events belong to the caller (photon_state): the library creates nothing.
 static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* out_tokens, const photon_trace* tr) {
   const photon_config& c = *x.c;
   const int D = c.D, L = c.L, Bt = x.Bt;
   float* h = x.f(x.o_h);
   float* cond = x.f(x.p.cond);
 
-  PHOTON_LAUNCH(KC_MISC, x.st, step_begin_kernel, dim3(blocks_for(Bt)), dim3(256), 0, x.st, x.s->seq_len, Bt);
+  PHOTON_LAUNCH(KC_MISC, x.st, step_begin_kernel, dim3(blocks_for(Bt)), dim3(256), 0, x.st, x.s->seq_len, Bt, x.s->S_max, x.s->status,
+                x.bar_words(), x.bar_word_count());
   PHOTON_TRY(check_launch("step_begin_kernel"));
 
   float* fresh[PHOTON_MAX_LEVELS];
@@ -527,7 +561,7 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
     for (int j = 0; j < C; ++j) {
       const int q_len = (j == 0) ? R : 1;
       const int q_pos = (j == 0) ? 0 : R + j - 1;
-      PHOTON_TRY(local_module_pass(x, l, n, q_len, q_pos, in));
+      PHOTON_TRY(local_module_pass(x, l, n, q_len, q_pos, in, !forked));
       // item j = final norm of the last row of each chunk.  At the token level of a hierarchy the item only feeds the
       // vocabulary projection, which then applies the norm itself (one launch less per sub-step) unless the caller
       // asked to see the items.
@@ -557,11 +591,11 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
       }
     }
     if (l == L && L >= 2 && x.overlap && x.hs == nullptr) {
-      PHOTON_TRY(ensure_side_stream());
-      if (hipEventRecord(g_fork, x.st) != hipSuccess || hipStreamWaitEvent(g_side, g_fork, 0) != hipSuccess)
+      hipStream_t side_st = (hipStream_t)x.s->side_stream;
+      if (hipEventRecord((hipEvent_t)x.s->fork_event, x.st) != hipSuccess || hipStreamWaitEvent(side_st, (hipEvent_t)x.s->fork_event, 0) != hipSuccess)
         return fail(PHOTON_ERR_HIP, "decode step: cannot fork the STEP branch");
       Ctx side = x;
-      side.st = g_side;
+      side.st = side_st;
       side.o_h = x.p.h2; side.o_attn = x.p.attn2; side.o_qkv = x.p.qkv2; side.o_qrot = x.p.qrot2; side.o_act = x.p.act2; side.o_many = x.p.many2;
       PHOTON_TRY(chunk_and_step(side, units, tr));
       forked = true;
@@ -586,8 +620,14 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
     PHOTON_TRY(chunk_and_step(x, bott, tr));
   } else if (!forked) PHOTON_TRY(chunk_and_step(x, fresh[L - 1], tr));
   else {
-    if (hipEventRecord(g_join, g_side) != hipSuccess || hipStreamWaitEvent(x.st, g_join, 0) != hipSuccess)
+    if (hipEventRecord((hipEvent_t)x.s->join_event, (hipStream_t)x.s->side_stream) != hipSuccess ||
+        hipStreamWaitEvent(x.st, (hipEvent_t)x.s->join_event, 0) != hipSuccess)
       return fail(PHOTON_ERR_HIP, "decode step: cannot join the STEP branch");
+  }
+  if (x.s->status != nullptr && *x.bar_next > 0) {
+    PHOTON_LAUNCH(KC_MISC, x.st, step_end_kernel, dim3(1), dim3(64), 0, x.st,
+                  (const unsigned*)(x.bar_words() + (size_t)x.p.bar_slots * PM_BAR_WORDS), x.s->status);
+    PHOTON_TRY(check_launch("step_end_kernel"));
   }
   return PHOTON_OK;
 }
@@ -702,6 +742,11 @@ static int32_t prefill_impl(const Ctx& x, Ctx e, const PrefillPlan& pp, const ph
 
   // Carries: teacher-forced decode of the last chunk of every level l >= 2 (one chunk per sequence), on the
   // decode step's own buffers.  Inputs of sub-step j >= 1 are the encoder-side states of the chunk (reading G7).
+  if (L >= 2) {
+    PHOTON_LAUNCH(KC_MISC, x.st, step_begin_kernel, dim3(1), dim3(256), 0, x.st, (int32_t*)nullptr, 0, (int64_t)0, (int32_t*)nullptr,
+                  x.bar_words(), x.bar_word_count());
+    PHOTON_TRY(check_launch("step_begin_kernel"));
+  }
   const float* cond = pair;                                // level-l latent before the last one, one row per sequence
   int64_t cond_ld = D;
   float* dh = x.f(x.o_h);
@@ -838,7 +883,10 @@ extern "C" int32_t photon_prefill(const photon_config* cfg, const photon_weights
   const PrefillPlan pp = make_prefill_plan(c, Bt, T);
   PHOTON_REQUIRE(workspace != nullptr && aligned16(workspace) && workspace_bytes >= pp.total, PHOTON_ERR_WORKSPACE,
                  "%s: workspace of %zu bytes needed (got %zu)", __func__, pp.total, workspace_bytes);
+  int bar_next = 0;
+  x.bar_next = &bar_next;
   Ctx e = x;                                               // same configuration and stream, the big buffers
+  e.bar_next = nullptr;
   e.base = reinterpret_cast<char*>(workspace);
   e.o_h = pp.h; e.o_attn = pp.attn; e.o_qkv = pp.qkv; e.o_qrot = 0; e.o_act = pp.act; e.o_many = pp.many;
   e.p.many_K = pp.many_K;
@@ -876,13 +924,31 @@ static int32_t decode_entry(const char* fn, const photon_config* cfg, const phot
   x.c = cfg; x.w = w; x.s = st; x.Bt = Bt; x.st = (hipStream_t)stream;
   x.p = make_plan(c, Bt, st->S_max);
   x.bf16 = (c.dt == PHOTON_BF16);
-  x.overlap = !g_profile_on;   // per-kernel timing wants one stream: concurrency would inflate the bracketed times
+  // the top-level update runs beside the lower levels when the caller lent a second stream and two events
+  // (per-kernel timing wants one stream: concurrency would inflate the bracketed times)
+  x.overlap = !g_profile_on && st->side_stream != nullptr && st->fork_event != nullptr && st->join_event != nullptr;
+  PHOTON_REQUIRE(st->side_stream == nullptr || st->side_stream != stream, PHOTON_ERR_INVALID_ARG,
+                 "%s: state.side_stream must differ from the stream of the call", fn);
   x.ew = ew; x.hs = hst;
   x.o_h = x.p.h; x.o_attn = x.p.attn; x.o_qkv = x.p.qkv; x.o_qrot = x.p.qrot; x.o_act = x.p.act; x.o_many = x.p.many;
   PHOTON_REQUIRE(st->workspace != nullptr && aligned16(st->workspace) && st->workspace_bytes >= x.p.total, PHOTON_ERR_WORKSPACE,
                  "%s: workspace of %zu bytes needed (got %zu)", fn, x.p.total, st->workspace_bytes);
   x.base = reinterpret_cast<char*>(st->workspace);
+  int bar_next = 0;
+  x.bar_next = &bar_next;
   return decode_step_impl(x, forced_tokens, out_tokens, trace);
+}
+
+extern "C" int32_t photon_set_persistent(int32_t on) {
+  g_no_persistent = (on == 0);
+  return PHOTON_OK;
+}
+
+extern "C" int32_t photon_set_barrier_wait_limit(int64_t ticks) {
+  clear_error();
+  PHOTON_REQUIRE(ticks > 0, PHOTON_ERR_INVALID_ARG, "%s: ticks=%lld must be positive", __func__, (long long)ticks);
+  persistent_module_set_spin_ticks(ticks);
+  return PHOTON_OK;
 }
 
 extern "C" int32_t photon_decode_step(const photon_config* cfg, const photon_weights* w, const photon_state* st, int32_t Bt,
