@@ -112,6 +112,25 @@ PHOTON_API int32_t photon_coarse_decode_attn(const void* q, const void* k_cache,
                                   photon_dtype dt, void* stream);
 
 /* --------------------------------------------------------------------------
+ * photon_coarse_decode_attn for callers that cannot allocate device memory and
+ * have no workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, kernels and results as
+ * photon_coarse_decode_attn, but the split partials go to a scratch array built
+ * into the library (photon_coarse_decode_attn_static_capacity() bytes = 4 MiB,
+ * held by every GPU the library runs on until the process ends) instead of a
+ * caller workspace.  Nothing is allocated or freed, here or in the runtime.
+ * A shape whose partials (photon_coarse_decode_attn_workspace_bytes()) exceed
+ * the capacity is rejected with PHOTON_ERR_WORKSPACE.  All calls on one GPU
+ * share that GPU's array: calls must be stream-ordered; calls that overlap on
+ * one GPU (two streams, two host threads) race on the partials.
+ * -------------------------------------------------------------------------- */
+PHOTON_API size_t photon_coarse_decode_attn_static_capacity(void);
+PHOTON_API int32_t photon_coarse_decode_attn_static(const void* q, const void* k_cache, const void* v_cache,
+                                         const int32_t* seq_len, void* out,
+                                         int32_t Bt, int32_t H, int32_t d_h, int64_t S_max, float scale,
+                                         int32_t n_splits, photon_dtype dt, void* stream);
+
+/* --------------------------------------------------------------------------
  * Chunk-local causal attention of the local decoders (paper Eq. 6-7): every
  * chunk is an independent window of W positions; query i (0 <= i < q_len) sits
  * at window position q_pos + i and attends to keys 0 .. q_pos + i of its own

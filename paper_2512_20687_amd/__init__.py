@@ -19,6 +19,8 @@ from .binding import (  # noqa: F401
     photon_chunker_project,
     photon_coarse_decode_attn,
     photon_coarse_decode_attn_auto_splits,
+    photon_coarse_decode_attn_static,
+    photon_coarse_decode_attn_static_capacity,
     photon_coarse_decode_attn_workspace_bytes,
     photon_decode_step,
     photon_encoder_attn,

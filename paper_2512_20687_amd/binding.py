@@ -41,6 +41,8 @@ def load_library() -> C.CDLL:
         "photon_coarse_decode_attn_workspace_bytes": (sz, [i32, i32, i32, i32]),
         "photon_coarse_decode_attn_auto_splits": (i32, [i32, i32, i64]),
         "photon_coarse_decode_attn": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i64, f32, i32, vp, sz, i32, vp]),
+        "photon_coarse_decode_attn_static_capacity": (sz, []),
+        "photon_coarse_decode_attn_static": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i64, f32, i32, i32, vp]),
         "photon_chunk_local_attn": (i32, [vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, f32, i32, vp]),
         "photon_linear": (i32, [vp, vp, vp, f32, vp, vp, vp, i32, i32, i32, i32, i32, vp]),
     }
@@ -143,6 +145,25 @@ def photon_coarse_decode_attn(q, k_cache, v_cache, seq_len, out, scale: Optional
         raise PhotonError(-1, "8-bit caches go with fp32 queries and outputs")
     _check(lib.photon_coarse_decode_attn(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_len), _ptr(out), Bt, H, d_h,
                                          S_max, scale, n_splits, _ptr(workspace), ws_bytes, _dt(k_cache), _stream()))
+    return out
+
+
+def photon_coarse_decode_attn_static_capacity() -> int:
+    return int(load_library().photon_coarse_decode_attn_static_capacity())
+
+
+def photon_coarse_decode_attn_static(q, k_cache, v_cache, seq_len, out, scale: Optional[float] = None, n_splits: int = 0):
+    """photon_coarse_decode_attn with the split partials in the library's built-in scratch array (no workspace,
+    no allocation); same tensor layouts."""
+    lib = load_library()
+    Bt, H, S_max, d_p = k_cache.shape
+    d_h = int(q.shape[-1])
+    if d_p != photon_kv_row_elems(d_h) or tuple(v_cache.shape) != tuple(k_cache.shape):
+        raise PhotonError(-1, f"cache rows hold {d_p} elements, head size {d_h} needs {photon_kv_row_elems(d_h)}")
+    if scale is None:
+        scale = 1.0 / math.sqrt(d_h)
+    _check(lib.photon_coarse_decode_attn_static(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_len), _ptr(out), Bt, H, d_h,
+                                                S_max, scale, n_splits, _dt(k_cache), _stream()))
     return out
 
 

@@ -12,6 +12,8 @@
 //    keeps a whole (chunk, head) K/V tile in registers; nothing is re-read.
 #include "photon_attn.h"
 
+#include <mutex>
+
 #include "photon_device.h"
 #include "photon_host.h"
 
@@ -620,6 +622,65 @@ extern "C" int32_t photon_coarse_decode_attn(const void* q, const void* k_cache,
   }
   return launch_coarse_attn(dt == PHOTON_F32 ? KV_F32 : dt == PHOTON_BF16 ? KV_BF16 : KV_FP8, dt != PHOTON_BF16, d_h, q, k_cache, v_cache, seq_len, out,
                             Bt, H, S_max, scale, n_splits, workspace, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------ entry point that allocates nothing
+// The split partials of the coarse attention live in a file-scope device array instead of a caller workspace.
+// Every GPU holds its own copy of the array at its own address: the address is looked up once per device, with
+// that device current, and only that pointer (never the array's name, which on the host is a stand-in and no
+// device address) goes to kernels.
+namespace photon {
+constexpr size_t COARSE_STATIC_BYTES = (size_t)4 << 20;
+constexpr int COARSE_STATIC_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[COARSE_STATIC_BYTES];
+static void* g_scratch_ptr[COARSE_STATIC_MAX_DEVICES] = {nullptr};
+static std::mutex g_scratch_mu;
+
+// Device address of this GPU's copy of `scratch` (nullptr + error text on failure).
+static void* static_scratch_for_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= COARSE_STATIC_MAX_DEVICES) {
+    (void)hipGetLastError();
+    fail(PHOTON_ERR_HIP, "static scratch: cannot identify the current device (%d)", dev);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      fail(PHOTON_ERR_HIP, "static scratch: hipGetSymbolAddress failed on device %d: %s", dev, hipGetErrorString(e));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace photon
+
+extern "C" size_t photon_coarse_decode_attn_static_capacity(void) { return photon::COARSE_STATIC_BYTES; }
+
+extern "C" int32_t photon_coarse_decode_attn_static(const void* q, const void* k_cache, const void* v_cache,
+                                                    const int32_t* seq_len, void* out, int32_t Bt, int32_t H, int32_t d_h,
+                                                    int64_t S_max, float scale, int32_t n_splits, photon_dtype dt, void* stream) {
+  clear_error();
+  PHOTON_REQUIRE(Bt > 0 && H > 0 && S_max > 0, PHOTON_ERR_INVALID_ARG, "%s: Bt=%d H=%d S_max=%lld must be positive", __func__, Bt, H,
+                 (long long)S_max);
+  PHOTON_REQUIRE(d_h >= 1 && d_h <= 128, PHOTON_ERR_UNSUPPORTED, "%s: d_h=%d not in [1, 128]", __func__, d_h);
+  PHOTON_REQUIRE(n_splits >= 0 && n_splits <= 1024, PHOTON_ERR_INVALID_ARG, "%s: n_splits=%d out of [0, 1024]", __func__, n_splits);
+  if (n_splits == 0) n_splits = coarse_auto_splits(Bt, H, S_max);
+  const size_t need = photon_coarse_decode_attn_workspace_bytes(Bt, H, d_h, n_splits);
+  PHOTON_REQUIRE(need <= COARSE_STATIC_BYTES, PHOTON_ERR_WORKSPACE,
+                 "%s: Bt=%d H=%d d_h=%d n_splits=%d needs %zu bytes of split partials, the built-in scratch holds %zu; "
+                 "use photon_coarse_decode_attn with a workspace", __func__, Bt, H, d_h, n_splits, need, COARSE_STATIC_BYTES);
+  void* ws = nullptr;
+  if (n_splits > 1) {
+    ws = static_scratch_for_current_device();
+    if (ws == nullptr) return PHOTON_ERR_HIP;
+  }
+  // every partial the merge reads is written by this call's attention kernel first: nothing has to start at zero
+  return photon_coarse_decode_attn(q, k_cache, v_cache, seq_len, out, Bt, H, d_h, S_max, scale, n_splits, ws, need, dt, stream);
 }
 
 extern "C" int32_t photon_chunk_local_attn(const void* q, const void* k, const void* v, void* out, int64_t n_chunks,

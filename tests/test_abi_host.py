@@ -48,6 +48,11 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.photon_coarse_decode_attn(p, p, p, p, p, 1, 2, 64, 4096, 0.1, 4, None, 0, 0, None) == -3
     assert lib.photon_coarse_decode_attn(p, p, p, p, p, 0, 2, 64, 16, 0.1, 1, None, 0, 0, None) == -1
     assert lib.photon_coarse_decode_attn(p, p, p, p, p, 1, 2, 64, 16, 0.1, 1, None, 0, 7, None) == -2
+    # the entry point that allocates nothing: what does not fit its built-in scratch is rejected before any device call
+    assert lib.photon_coarse_decode_attn_static_capacity() == 4 << 20
+    assert lib.photon_coarse_decode_attn_static(p, p, p, p, p, 64, 64, 128, 1024, 0.1, 2, 1, None) == -3
+    assert b"built-in scratch" in lib.photon_last_error()
+    assert lib.photon_coarse_decode_attn_static(p, p, p, p, p, 0, 2, 64, 16, 0.1, 1, 1, None) == -1
     # window and query range
     assert lib.photon_chunk_local_attn(p, p, p, p, 4, 17, 1, 0, 2, 64, 0.1, 1, None) == -2
     assert lib.photon_chunk_local_attn(p, p, p, p, 4, 4, 2, 3, 2, 64, 0.1, 1, None) == -1
