@@ -1,7 +1,7 @@
 """Per-kernel throughput of the hot path's entry points at the shapes of the
 benchmark configurations, each against the roofline that bounds it.
 
-    python -m paper_2512_20687_amd.kernel_bench [--only probe,a1,a2,a3,encoder,prefill,schedules,linear]
+    python -m paper_2512_20687_amd.kernel_bench [--only copy,module,probe,a1,a2,a3,encoder,prefill,schedules,linear]
 
 Prints one JSON object per line: a streaming-read ceiling (a trivial read-only
 kernel over 2 GiB), the chunker GEMM (bf16 MFMA peak), the coarse decode
@@ -273,6 +273,69 @@ def bench_schedules():
     torch.cuda.empty_cache()
 
 
+def bench_copy():
+    """One plain device-to-device copy of exactly 1 GiB (the runtime's own kernel): known traffic, 1 048 576 KiB read and
+    as much written, against which the readings of the FETCH_SIZE / WRITE_SIZE counters are scaled."""
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    us = _time_us(lambda i: dst.copy_(src), 1, warm=0)
+    _emit("device-to-device copy (runtime)", "1 GiB read + 1 GiB written, one launch", us, bytes_=2 * src.numel())
+    del src, dst
+
+
+def bench_module():
+    """All blocks of a local decoder on the rows of one decode sub-step (Eq. 6-7) at the configuration-3 widths: as ONE
+    persistent launch (phases meeting at grid barriers) and as the separate launches it replaces; bytes = the
+    module's matrices, streamed once."""
+    import os
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import seeded_inputs as si
+    from dataclasses import replace
+    wl = si.WORKLOADS["cfg3_bf16_128k"]
+    for Bt, what in ((4, "top level: 4 rows"), (16, "16 rows")):
+        # a one-level model whose only decoder is the module under test: one step = C_1 module passes + small glue
+        cfg = replace(wl.cfg, L=1, C=(4,), R=(1,), vocab=64)
+        w = si.make_weights(cfg, 0, encoders=False, device="cuda")
+        model = ph.PhotonModel(cfg, w)
+        del w
+        state = ph.PhotonState(model, Bt, 64)
+        out = torch.zeros((Bt, cfg.meta_context), dtype=torch.int32, device="cuda")
+        module_bytes = cfg.n_layers * (4 * cfg.D * cfg.D + 3 * cfg.D * cfg.d_ff) * 2
+        for persistent in (True, False):
+            ph.photon_set_persistent(persistent)
+            state.seq_len.zero_()
+            ph.photon_profile_reset()
+            ph.photon_decode_step(model, state, out)
+            torch.cuda.synchronize()
+            ph.photon_profile_enable(True)
+            n_steps = 6
+            for _ in range(n_steps):
+                state.seq_len.zero_()
+                ph.photon_decode_step(model, state, out)
+            torch.cuda.synchronize()
+            ph.photon_profile_enable(False)
+            prof = ph.photon_profile_get()
+            ph.photon_profile_reset()
+            passes = n_steps * cfg.C[0]
+            if persistent:
+                n, ms = prof["persistent_module_kernel"]
+                assert n == passes, (n, passes)
+                _emit("persistent_module_kernel", f"cfg3 widths, 8 blocks, {what}: one launch per pass", ms * 1e3 / n, bytes_=module_bytes)
+            else:
+                lin = prof["linear_bf16_kernels"]
+                att = prof["local_attn_kernel"]
+                # the step's other linear launches (converter, LM head, chunker, top STEP) are taken out by their count:
+                # a pass is 4 linear launches + 1 attention launch per block
+                per_pass_launches = 5 * cfg.n_layers
+                lin_ms_module = lin[1] * (4 * cfg.n_layers * passes) / lin[0]
+                us = (lin_ms_module + att[1]) * 1e3 / passes
+                _emit("separate launches (kernels only, no gaps)", f"cfg3 widths, 8 blocks, {what}: {per_pass_launches} launches per pass", us,
+                      bytes_=module_bytes)
+        ph.photon_set_persistent(True)
+        del model, state
+        torch.cuda.empty_cache()
+
+
 def bench_linear():
     """Few-row linear maps of one configuration-3 block at the row counts of the decode sub-steps."""
     shapes = ((6144, 2048, 0, True, "QKV + norm"), (2048, 2048, 1, False, "O + residual"), (5120, 2048, 2, True, "gate/up + norm + SwiGLU"),
@@ -295,7 +358,7 @@ def bench_linear():
             del ws
 
 
-ALL = {"probe": bench_probe, "a1": bench_a1, "a2": bench_a2, "a3": bench_a3, "encoder": bench_encoder_attn, "prefill": bench_prefill, "schedules": bench_schedules, "linear": bench_linear}
+ALL = {"copy": bench_copy, "module": bench_module, "probe": bench_probe, "a1": bench_a1, "a2": bench_a2, "a3": bench_a3, "encoder": bench_encoder_attn, "prefill": bench_prefill, "schedules": bench_schedules, "linear": bench_linear}
 
 
 def main(argv=None):
