@@ -52,7 +52,7 @@ def weights_to_f64(w):
 
 # --------------------------------------------------------------------------
 # 8-bit storage of the coarse K/V cache (a variant beyond the paper, which
-# states no storage precision).  reading G17: the OCP 8-bit floating-point
+# states no storage precision).  reading G19: the OCP 8-bit floating-point
 # format E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no
 # infinities, the all-ones pattern is NaN, largest finite value 448), round to
 # nearest even from the value being stored, saturating, no scale factor.
@@ -94,7 +94,7 @@ def e4m3_round(x):
 
 def kv_store(cfg, x):
     """What the coarse K/V cache holds for the value x: x itself, or its E4M3
-    rounding when the configuration stores the cache in 8 bits (reading G17)."""
+    rounding when the configuration stores the cache in 8 bits (reading G19)."""
     return e4m3_round(x) if getattr(cfg, "kv_dtype", "") == "fp8" else f64(x)
 
 

@@ -58,7 +58,7 @@ def test_coarse_parity(dtype, Bt, H, d_h, S_max, seq, n_splits):
                                                (3, 2, 32, 90, [90, 0, 17])])
 @pytest.mark.parametrize("n_splits", [1, 3, 0])
 def test_coarse_parity_8bit_cache(Bt, H, d_h, S_max, seq, n_splits):
-    """K/V held as E4M3 bit patterns (reading G17), queries and outputs fp32: the kernel must decode every one of the
+    """K/V held as E4M3 bit patterns (reading G19), queries and outputs fp32: the kernel must decode every one of the
     bytes the way the format defines; the oracle attends over the decoded values."""
     require_gpu()
     import paper_2512_20687_amd as ph

@@ -266,7 +266,7 @@ def _adjacent_codes(got_codes, want_values):
 
 @pytest.mark.parametrize("kw,Bt", [(dict(), 3), (dict(D=832, H=16, d_h=52, d_ff=1024, R=(2, 2), n_layers=1), 2)])
 def test_bf16_step_with_8bit_cache(kw, Bt):
-    """Coarse K/V held in 8 bits (reading G17): the step reads E4M3 entries and appends the E4M3 rounding of the new
+    """Coarse K/V held in 8 bits (reading G19): the step reads E4M3 entries and appends the E4M3 rounding of the new
     ones; everything else is as in the bf16 configurations."""
     require_gpu()
     import paper_2512_20687_amd as ph

@@ -482,7 +482,7 @@ def test_kv_byte_model():
     assert list(st["seq_len"]) == [6, 6]
 
 
-# ---------------------------------------------------------------- 8-bit cache storage (reading G17)
+# ---------------------------------------------------------------- 8-bit cache storage (reading G19)
 
 def _e4m3_table():
     """All 256 bit patterns decoded field by field (sign, 4-bit exponent with bias 7, 3-bit mantissa), in plain Python."""
