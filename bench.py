@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--workload", default="cfg3_bf16_128k")
     ap.add_argument("--no-graph", action="store_true", help="enqueue every step instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (CPU baseline) leg")
+    ap.add_argument("--no-pipeline", action="store_true",
+                    help="join the lower levels at the end of every step instead of letting them run beside the next step's top level")
+    ap.add_argument("--steps-per-graph", type=int, default=8, help="decode steps captured in one HIP graph (pipelined mode)")
     ap.add_argument("--no-persistent", action="store_true",
                     help="run every module pass as separate launches instead of one persistent launch (comparison)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -127,7 +130,7 @@ def main():
     dev = "cuda"
     esz = 2 if cfg.dtype == "bf16" else 4
     Bt, S0 = wl.Bt, wl.S0
-    total_steps = args.warmup + args.steps + 4
+    total_steps = args.warmup + args.steps + 4 + 3 * max(1, args.steps_per_graph)
     S_max = (S0 + total_steps + 8 + 127) // 128 * 128      # cache capacity: a multiple of 128 entries (16 KB pitch at d_h=64 bf16)
 
     t_setup = time.perf_counter()
@@ -135,14 +138,21 @@ def main():
     model = ph.PhotonModel(cfg, weights)
     del weights
     st0 = si.make_decode_state(cfg, Bt, S0, S_max, seed=0, device=dev)
-    state = ph.PhotonState(model, Bt, S_max, **{k: st0[k] for k in ("k", "v", "seq_len", "x_top", "carry")})
+    pipelined = not args.no_pipeline and cfg.L >= 2
+    state = ph.PhotonState(model, Bt, S_max, pipeline=pipelined, **{k: st0[k] for k in ("k", "v", "seq_len", "x_top", "carry")})
     del st0
-    out_tokens = torch.zeros((Bt, cfg.meta_context), dtype=torch.int32, device=dev)
+    # steps per captured graph: a divisor of --steps, so that exactly --steps steps are timed
+    spg = math.gcd(args.steps, max(1, args.steps_per_graph)) if pipelined else 1
+    out_tokens = torch.zeros((spg, Bt, cfg.meta_context), dtype=torch.int32, device=dev)
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
 
     def step():
-        ph.photon_decode_step(model, state, out_tokens)
+        """spg decode steps; pipelined: every step's lower levels (the token decode) run on beside the next step's
+        top level, and are joined after the last one, inside the timed region."""
+        for i in range(spg):
+            ph.photon_decode_step(model, state, out_tokens[i])
+        ph.photon_decode_join(state)
 
     if args.calib_copy:                                   # 1 GiB read + 1 GiB written by a plain copy kernel
         a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
@@ -155,9 +165,9 @@ def main():
     mode = "eager"
     if not args.no_graph:
         try:
-            step()                                        # one eager step first (lazy module load, etc.)
+            step()                                        # one eager block first (lazy module load, etc.)
             torch.cuda.synchronize()
-            state.seq_len.sub_(1)
+            state.seq_len.sub_(spg)
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph):
                 step()
@@ -170,13 +180,13 @@ def main():
             state.seq_len.fill_(S0)
 
     run = (lambda: graph.replay()) if graph is not None else step
-    for _ in range(args.warmup):
+    for _ in range((args.warmup + spg - 1) // spg):
         run()
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record()
-    for _ in range(args.steps):
+    for _ in range(args.steps // spg):
         run()
     ev1.record()
     torch.cuda.synchronize()
@@ -191,7 +201,7 @@ def main():
     ph.photon_profile_reset()
     ph.photon_profile_enable(True)
     for _ in range(prof_steps):
-        step()
+        ph.photon_decode_step(model, state, out_tokens[0])
     torch.cuda.synchronize()
     ph.photon_profile_enable(False)
     prof = ph.photon_profile_get()
@@ -255,7 +265,9 @@ def main():
                    "head_dim": cfg.d_h, "layers_per_module": cfg.n_layers, "d_ff": cfg.d_ff, "vocab": cfg.vocab,
                    "batch": Bt, "context_tokens": wl.T, "coarse_kv_len_start": S0, "coarse_kv_len_end": S_end,
                    "tokens_per_step": tokens_per_step, "mode": mode,
-                   "schedule": "separate_launches" if args.no_persistent else "persistent_module_passes"},
+                   "steps_per_graph": spg,
+                   "schedule": ("lower levels pipelined across steps on a second stream" if pipelined else
+                                "separate_launches" if args.no_persistent else "persistent module passes at the top level")},
         "kv_read_gbs": kv_gbs, "kv_read_frac_of_hbm_peak": kv_gbs / HBM_PEAK_GBS,
         "kv_read_isolated": {"gbs": kv_iso_gbs, "frac_of_hbm_peak": kv_iso_gbs / HBM_PEAK_GBS, "us_per_launch": iso_us,
                              "bytes_per_launch": iso_bytes, "n_splits": ns, "launches": iso[0]},

@@ -280,10 +280,20 @@ typedef struct photon_state {
   size_t workspace_bytes;
   int32_t* status;      /* NULL, or a device word the step ORs photon_step_status bits into (never cleared by the library) */
   void* side_stream;    /* NULL, or a hipStream_t other than the call's stream, owned by the caller and used by one state
-                           at a time: with both events given, the top-level update (ii)-(iii) of an L >= 2 model runs on
-                           it beside the lower levels and is joined back before the call's work ends */
+                           at a time: with fork_event and join_event given, the levels below the top of an L >= 2 model
+                           run on it beside the top-level update (ii)-(iii) and are joined back before the call's work
+                           ends (unless pipeline is set) */
   void* fork_event;     /* hipEvent_t (timing may be disabled), recorded and waited on by the step; NULL: no side stream */
   void* join_event;     /* hipEvent_t, likewise */
+  void* free_event;     /* hipEvent_t, needed only for pipelined steps */
+  int32_t pipeline;     /* 0: every call joins the side stream before its work ends.  1 (needs side_stream and the three
+                           events; recursive generation only): the levels below the top, which turn the top-level
+                           decoder's output into this step's tokens and feed nothing back into the recurrence
+                           X^(L)_g -> X^(L)_{g+1}, are left running on the side stream when the call returns, so that
+                           they also run beside the NEXT step's top level.  out_tokens (and the trace buffers of the
+                           lower levels) of such a step are complete only after photon_decode_join(); successive
+                           pipelined steps must be given distinct out_tokens buffers if all are to be read */
+  int32_t lower_levels_pending;   /* maintained by the library: non-zero between a pipelined step and the join.  Set to 0 once */
 } photon_state;
 
 /* Bits of photon_state.status. */
@@ -309,9 +319,15 @@ PHOTON_API size_t photon_decode_step_workspace_bytes(const photon_config* cfg, i
  * both happen inside the call, on st->side_stream when the caller lends one);
  * tokens stay on the device.  The library creates no stream or event, so any
  * call may be made under stream capture. */
-PHOTON_API int32_t photon_decode_step(const photon_config* cfg, const photon_weights* w, const photon_state* st,
+PHOTON_API int32_t photon_decode_step(const photon_config* cfg, const photon_weights* w, photon_state* st,
                                       int32_t Bt, const int32_t* forced_tokens, int32_t* out_tokens,
                                       const photon_trace* trace, void* stream);
+
+/* Makes `stream` wait for the lower levels that pipelined steps (photon_state.pipeline) left running on the side
+ * stream; afterwards, in stream order, every out_tokens buffer of those steps is complete.  A no-op when nothing is
+ * outstanding.  Must be called (under stream capture: inside the same capture) before the state is used by anything
+ * but further pipelined steps. */
+PHOTON_API int32_t photon_decode_join(photon_state* st, void* stream);
 
 /* Schedule of a local decoder's module pass (all blocks of G^(l) on the rows of one decode sub-step, Eq. 6-7) when
  * it holds at most 16 rows of a bf16 configuration: on != 0 (the default) runs it as ONE persistent launch, one
@@ -387,7 +403,7 @@ PHOTON_API int32_t photon_prefill(const photon_config* cfg, const photon_weights
  * Runs on `stream` only.
  * -------------------------------------------------------------------------- */
 PHOTON_API int32_t photon_hiergen_step(const photon_config* cfg, const photon_weights* w, const photon_encoder_weights* ew,
-                                       const photon_state* st, const photon_hier_state* hst, int32_t Bt,
+                                       photon_state* st, const photon_hier_state* hst, int32_t Bt,
                                        const int32_t* forced_tokens, int32_t* out_tokens, const photon_trace* trace,
                                        void* stream);
 

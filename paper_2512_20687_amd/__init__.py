@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     photon_coarse_decode_attn_static,
     photon_coarse_decode_attn_static_capacity,
     photon_coarse_decode_attn_workspace_bytes,
+    photon_decode_join,
     photon_decode_step,
     photon_encoder_attn,
     photon_encoder_attn_workspace_bytes,

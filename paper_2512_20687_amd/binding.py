@@ -315,7 +315,8 @@ class _EncoderWeights(C.Structure):
 class _State(C.Structure):
     _fields_ = [("k_cache", C.c_void_p), ("v_cache", C.c_void_p), ("seq_len", C.c_void_p), ("x_top", C.c_void_p),
                 ("carry", C.c_void_p), ("S_max", C.c_int64), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
-                ("status", C.c_void_p), ("side_stream", C.c_void_p), ("fork_event", C.c_void_p), ("join_event", C.c_void_p)]
+                ("status", C.c_void_p), ("side_stream", C.c_void_p), ("fork_event", C.c_void_p), ("join_event", C.c_void_p),
+                ("free_event", C.c_void_p), ("pipeline", C.c_int32), ("lower_levels_pending", C.c_int32)]
 
 
 class _HierState(C.Structure):
@@ -436,9 +437,10 @@ class PhotonState:
     state, carries, and the step's workspace."""
 
     def __init__(self, model: PhotonModel, Bt: int, S_max: int, k=None, v=None, seq_len=None, x_top=None, carry=None,
-                 side_stream: bool = True):
-        """side_stream: lend the step a second stream and two events (torch's) so that the top-level update of an
-        L >= 2 model runs beside the lower levels; False keeps the whole step on the caller's stream."""
+                 side_stream: bool = True, pipeline: bool = False):
+        """side_stream: lend the step a second stream and three events (torch's) so that the levels below the top of an
+        L >= 2 model run beside the top-level update; False keeps the whole step on the caller's stream.
+        pipeline: leave those levels running when a step returns (photon_decode_join completes them)."""
         cfg, dev = model.cfg, model.device
         lib = load_library()
         _register_step(lib)
@@ -478,12 +480,13 @@ class PhotonState:
         self.side_stream = self.fork_event = self.join_event = None
         if side_stream and cfg.L >= 2:
             self.side_stream = torch.cuda.Stream(device=dev)
-            self.fork_event, self.join_event = torch.cuda.Event(), torch.cuda.Event()
-            for ev in (self.fork_event, self.join_event):      # torch creates the HIP event on first use
+            self.fork_event, self.join_event, self.free_event = torch.cuda.Event(), torch.cuda.Event(), torch.cuda.Event()
+            for ev in (self.fork_event, self.join_event, self.free_event):      # torch creates the HIP event on first use
                 ev.record(self.side_stream)
             self.side_stream.synchronize()
             s.side_stream = self.side_stream.cuda_stream
-            s.fork_event, s.join_event = self.fork_event.cuda_event, self.join_event.cuda_event
+            s.fork_event, s.join_event, s.free_event = self.fork_event.cuda_event, self.join_event.cuda_event, self.free_event.cuda_event
+            s.pipeline = 1 if pipeline else 0
         self.c_state = s
 
 
@@ -581,6 +584,14 @@ def photon_hiergen_step(model: PhotonModel, state: PhotonState, hier: PhotonHier
                                    C.byref(state.c_state), C.byref(hier.c_state), state.Bt, _ptr(forced_tokens), _ptr(out_tokens),
                                    C.byref(tr) if tr is not None else None, _stream()))
     return out_tokens
+
+
+def photon_decode_join(state: PhotonState) -> None:
+    """Join the lower levels that pipelined steps left running on the state's side stream into the current stream."""
+    lib = load_library()
+    lib.photon_decode_join.restype = C.c_int32
+    lib.photon_decode_join.argtypes = [C.POINTER(_State), C.c_void_p]
+    _check(lib.photon_decode_join(C.byref(state.c_state), _stream()))
 
 
 def photon_decode_step(model: PhotonModel, state: PhotonState, out_tokens: torch.Tensor,

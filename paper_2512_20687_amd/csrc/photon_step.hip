@@ -214,7 +214,9 @@ struct Plan {
   int n_splits = 1;
   size_t coarse_ws = 0, coarse_ws_bytes = 0;
   size_t h = 0, attn = 0, qkv = 0, qrot = 0, act = 0, cond = 0, logits = 0, a_hat = 0;
-  size_t h2 = 0, attn2 = 0, qkv2 = 0, qrot2 = 0, act2 = 0;   // second set (Bt rows) for the STEP branch that runs beside the lower levels
+  size_t h2 = 0, attn2 = 0, qkv2 = 0, qrot2 = 0, act2 = 0;   // second set for the main line of a hierarchy (top-level decoder, then STEP)
+  int64_t rows2 = 0;                             // its rows: Bt chunks x R_L converter rows
+  size_t cond_top = 0;                           // conditioning latents of the level-(L-1) chunks (written on the main line)
   size_t many = 0, many2 = 0;                    // scratch of the many-row linear path (0 rows: absent), main and STEP branch
   size_t hx[PHOTON_MAX_LEVELS] = {0}, hA = 0;    // hierarchical generation: encoder-side new units of level l, chunker outputs
   int many_K = 0;                                // widest contraction it is sized for
@@ -255,16 +257,18 @@ static Plan make_plan(const photon_config& c, int Bt, int64_t S_max) {
   p.logits = bump(cur, (size_t)p.chunks[1] * c.vocab * f);
   p.a_hat = bump(cur, (size_t)Bt * D * f);
   p.hA = bump(cur, (size_t)p.chunks[1] * D * f);
-  p.h2 = bump(cur, (size_t)Bt * D * f);
-  p.attn2 = bump(cur, (size_t)Bt * D * f);
-  p.qkv2 = bump(cur, (size_t)Bt * 3 * D * f);
-  p.qrot2 = bump(cur, (size_t)Bt * D * f);
-  p.act2 = bump(cur, (size_t)Bt * F * f);
+  p.rows2 = (int64_t)Bt * c.R[c.L - 1];
+  p.h2 = bump(cur, (size_t)p.rows2 * D * f);
+  p.attn2 = bump(cur, (size_t)p.rows2 * D * f);
+  p.qkv2 = bump(cur, (size_t)p.rows2 * 3 * D * f);
+  p.qrot2 = bump(cur, (size_t)p.rows2 * D * f);
+  p.act2 = bump(cur, (size_t)p.rows2 * F * f);
+  p.cond_top = bump(cur, (size_t)(c.L >= 2 ? p.chunks[c.L - 1] : 1) * D * f);
   if (c.dt == PHOTON_BF16) {
     p.many_K = (int)(D > F ? D : F);
     if ((int64_t)c.C[c.L - 1] * D > p.many_K) p.many_K = (int)(c.C[c.L - 1] * D);   // the top chunker contracts over C_L * D
     if (p.rows_max >= LINEAR_MID_ROWS) p.many = bump(cur, linear_many_workspace_bytes(p.rows_max, p.many_K, (int)(2 * F)));
-    if (Bt >= LINEAR_MID_ROWS) p.many2 = bump(cur, linear_many_workspace_bytes(Bt, p.many_K, (int)(2 * F)));
+    if (p.rows2 >= LINEAR_MID_ROWS) p.many2 = bump(cur, linear_many_workspace_bytes(p.rows2, p.many_K, (int)(2 * F)));
   }
   for (int l = 1; l <= c.L; ++l) {
     p.fresh[l - 1] = bump(cur, (size_t)p.chunks[l] * c.C[l - 1] * D * f);
@@ -533,11 +537,96 @@ static int32_t chunk_and_step(const Ctx& x, const float* bottleneck, const photo
 // The top-level update depends only on the level-L decoder's output, not on the lower levels that turn it into
 // tokens, so for L >= 2 it can run on a second stream beside them (fork after level L, join at the end of the
 // step).  That stream and the two events belong to the caller (photon_state): the library creates nothing.
-static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* out_tokens, const photon_trace* tr) {
+// All sub-steps of the level-l local decoder on this context's stream and buffers: n chunks, each conditioned on a row
+// of cond_in; the new level-(l-1) units go to `units` ([n * C_l, D], item j of chunk ch at row ch * C_l + j); at level 1
+// the logits, the token choice and the decoder-side embedding fed back.  after_converter: recorded on the stream once
+// the converter, the only reader of cond_in, is enqueued (nullptr: nothing to record).
+static int32_t decode_level(const Ctx& x, int l, const float* cond_in, float* units, const int32_t* forced, int32_t* out_tokens,
+                            const photon_trace* tr, bool alone, hipEvent_t after_converter) {
   const photon_config& c = *x.c;
-  const int D = c.D, L = c.L, Bt = x.Bt;
+  const int D = c.D, L = c.L;
+  const int C = c.C[l - 1], R = c.R[l - 1];
+  const int64_t n = x.p.chunks[l];
+  const photon_module_weights& mod = x.w->dec[l - 1];
   float* h = x.f(x.o_h);
-  float* cond = x.f(x.p.cond);
+  // sub-step 0: the converter's R vectors at window positions 0..R-1 (row ch*R + r of a flat [n*R, D] view of h)
+  PHOTON_TRY(linear(x, cond_in, D, x.w->conv_w[l - 1], nullptr, x.w->conv_b[l - 1], nullptr, 0, h, (int64_t)R * D, (int)n, R * D, D,
+                    EPI_PLAIN));
+  if (after_converter != nullptr && hipEventRecord(after_converter, x.st) != hipSuccess)
+    return fail(PHOTON_ERR_HIP, "decode step: cannot record the event that frees the conditioning buffer");
+  RowsIn in;
+  in.ptr = h; in.ld = D;
+  for (int j = 0; j < C; ++j) {
+    const int q_len = (j == 0) ? R : 1;
+    const int q_pos = (j == 0) ? 0 : R + j - 1;
+    PHOTON_TRY(local_module_pass(x, l, n, q_len, q_pos, in, alone));
+    // item j = final norm of the last row of each chunk.  At the token level of a hierarchy the item only feeds the
+    // vocabulary projection, which then applies the norm itself (one launch less per sub-step) unless the caller
+    // asked to see the items.
+    const bool norm_in_head = (l == 1 && L >= 2 && !(tr && tr->new_units[0]));
+    if (!norm_in_head) PHOTON_TRY(norm(x, h, q_len, q_len - 1, mod.g_final, units, C, j, (int)n));
+    if (l >= 2) {                                          // Eq. 6: the module's own output is the next input
+      in.ptr = units + (int64_t)j * D; in.ld = (int64_t)C * D;
+    } else {
+      float* lg = (tr && tr->logits) ? tr->logits + (int64_t)j * c.vocab : x.f(x.p.logits);
+      const int64_t ld = (tr && tr->logits) ? (int64_t)C * c.vocab : c.vocab;
+      // logits of item j of every chunk: rows of `units` with pitch C*D
+      if (norm_in_head)
+        PHOTON_TRY(linear(x, h + (int64_t)(q_len - 1) * D, (int64_t)q_len * D, x.w->W_lm, mod.g_final, nullptr, nullptr, 0, lg, ld, (int)n,
+                          c.vocab, D, EPI_PLAIN));
+      else
+        PHOTON_TRY(linear(x, units + (int64_t)j * D, (int64_t)C * D, x.w->W_lm, nullptr, nullptr, nullptr, 0, lg, ld, (int)n, c.vocab, D,
+                          EPI_PLAIN));
+      float* x_next = (j + 1 < C) ? h : nullptr;           // decoder-side embedding of the chosen token
+      if (x.bf16)
+        PHOTON_LAUNCH(KC_CHOOSE_TOKEN, x.st, choose_token_kernel<bf16_t>, dim3((unsigned)n), dim3(CHOOSE_THREADS), 0, x.st, lg, ld, c.vocab,
+                      forced, out_tokens, C, j, (const bf16_t*)x.w->E_dec, x_next, D);
+      else
+        PHOTON_LAUNCH(KC_CHOOSE_TOKEN, x.st, choose_token_kernel<float>, dim3((unsigned)n), dim3(CHOOSE_THREADS), 0, x.st, lg, ld, c.vocab,
+                      forced, out_tokens, C, j, (const float*)x.w->E_dec, x_next, D);
+      PHOTON_TRY(check_launch("choose_token_kernel"));
+      in.ptr = h; in.ld = D;
+    }
+  }
+  return PHOTON_OK;
+}
+
+// Conditioning of the level-(l-1) chunks from the new level-(l-1) units of this step and the carry, which is updated.
+static int32_t condition_lower(const Ctx& x, int l, const float* units, float* cond) {
+  const photon_config& c = *x.c;
+  const int64_t n = x.p.chunks[l];
+  const int C = c.C[l - 1], D = c.D, Bt = x.Bt;
+  const int64_t per_seq = n * C / Bt;
+  float* carry = x.s->carry + (int64_t)(l - 2) * Bt * D;
+  PHOTON_LAUNCH(KC_MISC, x.st, shift_condition_kernel, dim3(blocks_for(n * C * D)), dim3(256), 0, x.st, units, carry, cond, Bt, (int)per_seq, D);
+  PHOTON_TRY(check_launch("shift_condition_kernel"));
+  PHOTON_LAUNCH(KC_MISC, x.st, update_carry_kernel, dim3(blocks_for((int64_t)Bt * D)), dim3(256), 0, x.st, units, carry, Bt, (int)per_seq, D);
+  return check_launch("update_carry_kernel");
+}
+
+// The levels below the top, in order, on this context's stream: level L-1 hangs off cond_top, every further level off
+// the units of the level above it.
+static int32_t decode_lower_levels(const Ctx& x, const float* cond_top, float* const* fresh, const int32_t* forced, int32_t* out_tokens,
+                                   const photon_trace* tr, bool alone, hipEvent_t after_first_converter) {
+  const float* cond_in = cond_top;
+  for (int l = x.c->L - 1; l >= 1; --l) {
+    PHOTON_TRY(decode_level(x, l, cond_in, fresh[l - 1], forced, out_tokens, tr, alone, l == x.c->L - 1 ? after_first_converter : nullptr));
+    if (l >= 2) {
+      PHOTON_TRY(condition_lower(x, l, fresh[l - 1], x.f(x.p.cond)));
+      cond_in = x.f(x.p.cond);
+    }
+  }
+  return PHOTON_OK;
+}
+
+// One step.  The recurrence of recursive generation runs through the top level only: X^(L)_g -> top-level decoder ->
+// chunker -> STEP -> X^(L)_{g+1} (Section 2.3.3 (i)-(iii)); the lower levels, which turn the top-level decoder's
+// output into tokens, hang off it as a leaf (the next step reads only the carries, which the main line itself
+// updates).  With a side stream lent by the caller the lower levels run there, beside the chunker and STEP; in
+// pipelined mode they are not joined at the end of the call, so that they also run beside the next step's top level.
+static int32_t decode_step_impl(const Ctx& x, photon_state* st, const int32_t* forced, int32_t* out_tokens, const photon_trace* tr) {
+  const photon_config& c = *x.c;
+  const int L = c.L, Bt = x.Bt;
 
   PHOTON_LAUNCH(KC_MISC, x.st, step_begin_kernel, dim3(blocks_for(Bt)), dim3(256), 0, x.st, x.s->seq_len, Bt, x.s->S_max, x.s->status,
                 x.bar_words(), x.bar_word_count());
@@ -546,85 +635,59 @@ static int32_t decode_step_impl(const Ctx& x, const int32_t* forced, int32_t* ou
   float* fresh[PHOTON_MAX_LEVELS];
   for (int l = 0; l < L; ++l) fresh[l] = (tr && tr->new_units[l]) ? tr->new_units[l] : x.f(x.p.fresh[l]);
 
-  const float* cond_in = x.s->x_top;                       // level L: one chunk per sequence, conditioned on X^(L)_g
-  bool forked = false;
-  for (int l = L; l >= 1; --l) {
-    const int C = c.C[l - 1], R = c.R[l - 1];
-    const int64_t n = x.p.chunks[l];
-    const photon_module_weights& mod = x.w->dec[l - 1];
-    float* units = fresh[l - 1];                           // [n * C, D]: chunk-major, item j of chunk ch at row ch*C + j
-    // sub-step 0: the converter's R vectors at window positions 0..R-1 (row ch*R + r of a flat [n*R, D] view of p.h)
-    PHOTON_TRY(linear(x, cond_in, D, x.w->conv_w[l - 1], nullptr, x.w->conv_b[l - 1], nullptr, 0, h, (int64_t)R * D, (int)n, R * D,
-                      D, EPI_PLAIN));
-    RowsIn in;
-    in.ptr = h; in.ld = D;
-    for (int j = 0; j < C; ++j) {
-      const int q_len = (j == 0) ? R : 1;
-      const int q_pos = (j == 0) ? 0 : R + j - 1;
-      PHOTON_TRY(local_module_pass(x, l, n, q_len, q_pos, in, !forked));
-      // item j = final norm of the last row of each chunk.  At the token level of a hierarchy the item only feeds the
-      // vocabulary projection, which then applies the norm itself (one launch less per sub-step) unless the caller
-      // asked to see the items.
-      const bool norm_in_head = (l == 1 && L >= 2 && !(tr && tr->new_units[0]));
-      if (!norm_in_head) PHOTON_TRY(norm(x, h, q_len, q_len - 1, mod.g_final, units, C, j, (int)n));
-      if (l >= 2) {                                        // Eq. 6: the module's own output is the next input
-        in.ptr = units + (int64_t)j * D; in.ld = (int64_t)C * D;
-      } else {
-        float* lg = (tr && tr->logits) ? tr->logits + (int64_t)j * c.vocab : x.f(x.p.logits);
-        const int64_t ld = (tr && tr->logits) ? (int64_t)C * c.vocab : c.vocab;
-        // logits of item j of every chunk: rows of `units` with pitch C*D
-        if (norm_in_head)
-          PHOTON_TRY(linear(x, h + (int64_t)(q_len - 1) * D, (int64_t)q_len * D, x.w->W_lm, mod.g_final, nullptr, nullptr, 0, lg, ld, (int)n,
-                            c.vocab, D, EPI_PLAIN));
-        else
-          PHOTON_TRY(linear(x, units + (int64_t)j * D, (int64_t)C * D, x.w->W_lm, nullptr, nullptr, nullptr, 0, lg, ld, (int)n,
-                            c.vocab, D, EPI_PLAIN));
-        float* x_next = (j + 1 < C) ? h : nullptr;         // decoder-side embedding of the chosen token
-        if (x.bf16)
-          PHOTON_LAUNCH(KC_CHOOSE_TOKEN, x.st, choose_token_kernel<bf16_t>, dim3((unsigned)n), dim3(CHOOSE_THREADS), 0, x.st, lg, ld, c.vocab,
-                        forced, out_tokens, C, j, (const bf16_t*)x.w->E_dec, x_next, D);
-        else
-          PHOTON_LAUNCH(KC_CHOOSE_TOKEN, x.st, choose_token_kernel<float>, dim3((unsigned)n), dim3(CHOOSE_THREADS), 0, x.st, lg, ld, c.vocab,
-                        forced, out_tokens, C, j, (const float*)x.w->E_dec, x_next, D);
-        PHOTON_TRY(check_launch("choose_token_kernel"));
-        in.ptr = h; in.ld = D;
-      }
-    }
-    if (l == L && L >= 2 && x.overlap && x.hs == nullptr) {
-      hipStream_t side_st = (hipStream_t)x.s->side_stream;
-      if (hipEventRecord((hipEvent_t)x.s->fork_event, x.st) != hipSuccess || hipStreamWaitEvent(side_st, (hipEvent_t)x.s->fork_event, 0) != hipSuccess)
-        return fail(PHOTON_ERR_HIP, "decode step: cannot fork the STEP branch");
+  const bool pipelined = x.overlap && st->pipeline != 0;
+  // the main line of a hierarchy has its own activation buffers: the lower levels of this (or, pipelined, of the
+  // previous) step work on the first set meanwhile
+  Ctx top = x;
+  if (L >= 2) {
+    top.o_h = x.p.h2; top.o_attn = x.p.attn2; top.o_qkv = x.p.qkv2; top.o_qrot = x.p.qrot2; top.o_act = x.p.act2; top.o_many = x.p.many2;
+  }
+  // level L: one chunk per sequence, conditioned on X^(L)_g.  Persistent launches only when nothing runs beside them
+  // (a pipelined state keeps the separate launches also while a profiler holds the step on one stream, so that what
+  // is profiled is what is timed).
+  PHOTON_TRY(decode_level(top, L, x.s->x_top, fresh[L - 1], forced, out_tokens, tr, st->pipeline == 0, nullptr));
+
+  if (L >= 2) {
+    float* cond_top = x.f(x.p.cond_top);
+    hipStream_t side_st = (hipStream_t)st->side_stream;
+    if (pipelined && st->lower_levels_pending != 0 &&
+        hipStreamWaitEvent(x.st, (hipEvent_t)st->free_event, 0) != hipSuccess)      // the previous step's lower levels have read cond_top
+      return fail(PHOTON_ERR_HIP, "decode step: cannot wait for the conditioning buffer");
+    PHOTON_TRY(condition_lower(top, L, fresh[L - 1], cond_top));
+    if (x.overlap && x.hs == nullptr) {
+      if (hipEventRecord((hipEvent_t)st->fork_event, x.st) != hipSuccess || hipStreamWaitEvent(side_st, (hipEvent_t)st->fork_event, 0) != hipSuccess)
+        return fail(PHOTON_ERR_HIP, "decode step: cannot fork the lower levels");
       Ctx side = x;
       side.st = side_st;
-      side.o_h = x.p.h2; side.o_attn = x.p.attn2; side.o_qkv = x.p.qkv2; side.o_qrot = x.p.qrot2; side.o_act = x.p.act2; side.o_many = x.p.many2;
-      PHOTON_TRY(chunk_and_step(side, units, tr));
-      forked = true;
+      side.bar_next = nullptr;
+      PHOTON_TRY(decode_lower_levels(side, cond_top, fresh, forced, out_tokens, tr, false, pipelined ? (hipEvent_t)st->free_event : nullptr));
+      PHOTON_TRY(chunk_and_step(top, fresh[L - 1], tr));
+      if (pipelined) {
+        st->lower_levels_pending = 1;
+      } else if (hipEventRecord((hipEvent_t)st->join_event, side_st) != hipSuccess || hipStreamWaitEvent(x.st, (hipEvent_t)st->join_event, 0) != hipSuccess) {
+        return fail(PHOTON_ERR_HIP, "decode step: cannot join the lower levels");
+      }
+    } else {
+      // one stream: persistent launches where eligible, unless the state has a side stream and is merely held on one
+      // stream by the profiler (what is profiled is then what is timed)
+      const bool side_lent = st->side_stream != nullptr && st->fork_event != nullptr && st->join_event != nullptr;
+      PHOTON_TRY(decode_lower_levels(x, cond_top, fresh, forced, out_tokens, tr, !side_lent || x.hs != nullptr, nullptr));
+      if (x.hs != nullptr) {
+        const float* bott = nullptr;
+        PHOTON_TRY(hier_reencode(x, out_tokens, &bott));
+        PHOTON_TRY(chunk_and_step(top, bott, tr));
+      } else {
+        PHOTON_TRY(chunk_and_step(top, fresh[L - 1], tr));
+      }
     }
-    if (l >= 2) {
-      // chunks of level l-1: one per new level-(l-1) unit, hanging off the previous unit
-      const int64_t per_seq = n * C / Bt;
-      float* carry = x.s->carry + (int64_t)(l - 2) * Bt * D;
-      PHOTON_LAUNCH(KC_MISC, x.st, shift_condition_kernel, dim3(blocks_for(n * C * D)), dim3(256), 0, x.st, units, carry, cond, Bt,
-                    (int)per_seq, D);
-      PHOTON_TRY(check_launch("shift_condition_kernel"));
-      PHOTON_LAUNCH(KC_MISC, x.st, update_carry_kernel, dim3(blocks_for((int64_t)Bt * D)), dim3(256), 0, x.st, units, carry, Bt,
-                    (int)per_seq, D);
-      PHOTON_TRY(check_launch("update_carry_kernel"));
-      cond_in = cond;
-    }
-  }
-
-  if (x.hs != nullptr) {
+  } else if (x.hs != nullptr) {
     const float* bott = nullptr;
     PHOTON_TRY(hier_reencode(x, out_tokens, &bott));
     PHOTON_TRY(chunk_and_step(x, bott, tr));
-  } else if (!forked) PHOTON_TRY(chunk_and_step(x, fresh[L - 1], tr));
-  else {
-    if (hipEventRecord((hipEvent_t)x.s->join_event, (hipStream_t)x.s->side_stream) != hipSuccess ||
-        hipStreamWaitEvent(x.st, (hipEvent_t)x.s->join_event, 0) != hipSuccess)
-      return fail(PHOTON_ERR_HIP, "decode step: cannot join the STEP branch");
+  } else {
+    PHOTON_TRY(chunk_and_step(x, fresh[L - 1], tr));
   }
-  if (x.s->status != nullptr && *x.bar_next > 0) {
+  if (x.s->status != nullptr && x.bar_next != nullptr && *x.bar_next > 0) {
     PHOTON_LAUNCH(KC_MISC, x.st, step_end_kernel, dim3(1), dim3(64), 0, x.st,
                   (const unsigned*)(x.bar_words() + (size_t)x.p.bar_slots * PM_BAR_WORDS), x.s->status);
     PHOTON_TRY(check_launch("step_end_kernel"));
@@ -894,7 +957,7 @@ extern "C" int32_t photon_prefill(const photon_config* cfg, const photon_weights
 }
 
 static int32_t decode_entry(const char* fn, const photon_config* cfg, const photon_weights* w, const photon_encoder_weights* ew,
-                            const photon_state* st, const photon_hier_state* hst, int32_t Bt, const int32_t* forced_tokens,
+                            photon_state* st, const photon_hier_state* hst, int32_t Bt, const int32_t* forced_tokens,
                             int32_t* out_tokens, const photon_trace* trace, void* stream) {
   PHOTON_REQUIRE(cfg && w && st, PHOTON_ERR_INVALID_ARG, "%s: cfg, w and st must not be null", fn);
   PHOTON_TRY(validate_config(cfg, Bt, st->S_max));
@@ -929,6 +992,11 @@ static int32_t decode_entry(const char* fn, const photon_config* cfg, const phot
   x.overlap = !g_profile_on && st->side_stream != nullptr && st->fork_event != nullptr && st->join_event != nullptr;
   PHOTON_REQUIRE(st->side_stream == nullptr || st->side_stream != stream, PHOTON_ERR_INVALID_ARG,
                  "%s: state.side_stream must differ from the stream of the call", fn);
+  PHOTON_REQUIRE(st->pipeline == 0 || (hst == nullptr && st->side_stream != nullptr && st->fork_event != nullptr && st->join_event != nullptr &&
+                                       st->free_event != nullptr),
+                 PHOTON_ERR_INVALID_ARG, "%s: pipelined steps need side_stream, fork_event, join_event and free_event (recursive generation only)", fn);
+  PHOTON_REQUIRE(st->pipeline != 0 || st->lower_levels_pending == 0, PHOTON_ERR_INVALID_ARG,
+                 "%s: the lower levels of a pipelined step are still outstanding: call photon_decode_join first", fn);
   x.ew = ew; x.hs = hst;
   x.o_h = x.p.h; x.o_attn = x.p.attn; x.o_qkv = x.p.qkv; x.o_qrot = x.p.qrot; x.o_act = x.p.act; x.o_many = x.p.many;
   PHOTON_REQUIRE(st->workspace != nullptr && aligned16(st->workspace) && st->workspace_bytes >= x.p.total, PHOTON_ERR_WORKSPACE,
@@ -936,7 +1004,7 @@ static int32_t decode_entry(const char* fn, const photon_config* cfg, const phot
   x.base = reinterpret_cast<char*>(st->workspace);
   int bar_next = 0;
   x.bar_next = &bar_next;
-  return decode_step_impl(x, forced_tokens, out_tokens, trace);
+  return decode_step_impl(x, st, forced_tokens, out_tokens, trace);
 }
 
 extern "C" int32_t photon_set_persistent(int32_t on) {
@@ -951,7 +1019,19 @@ extern "C" int32_t photon_set_barrier_wait_limit(int64_t ticks) {
   return PHOTON_OK;
 }
 
-extern "C" int32_t photon_decode_step(const photon_config* cfg, const photon_weights* w, const photon_state* st, int32_t Bt,
+extern "C" int32_t photon_decode_join(photon_state* st, void* stream) {
+  clear_error();
+  PHOTON_REQUIRE(st != nullptr, PHOTON_ERR_INVALID_ARG, "%s: st is null", __func__);
+  if (st->lower_levels_pending == 0) return PHOTON_OK;
+  PHOTON_REQUIRE(st->side_stream != nullptr && st->join_event != nullptr, PHOTON_ERR_INVALID_ARG, "%s: the state has no side stream", __func__);
+  if (hipEventRecord((hipEvent_t)st->join_event, (hipStream_t)st->side_stream) != hipSuccess ||
+      hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)st->join_event, 0) != hipSuccess)
+    return fail(PHOTON_ERR_HIP, "%s: cannot join the lower levels", __func__);
+  st->lower_levels_pending = 0;
+  return PHOTON_OK;
+}
+
+extern "C" int32_t photon_decode_step(const photon_config* cfg, const photon_weights* w, photon_state* st, int32_t Bt,
                                       const int32_t* forced_tokens, int32_t* out_tokens, const photon_trace* trace,
                                       void* stream) {
   clear_error();
@@ -959,7 +1039,7 @@ extern "C" int32_t photon_decode_step(const photon_config* cfg, const photon_wei
 }
 
 extern "C" int32_t photon_hiergen_step(const photon_config* cfg, const photon_weights* w, const photon_encoder_weights* ew,
-                                       const photon_state* st, const photon_hier_state* hst, int32_t Bt,
+                                       photon_state* st, const photon_hier_state* hst, int32_t Bt,
                                        const int32_t* forced_tokens, int32_t* out_tokens, const photon_trace* trace,
                                        void* stream) {
   clear_error();

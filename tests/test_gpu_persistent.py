@@ -129,3 +129,83 @@ def test_full_cache_is_reported_not_overrun():
     # sequence 1's entries beyond its new one, and everything of sequence 2 below its new one, are untouched
     assert torch.equal(state.k[:, 1, :, 6:], guard_k[:, 1, :, 6:]) and torch.equal(state.k[:, 2, :, : S_max - 1], guard_k[:, 2, :, : S_max - 1])
     assert bool(torch.isfinite(state.x_top).all())
+
+
+@pytest.mark.parametrize("kw,Bt", [(dict(), 3), (dict(L=3, C=(2, 2, 4), R=(1, 2, 1), n_layers=1), 2), (dict(D=1024, H=16, d_ff=2560, n_layers=2), 16)])
+def test_pipelined_steps_equal_joined_steps(kw, Bt):
+    """The lower levels of a step feed nothing back into the recurrence through the top level (the next step reads only
+    the carries, which the main line updates): left running on the side stream beside the next step's top level they
+    must produce, after photon_decode_join, exactly the tokens, state and cache of steps that join one by one."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    base = dict(L=2, C=(4, 4), R=(1, 1), D=256, H=4, d_h=64, n_layers=2, d_ff=640, vocab=1024, dtype="bf16")
+    base.update(kw)
+    cfg = si.PhotonConfig(**base)
+    w = si.make_weights(cfg, 95, encoders=False)
+    S, S_max, n_steps = 20, 40, 5
+    st = si.make_decode_state(cfg, Bt, S, S_max, seed=96)
+    model = ph.PhotonModel(cfg, w)
+    forced = [dev(si.make_tokens(cfg.vocab, Bt, cfg.meta_context, 200 + i)) for i in range(n_steps)]
+    ph.photon_set_persistent(False)                 # same kernels in both runs: the comparison is bit for bit
+    try:
+        res = {}
+        for mode in ("joined", "pipelined", "graph"):
+            state = ph.PhotonState(model, Bt, S_max, k=st["k"], v=st["v"], seq_len=st["seq_len"], x_top=st["x_top"], carry=st["carry"],
+                                   pipeline=(mode != "joined"))
+            toks = torch.full((n_steps, Bt, cfg.meta_context), -1, dtype=torch.int32, device="cuda")
+            logits = torch.zeros((n_steps, Bt, cfg.meta_context, cfg.vocab), device="cuda")
+
+            def run():
+                for i in range(n_steps):
+                    ph.photon_decode_step(model, state, toks[i], forced_tokens=forced[i], trace={"logits": logits[i]})
+                ph.photon_decode_join(state)
+
+            if mode == "graph":                     # all steps and the join in one captured graph, replayed once
+                keep = {n: getattr(state, n).clone() for n in ("k", "v", "seq_len", "x_top", "carry")}
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    run()
+                for n, t in keep.items():
+                    getattr(state, n).copy_(t)
+                g.replay()
+            else:
+                run()
+            torch.cuda.synchronize()
+            assert int(state.status.item()) == 0 and int(state.c_state.lower_levels_pending) == 0
+            res[mode] = (toks, logits, state)
+        for mode in ("pipelined", "graph"):
+            assert torch.equal(res[mode][0], res["joined"][0]), mode
+            assert torch.equal(res[mode][1], res["joined"][1]), mode
+            for n in ("k", "v", "x_top", "carry", "seq_len"):
+                assert torch.equal(getattr(res[mode][2], n), getattr(res["joined"][2], n)), (mode, n)
+        assert res["joined"][2].seq_len.cpu().tolist() == [S + n_steps] * Bt
+        # and the steps follow the oracle (tokens forced; the state runs free over the steps)
+        ost = po.state_to_f64(st)
+        w64 = po.weights_to_f64(w)
+        for i in range(n_steps):
+            otr = po.decode_step(cfg, w64, ost, forced_tokens=forced[i].cpu().numpy())
+            assert nerr(res["pipelined"][1][i], otr["logits"]) <= TOL["bf16"], i
+        assert nerr(res["pipelined"][2].x_top, ost["x_top"]) <= TOL["bf16"]
+    finally:
+        ph.photon_set_persistent(True)
+
+
+def test_pipelined_state_refuses_unjoined_use():
+    """A state with outstanding lower levels may only take further pipelined steps or the join."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    cfg = si.PhotonConfig(L=2, C=(4, 4), R=(1, 1), D=256, H=4, d_h=64, n_layers=1, d_ff=640, vocab=1024, dtype="bf16")
+    w = si.make_weights(cfg, 97, encoders=False)
+    st = si.make_decode_state(cfg, 2, 10, 24, seed=98)
+    model = ph.PhotonModel(cfg, w)
+    state = ph.PhotonState(model, 2, 24, k=st["k"], v=st["v"], seq_len=st["seq_len"], x_top=st["x_top"], carry=st["carry"], pipeline=True)
+    toks = torch.empty((2, 16), dtype=torch.int32, device="cuda")
+    ph.photon_decode_step(model, state, toks)
+    assert state.c_state.lower_levels_pending == 1
+    state.c_state.pipeline = 0
+    with pytest.raises(ph.PhotonError):
+        ph.photon_decode_step(model, state, toks)
+    ph.photon_decode_join(state)
+    ph.photon_decode_step(model, state, toks)        # joined: an ordinary step again
+    torch.cuda.synchronize()
+    assert state.seq_len.cpu().tolist() == [12, 12]
