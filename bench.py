@@ -59,13 +59,10 @@ def weight_bytes_per_step(cfg, esz):
     return total
 
 
-def cpu_baseline(wl, min_seconds=12.0, max_steps=120):
-    """Time the oracle's decode step on the host cores on a bounded sample of the
-    workload: same widths, heads, context length and batch, but `sample_layers`
-    blocks per module instead of n_layers, repeated for about `min_seconds`; the
-    time is scaled by n_layers / sample_layers (embedding, LM-head and converter
-    work is thereby over-counted, which flatters the GPU slightly less than the
-    CPU deserves; the figure is a baseline, not a target)."""
+def cpu_baseline(wl, min_seconds=12.0, max_steps=40):
+    """Time the oracle's decode step on the host cores on a bounded sample of the workload: the configuration itself
+    (same widths, heads, blocks per module, vocabulary, batch and context length), a few steps, repeated for about
+    `min_seconds`.  The figure is a baseline, not a target."""
     import seeded_inputs as si
     from oracle import photon_oracle as po
     try:
@@ -73,23 +70,21 @@ def cpu_baseline(wl, min_seconds=12.0, max_steps=120):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    sample_layers = min(2, wl.cfg.n_layers)
-    cfg = si.shrink(wl.cfg, n_layers=sample_layers)
+    cfg = wl.cfg
     Bt, S = wl.Bt, wl.S0
     w = po.weights_to_f64(si.make_weights(cfg, 0, encoders=False))
     st = po.state_to_f64(si.make_decode_state(cfg, Bt, S, S + max_steps + 2, seed=0))
     forced = si.make_tokens(cfg.vocab, Bt, cfg.meta_context, 1)
     n = 0
     t0 = time.perf_counter()
-    while n < max_steps and (n < 1 or time.perf_counter() - t0 < min_seconds):
+    while n < max_steps and (n < 2 or time.perf_counter() - t0 < min_seconds):
         po.decode_step(cfg, w, st, forced_tokens=forced)
         n += 1
     dt = time.perf_counter() - t0
-    scale = wl.cfg.n_layers / sample_layers
     return {
-        "value": n * Bt * cfg.meta_context / (dt * scale), "unit": "tokens/s", "cores": int(threads), "kind": "oracle-numpy",
-        "sample": f"{n} oracle decode steps at {wl.name} shapes (D={cfg.D}, H={cfg.H}, Bt={Bt}, coarse S={S}, vocab={cfg.vocab}) "
-                  f"with {sample_layers} of {wl.cfg.n_layers} blocks per module: {dt:.1f} s measured, time scaled x{scale:g}",
+        "value": n * Bt * cfg.meta_context / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle-numpy",
+        "sample": f"{n} oracle decode steps (numpy float64) of {wl.name} as it stands (D={cfg.D}, H={cfg.H}, {cfg.n_layers} blocks per module, "
+                  f"Bt={Bt}, coarse S={S}, vocab={cfg.vocab}): {dt:.1f} s measured",
         "seconds_measured": dt,
     }
 

@@ -431,7 +431,8 @@ PHOTON_API double photon_mfma_probe(int32_t iters, int32_t random_operands, void
  * Per-kernel timing for benchmarks.  While enabled, every kernel launch of the
  * library carries a pair of HIP events attached to the dispatch itself (start
  * and end of the kernel as the command processor stamps them, on the launch
- * stream); this allocates events and must not be used under stream capture.
+ * stream); this allocates events (at most 65536 pairs between two resets, later
+ * launches go untimed) and must not be used under stream capture.
  * Kernels are grouped in classes 0 .. photon_profile_num_classes()-1, named by
  * photon_profile_class_name().  photon_profile_get() waits for the recorded
  * events of a class and returns the launch count and the summed elapsed

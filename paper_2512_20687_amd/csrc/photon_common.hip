@@ -35,7 +35,14 @@ const char* const kClassNames[KC_COUNT] = {
     "choose_token_kernel", "misc", "persistent_module_kernel"};
 }  // namespace
 
+// At most this many launches are timed between two resets (each holds two events); further launches go untimed.
+constexpr size_t PROFILE_MAX_RECORDS = 1 << 16;
+
 bool profile_pair(int cls, hipEvent_t* start, hipEvent_t* stop) {
+  {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (g_prof.size() >= PROFILE_MAX_RECORDS) return false;
+  }
   ProfRec r{cls, nullptr, nullptr};
   if (hipEventCreate(&r.start) != hipSuccess) return false;
   if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return false; }
