@@ -338,6 +338,13 @@ PHOTON_API int32_t photon_decode_join(photon_state* st, void* stream);
  * concurrently on different streams serialise on the barrier waits (and fail with the error word set after 10 s). */
 PHOTON_API int32_t photon_set_persistent(int32_t on);
 
+/* Measurement aid for benchmarks.  While `stamps` (device memory, room for 16 * 16 values of 8 bytes) is set, workgroup
+ * 0 of every persistent launch notes the device's constant 100 MHz clock at the milestones of every phase, 14 per
+ * block in this order: QKV contraction done; its epilogue and stores issued; barrier passed; attention done; barrier;
+ * O contraction; epilogue; barrier; gate/up contraction; epilogue; barrier; down contraction; epilogue; barrier (the
+ * last block has no final barrier).  NULL switches it off.  Process-wide; the buffer is the caller's. */
+PHOTON_API int32_t photon_persistent_trace(uint64_t* stamps);
+
 /* Bound of a grid-barrier wait inside a persistent launch, in ticks of the device's constant 100 MHz clock (default
  * 10^9 = 10 s; process-wide).  A wait that runs out sets PHOTON_STATUS_BARRIER_TIMEOUT and makes every workgroup
  * leave the kernel normally.  Meant for tests of that path (a limit of a few ticks makes the first real wait run out). */

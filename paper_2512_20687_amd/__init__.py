@@ -33,6 +33,7 @@ from .binding import (  # noqa: F401
     photon_last_error,
     photon_linear,
     photon_mfma_probe,
+    photon_persistent_trace,
     photon_prefill,
     photon_prefill_workspace_bytes,
     photon_profile_enable,

@@ -230,6 +230,16 @@ def photon_set_persistent(on: bool) -> None:
     _check(lib.photon_set_persistent(1 if on else 0))
 
 
+def photon_persistent_trace(stamps: Optional[torch.Tensor]) -> None:
+    """stamps: int64 device tensor with room for 256 clock values, or None to switch the trace off."""
+    lib = load_library()
+    lib.photon_persistent_trace.argtypes = [C.c_void_p]
+    lib.photon_persistent_trace.restype = C.c_int32
+    if stamps is not None and (stamps.dtype != torch.int64 or stamps.numel() < 256):
+        raise PhotonError(-1, "stamps must be an int64 tensor of at least 256 elements")
+    _check(lib.photon_persistent_trace(_ptr(stamps)))
+
+
 def photon_set_barrier_wait_limit(ticks: int) -> None:
     """Bound of a grid-barrier wait of a persistent launch in 10 ns ticks (default 10**9)."""
     lib = load_library()

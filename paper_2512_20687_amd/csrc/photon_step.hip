@@ -1012,6 +1012,11 @@ extern "C" int32_t photon_set_persistent(int32_t on) {
   return PHOTON_OK;
 }
 
+extern "C" int32_t photon_persistent_trace(uint64_t* stamps) {
+  persistent_module_set_stamps(reinterpret_cast<unsigned long long*>(stamps));
+  return PHOTON_OK;
+}
+
 extern "C" int32_t photon_set_barrier_wait_limit(int64_t ticks) {
   clear_error();
   PHOTON_REQUIRE(ticks > 0, PHOTON_ERR_INVALID_ARG, "%s: ticks=%lld must be positive", __func__, (long long)ticks);

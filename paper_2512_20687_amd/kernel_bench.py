@@ -321,6 +321,23 @@ def bench_module():
                 n, ms = prof["persistent_module_kernel"]
                 assert n == passes, (n, passes)
                 _emit("persistent_module_kernel", f"cfg3 widths, 8 blocks, {what}: one launch per pass", ms * 1e3 / n, bytes_=module_bytes)
+                # where a block's time goes: workgroup 0's clock at the milestones of every phase (one more step, traced)
+                stamps = torch.zeros(256, dtype=torch.int64, device="cuda")
+                ph.photon_persistent_trace(stamps)
+                state.seq_len.zero_()
+                ph.photon_decode_step(model, state, out)
+                torch.cuda.synchronize()
+                ph.photon_persistent_trace(None)
+                t = stamps.cpu().tolist()                  # the last launch of the step overwrote the earlier ones
+                names = ("qkv_contract", "qkv_epilogue", "barrier", "attention", "barrier", "o_contract", "o_epilogue", "barrier",
+                         "gateup_contract", "gateup_epilogue", "barrier", "down_contract", "down_epilogue", "barrier")
+                nl = cfg.n_layers
+                per = {}
+                for k in range(14):
+                    v = [(t[l * 14 + k] - t[l * 14 + k - 1]) / 100.0 for l in range(1, nl) if l * 14 + k < 14 * nl - 1]
+                    per[names[k]] = per.get(names[k], 0.0) + sum(v) / len(v)
+                print(json.dumps({"kernel": "persistent_module_kernel", "shape": f"cfg3 widths, {what}", "us_per_block_by_phase":
+                                  {k: round(v, 2) for k, v in per.items()}, "us_per_block": round(sum(per.values()), 2)}), flush=True)
             else:
                 lin = prof["linear_bf16_kernels"]
                 att = prof["local_attn_kernel"]
