@@ -911,6 +911,8 @@ extern "C" int32_t photon_prefill(const photon_config* cfg, const photon_weights
   const photon_config& c = *cfg;
   PHOTON_TRY(validate_prefill(c, Bt, T, st->S_max));
   PHOTON_REQUIRE(tokens != nullptr, PHOTON_ERR_INVALID_ARG, "%s: tokens is null", __func__);
+  PHOTON_REQUIRE(st->lower_levels_pending == 0, PHOTON_ERR_INVALID_ARG,
+                 "%s: the lower levels of a pipelined step are still outstanding on this state: call photon_decode_join first", __func__);
   PHOTON_REQUIRE_PTR(st->k_cache);
   PHOTON_REQUIRE_PTR(st->v_cache);
   PHOTON_REQUIRE_PTR(st->x_top);
