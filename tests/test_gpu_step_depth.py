@@ -159,3 +159,75 @@ def test_bf16_error_over_free_running_steps():
     _report("bf16_free_running", growth)
     assert all(v <= TOL["bf16"] for v in growth.values()), growth
     assert state.seq_len.cpu().tolist() == [S + 8] * Bt
+
+
+def test_bench_configuration_graph_replay_against_oracle():
+    """The configuration and launch shape bench.py times: configuration 3 at full size (8 blocks per module, coarse
+    length 8192, weights and state drawn on the GPU as the benchmark draws them), a pipelined state, several steps and
+    the join captured in ONE graph and replayed.  The oracle recomputes the first two steps from the same inputs
+    (copied back), tokens forced to the library's own choices.  The first step is held to the bf16 bar; the second
+    step and the final state run free inside the graph (nothing can be re-synchronised between captured steps), so
+    their error, which a random 8-block network on an N(0,1) state amplifies about 2.7-fold per step, is reported and
+    only sanity-bounded."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    wl = si.WORKLOADS["cfg3_bf16_128k"]
+    cfg, Bt, S0 = wl.cfg, wl.Bt, wl.S0
+    n_steps = 2
+    S_max = (S0 + 16 + 127) // 128 * 128
+    weights = si.make_weights(cfg, 0, encoders=False, device="cuda")
+    model = ph.PhotonModel(cfg, weights)
+    st0 = si.make_decode_state(cfg, Bt, S0, S_max, seed=0, device="cuda")
+    state = ph.PhotonState(model, Bt, S_max, pipeline=True, **{k: st0[k] for k in ("k", "v", "seq_len", "x_top", "carry")})
+    keep = {n: getattr(state, n).clone() for n in ("seq_len", "x_top", "carry")}
+    toks = torch.zeros((n_steps, Bt, cfg.meta_context), dtype=torch.int32, device="cuda")
+    logits = torch.zeros((n_steps, Bt, cfg.meta_context, cfg.vocab), device="cuda")
+
+    def block():
+        for i in range(n_steps):
+            ph.photon_decode_step(model, state, toks[i], trace={"logits": logits[i]})
+        ph.photon_decode_join(state)
+
+    block()                                           # eager once (as the benchmark does), then rewind and capture
+    torch.cuda.synchronize()
+    for n, t in keep.items():
+        getattr(state, n).copy_(t)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        block()
+    for n, t in keep.items():
+        getattr(state, n).copy_(t)
+    logits.zero_()
+    g.replay()
+    torch.cuda.synchronize()
+    assert int(state.status.item()) == 0
+    assert state.seq_len.cpu().tolist() == [S0 + n_steps] * Bt
+
+    # the oracle on the same inputs
+    def cpu(t):
+        return t.float().cpu().numpy()
+    w_np = {"E_dec": cpu(weights["E_dec"]), "W_lm": cpu(weights["W_lm"]), "enc": [], "dec": []}
+    def mod_np(m):
+        return {"layers": [{k: cpu(v) for k, v in lay.items()} for lay in m["layers"]], "g_final": cpu(m["g_final"])}
+    for e in weights["enc"]:
+        w_np["enc"].append({} if not e else {"chunker": {k: cpu(v) for k, v in e["chunker"].items()}, "module": mod_np(e["module"])})
+    for d in weights["dec"]:
+        w_np["dec"].append({"converter": {k: cpu(v) for k, v in d["converter"].items()}, "x0": cpu(d["x0"]), "module": mod_np(d["module"])})
+    w64 = po.weights_to_f64(w_np)
+    del w_np
+    ost = {"k": cpu(st0["k"])[..., :cfg.d_h].astype(np.float64), "v": cpu(st0["v"])[..., :cfg.d_h].astype(np.float64),
+           "seq_len": np.full((Bt,), S0, np.int64), "x_top": cpu(keep["x_top"]).astype(np.float64), "carry": cpu(keep["carry"]).astype(np.float64)}
+    errs = {}
+    for i in range(n_steps):
+        otr = po.decode_step(cfg, w64, ost, forced_tokens=toks[i].cpu().numpy())
+        errs[f"step{i}_logits"] = nerr(logits[i], otr["logits"])
+        # the library's greedy tokens are the oracle's wherever the oracle's two best logits are clearly apart
+        lg = otr["logits"]
+        top2 = np.sort(lg, axis=-1)[..., -2:]
+        clear = (top2[..., 1] - top2[..., 0]) > 10 * TOL["bf16"] * np.abs(lg).max()
+        assert np.array_equal(toks[i].cpu().numpy()[clear], lg.argmax(-1)[clear])
+    errs["x_top"] = nerr(state.x_top, ost["x_top"])
+    errs["carry"] = nerr(state.carry, ost["carry"])
+    _report("bench_configuration_graph", errs)
+    assert errs["step0_logits"] <= TOL["bf16"], errs
+    assert all(v <= 5 * TOL["bf16"] for v in errs.values()), errs
