@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (CPU baseline) leg")
     ap.add_argument("--no-pipeline", action="store_true",
                     help="join the lower levels at the end of every step instead of letting them run beside the next step's top level")
-    ap.add_argument("--steps-per-graph", type=int, default=8, help="decode steps captured in one HIP graph (pipelined mode)")
+    ap.add_argument("--steps-per-graph", type=int, default=16, help="decode steps captured in one HIP graph (pipelined mode)")
     ap.add_argument("--no-persistent", action="store_true",
                     help="run every module pass as separate launches instead of one persistent launch (comparison)")
     ap.add_argument("--calib-copy", action="store_true",
