@@ -88,3 +88,15 @@ def test_binding_constants_match_the_header():
     assert define["PHOTON_LINEAR_OUT_BF16"] == b.PHOTON_LINEAR_OUT_BF16
     # the two flags stay clear of the epilogue codes 0..2
     assert define["PHOTON_LINEAR_X_BF16"] & 3 == 0 and define["PHOTON_LINEAR_OUT_BF16"] & 3 == 0
+
+
+def test_schedule_controls_validate_on_the_host(lib):
+    lib.photon_decode_join.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    lib.photon_set_barrier_wait_limit.argtypes = [ctypes.c_int64]
+    assert lib.photon_decode_join(None, None) == -1
+    assert b"st is null" in lib.photon_last_error()
+    assert lib.photon_set_barrier_wait_limit(0) == -1 and lib.photon_set_barrier_wait_limit(-5) == -1
+    assert lib.photon_set_barrier_wait_limit(10 ** 9) == 0
+    assert lib.photon_set_persistent(0) == 0 and lib.photon_set_persistent(1) == 0
+    lib.photon_persistent_trace.argtypes = [ctypes.c_void_p]
+    assert lib.photon_persistent_trace(None) == 0
