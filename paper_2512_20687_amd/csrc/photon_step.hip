@@ -155,7 +155,7 @@ __global__ __launch_bounds__(CHOOSE_THREADS) void choose_token_kernel(const floa
 }
 
 // Conditioning of the next lower level: sequence b's chunks hang off [carry[b], new[b,0], ..., new[b,n-2]];
-// new[b,n-1] becomes the carry.
+// new[b,n-1] becomes the carry.  One launch: a thread reads the carry element it is about to replace.
 __global__ __launch_bounds__(256) void shift_condition_kernel(const float* __restrict__ fresh, float* __restrict__ carry,
                                                               float* __restrict__ cond, int Bt, int n, int D) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -163,13 +163,12 @@ __global__ __launch_bounds__(256) void shift_condition_kernel(const float* __res
   const int d = (int)(idx % D);
   const int i = (int)((idx / D) % n);
   const int b = (int)(idx / ((int64_t)D * n));
-  cond[idx] = (i == 0) ? carry[(int64_t)b * D + d] : fresh[((int64_t)b * n + i - 1) * D + d];
-}
-__global__ __launch_bounds__(256) void update_carry_kernel(const float* __restrict__ fresh, float* __restrict__ carry, int Bt, int n, int D) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (int64_t)Bt * D) return;
-  const int d = (int)(idx % D), b = (int)(idx / D);
-  carry[idx] = fresh[((int64_t)b * n + n - 1) * D + d];
+  if (i == 0) {                                           // the only reader and the only writer of carry[b, d]
+    cond[idx] = carry[(int64_t)b * D + d];
+    carry[(int64_t)b * D + d] = fresh[((int64_t)b * n + n - 1) * D + d];
+  } else {
+    cond[idx] = fresh[((int64_t)b * n + i - 1) * D + d];
+  }
 }
 
 // Start of a step: count the entry this step will append to every sequence's coarse cache, and clear the barrier
@@ -599,9 +598,7 @@ static int32_t condition_lower(const Ctx& x, int l, const float* units, float* c
   const int64_t per_seq = n * C / Bt;
   float* carry = x.s->carry + (int64_t)(l - 2) * Bt * D;
   PHOTON_LAUNCH(KC_MISC, x.st, shift_condition_kernel, dim3(blocks_for(n * C * D)), dim3(256), 0, x.st, units, carry, cond, Bt, (int)per_seq, D);
-  PHOTON_TRY(check_launch("shift_condition_kernel"));
-  PHOTON_LAUNCH(KC_MISC, x.st, update_carry_kernel, dim3(blocks_for((int64_t)Bt * D)), dim3(256), 0, x.st, units, carry, Bt, (int)per_seq, D);
-  return check_launch("update_carry_kernel");
+  return check_launch("shift_condition_kernel");
 }
 
 // The levels below the top, in order, on this context's stream: level L-1 hangs off cond_top, every further level off
