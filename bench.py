@@ -227,6 +227,9 @@ def main():
                 "share_of_kernel_time": dk["ms_per_step"] / sum(k["ms_per_step"] for k in kernels.values())}
     ca = kernels.get("coarse_attn_kernel", {})
     kv_gbs = ca.get("gbs", 0.0)
+    # the whole operation a2: the attention kernel and the merge of its split partials (a separate tiny launch)
+    a2_ms = ca.get("ms_per_step", 0.0) + kernels.get("coarse_merge_kernel", {}).get("ms_per_step", 0.0)
+    kv_gbs_with_merge = alg_bytes["coarse_attn_kernel"] / (a2_ms * 1e-3) / 1e9 if a2_ms > 0 else 0.0
 
     # ---- the coarse-attention kernel alone at the same shape (rotating over the layers' caches) ----
     q = torch.randn((Bt, H, d_h), device=dev, dtype=torch.float32).to(model.mat_dtype)
@@ -264,6 +267,7 @@ def main():
                    "schedule": ("lower levels pipelined across steps on a second stream" if pipelined else
                                 "separate_launches" if args.no_persistent else "persistent module passes at the top level")},
         "kv_read_gbs": kv_gbs, "kv_read_frac_of_hbm_peak": kv_gbs / HBM_PEAK_GBS,
+        "kv_read_with_merge_gbs": kv_gbs_with_merge, "kv_read_with_merge_frac_of_hbm_peak": kv_gbs_with_merge / HBM_PEAK_GBS,
         "kv_read_isolated": {"gbs": kv_iso_gbs, "frac_of_hbm_peak": kv_iso_gbs / HBM_PEAK_GBS, "us_per_launch": iso_us,
                              "bytes_per_launch": iso_bytes, "n_splits": ns, "launches": iso[0]},
         "kv_read_bytes_per_launch": kv_launch_bytes,
