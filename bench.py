@@ -136,16 +136,17 @@ def main():
     pipelined = not args.no_pipeline and cfg.L >= 2
     state = ph.PhotonState(model, Bt, S_max, pipeline=pipelined, **{k: st0[k] for k in ("k", "v", "seq_len", "x_top", "carry")})
     del st0
-    # steps per captured graph: a divisor of --steps, so that exactly --steps steps are timed
-    spg = math.gcd(args.steps, max(1, args.steps_per_graph)) if pipelined else 1
+    # steps per captured graph; a shorter tail graph makes up the remainder, so that exactly --steps steps are timed
+    spg = max(1, min(args.steps_per_graph, args.steps)) if pipelined else 1
+    tail = args.steps % spg
     out_tokens = torch.zeros((spg, Bt, cfg.meta_context), dtype=torch.int32, device=dev)
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
 
-    def step():
-        """spg decode steps; pipelined: every step's lower levels (the token decode) run on beside the next step's
-        top level, and are joined after the last one, inside the timed region."""
-        for i in range(spg):
+    def step(n=None):
+        """n (default spg) decode steps; pipelined: every step's lower levels (the token decode) run on beside the next
+        step's top level, and are joined after the last one, inside the timed region."""
+        for i in range(spg if n is None else n):
             ph.photon_decode_step(model, state, out_tokens[i])
         ph.photon_decode_join(state)
 
@@ -156,7 +157,7 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
-    graph = None
+    graph = graph_tail = None
     mode = "eager"
     if not args.no_graph:
         try:
@@ -166,11 +167,15 @@ def main():
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph):
                 step()
+            if tail:
+                graph_tail = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph_tail):
+                    step(tail)
             mode = "hip_graph_replay"
             state.seq_len.fill_(S0)
         except Exception as e:                            # capture unsupported: fall back to eager enqueue
             print(f"[bench] graph capture failed ({e}); timing eager enqueue", file=sys.stderr)
-            graph = None
+            graph = graph_tail = None
             mode = "eager"
             state.seq_len.fill_(S0)
 
@@ -183,6 +188,8 @@ def main():
     ev0.record()
     for _ in range(args.steps // spg):
         run()
+    if tail:
+        graph_tail.replay() if graph_tail is not None else step(tail)
     ev1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
