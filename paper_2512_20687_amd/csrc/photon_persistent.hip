@@ -11,15 +11,19 @@
 //   * what one phase hands the next (a few rows: q|k|v, attention rows, the residual stream, hidden rows) is
 //     written with agent-scope write-through stores, waited for before the arrival, and read with agent-scope
 //     loads: the eight XCDs' L2 caches are not coherent with each other, these accesses are served beyond them;
-//   * the weights of a phase do not depend on what the barrier protects, so each workgroup requests its first
-//     weight fragments of the NEXT phases before it finishes the current one: they arrive during the epilogue,
-//     the barrier and the activation staging, and HBM keeps streaming across phase boundaries;
+//   * the weights of a phase do not depend on what the barrier protects, so a workgroup requests its share of a
+//     matrix one to three phases ahead, in groups placed right behind the activation loads of those earlier phases
+//     (vector-memory operations of a wave complete in order: a request placed anywhere else would hold back
+//     either that phase's stores, and with them the barrier, or the next phase's activations); a wave's whole
+//     share of a matrix sits in registers when its phase begins, and HBM streams while the phases before compute;
 //   * a linear phase is the few-row resident-activation map (one MFMA tile per 8 output columns, 128-byte weight
 //     lines folded into the tile's row halves, fp32 activations split into bf16 head + remainder in LDS, bf16
-//     activations taken as fragments straight from memory), with one staging slot per wave; the waves of a
-//     workgroup take their k chunks in an order rotated per workgroup so that the workgroups of an XCD do not all
-//     ask for the same activation lines at once; partial tiles are still summed in chunk order, so the arithmetic
-//     equals that of the separate launches.
+//     activations taken as fragments straight from memory); both k chunks of a wave are staged before its first
+//     MFMA, so that the activations' landing registers are free while the accumulators are live (registers, not
+//     LDS, are what this kernel runs out of: a spilled value comes back through the same in-order queue as the
+//     weight prefetch and stalls its phase); the waves of a workgroup take their k chunks in an order rotated per
+//     workgroup so that the workgroups of an XCD do not all ask for the same activation lines at once; partial
+//     tiles are still summed in chunk order, so the arithmetic equals that of the separate launches.
 #include "photon_persistent.h"
 
 #include <mutex>
@@ -86,8 +90,9 @@ struct PmArgs {
 // launch.  Returns false when the wait ran out or another workgroup reported that: the caller leaves the kernel.
 // YOUNGER: vector-memory loads this wave has issued, on every path, after its last store of the phase (the weight
 // prefetch of later phases).  Vector-memory operations complete in order, so "at most YOUNGER outstanding" means the
-// stores have completed while the prefetch stays in flight across the barrier.  (A plain wait for everything would
-// hold the arrival back until the prefetched weights had landed, and the memory system would idle at every barrier.)
+// stores have completed while such a prefetch stays in flight across the barrier.  (The schedule in the kernel
+// now places every prefetch group ahead of the stores of its phase, where it lands under the phase's arithmetic:
+// YOUNGER is 0 at every barrier.)
 constexpr int pm_wait_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 template <int YOUNGER>
 __device__ __forceinline__ bool grid_sync(unsigned* bar, unsigned* err, int* flag, int g, int G, unsigned round, long long spin_ticks) {
