@@ -728,15 +728,21 @@ unsigned long long* g_pm_stamps = nullptr;                         // see persis
 long long g_pm_spin_ticks = 1000000000LL;                          // bound of a barrier wait: 10 s of the 100 MHz clock
 struct KernelState { bool checked = false, ok = false; };
 std::mutex g_pm_mu;
-KernelState g_pm_state[5][3][2][2];
+constexpr int PM_MAX_DEVICES = 64;
+KernelState g_pm_state[PM_MAX_DEVICES][5][3][2][2];              // per device: attributes and occupancy are the device's
 
 // One-time set-up of an instantiation: allow its dynamic LDS, and make sure the device holds the whole grid at once.
 bool kernel_ready(PmKernel k, const Shape& s) {
   const int key = s.tq * 1000 + s.to * 100 + s.tg * 10 + s.td;
   const int ki = key == 1111 ? 0 : key == 1121 ? 1 : key == 2131 ? 2 : key == 3141 ? 3 : 4;
   const int xi = s.xp == 2 ? 0 : s.xp == 4 ? 1 : 2;
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= PM_MAX_DEVICES) {
+    (void)hipGetLastError();
+    return false;
+  }
   std::lock_guard<std::mutex> lk(g_pm_mu);
-  KernelState& st = g_pm_state[ki][xi][s.dh == 64 ? 0 : 1][s.nk == 4 ? 0 : 1];
+  KernelState& st = g_pm_state[dev][ki][xi][s.dh == 64 ? 0 : 1][s.nk == 4 ? 0 : 1];
   if (st.checked) return st.ok;
   st.checked = true;
   st.ok = false;
@@ -744,8 +750,7 @@ bool kernel_ready(PmKernel k, const Shape& s) {
     (void)hipGetLastError();
     return false;
   }
-  int dev = 0, cus = 0, per_cu = 0;
-  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
       hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(k), PM_THREADS, PM_LDS_LIMIT) != hipSuccess) {
     (void)hipGetLastError();
     return false;
