@@ -36,6 +36,11 @@ int32_t launch_linear(const LinearArgs& a, hipStream_t st);
 // (the caller then takes the streaming kernel).  Arguments must have passed launch_linear's checks.
 bool launch_linear_resident(const LinearArgs& a, hipStream_t st);
 
+// bf16 weights, fp32 activations of 17-32 rows, plain or SwiGLU epilogue, contraction length at most 2048: two row tiles of
+// 16 per workgroup at the accuracy (and with the per-row arithmetic) of the 16-row kernel; the matrix is streamed once.
+// Returns true when the launch was issued.
+bool launch_linear_resident_x2(const LinearArgs& a, hipStream_t st);
+
 // Many rows (dozens and up) with bf16 weights: row kernel (norm, rounding to bf16) + tiled MFMA
 // contraction + (SwiGLU) row kernel.  `workspace` holds linear_many_workspace_bytes(rows, K_max, N2_max)
 // bytes, K_max >= every K and N2_max >= every 2N of a SwiGLU call that will be issued with it.

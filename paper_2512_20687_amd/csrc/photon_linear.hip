@@ -358,6 +358,7 @@ int32_t launch_linear(const LinearArgs& a, hipStream_t st) {
   if (a.w_bf16) {
     if (a.K % FL_KBLOCK != 0 || a.N % 16 != 0 || a.ldx % 4 != 0 || a.ldo % 4 != 0 || (a.res && a.ldres % 4 != 0))
       return fail(PHOTON_ERR_UNSUPPORTED, "linear (bf16): K=%d must be a multiple of 64, N=%d of 16, row pitches of 4", a.K, a.N);
+    if (launch_linear_resident_x2(a, st)) return check_launch("resident_linear_f32x2_kernel");   // 17-32 fp32 rows: one weight pass
     if (launch_linear_resident(a, st)) return check_launch("resident_linear_bf16_kernel");
     if (a.x_bf16) return fail(PHOTON_ERR_UNSUPPORTED, "linear: bf16 activations need a plain or residual epilogue without norm, N=%d a multiple of 8", a.N);
     switch (a.epilogue) {

@@ -349,6 +349,234 @@ __global__ __launch_bounds__(RL_THREADS) void resident_linear_bf16_kernel(
   }
 }
 
+// Two row tiles of 16 with fp32 activations (17-32 rows): the weights, once in registers, meet both tiles, so the matrix
+// is streamed once for up to 32 rows at the accuracy of the 16-row kernel (bf16 head + remainder of every activation;
+// every row's arithmetic, chunk assignment and summation order are those of the kernel above, so a row's result does
+// not depend on which of the two kernels computed it).  The contraction length is at most 2048 (two chunks per wave):
+// chunk 0 of both tiles is staged, contracted, then chunk 1 is staged over it (LDS operations of a wave execute in
+// order), so LDS holds one staging slot per tile and wave: 139 KB, as the 16-row kernel with its two chunks.
+template <int EPI, bool NORM, int TMAX>
+__global__ __launch_bounds__(RL_THREADS) void resident_linear_f32x2_kernel(
+    const float* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ W, const float* __restrict__ gain, float eps,
+    const float* __restrict__ bias, float* out, int64_t ldo, int M, int N, int K, int unit_base, int unit_rem, int wave_bytes, int out_bf16) {
+  constexpr int CB = RL_CB, XP = 8, ROWS = 16, RT = 2;
+  constexpr int GP = rl_group_pitch(ROWS);
+  constexpr int SLOT = rl_chunk_bytes(ROWS);
+  constexpr int TT = TMAX;
+  constexpr int UC = (EPI == EPI_SWIGLU) ? 4 : 8;
+  extern __shared__ __align__(16) char smem[];                     // [8 waves][wave_bytes], then row statistics [2 tiles][8][16]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lrow = lane & 15, lq = lane >> 4;
+  char* my_area = smem + wave * wave_bytes;
+  float* ssum = reinterpret_cast<float*>(smem + RL_WAVES * wave_bytes);
+
+  const int g = blockIdx.x;
+  const int u_cnt = unit_base + (g < unit_rem ? 1 : 0);
+  const int u0 = g * unit_base + (g < unit_rem ? g : unit_rem);
+  const int tiles = u_cnt;
+  const int n0 = u0 * UC;
+  uint32_t w_lane[TT];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) {
+    const int uu = t < tiles ? t : tiles - 1;
+    const int r = lrow & 7;
+    const int n = (EPI == EPI_SWIGLU) ? (r < 4 ? 0 : N) + n0 + uu * 4 + (r & 3) : n0 + uu * 8 + r;
+    w_lane[t] = ((uint32_t)n * (uint32_t)K + (uint32_t)(lq + 4 * (lrow >> 3)) * 8u) * 2u;
+  }
+  const char* w_base = reinterpret_cast<const char*>(W);
+  const int total_blocks = K / RL_KBLOCK;
+  const int chunks = (total_blocks + CB - 1) / CB;
+  const int n_my = wave < chunks ? (chunks - wave + RL_WAVES - 1) / RL_WAVES : 0;   // 0, 1 or 2 (host-checked)
+
+  float4_t acc[RT][TT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int t = 0; t < TT; ++t) acc[rt][t] = float4_t{0.f, 0.f, 0.f, 0.f};
+  float ss[RT][XP];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int i = 0; i < XP; ++i) ss[rt][i] = 0.f;
+
+  auto load_w = [&](int j, auto& w) {
+    const int chunk = wave + j * RL_WAVES;
+#pragma unroll
+    for (int b = 0; b < CB; ++b) {
+      int blk = chunk * CB + b;
+      blk = blk < total_blocks ? blk : total_blocks - 1;
+      const char* wp = w_base + (int64_t)blk * (RL_KBLOCK * 2);
+#pragma unroll
+      for (int t = 0; t < TT; ++t) w[t][b] = load16_stream(wp + w_lane[t]);
+    }
+  };
+  const int c4 = lane & 31;
+  auto load_x = [&](int j, int rt, float4_t (&xr)[XP + 1]) {
+    const int chunk = wave + j * RL_WAVES;
+    int blk = chunk * CB + (c4 >> 4);
+    blk = blk < total_blocks ? blk : total_blocks - 1;
+    const uint32_t kb = (uint32_t)blk * (RL_KBLOCK * 4);
+#pragma unroll
+    for (int i = 0; i < XP; ++i) {
+      int m = rt * 16 + i * 2 + (lane >> 5);
+      m = m < M ? m : M - 1;
+      xr[i] = *reinterpret_cast<const float4_t*>(reinterpret_cast<const char*>(x) + ((int64_t)m * ldx + (c4 & 15) * 4) * 4 + kb);
+    }
+    if (NORM) xr[XP] = *reinterpret_cast<const float4_t*>(reinterpret_cast<const char*>(gain) + (kb + (c4 & 15) * 16));
+  };
+  auto stage = [&](int j, int rt, const float4_t (&xr)[XP + 1]) {
+    const int chunk = wave + j * RL_WAVES;
+    char* hi = my_area + rt * SLOT;
+    char* lo = hi + 16 * GP;
+    const bool k_live = chunk * RL_CHUNK_K + c4 * 4 < K;
+    const int group = c4 >> 1;
+#pragma unroll
+    for (int i = 0; i < XP; ++i) {
+      const int row = i * 2 + (lane >> 5);
+      float4_t v = (k_live && rt * 16 + row < M) ? xr[i] : float4_t{0.f, 0.f, 0.f, 0.f};
+      ss[rt][i] = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss[rt][i]))));
+      if (NORM) v *= xr[XP];
+      uint32_t h01, l01, h23, l23;
+      split_bf16x2(v.x, v.y, h01, l01);
+      split_bf16x2(v.z, v.w, h23, l23);
+      const int off = group * GP + row * 16 + (c4 & 1) * 8;
+      *reinterpret_cast<uint2*>(hi + off) = uint2{h01, h23};
+      *reinterpret_cast<uint2*>(lo + off) = uint2{l01, l23};
+    }
+  };
+  auto mma = [&](int j, const auto& w) {
+    const int chunk = wave + j * RL_WAVES;
+#pragma unroll
+    for (int b = 0; b < CB; ++b) {
+      if (chunk * CB + b < total_blocks) {
+#pragma unroll
+        for (int half2 = 0; half2 < 2; ++half2) {
+          const int off = ((b * 2 + half2) * 4 + lq) * GP + lrow * 16;
+          bf16x8_t bh[RT], bl[RT];
+#pragma unroll
+          for (int rt = 0; rt < RT; ++rt) {
+            bh[rt] = as_bf16x8(*reinterpret_cast<const uint4_t*>(my_area + rt * SLOT + off));
+            bl[rt] = as_bf16x8(*reinterpret_cast<const uint4_t*>(my_area + rt * SLOT + 16 * GP + off));
+          }
+#pragma unroll
+          for (int t = 0; t < TT; ++t) {
+            const bf16x8_t a = as_bf16x8(half2 ? rotate8(w[t][b]) : w[t][b]);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+              acc[rt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh[rt], acc[rt][t], 0, 0, 0);
+              acc[rt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl[rt], acc[rt][t], 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+  };
+
+  // With four or five tiles per workgroup the registers do not hold both chunks' weights beside the activations of
+  // two row tiles: chunk 1's weights are then requested only once chunk 0's are in the matrix cores (into the same
+  // registers); their latency is partly covered by chunk 0's MFMAs and the staging of chunk 1.
+  constexpr bool LATE_W = TMAX >= 4;
+  uint4_t wa[TT][CB], wb[LATE_W ? 1 : TT][CB];
+  float4_t xa[XP + 1], xb[XP + 1];
+  if (n_my > 0) {
+    load_x(0, 0, xa);                                              // activations first: loads return in order
+    load_x(0, 1, xb);
+    load_w(0, wa);
+    stage(0, 0, xa);
+    stage(0, 1, xb);
+    if (n_my > 1) {
+      load_x(1, 0, xa);
+      load_x(1, 1, xb);
+      if constexpr (!LATE_W) load_w(1, wb);
+    }
+    mma(0, wa);
+    if (n_my > 1) {
+      if constexpr (LATE_W) load_w(1, wa);
+      stage(1, 0, xa);                                             // over chunk 0's slots: its operand reads were issued before
+      stage(1, 1, xb);
+      if constexpr (LATE_W) mma(1, wa); else mma(1, wb);
+    }
+  }
+
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int i = 0; i < XP; ++i) {
+      const float v = group_sum<32>(ss[rt][i]);
+      if ((lane & 31) == 0) ssum[(rt * RL_WAVES + wave) * 16 + i * 2 + (lane >> 5)] = v;
+    }
+  __syncthreads();
+  float4_t* red = reinterpret_cast<float4_t*>(my_area);
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int t = 0; t < TT; ++t) red[(rt * TT + t) * 64 + lane] = acc[rt][t];
+  __syncthreads();
+
+  if (wave >= TMAX || wave >= tiles) return;
+  const int t = wave;
+  if (lq >= (EPI == EPI_SWIGLU ? 1 : 2)) return;
+  const int n_out = n0 + t * UC + lq * 4;
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int m = rt * 16 + lrow;
+    if (m >= M) continue;
+    float4_t extra = float4_t{0.f, 0.f, 0.f, 0.f};
+    if (bias != nullptr) extra = *reinterpret_cast<const float4_t*>(bias + n_out);
+    float4_t y = float4_t{0.f, 0.f, 0.f, 0.f}, yu = float4_t{0.f, 0.f, 0.f, 0.f};
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < RL_WAVES; ++w) {
+      const float4_t* rw = reinterpret_cast<const float4_t*>(smem + w * wave_bytes);
+      y += rw[(rt * TT + t) * 64 + lane];
+      if (EPI == EPI_SWIGLU) yu += rw[(rt * TT + t) * 64 + lane + 16];
+      tot += ssum[(rt * RL_WAVES + w) * 16 + lrow];
+    }
+    if (NORM) {
+      const float r = 1.0f / sqrtf(tot / (float)K + eps);
+      y *= r;
+      yu *= r;
+    }
+    if (EPI == EPI_SWIGLU) {
+      y.x = silu(y.x) * yu.x; y.y = silu(y.y) * yu.y; y.z = silu(y.z) * yu.z; y.w = silu(y.w) * yu.w;
+    }
+    y += extra;
+    if (out_bf16)
+      *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(out) + (int64_t)m * ldo + n_out) = uint2{pack_bf16x2(y.x, y.y), pack_bf16x2(y.z, y.w)};
+    else
+      *reinterpret_cast<float4_t*>(out + (int64_t)m * ldo + n_out) = y;
+  }
+}
+
+template <int EPI, bool NORM, int TMAX>
+bool launch_f32x2_t(const LinearArgs& a, hipStream_t st, int G, int ub, int ur, int wave_bytes, size_t lds) {
+  auto kern = resident_linear_f32x2_kernel<EPI, NORM, TMAX>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, RL_LDS_LIMIT) != hipSuccess) {
+      (void)hipGetLastError();
+      return false;
+    }
+    attr_done = true;
+  }
+  PHOTON_LAUNCH(KC_SKINNY_GEMM, st, kern, dim3(G), dim3(RL_THREADS), lds, st, a.x, a.ldx, (const bf16_t*)a.W, a.gain, a.eps, a.bias, a.out,
+                a.ldo, a.M, a.N, a.K, ub, ur, wave_bytes, a.out_bf16 ? 1 : 0);
+  return true;
+}
+
+template <int EPI, bool NORM>
+bool launch_f32x2_e(const LinearArgs& a, hipStream_t st, int tmax, int G, int ub, int ur, int wave_bytes, size_t lds) {
+  switch (tmax) {
+    case 1: return launch_f32x2_t<EPI, NORM, 1>(a, st, G, ub, ur, wave_bytes, lds);
+    case 2: return launch_f32x2_t<EPI, NORM, 2>(a, st, G, ub, ur, wave_bytes, lds);
+    case 3: return launch_f32x2_t<EPI, NORM, 3>(a, st, G, ub, ur, wave_bytes, lds);
+    case 4: return launch_f32x2_t<EPI, NORM, 4>(a, st, G, ub, ur, wave_bytes, lds);
+    case 5: return launch_f32x2_t<EPI, NORM, 5>(a, st, G, ub, ur, wave_bytes, lds);
+  }
+  return false;
+}
+
 template <int EPI, int XP, bool NORM, int TMAX, bool XB = false, int RT = 1>
 bool launch_resident_t(const LinearArgs& a, hipStream_t st, int G, int unit_base, int unit_rem, int wave_bytes, size_t lds) {
   auto kern = resident_linear_bf16_kernel<EPI, XP, NORM, TMAX, XB, RT>;
@@ -465,6 +693,32 @@ bool launch_linear_resident(const LinearArgs& a, hipStream_t st) {
     case EPI_RESID: return launch_resident_e<EPI_RESID, false>(a, st, xp, tmax, G, ub, ur, wave_bytes, lds);
     default: return launch_resident_e<EPI_SWIGLU, true>(a, st, xp, tmax, G, ub, ur, wave_bytes, lds);
   }
+}
+
+// fp32 activations of 17-32 rows at the accuracy of the 16-row kernel (see resident_linear_f32x2_kernel): plain (with an
+// optional pre-norm and bias) and SwiGLU epilogues, contraction length at most 2048, at most 5 tiles per workgroup.
+// Returns true when the launch was issued here.
+bool launch_linear_resident_x2(const LinearArgs& a, hipStream_t st) {
+  if (!a.w_bf16 || a.x_bf16 || a.M <= 16 || a.M > 32 || a.K % RL_KBLOCK != 0 || a.N % 8 != 0) return false;
+  if (a.K > RL_WAVES * 2 * RL_CHUNK_K) return false;                // two chunks per wave
+  if (a.ldx % 4 != 0 || a.ldo % 4 != 0) return false;
+  if (a.epilogue == EPI_RESID || (a.epilogue == EPI_SWIGLU && a.gain == nullptr)) return false;
+  const bool norm = a.gain != nullptr;
+  const int64_t w_rows = (a.epilogue == EPI_SWIGLU) ? 2 * (int64_t)a.N : a.N;
+  if (w_rows * a.K * 2 >= ((int64_t)1 << 32)) return false;
+  const int units = a.N / ((a.epilogue == EPI_SWIGLU) ? 4 : 8);
+  constexpr int CUS = 256;
+  if (units > CUS * 5) return false;
+  const int G = units < CUS ? units : CUS;
+  const int ub = units / G, ur = units % G;
+  const int tmax = ub + (ur ? 1 : 0);
+  int wave_bytes = 2 * rl_chunk_bytes(16);
+  if (wave_bytes < 2 * tmax * 1024) wave_bytes = 2 * tmax * 1024;
+  const size_t lds = (size_t)RL_WAVES * wave_bytes + 2 * RL_WAVES * 16 * sizeof(float);
+  if (lds > (size_t)RL_LDS_LIMIT) return false;
+  if (a.epilogue == EPI_SWIGLU) return launch_f32x2_e<EPI_SWIGLU, true>(a, st, tmax, G, ub, ur, wave_bytes, lds);
+  return norm ? launch_f32x2_e<EPI_PLAIN, true>(a, st, tmax, G, ub, ur, wave_bytes, lds)
+              : launch_f32x2_e<EPI_PLAIN, false>(a, st, tmax, G, ub, ur, wave_bytes, lds);
 }
 
 }  // namespace photon

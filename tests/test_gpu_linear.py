@@ -163,3 +163,33 @@ def test_linear_swiglu_on_bf16_rows(M, N, K):
     assert nerr(full, ref) <= 2 * TOL["f32"]
     assert torch.equal(out, full.to(torch.bfloat16))
 
+
+
+@pytest.mark.parametrize("M,N,K,epilogue,norm,bias", [
+    (32, 6144, 2048, 0, True, False),      # QKV with pre-norm: 3 tiles per workgroup
+    (24, 5120, 2048, 2, True, False),      # gate/up with SwiGLU: 5 tiles per workgroup, second chunk's weights requested late
+    (17, 2048, 2048, 0, False, True),      # a converter: no norm, bias; one live row in the second tile
+    (32, 4096, 1664, 2, True, False),      # 4 tiles, a width that is not a power of two
+    (20, 96, 128, 0, True, True),          # fewer units than compute units, one chunk only
+])
+def test_linear_17_to_32_rows_equal_the_16_row_kernel_bit_for_bit(M, N, K, epilogue, norm, bias):
+    """17-32 fp32 rows take two row tiles per workgroup (the matrix is streamed once); every row's arithmetic is that
+    of the 16-row kernel, so the result equals, bit for bit, what two calls of at most 16 rows give, and the oracle's."""
+    require_gpu()
+    import paper_2512_20687_amd as ph
+    rows_w = 2 * N if epilogue == 2 else N
+    x = si.make_normal((M, K), 5, "f32")
+    w = si.make_normal((rows_w, K), 6, "bf16", std=0.05)
+    gain = si.make_normal((K,), 7, "f32", std=0.3) + 1.0 if norm else None
+    b = si.make_normal((N,), 8, "f32", std=0.1) if bias else None
+    ref = oracle_linear(x, w, gain, 1e-5, b, None, epilogue, N)
+    opt = lambda a: None if a is None else dev(np.asarray(a, np.float32))
+    xd, wd, gd, bd = dev(x), dev(w, "bf16"), opt(gain), opt(b)
+    whole = torch.full((M, N), float("nan"), device="cuda")
+    ph.photon_linear(xd, wd, whole, gain=gd, rms_eps=1e-5, bias=bd, epilogue=epilogue)
+    parts = torch.full((M, N), float("nan"), device="cuda")
+    ph.photon_linear(xd[:16].contiguous(), wd, parts[:16], gain=gd, rms_eps=1e-5, bias=bd, epilogue=epilogue)
+    ph.photon_linear(xd[16:].contiguous(), wd, parts[16:], gain=gd, rms_eps=1e-5, bias=bd, epilogue=epilogue)
+    torch.cuda.synchronize()
+    assert torch.equal(whole, parts)
+    assert nerr(whole, ref) <= 2 * TOL["f32"]
